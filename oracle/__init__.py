@@ -1,0 +1,151 @@
+"""CPU oracle for the GEMM lineage -- TEST INFRASTRUCTURE ONLY.
+
+ctypes wrapper around ``gemm_oracle.c`` (plain C, fp64 accumulation).  Only the
+test-suite, the smoke check and the benchmark's CPU-baseline leg may import this
+package; the GPU library never does, and this package never imports the GPU
+library.  See the header of ``gemm_oracle.c`` for the definition it implements
+and for the list of pins that hold it in place.
+
+Arrays are numpy; integer-coded dtypes are passed as their raw bit patterns
+(``uint16`` for bf16/fp16, ``uint8`` for e4m3, ``float32`` for fp32).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+F32, BF16, F16, E4M3 = 0, 1, 2, 3
+ROW_MAJOR, COL_MAJOR = 0, 1
+
+_DIR = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_DIR, "gemm_oracle.c")
+_LIB = os.path.join(_DIR, "libgemm_oracle.so")
+
+_NP_STORAGE = {F32: np.float32, BF16: np.uint16, F16: np.uint16, E4M3: np.uint8}
+
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (no fast-math: fp64 semantics are the point)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-fno-fast-math",
+               "-ffp-contract=off", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _bind(path: str):
+    """Open an oracle shared object and declare its prototypes."""
+    lib = ctypes.CDLL(path)
+    i64, vp = ctypes.c_int64, ctypes.c_void_p
+    lib.oracle_decode.restype = ctypes.c_double
+    lib.oracle_decode.argtypes = [ctypes.c_int, ctypes.c_uint32]
+    lib.oracle_gemm.restype = ctypes.c_int
+    lib.oracle_gemm.argtypes = ([ctypes.c_int] * 3 + [i64] * 4 + [vp, i64, i64, vp, i64, i64]
+                                + [vp, vp, vp, vp, i64, i64])
+    lib.oracle_gemm_points.restype = ctypes.c_int
+    lib.oracle_gemm_points.argtypes = ([ctypes.c_int] * 3 + [i64] * 4 + [vp, i64, i64, vp, i64, i64]
+                                       + [vp, vp, i64, vp, vp, vp, vp, vp])
+    lib.oracle_num_threads.restype = ctypes.c_int
+    return lib
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = _bind(_LIB)
+    return _lib
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def decode(dtype: int, codes: np.ndarray) -> np.ndarray:
+    """Decode an array of stored bit patterns to fp64 values, one C call per element
+    for small arrays and a table lookup (built from those C calls) otherwise."""
+    lib = _load()
+    codes = np.asarray(codes)
+    if dtype == F32:
+        bits = codes.astype(np.float32).view(np.uint32) if codes.dtype.kind == "f" else codes.astype(np.uint32)
+        flat = bits.ravel()
+        if flat.size > 4096:
+            # fp32 -> fp64 widening is exact; spot-checked against oracle_decode in the pins
+            return flat.view(np.float32).astype(np.float64).reshape(codes.shape)
+        return np.array([lib.oracle_decode(F32, int(c)) for c in flat], dtype=np.float64).reshape(codes.shape)
+    nbits = 16 if dtype in (BF16, F16) else 8
+    table = np.array([lib.oracle_decode(dtype, c) for c in range(1 << nbits)], dtype=np.float64)
+    return table[codes.astype(np.int64)]
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _check_storage(dtype: int, a: np.ndarray, name: str) -> np.ndarray:
+    want = _NP_STORAGE[dtype]
+    if a.dtype != want:
+        raise TypeError(f"{name}: dtype code {dtype} is stored as {want}, got {a.dtype}")
+    if not a.flags["C_CONTIGUOUS"]:
+        raise ValueError(f"{name} must be a contiguous buffer (layout is described by ld/stride)")
+    return a
+
+
+def gemm(dtype: int, layout_a: int, layout_b: int, M: int, N: int, K: int,
+         A: np.ndarray, lda: int, B: np.ndarray, ldb: int, *, batch: int = 1,
+         stride_a: int = 0, stride_b: int = 0,
+         scale_a: Optional[np.ndarray] = None, scale_b: Optional[np.ndarray] = None
+         ) -> Tuple[np.ndarray, np.ndarray]:
+    """Full oracle product.  Returns (C_ref, D), each fp64 of shape (batch, M, N)."""
+    lib = _load()
+    A = _check_storage(dtype, A, "A")
+    B = _check_storage(dtype, B, "B")
+    if scale_a is not None:
+        scale_a = np.ascontiguousarray(scale_a, dtype=np.float32)
+    if scale_b is not None:
+        scale_b = np.ascontiguousarray(scale_b, dtype=np.float32)
+    C = np.zeros((batch, M, N), dtype=np.float64)
+    D = np.zeros((batch, M, N), dtype=np.float64)
+    rc = lib.oracle_gemm(dtype, layout_a, layout_b, M, N, K, batch,
+                         _ptr(A), lda, stride_a, _ptr(B), ldb, stride_b,
+                         _ptr(scale_a), _ptr(scale_b), _ptr(C), _ptr(D), max(N, 1), M * N)
+    if rc != 0:
+        raise ValueError(f"oracle_gemm rejected its arguments (code {rc})")
+    return C, D
+
+
+def gemm_points(dtype: int, layout_a: int, layout_b: int, M: int, N: int, K: int,
+                A: np.ndarray, lda: int, B: np.ndarray, ldb: int,
+                pb: np.ndarray, pi: np.ndarray, pj: np.ndarray, *, batch: int = 1,
+                stride_a: int = 0, stride_b: int = 0,
+                scale_a: Optional[np.ndarray] = None, scale_b: Optional[np.ndarray] = None
+                ) -> Tuple[np.ndarray, np.ndarray]:
+    """Oracle values at selected (batch, i, j) points.  Returns (C_ref, D), each fp64 of shape (n,)."""
+    lib = _load()
+    A = _check_storage(dtype, A, "A")
+    B = _check_storage(dtype, B, "B")
+    pb = np.ascontiguousarray(pb, dtype=np.int64)
+    pi = np.ascontiguousarray(pi, dtype=np.int64)
+    pj = np.ascontiguousarray(pj, dtype=np.int64)
+    n = pb.size
+    if pi.size != n or pj.size != n:
+        raise ValueError("point index arrays differ in length")
+    if scale_a is not None:
+        scale_a = np.ascontiguousarray(scale_a, dtype=np.float32)
+    if scale_b is not None:
+        scale_b = np.ascontiguousarray(scale_b, dtype=np.float32)
+    C = np.zeros(n, dtype=np.float64)
+    D = np.zeros(n, dtype=np.float64)
+    rc = lib.oracle_gemm_points(dtype, layout_a, layout_b, M, N, K, batch,
+                                _ptr(A), lda, stride_a, _ptr(B), ldb, stride_b,
+                                _ptr(scale_a), _ptr(scale_b), n, _ptr(pb), _ptr(pi), _ptr(pj),
+                                _ptr(C), _ptr(D))
+    if rc != 0:
+        raise ValueError(f"oracle_gemm_points rejected its arguments (code {rc})")
+    return C, D
