@@ -1,0 +1,154 @@
+/*
+ * gemm_lineage.h -- C ABI of the GEMM kernel lineage for AMD Instinct MI355X (gfx950).
+ *
+ * The library holds one workload, the dense product C = s * (A . B) with fp32
+ * accumulation, as an ordered lineage of hand-written kernel states
+ *
+ *     L = (K0, tau_1, K1, ..., tau_n, K_n = K*)            (paper Sec. 3.1)
+ *
+ * from a naive kernel to the expert one.  Each state adds one optimisation
+ * intent of the paper's Table 1 ("tile / sm_stage", "vectorize_global",
+ * "cp.async + pipeline", "mma" + "ldmatrix.swizzle", "templatize"), realised
+ * for CDNA4: LDS staging, 16-byte global loads with masked tails, a
+ * double-buffered LDS pipeline, wave64 MFMA with a conflict-free LDS operand
+ * layout.  Every state can be launched on its own so that the validation gate
+ * (compile -> correctness -> profile, Sec. 3.1 / Sec. 4.1) can be applied at
+ * every step of the lineage.
+ *
+ * Conventions for every entry point
+ *   - A, B, C, scale_a, scale_b and workspace are DEVICE pointers owned by the
+ *     caller; descriptors and query results are HOST memory owned by the caller.
+ *   - The library allocates and frees nothing and keeps no state between calls.
+ *   - Launches are asynchronous on the given stream; nothing synchronises.
+ *   - Errors are returned as gemm_status_t values; no exception crosses the ABI.
+ *     On any status other than GEMM_OK no kernel was launched and C is untouched.
+ *   - A variant never substitutes another variant (Sec. B "wrapper" audit: a
+ *     submission that falls back to a reference is not a kernel).  When the
+ *     fast path of a variant does not apply, either its own documented slow
+ *     path runs (and gemm_query names it) or, with GEMM_FLAG_STRICT, the call
+ *     is refused with GEMM_ERR_PRECONDITION.
+ */
+#ifndef GEMM_LINEAGE_H
+#define GEMM_LINEAGE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    GEMM_OK = 0,
+    GEMM_ERR_BAD_ARG = 1,           /* null pointer, negative size, ld smaller than the extent ... */
+    GEMM_ERR_BAD_VARIANT = 2,       /* variant id outside [0, GEMM_VARIANT_COUNT) */
+    GEMM_ERR_UNSUPPORTED_DTYPE = 3, /* in/out dtype pair the library does not implement */
+    GEMM_ERR_PRECONDITION = 4,      /* a condition the variant relies on does not hold (see gemm_query) */
+    GEMM_ERR_WORKSPACE = 5,         /* workspace missing or smaller than gemm_query reports */
+    GEMM_ERR_LAUNCH = 6             /* the HIP runtime refused the launch */
+} gemm_status_t;
+
+/* Storage formats.  bf16/fp16 are 2-byte IEEE-style patterns, GEMM_FP8_E4M3 is the
+ * OCP 8-bit E4M3 format (bias 7, max 448, no infinities). */
+typedef enum { GEMM_F32 = 0, GEMM_BF16 = 1, GEMM_F16 = 2, GEMM_FP8_E4M3 = 3 } gemm_dtype_t;
+
+/* Row-major: element (r, c) at r*ld + c.  Column-major: at c*ld + r. */
+typedef enum { GEMM_ROW_MAJOR = 0, GEMM_COL_MAJOR = 1 } gemm_layout_t;
+
+/* The lineage, in forward order (Sec. 3.1, Table 1). */
+typedef enum {
+    GEMM_K0_NAIVE = 0,      /* one thread per output element, operands read from global memory */
+    GEMM_K1_LDS_TILED = 1,  /* + "tile / sm_stage": workgroup output tiles, K slabs staged through LDS */
+    GEMM_K2_VECTORIZED = 2, /* + "vectorize_global": 16-byte global loads, element-masked tails */
+    GEMM_K3_PIPELINED = 3,  /* + "pipeline": double-buffered LDS, next slab in flight during compute */
+    GEMM_K4_MFMA = 4,       /* + "mma" / "swizzle": wave64 MFMA, swizzled LDS operand layout */
+    GEMM_VARIANT_COUNT = 5
+} gemm_variant_t;
+
+/* Conditions a variant may rely on (Table 1's precondition column; Sec. 1: vectorised
+ * loads need alignment and tail handling, pipelining needs staged data movement, matrix
+ * intrinsics need compatible tile shapes, layouts and hardware support). */
+enum {
+    GEMM_COND_ALIGN16_A      = 1u << 0,  /* base pointer of A (incl. batch stride) is 16-byte aligned */
+    GEMM_COND_ALIGN16_B      = 1u << 1,
+    GEMM_COND_ALIGN16_C      = 1u << 2,
+    GEMM_COND_LD16_A         = 1u << 3,  /* lda * element size is a multiple of 16 bytes */
+    GEMM_COND_LD16_B         = 1u << 4,
+    GEMM_COND_LD16_C         = 1u << 5,
+    GEMM_COND_TILE_DIV_M     = 1u << 6,  /* M is a multiple of the variant's BM */
+    GEMM_COND_TILE_DIV_N     = 1u << 7,
+    GEMM_COND_TILE_DIV_K     = 1u << 8,
+    GEMM_COND_K_CONTIG_A     = 1u << 9,  /* A stored with K contiguous (row-major) */
+    GEMM_COND_K_CONTIG_B     = 1u << 10, /* B stored with K contiguous (column-major) */
+    GEMM_COND_DTYPE_HAS_MFMA = 1u << 11, /* the input dtype has a matrix instruction on gfx950 */
+    GEMM_COND_LDS_STAGED     = 1u << 12, /* operands pass through LDS (holds from K1 on) */
+    GEMM_COND_SMALL_M        = 1u << 13  /* M <= 16: the streaming (bandwidth-bound) path applies */
+};
+
+enum {
+    GEMM_FLAG_STRICT = 1u << 0  /* refuse (GEMM_ERR_PRECONDITION) instead of taking a variant's slow path */
+};
+
+typedef struct {
+    int64_t M, N, K;                 /* logical sizes: A is M x K, B is K x N, C is M x N; >= 0 */
+    int64_t batch;                   /* number of independent problems, >= 1 */
+    int32_t in_dtype, out_dtype;     /* gemm_dtype_t; accumulation is always fp32 */
+    int32_t layout_a, layout_b;      /* gemm_layout_t; C is always row-major */
+    int64_t lda, ldb, ldc;           /* leading dimensions, in elements */
+    int64_t stride_a, stride_b, stride_c; /* elements between consecutive batch items */
+    const float *scale_a, *scale_b;  /* device: one fp32 per batch item each, or NULL (= 1).  The
+                                        epilogue multiplies the fp32 accumulator by scale_a[b]*scale_b[b]
+                                        before rounding to out_dtype (round to nearest even). */
+    void *workspace;                 /* device scratch; NULL allowed when gemm_query reports 0 bytes */
+    size_t workspace_bytes;
+    void *stream;                    /* hipStream_t; NULL = the default stream */
+    uint32_t flags;                  /* GEMM_FLAG_* */
+    uint32_t reserved;               /* must be 0 */
+} gemm_desc_t;
+
+typedef struct {
+    uint32_t required;        /* conditions the variant's fast path relies on for this dtype */
+    uint32_t violated;        /* subset of `required` that does not hold for this call */
+    uint32_t holds;           /* every GEMM_COND_* bit that holds for this call */
+    int32_t  bm, bn, bk;      /* workgroup tile (0 where meaningless) */
+    int32_t  threads;         /* workgroup size */
+    int32_t  stages;          /* LDS buffers in flight */
+    int32_t  lds_bytes;       /* static + dynamic LDS per workgroup */
+    int64_t  grid;            /* workgroups launched */
+    size_t   workspace_bytes; /* scratch the call needs */
+    char     path[64];        /* name of the code path gemm_run_ex would take */
+} gemm_query_t;
+
+/*
+ * gemm_run: the short form named in the lineage's problem statement.  Batch 1, tight
+ * leading dimensions, output dtype = input dtype (bf16 for fp8 input), no scales, default
+ * stream, layouts A row-major and B row-major for GEMM_F32/GEMM_F16, A row-major and B
+ * column-major (K contiguous) for GEMM_BF16/GEMM_FP8_E4M3.
+ */
+int gemm_run(int variant, int64_t M, int64_t N, int64_t K, int dtype,
+             const void *A, const void *B, void *C);
+
+/* gemm_run_ex: full form.  Validates, checks the variant's conditions, launches on d->stream. */
+int gemm_run_ex(int variant, const gemm_desc_t *d, const void *A, const void *B, void *C);
+
+/* gemm_query: host only, launches nothing.  Reports which conditions the variant relies on,
+ * which of them this call violates, the path that would run and its launch geometry.  A, B, C
+ * may be NULL (then the ALIGN16 conditions are reported as holding).  Returns the status
+ * gemm_run_ex would return before launching. */
+int gemm_query(int variant, const gemm_desc_t *d, const void *A, const void *B, const void *C,
+               gemm_query_t *out);
+
+/* gemm_default_desc: fills *d with the defaults gemm_run uses for (M, N, K, dtype). */
+int gemm_default_desc(gemm_desc_t *d, int64_t M, int64_t N, int64_t K, int dtype);
+
+const char *gemm_status_string(int status);
+const char *gemm_variant_name(int variant);
+const char *gemm_variant_intent(int variant); /* Table 1 intent the transition into this state adds */
+const char *gemm_cond_name(uint32_t single_bit);
+int gemm_variant_count(void);
+int gemm_abi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GEMM_LINEAGE_H */

@@ -1,0 +1,95 @@
+// Shared device/host declarations for the GEMM lineage kernels (gfx950 only).
+//
+// Every lineage state computes the same thing (paper Sec. 3.1: a lineage is a sequence of
+// validated states of ONE kernel): C[b,i,j] = round_out(s_b * sum_k dec(A[b,i,k]) dec(B[b,k,j]))
+// with fp32 accumulation, s_b = scale_a[b]*scale_b[b].  This header holds the pieces all states
+// share: the launch argument block, exact decoders of the four storage formats, and the
+// round-to-nearest-even output conversion.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/gemm_lineage.h"
+
+namespace gl {
+
+// Launch arguments, passed to kernels by value.  Strides are in elements.
+struct Args {
+    const void* A;
+    const void* B;
+    void* C;
+    const float* scale_a;
+    const float* scale_b;
+    void* workspace;
+    int64_t M, N, K, batch;
+    int64_t a_si, a_sk;  // A(i,k) at i*a_si + k*a_sk
+    int64_t b_sk, b_sj;  // B(k,j) at k*b_sk + j*b_sj
+    int64_t ldc;
+    int64_t stride_a, stride_b, stride_c;
+    int32_t in_dtype, out_dtype;
+    hipStream_t stream;
+};
+
+// ---- storage formats ------------------------------------------------------------------------
+struct F32 { using raw = float;    static constexpr int BYTES = 4; static constexpr int ID = GEMM_F32; };
+struct BF16 { using raw = uint16_t; static constexpr int BYTES = 2; static constexpr int ID = GEMM_BF16; };
+struct F16 { using raw = uint16_t; static constexpr int BYTES = 2; static constexpr int ID = GEMM_F16; };
+struct E4M3 { using raw = uint8_t;  static constexpr int BYTES = 1; static constexpr int ID = GEMM_FP8_E4M3; };
+
+template <typename T> __device__ __forceinline__ float decode(typename T::raw v);
+
+template <> __device__ __forceinline__ float decode<F32>(float v) { return v; }
+template <> __device__ __forceinline__ float decode<BF16>(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
+template <> __device__ __forceinline__ float decode<F16>(uint16_t v) { return (float)__builtin_bit_cast(_Float16, v); }
+// OCP E4M3: bias 7; e==0 is subnormal (m * 2^-9); S.1111.111 is NaN; no infinities.
+template <> __device__ __forceinline__ float decode<E4M3>(uint8_t v)
+{
+    const uint32_t s = (uint32_t)(v & 0x80u) << 24, e = (v >> 3) & 0xFu, m = v & 0x7u;
+    if ((v & 0x7Fu) == 0x7Fu) return __uint_as_float(s | 0x7FC00000u);
+    if (e == 0) return __uint_as_float(s | __float_as_uint((float)m * 0x1p-9f));
+    return __uint_as_float(s | ((e + 120u) << 23) | (m << 20));
+}
+
+// fp32 -> bf16 bits, round to nearest even (NaN kept quiet).
+__device__ __forceinline__ uint16_t encode_bf16(float x)
+{
+    uint32_t b = __float_as_uint(x);
+    if ((b & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((b >> 16) | 0x40u);
+    b += 0x7FFFu + ((b >> 16) & 1u);
+    return (uint16_t)(b >> 16);
+}
+__device__ __forceinline__ uint16_t encode_f16(float x) { return __builtin_bit_cast(uint16_t, (_Float16)x); }
+
+// Epilogue store of one element; out_dtype is uniform across the launch.
+__device__ __forceinline__ void store_out(void* C, int64_t idx, float v, int out_dtype)
+{
+    if (out_dtype == GEMM_F32) ((float*)C)[idx] = v;
+    else if (out_dtype == GEMM_BF16) ((uint16_t*)C)[idx] = encode_bf16(v);
+    else ((uint16_t*)C)[idx] = encode_f16(v);
+}
+
+__device__ __forceinline__ float batch_scale(const Args& a, int64_t b)
+{
+    float s = 1.0f;
+    if (a.scale_a) s *= a.scale_a[b];
+    if (a.scale_b) s *= a.scale_b[b];
+    return s;
+}
+
+// ---- host-side launchers, one per translation unit ---------------------------------------------
+// Each returns hipSuccess or the launch error.  `path` selects a code path that the caller
+// (gemm_api.hip) has already proven legal for these arguments.
+enum ValuPath { VALU_SCALAR = 0, VALU_VEC16 = 1 };
+enum MfmaPath { MFMA_ELEMENTWISE = 0, MFMA_VEC16 = 1, MFMA_SKINNY = 2 };
+
+hipError_t launch_k0(const Args& a);
+hipError_t launch_valu_tiled(int variant, int path, const Args& a);
+hipError_t launch_k4(int path, const Args& a);
+
+// Geometry reported by gemm_query (kept next to the kernels that define it).
+struct Geometry { int bm, bn, bk, threads, stages, lds_bytes; int64_t grid; };
+Geometry geometry_k0(const Args& a);
+Geometry geometry_valu_tiled(int variant, int path, const Args& a);
+Geometry geometry_k4(int path, const Args& a);
+
+}  // namespace gl

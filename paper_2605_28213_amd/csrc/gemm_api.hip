@@ -1,0 +1,290 @@
+// C ABI of the GEMM lineage: argument validation, the per-variant precondition check and the
+// dispatch to the kernel of exactly the requested lineage state.  Host code only.
+//
+// The precondition bookkeeping is the deterministic part of what the paper calls a skill's
+// `pre` and `risk` fields (Sec. 3.1): for every state it names the conditions the fast path
+// relies on, which of them a given call violates, and what happens then (the state's own
+// masked path, or a refusal under GEMM_FLAG_STRICT).  No state ever runs another state's kernel.
+#include <string.h>
+
+#include "common.hpp"
+
+using namespace gl;
+
+namespace {
+
+constexpr int ABI_VERSION = 1;
+
+bool dtype_pair_supported(int in, int out)
+{
+    switch (in) {
+    case GEMM_F32: return out == GEMM_F32;
+    case GEMM_BF16: return out == GEMM_BF16 || out == GEMM_F32;
+    case GEMM_F16: return out == GEMM_F16 || out == GEMM_F32;
+    case GEMM_FP8_E4M3: return out == GEMM_BF16 || out == GEMM_F32;
+    default: return false;
+    }
+}
+
+int elem_size(int dt) { return dt == GEMM_F32 ? 4 : dt == GEMM_FP8_E4M3 ? 1 : 2; }
+
+bool aligned16(const void* p, int64_t batch, int64_t stride, int es)
+{
+    if (p && ((uintptr_t)p & 15u)) return false;
+    return batch <= 1 || (stride * es) % 16 == 0;
+}
+
+struct Plan {
+    int status = GEMM_OK;
+    bool empty = false;     // nothing to compute (M, N or batch extent 0)
+    int path = 0;           // launcher-specific
+    Args args{};
+    gemm_query_t q{};
+};
+
+int validate(int variant, const gemm_desc_t* d, const void* A, const void* B, const void* C, bool need_ptrs)
+{
+    if (variant < 0 || variant >= GEMM_VARIANT_COUNT) return GEMM_ERR_BAD_VARIANT;
+    if (!d) return GEMM_ERR_BAD_ARG;
+    if (d->M < 0 || d->N < 0 || d->K < 0 || d->batch < 1 || d->reserved != 0) return GEMM_ERR_BAD_ARG;
+    if (d->M > (int64_t)1 << 30 || d->N > (int64_t)1 << 30 || d->K > (int64_t)1 << 30 || d->batch > 65535) return GEMM_ERR_BAD_ARG;
+    if (d->in_dtype < 0 || d->in_dtype > GEMM_FP8_E4M3 || d->out_dtype < 0 || d->out_dtype > GEMM_FP8_E4M3)
+        return GEMM_ERR_UNSUPPORTED_DTYPE;
+    if (!dtype_pair_supported(d->in_dtype, d->out_dtype)) return GEMM_ERR_UNSUPPORTED_DTYPE;
+    if ((d->layout_a != GEMM_ROW_MAJOR && d->layout_a != GEMM_COL_MAJOR) ||
+        (d->layout_b != GEMM_ROW_MAJOR && d->layout_b != GEMM_COL_MAJOR))
+        return GEMM_ERR_BAD_ARG;
+    if (d->flags & ~(uint32_t)GEMM_FLAG_STRICT) return GEMM_ERR_BAD_ARG;
+    const int64_t min_lda = d->layout_a == GEMM_ROW_MAJOR ? d->K : d->M;
+    const int64_t min_ldb = d->layout_b == GEMM_ROW_MAJOR ? d->N : d->K;
+    if (d->lda < 1 || d->ldb < 1 || d->ldc < 1) return GEMM_ERR_BAD_ARG;
+    if (d->lda < min_lda || d->ldb < min_ldb || d->ldc < d->N) return GEMM_ERR_BAD_ARG;
+    if (d->stride_a < 0 || d->stride_b < 0 || d->stride_c < 0) return GEMM_ERR_BAD_ARG;
+    if (d->batch > 1 && d->M > 0 && d->N > 0 && d->stride_c < (d->M - 1) * d->ldc + d->N) return GEMM_ERR_BAD_ARG;
+    if (need_ptrs && d->M > 0 && d->N > 0) {
+        if (!C) return GEMM_ERR_BAD_ARG;
+        if (d->K > 0 && (!A || !B)) return GEMM_ERR_BAD_ARG;
+    }
+    return GEMM_OK;
+}
+
+// Grid limits of the launchers (65535 workgroups along y/z, 2^31-1 along x).
+bool grid_fits(int variant, const gemm_desc_t* d)
+{
+    const int64_t lim = 65535;
+    if (variant == GEMM_K0_NAIVE) return (d->M + 15) / 16 <= lim;
+    if (variant == GEMM_K1_LDS_TILED) return (d->M + 63) / 64 <= lim;
+    if (variant == GEMM_K2_VECTORIZED || variant == GEMM_K3_PIPELINED) return (d->M + 127) / 128 <= lim;
+    return ((d->M + 255) / 256) * ((d->N + 255) / 256) < ((int64_t)1 << 31);
+}
+
+Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, const void* C, bool need_ptrs)
+{
+    Plan p;
+    p.status = validate(variant, d, A, B, C, need_ptrs);
+    if (p.status != GEMM_OK) return p;
+    if (!grid_fits(variant, d)) { p.status = GEMM_ERR_BAD_ARG; return p; }
+
+    Args& a = p.args;
+    a.A = A; a.B = B; a.C = (void*)C;
+    a.scale_a = d->scale_a; a.scale_b = d->scale_b;
+    a.workspace = d->workspace;
+    a.M = d->M; a.N = d->N; a.K = d->K; a.batch = d->batch;
+    a.a_si = d->layout_a == GEMM_ROW_MAJOR ? d->lda : 1;
+    a.a_sk = d->layout_a == GEMM_ROW_MAJOR ? 1 : d->lda;
+    a.b_sk = d->layout_b == GEMM_ROW_MAJOR ? d->ldb : 1;
+    a.b_sj = d->layout_b == GEMM_ROW_MAJOR ? 1 : d->ldb;
+    a.ldc = d->ldc;
+    a.stride_a = d->stride_a; a.stride_b = d->stride_b; a.stride_c = d->stride_c;
+    a.in_dtype = d->in_dtype; a.out_dtype = d->out_dtype;
+    a.stream = (hipStream_t)d->stream;
+    p.empty = d->M == 0 || d->N == 0;
+
+    const int es = elem_size(d->in_dtype), eo = elem_size(d->out_dtype);
+    uint32_t holds = 0;
+    if (aligned16(A, d->batch, d->stride_a, es)) holds |= GEMM_COND_ALIGN16_A;
+    if (aligned16(B, d->batch, d->stride_b, es)) holds |= GEMM_COND_ALIGN16_B;
+    if (aligned16(C, d->batch, d->stride_c, eo)) holds |= GEMM_COND_ALIGN16_C;
+    if ((d->lda * es) % 16 == 0) holds |= GEMM_COND_LD16_A;
+    if ((d->ldb * es) % 16 == 0) holds |= GEMM_COND_LD16_B;
+    if ((d->ldc * eo) % 16 == 0) holds |= GEMM_COND_LD16_C;
+    if (d->layout_a == GEMM_ROW_MAJOR) holds |= GEMM_COND_K_CONTIG_A;
+    if (d->layout_b == GEMM_COL_MAJOR) holds |= GEMM_COND_K_CONTIG_B;
+    if (d->in_dtype != GEMM_F32) holds |= GEMM_COND_DTYPE_HAS_MFMA;
+    if (variant >= GEMM_K1_LDS_TILED) holds |= GEMM_COND_LDS_STAGED;
+    if (d->M <= 16) holds |= GEMM_COND_SMALL_M;
+
+    const uint32_t vecA = GEMM_COND_ALIGN16_A | GEMM_COND_LD16_A, vecB = GEMM_COND_ALIGN16_B | GEMM_COND_LD16_B;
+    uint32_t required = 0;
+    Geometry g{};
+    const char* path = "";
+    switch (variant) {
+    case GEMM_K0_NAIVE:
+        g = geometry_k0(a);
+        path = "naive";
+        break;
+    case GEMM_K1_LDS_TILED:
+        required = GEMM_COND_LDS_STAGED;
+        g = geometry_valu_tiled(variant, 0, a);
+        path = "lds-tiled";
+        break;
+    case GEMM_K2_VECTORIZED:
+    case GEMM_K3_PIPELINED: {
+        required = vecA | vecB | (variant == GEMM_K3_PIPELINED ? (uint32_t)GEMM_COND_LDS_STAGED : 0u);
+        const bool va = (holds & vecA) == vecA, vb = (holds & vecB) == vecB;
+        p.path = (va ? 1 : 0) | (vb ? 2 : 0);
+        path = va && vb ? "vec16" : va ? "vec16(A)+elementwise-masked(B)" : vb ? "elementwise-masked(A)+vec16(B)"
+                                                                              : "elementwise-masked";
+        g = geometry_valu_tiled(variant, p.path, a);
+        break;
+    }
+    default: {  // GEMM_K4_MFMA
+        required = GEMM_COND_DTYPE_HAS_MFMA | GEMM_COND_LDS_STAGED | vecA | vecB | GEMM_COND_K_CONTIG_A | GEMM_COND_K_CONTIG_B;
+        const bool va = (holds & (vecA | GEMM_COND_K_CONTIG_A)) == (vecA | GEMM_COND_K_CONTIG_A);
+        const bool vb = (holds & (vecB | GEMM_COND_K_CONTIG_B)) == (vecB | GEMM_COND_K_CONTIG_B);
+        const int64_t kvec = 16 / es;
+        const bool skinny = (holds & GEMM_COND_SMALL_M) && va && vb && d->K % kvec == 0 && d->K > 0 &&
+                            (d->in_dtype == GEMM_BF16 || d->in_dtype == GEMM_F16);
+        if (skinny) {
+            p.path = MFMA_SKINNY;
+            path = "mfma16-stream(small-M)";
+        } else {
+            p.path = (va && vb ? MFMA_VEC16 : MFMA_ELEMENTWISE) | (((va ? 1 : 0) | (vb ? 2 : 0)) << 8);
+            path = va && vb ? "mfma32-vec16" : va ? "mfma32-vec16(A)+elementwise-masked(B)"
+                            : vb ? "mfma32-elementwise-masked(A)+vec16(B)" : "mfma32-elementwise-masked";
+        }
+        if (holds & GEMM_COND_DTYPE_HAS_MFMA) g = geometry_k4(p.path & 0xFF, a);
+        else path = "refused(no matrix instruction for this dtype)";
+        break;
+    }
+    }
+    if (g.bm > 0 && d->M % g.bm == 0) holds |= GEMM_COND_TILE_DIV_M;
+    if (g.bn > 0 && d->N % g.bn == 0) holds |= GEMM_COND_TILE_DIV_N;
+    if (g.bk > 0 && d->K % g.bk == 0) holds |= GEMM_COND_TILE_DIV_K;
+
+    gemm_query_t& q = p.q;
+    q.required = required;
+    q.holds = holds;
+    q.violated = required & ~holds;
+    q.bm = g.bm; q.bn = g.bn; q.bk = g.bk;
+    q.threads = g.threads; q.stages = g.stages; q.lds_bytes = g.lds_bytes;
+    q.grid = p.empty ? 0 : g.grid;
+    q.workspace_bytes = 0;
+    strncpy(q.path, path, sizeof(q.path) - 1);
+
+    const bool hard = (q.violated & GEMM_COND_DTYPE_HAS_MFMA) != 0;   // no slow path exists for this one
+    if (hard || (q.violated && (d->flags & GEMM_FLAG_STRICT))) p.status = GEMM_ERR_PRECONDITION;
+    else if (q.workspace_bytes > 0 && (!d->workspace || d->workspace_bytes < q.workspace_bytes) && need_ptrs)
+        p.status = GEMM_ERR_WORKSPACE;
+    return p;
+}
+
+}  // namespace
+
+extern "C" {
+
+int gemm_default_desc(gemm_desc_t* d, int64_t M, int64_t N, int64_t K, int dtype)
+{
+    if (!d) return GEMM_ERR_BAD_ARG;
+    if (dtype < 0 || dtype > GEMM_FP8_E4M3) return GEMM_ERR_UNSUPPORTED_DTYPE;
+    if (M < 0 || N < 0 || K < 0) return GEMM_ERR_BAD_ARG;
+    memset(d, 0, sizeof(*d));
+    d->M = M; d->N = N; d->K = K; d->batch = 1;
+    d->in_dtype = dtype;
+    d->out_dtype = dtype == GEMM_FP8_E4M3 ? GEMM_BF16 : dtype;
+    d->layout_a = GEMM_ROW_MAJOR;
+    d->layout_b = (dtype == GEMM_F32 || dtype == GEMM_F16) ? GEMM_ROW_MAJOR : GEMM_COL_MAJOR;
+    d->lda = K > 0 ? K : 1;
+    d->ldb = d->layout_b == GEMM_ROW_MAJOR ? (N > 0 ? N : 1) : (K > 0 ? K : 1);
+    d->ldc = N > 0 ? N : 1;
+    d->stride_a = M * d->lda;
+    d->stride_b = (d->layout_b == GEMM_ROW_MAJOR ? K : N) * d->ldb;
+    d->stride_c = M * d->ldc;
+    return GEMM_OK;
+}
+
+int gemm_query(int variant, const gemm_desc_t* d, const void* A, const void* B, const void* C, gemm_query_t* out)
+{
+    if (!out) return GEMM_ERR_BAD_ARG;
+    Plan p = make_plan(variant, d, A, B, C, /*need_ptrs=*/false);
+    memset(out, 0, sizeof(*out));
+    if (p.status == GEMM_OK || p.status == GEMM_ERR_PRECONDITION || p.status == GEMM_ERR_WORKSPACE) *out = p.q;
+    return p.status;
+}
+
+int gemm_run_ex(int variant, const gemm_desc_t* d, const void* A, const void* B, void* C)
+{
+    Plan p = make_plan(variant, d, A, B, C, /*need_ptrs=*/true);
+    if (p.status != GEMM_OK) return p.status;
+    if (p.empty) return GEMM_OK;
+    hipError_t e;
+    switch (variant) {
+    case GEMM_K0_NAIVE: e = launch_k0(p.args); break;
+    case GEMM_K1_LDS_TILED:
+    case GEMM_K2_VECTORIZED:
+    case GEMM_K3_PIPELINED: e = launch_valu_tiled(variant, p.path, p.args); break;
+    default: e = launch_k4((p.path & 0xFF) == MFMA_SKINNY ? MFMA_SKINNY : p.path, p.args); break;
+    }
+    return e == hipSuccess ? GEMM_OK : GEMM_ERR_LAUNCH;
+}
+
+int gemm_run(int variant, int64_t M, int64_t N, int64_t K, int dtype, const void* A, const void* B, void* C)
+{
+    gemm_desc_t d;
+    int rc = gemm_default_desc(&d, M, N, K, dtype);
+    if (rc != GEMM_OK) return rc;
+    return gemm_run_ex(variant, &d, A, B, C);
+}
+
+const char* gemm_status_string(int s)
+{
+    switch (s) {
+    case GEMM_OK: return "ok";
+    case GEMM_ERR_BAD_ARG: return "bad argument";
+    case GEMM_ERR_BAD_VARIANT: return "unknown variant";
+    case GEMM_ERR_UNSUPPORTED_DTYPE: return "unsupported dtype";
+    case GEMM_ERR_PRECONDITION: return "precondition of the variant violated";
+    case GEMM_ERR_WORKSPACE: return "workspace missing or too small";
+    case GEMM_ERR_LAUNCH: return "kernel launch failed";
+    default: return "unknown status";
+    }
+}
+
+const char* gemm_variant_name(int v)
+{
+    static const char* names[] = {"K0_naive", "K1_lds_tiled", "K2_vectorized", "K3_pipelined", "K4_mfma"};
+    return (v >= 0 && v < GEMM_VARIANT_COUNT) ? names[v] : "?";
+}
+
+const char* gemm_variant_intent(int v)
+{
+    static const char* intents[] = {"(start of lineage)", "tile / sm_stage", "vectorize_global", "pipeline (double-buffered LDS)",
+                                    "mma + operand-layout swizzle"};
+    return (v >= 0 && v < GEMM_VARIANT_COUNT) ? intents[v] : "?";
+}
+
+const char* gemm_cond_name(uint32_t bit)
+{
+    switch (bit) {
+    case GEMM_COND_ALIGN16_A: return "ALIGN16_A";
+    case GEMM_COND_ALIGN16_B: return "ALIGN16_B";
+    case GEMM_COND_ALIGN16_C: return "ALIGN16_C";
+    case GEMM_COND_LD16_A: return "LD16_A";
+    case GEMM_COND_LD16_B: return "LD16_B";
+    case GEMM_COND_LD16_C: return "LD16_C";
+    case GEMM_COND_TILE_DIV_M: return "TILE_DIV_M";
+    case GEMM_COND_TILE_DIV_N: return "TILE_DIV_N";
+    case GEMM_COND_TILE_DIV_K: return "TILE_DIV_K";
+    case GEMM_COND_K_CONTIG_A: return "K_CONTIG_A";
+    case GEMM_COND_K_CONTIG_B: return "K_CONTIG_B";
+    case GEMM_COND_DTYPE_HAS_MFMA: return "DTYPE_HAS_MFMA";
+    case GEMM_COND_LDS_STAGED: return "LDS_STAGED";
+    case GEMM_COND_SMALL_M: return "SMALL_M";
+    default: return "?";
+    }
+}
+
+int gemm_variant_count(void) { return GEMM_VARIANT_COUNT; }
+int gemm_abi_version(void) { return ABI_VERSION; }
+
+}  // extern "C"

@@ -1,0 +1,189 @@
+"""GPU parity: every lineage variant against the CPU oracle, element by element, through the C ABI.
+
+Sizes here are ones the oracle finishes in seconds while still spanning several workgroup tiles of
+every variant (the largest tile is 256 x 256 x 128 B of K) and ending in ragged tails.  Full-size
+workloads are covered by tests/test_full_size_gpu.py.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2605_28213_amd import gemm
+from paper_2605_28213_amd import inputs as gen
+from tests import util
+
+pytestmark = pytest.mark.gpu
+
+VARIANTS = list(range(gemm.GEMM_VARIANT_COUNT))
+ROW, COL = gen.ROW_MAJOR, gen.COL_MAJOR
+
+
+def variants_for(dtype):
+    return [v for v in VARIANTS if not (v == gemm.GEMM_K4_MFMA and dtype == gen.F32)]
+
+
+def oracle_for(inp):
+    c = inp.cfg
+    return oracle.gemm(c.in_dtype, c.layout_a, c.layout_b, c.M, c.N, c.K, inp.A, inp.lda, inp.B, inp.ldb,
+                       batch=c.batch, stride_a=inp.stride_a, stride_b=inp.stride_b,
+                       scale_a=inp.scale_a, scale_b=inp.scale_b)
+
+
+def check(variant, inp, ref=None, out_dtype=None):
+    c = inp.cfg
+    C_ref, D = ref if ref is not None else oracle_for(inp)
+    rc, C, _ = util.run_config(variant, inp, out_dtype=out_dtype)
+    assert rc == gemm.GEMM_OK, gemm.gemm_status_string(rc)
+    err = util.norm_err(C[:, :, : c.N], C_ref, D)
+    assert err <= util.TOL[c.in_dtype], f"{gemm.gemm_variant_name(variant)} on {c.name}: normalised error {err:.3e}"
+    return err
+
+
+@pytest.mark.parametrize("name", ["C1", "C2_small", "C3_small", "C4_small", "C5_small"])
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_small_workloads_three_seeds(name, seed):
+    """The five workload families at reduced size (C1 is already small), all variants, seeds 0..2."""
+    cfg = gen.CONFIGS[name]
+    inp = gen.make_inputs(cfg, seed)
+    ref = oracle_for(inp)
+    for v in variants_for(cfg.in_dtype):
+        check(v, inp, ref)
+
+
+@pytest.mark.parametrize("dtype", [gen.F32, gen.BF16, gen.F16, gen.E4M3])
+@pytest.mark.parametrize("la,lb", [(ROW, ROW), (ROW, COL), (COL, ROW), (COL, COL)])
+@pytest.mark.parametrize("aligned", [True, False])
+def test_all_layouts_ragged_multi_tile(dtype, la, lb, aligned):
+    """M, N, K cross tile edges of every variant with a tail; leading dimensions either padded to a
+    16-byte multiple (fast paths) or tight and odd (masked paths)."""
+    M, N, K = 300, 270, 203
+    out = gen.BF16 if dtype == gen.E4M3 else dtype
+    pad = (lambda n: (n + 15) // 16 * 16) if aligned else (lambda n: n)
+    cfg = gen.Config("ragged", M, N, K, dtype, out, la, lb, "uniform",
+                     lda=pad(K if la == ROW else M), ldb=pad(N if lb == ROW else K), ldc=pad(N))
+    inp = gen.make_inputs(cfg, 11)
+    ref = oracle_for(inp)
+    for v in variants_for(dtype):
+        q = gemm.gemm_query(v, gemm.make_desc(M, N, K, dtype, out, la, lb, lda=inp.lda, ldb=inp.ldb, ldc=inp.ldc))
+        if v >= 2 and aligned and not (v == 4 and (la != ROW or lb != COL)):
+            assert "elementwise" not in q.path
+        if v >= 2 and not aligned and dtype != gen.E4M3:
+            assert "elementwise" in q.path
+        check(v, inp, ref)
+
+
+@pytest.mark.parametrize("dtype", [gen.F32, gen.BF16, gen.F16, gen.E4M3])
+def test_integer_inputs_give_bitwise_exact_fp32_output(dtype):
+    """Entries in {-2..2}, K <= 4096: every partial sum is an integer below 2^24, so any correct
+    fp32-accumulating kernel equals the exact product bit for bit, whatever its summation order."""
+    rng = np.random.default_rng(5)
+    M, N, K = 259, 130, 1000
+    la, lb = ROW, COL
+    A = gen.quantise(dtype, rng.integers(-2, 3, M * K).astype(np.float32))
+    B = gen.quantise(dtype, rng.integers(-2, 3, N * K).astype(np.float32))
+    cfg = gen.Config("ints", M, N, K, dtype, gen.F32, la, lb, "uniform")
+    inp = gen.Inputs(cfg, 0, A, B, K, K, N, M * K, N * K, M * N)
+    C_ref, D = oracle_for(inp)
+    for v in variants_for(dtype):
+        rc, C, _ = util.run_config(v, inp)
+        assert rc == gemm.GEMM_OK
+        np.testing.assert_array_equal(C, C_ref, err_msg=gemm.gemm_variant_name(v))
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (1, 7, 5), (16, 33, 64), (17, 16, 8), (5, 3, 0), (2, 600, 9), (33, 1, 4100)])
+@pytest.mark.parametrize("dtype", [gen.F32, gen.BF16, gen.E4M3])
+def test_degenerate_shapes(M, N, K, dtype):
+    out = gen.BF16 if dtype == gen.E4M3 else dtype
+    for la, lb in [(ROW, ROW), (ROW, COL)]:
+        cfg = gen.Config("tiny", M, N, K, dtype, out, la, lb, "uniform")
+        inp = gen.make_inputs(cfg, 3)
+        ref = oracle_for(inp)
+        for v in variants_for(dtype):
+            check(v, inp, ref)
+            if K == 0:
+                rc, C, _ = util.run_config(v, inp)
+                assert np.all(C == 0)
+
+
+def test_skinny_path_edges():
+    """The small-M streaming path: M below 16, N not a multiple of its column block, K a multiple of
+    8 only, fp16 as well as bf16, fp32 output."""
+    for dtype in (gen.BF16, gen.F16):
+        for (M, N, K) in [(16, 512, 1024), (7, 100, 136), (1, 33, 8), (16, 2049, 4104)]:
+            cfg = gen.Config("skinny", M, N, K, dtype, dtype, ROW, COL, "normal", std=0.02)
+            inp = gen.make_inputs(cfg, 4)
+            d = gemm.make_desc(M, N, K, dtype, dtype, ROW, COL)
+            assert gemm.gemm_query(4, d).path.startswith("mfma16-stream")
+            check(4, inp)
+            check(4, inp, out_dtype=gen.F32)
+
+
+def test_batched_strides_scales_and_padding_untouched():
+    """Batch strides larger than the matrices, ldc > N: the gaps keep their poison bytes."""
+    M, N, K, nb = 70, 50, 96, 3
+    cfg = gen.Config("batched", M, N, K, gen.E4M3, gen.BF16, ROW, COL, "normal", batch=nb, scaled=True,
+                     lda=K + 16, ldb=K + 32, ldc=N + 6)
+    inp = gen.make_inputs(cfg, 9)
+    inp.scale_a[1] = -1.5                                   # a negative scale must carry its sign
+    ref = oracle_for(inp)
+    for v in VARIANTS:
+        rc, C, raw = util.run_config(v, inp)
+        assert rc == gemm.GEMM_OK
+        assert util.norm_err(C[:, :, :N], ref[0], ref[1]) <= util.TOL[gen.E4M3]
+        pad = raw.cpu().numpy().view(np.uint16)[: nb * inp.stride_c].reshape(nb, M, inp.ldc)[:, :, N:]
+        assert np.all(pad == 0xFFFF), "bytes between rows of C were overwritten"
+
+
+def test_refusal_leaves_C_untouched_and_is_not_a_fallback():
+    """A variant asked to run outside its preconditions in strict mode, or on a dtype it has no
+    instruction for, returns an error and writes nothing (it must not quietly run something else)."""
+    inp = gen.make_inputs(gen.CONFIGS["C3_small"], 0)
+    for v in (2, 3, 4):
+        rc, _, raw = util.run_config(v, inp, flags=gemm.GEMM_FLAG_STRICT)
+        assert rc == gemm.GEMM_ERR_PRECONDITION
+        assert torch.all(raw == util.POISON)
+    inp1 = gen.make_inputs(gen.CONFIGS["C1"], 0)
+    rc, _, raw = util.run_config(gemm.GEMM_K4_MFMA, inp1)
+    assert rc == gemm.GEMM_ERR_PRECONDITION and torch.all(raw == util.POISON)
+
+
+def test_success_overwrites_every_output_and_is_deterministic():
+    inp = gen.make_inputs(gen.CONFIGS["C2_small"], 1)
+    for v in VARIANTS:
+        rc, C1, raw1 = util.run_config(v, inp)
+        rc2, C2, raw2 = util.run_config(v, inp)
+        assert rc == rc2 == gemm.GEMM_OK
+        assert np.all(np.isfinite(C1))                       # no poison left anywhere
+        assert torch.equal(raw1, raw2)                       # no atomics: run-to-run bitwise equal
+
+
+def test_gemm_run_short_form_uses_default_layouts():
+    M, N, K = 96, 80, 72
+    for dtype, lb in [(gen.F32, ROW), (gen.F16, ROW), (gen.BF16, COL), (gen.E4M3, COL)]:
+        out = gen.BF16 if dtype == gen.E4M3 else dtype
+        cfg = gen.Config("short", M, N, K, dtype, out, ROW, lb, "uniform")
+        inp = gen.make_inputs(cfg, 2)
+        C_ref, D = oracle_for(inp)
+        dA, dB = util.dev(inp.A), util.dev(inp.B)
+        for v in variants_for(dtype):
+            dC = util.out_buffer(M * N, out)
+            assert gemm.gemm_run(v, M, N, K, dtype, dA, dB, dC) == gemm.GEMM_OK
+            torch.cuda.synchronize()
+            C = util.decode_out(dC, out).reshape(1, M, N)
+            assert util.norm_err(C, C_ref, D) <= util.TOL[dtype]
+
+
+def test_launch_on_a_side_stream():
+    inp = gen.make_inputs(gen.CONFIGS["C2_small"], 0)
+    c = inp.cfg
+    C_ref, D = oracle_for(inp)
+    s = torch.cuda.Stream()
+    dA, dB = util.dev(inp.A), util.dev(inp.B)
+    dC = util.out_buffer(c.M * c.N, c.out_dtype)
+    torch.cuda.synchronize()
+    d = gemm.make_desc(c.M, c.N, c.K, c.in_dtype, c.out_dtype, c.layout_a, c.layout_b, stream=s)
+    assert gemm.gemm_run_ex(4, d, dA, dB, dC) == gemm.GEMM_OK
+    s.synchronize()
+    C = util.decode_out(dC, c.out_dtype).reshape(1, c.M, c.N)
+    assert util.norm_err(C, C_ref, D) <= util.TOL[c.in_dtype]

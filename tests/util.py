@@ -1,0 +1,71 @@
+"""Helpers shared by the GPU parity tests: device buffers, output decoding, the acceptance metric.
+
+The metric is the one the gate uses for every variant: max |C - C_ref| / D over all outputs with
+D = |s| * sum_k |A_ik| |B_kj| (both from the oracle), no NaN/Inf allowed.  Where D == 0 the
+numerator must be 0 too.  Tolerances per input dtype: fp32 1e-5, bf16/fp16 1e-2, e4m3 6e-2.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from paper_2605_28213_amd import gemm
+from paper_2605_28213_amd import inputs as gen
+
+TOL = {gen.F32: 1e-5, gen.BF16: 1e-2, gen.F16: 1e-2, gen.E4M3: 6e-2}
+OUT_BYTES = {gen.F32: 4, gen.BF16: 2, gen.F16: 2}
+POISON = 0xFF        # 0xFFFF / 0xFFFFFFFF are NaN patterns in bf16, fp16 and fp32
+
+
+def dev(arr: np.ndarray) -> torch.Tensor:
+    """Copy raw storage to the GPU as bytes (only the address is handed to the library)."""
+    flat = np.ascontiguousarray(arr).reshape(-1).view(np.uint8)
+    if flat.size == 0:
+        return torch.empty(16, dtype=torch.uint8, device="cuda")
+    return torch.from_numpy(flat.copy()).cuda()
+
+
+def out_buffer(n_elems: int, out_dtype: int) -> torch.Tensor:
+    return torch.full((max(n_elems, 1) * OUT_BYTES[out_dtype],), POISON, dtype=torch.uint8, device="cuda")
+
+
+def decode_out(buf: torch.Tensor, out_dtype: int) -> np.ndarray:
+    """Device bytes -> fp64 values, decoded with numpy's own dtype views."""
+    raw = buf.cpu().numpy()
+    if out_dtype == gen.F32:
+        return raw.view(np.float32).astype(np.float64)
+    if out_dtype == gen.F16:
+        return raw.view(np.float16).astype(np.float64)
+    return (raw.view(np.uint16).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def norm_err(C: np.ndarray, C_ref: np.ndarray, D: np.ndarray) -> float:
+    """max |C - C_ref| / D; +inf on any non-finite output or a non-zero error where D == 0."""
+    if not np.all(np.isfinite(C)):
+        return float("inf")
+    num = np.abs(C - C_ref)
+    zero = D == 0
+    if np.any(num[zero] != 0):
+        return float("inf")
+    if np.all(zero):
+        return 0.0
+    return float(np.max(num[~zero] / D[~zero]))
+
+
+def run_config(variant: int, inp: gen.Inputs, *, out_dtype=None, flags: int = 0, dA=None, dB=None):
+    """Launch one variant on one generated workload; returns (status, C as (batch, M, ldc) fp64, raw buffer)."""
+    cfg = inp.cfg
+    od = cfg.out_dtype if out_dtype is None else out_dtype
+    dA = dev(inp.A) if dA is None else dA
+    dB = dev(inp.B) if dB is None else dB
+    sa = torch.from_numpy(inp.scale_a).cuda() if inp.scale_a is not None else None
+    sb = torch.from_numpy(inp.scale_b).cuda() if inp.scale_b is not None else None
+    dC = out_buffer(cfg.batch * inp.stride_c, od)
+    d = gemm.make_desc(cfg.M, cfg.N, cfg.K, cfg.in_dtype, od, cfg.layout_a, cfg.layout_b,
+                       lda=inp.lda, ldb=inp.ldb, ldc=inp.ldc, batch=cfg.batch,
+                       stride_a=inp.stride_a, stride_b=inp.stride_b, stride_c=inp.stride_c,
+                       scale_a=sa, scale_b=sb, flags=flags)
+    rc = gemm.gemm_run_ex(variant, d, dA, dB, dC)
+    torch.cuda.synchronize()
+    C = decode_out(dC, od)
+    return rc, C[: cfg.batch * inp.stride_c].reshape(cfg.batch, cfg.M, inp.ldc) if cfg.M * inp.ldc else C, dC
