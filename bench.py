@@ -1,0 +1,177 @@
+"""Benchmark of the GEMM lineage on one MI355X.
+
+A step is one launch of the expert lineage state (K4, MFMA) on the headline workload: bf16
+8192 x 8192 x 8192, A row-major, B column-major, fp32 accumulation, bf16 output, operands
+resident in HBM before the timed region.  The timed region holds exactly --steps launches between
+two device synchronisations; every launch is also bracketed by HIP events on the launch stream, and
+the roofline figure uses the mean of those per-launch durations.  Operand sets are rotated over
+three copies so that no launch finds its inputs in the Infinity Cache left by its predecessor.
+
+The same JSON line carries, under "shapes", the expert state on the other four workloads (each
+against its own roofline: HBM for the M=16 shape) and, under "lineage", every state K0..K4 on the
+headline workload; under "cpu_baseline" the CPU oracle timed on a slab of rows of the same product.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK = {"mfma_bf16": 2500.0, "mfma_f16": 2500.0, "mfma_fp8": 5000.0, "valu_f32": 157.3, "hbm_GBs": 8000.0}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=25)
+    ap.add_argument("--no-extras", action="store_true", help="headline workload only (used for profiling)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        sys.exit("bench.py: this library runs on one GPU; there is no multi-GPU path to measure (use --gpus 1)")
+
+    import numpy as np
+    import torch
+
+    from paper_2605_28213_amd import build as gl_build
+    from paper_2605_28213_amd import gemm
+    from paper_2605_28213_amd import inputs as gen
+
+    if not os.path.exists(gemm.LIB_PATH):
+        gl_build.build()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    stream = torch.cuda.Stream()
+    NSETS = 3
+
+    def device_sets(cfg, seed=0):
+        inp = gen.make_inputs(cfg, seed)
+        sets = []
+        for _ in range(NSETS):
+            A = torch.from_numpy(inp.A.view(np.uint8).reshape(-1)).cuda()
+            B = torch.from_numpy(inp.B.view(np.uint8).reshape(-1)).cuda()
+            C = torch.empty(max(1, cfg.batch * inp.stride_c) * 4, dtype=torch.uint8, device="cuda")
+            sets.append((A, B, C))
+        sa = torch.from_numpy(inp.scale_a).cuda() if inp.scale_a is not None else None
+        sb = torch.from_numpy(inp.scale_b).cuda() if inp.scale_b is not None else None
+        d = gemm.make_desc(cfg.M, cfg.N, cfg.K, cfg.in_dtype, cfg.out_dtype, cfg.layout_a, cfg.layout_b,
+                           lda=inp.lda, ldb=inp.ldb, ldc=inp.ldc, batch=cfg.batch, stride_a=inp.stride_a,
+                           stride_b=inp.stride_b, stride_c=inp.stride_c, scale_a=sa, scale_b=sb, stream=stream)
+        return inp, sets, d, (sa, sb)
+
+    def timed(variant, sets, d, steps, warmup):
+        """Returns (wall seconds for `steps` launches, list of per-launch ms from HIP events)."""
+        for i in range(warmup):
+            A, B, C = sets[i % NSETS]
+            rc = gemm.gemm_run_ex(variant, d, A, B, C)
+            assert rc == gemm.GEMM_OK, gemm.gemm_status_string(rc)
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            A, B, C = sets[i % NSETS]
+            ev[i][0].record(stream)
+            gemm.gemm_run_ex(variant, d, A, B, C)
+            ev[i][1].record(stream)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        return wall, [a.elapsed_time(b) for a, b in ev]
+
+    def stats(ms):
+        s = sorted(ms)
+        n = len(s)
+        return {"median_us": 1e3 * s[n // 2], "mean_us": 1e3 * sum(s) / n, "min_us": 1e3 * s[0],
+                "p10_us": 1e3 * s[n // 10], "p90_us": 1e3 * s[(9 * n) // 10]}
+
+    def roofline_for(cfg, mean_us, bound):
+        if bound == "hbm":
+            ach = cfg.algorithmic_bytes / (mean_us * 1e-6) / 1e9
+            return {"bound": "hbm", "achieved": ach, "peak": PEAK["hbm_GBs"], "unit": "GB/s",
+                    "frac": ach / PEAK["hbm_GBs"], "traffic": None}
+        peak = PEAK["mfma_fp8"] if cfg.in_dtype == gen.E4M3 else PEAK["mfma_bf16"]
+        ach = cfg.flops / (mean_us * 1e-6) / 1e12
+        return {"bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak, "traffic": None}
+
+    # ---- headline: K4 on C2 ------------------------------------------------------------------
+    cfg = gen.CONFIGS["C2"]
+    inp, sets, d, keep = device_sets(cfg)
+    q = gemm.gemm_query(gemm.GEMM_K4_MFMA, d, *sets[0])
+    wall, ms = timed(gemm.GEMM_K4_MFMA, sets, d, args.steps, args.warmup)
+    st = stats(ms)
+    value = cfg.flops * args.steps / wall / 1e12
+    out = {
+        "metric": "GEMM TFLOP/s of the expert lineage state (K4 MFMA) on bf16 8192^3; per-shape roofline fractions under 'shapes'",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": 1e3 * wall / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "C2: bf16 GEMM M=N=K=8192, A row-major, B column-major, N(0,1)/sqrt(K), fp32 accumulate, bf16 out",
+                   "variant": gemm.gemm_variant_name(gemm.GEMM_K4_MFMA), "path": q.path,
+                   "tile": [q.bm, q.bn, q.bk], "threads": q.threads, "grid": q.grid,
+                   "cache_state": f"operands rotated over {NSETS} buffer sets"},
+        "launch_us": st,
+        "roofline": roofline_for(cfg, st["mean_us"], "mfma"),
+    }
+
+    if not args.no_extras:
+        # ---- the lineage on the headline workload (few launches for the slow early states) ---------
+        lineage = {}
+        for v in range(gemm.gemm_variant_count()):
+            n = 2 if v == 0 else 10
+            _, vms = timed(v, sets, d, n, 1)
+            m = sorted(vms)[len(vms) // 2]
+            lineage[gemm.gemm_variant_name(v)] = {"median_us": 1e3 * m, "TFLOP/s": cfg.flops / (m * 1e-3) / 1e12,
+                                                  "path": gemm.gemm_query(v, d, *sets[0]).path, "launches": n}
+        out["lineage"] = lineage
+    del sets, keep
+    torch.cuda.empty_cache()
+
+    if not args.no_extras:
+        shapes = {}
+        for name, bound in (("C1", "alu"), ("C3", "mfma"), ("C4", "hbm"), ("C5", "mfma")):
+            c = gen.CONFIGS[name]
+            v = gemm.GEMM_K3_PIPELINED if name == "C1" else gemm.GEMM_K4_MFMA
+            _, s2, d2, keep2 = device_sets(c)
+            _, sms = timed(v, s2, d2, 100, 25)
+            ss = stats(sms)
+            if bound == "alu":
+                ach = c.flops / (ss["mean_us"] * 1e-6) / 1e12
+                rl = {"bound": "alu", "achieved": ach, "peak": PEAK["valu_f32"], "unit": "TFLOP/s",
+                      "frac": ach / PEAK["valu_f32"], "traffic": None}
+            else:
+                rl = roofline_for(c, ss["mean_us"], bound)
+            entry = {"variant": gemm.gemm_variant_name(v), "path": gemm.gemm_query(v, d2, *s2[0]).path,
+                     "launch_us": ss, "TFLOP/s": c.flops / (ss["mean_us"] * 1e-6) / 1e12,
+                     "GB/s": c.algorithmic_bytes / (ss["mean_us"] * 1e-6) / 1e9, "roofline": rl}
+            if name == "C5":
+                entry["roofline_hbm"] = roofline_for(c, ss["mean_us"], "hbm")
+            shapes[name] = entry
+            del s2, keep2
+            torch.cuda.empty_cache()
+        out["shapes"] = shapes
+
+    if not args.no_cpu:
+        # ---- CPU oracle on a bounded sample of the headline workload ---------------------------------
+        import oracle
+        rows = 512
+        t0 = time.perf_counter()
+        oracle.gemm(cfg.in_dtype, cfg.layout_a, cfg.layout_b, rows, cfg.N, cfg.K, inp.A[: rows * inp.lda], inp.lda,
+                    inp.B, inp.ldb)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": 2.0 * rows * cfg.N * cfg.K / dt / 1e12, "unit": "TFLOP/s",
+                               "cores": oracle.num_threads(), "kind": "oracle",
+                               "sample": f"first {rows} rows of C of the same product ({rows}x8192x8192), {dt:.1f} s, "
+                                         "fp64 triple loop incl. operand decode"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -139,18 +139,24 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
         break;
     }
     default: {  // GEMM_K4_MFMA
-        required = GEMM_COND_DTYPE_HAS_MFMA | GEMM_COND_LDS_STAGED | vecA | vecB | GEMM_COND_K_CONTIG_A | GEMM_COND_K_CONTIG_B;
+        required = GEMM_COND_DTYPE_HAS_MFMA | GEMM_COND_LDS_STAGED | vecA | vecB | GEMM_COND_K_CONTIG_A | GEMM_COND_K_CONTIG_B |
+                   GEMM_COND_TILE_DIV_K;
         const bool va = (holds & (vecA | GEMM_COND_K_CONTIG_A)) == (vecA | GEMM_COND_K_CONTIG_A);
         const bool vb = (holds & (vecB | GEMM_COND_K_CONTIG_B)) == (vecB | GEMM_COND_K_CONTIG_B);
         const int64_t kvec = 16 / es;
         const bool skinny = (holds & GEMM_COND_SMALL_M) && va && vb && d->K % kvec == 0 && d->K > 0 &&
                             (d->in_dtype == GEMM_BF16 || d->in_dtype == GEMM_F16);
+        const bool kdiv = d->K % (128 / es) == 0;   // whole 128-byte slabs: the direct-to-LDS kernel masks nothing along K
         if (skinny) {
             p.path = MFMA_SKINNY;
             path = "mfma16-stream(small-M)";
+            required &= ~(uint32_t)GEMM_COND_TILE_DIV_K;
+        } else if (va && vb && kdiv) {
+            p.path = MFMA_VEC16 | (3 << 8);
+            path = "mfma32-direct-to-lds";
         } else {
-            p.path = (va && vb ? MFMA_VEC16 : MFMA_ELEMENTWISE) | (((va ? 1 : 0) | (vb ? 2 : 0)) << 8);
-            path = va && vb ? "mfma32-vec16" : va ? "mfma32-vec16(A)+elementwise-masked(B)"
+            p.path = MFMA_ELEMENTWISE | (((va ? 1 : 0) | (vb ? 2 : 0)) << 8);
+            path = va && vb ? "mfma32-vec16-masked" : va ? "mfma32-vec16(A)+elementwise-masked(B)"
                             : vb ? "mfma32-elementwise-masked(A)+vec16(B)" : "mfma32-elementwise-masked";
         }
         if (holds & GEMM_COND_DTYPE_HAS_MFMA) g = geometry_k4(p.path & 0xFF, a);

@@ -1,0 +1,471 @@
+// K4 kernels: K3 + "mma" + "ldmatrix.swizzle" (paper Table 1, "Compute & layout"), realised for
+// CDNA4 as wave64 MFMA with fp32 accumulators and an LDS operand layout in which the 16-byte
+// fragment reads of a wave are bank-conflict free.
+//
+// Preconditions recorded for this state (Table 1: "tile fits mma", "mma fragment layout";
+// Sec. 1: matrix intrinsics need compatible tile shapes, layouts and hardware support):
+//   - the input dtype has a matrix instruction (bf16, fp16, OCP e4m3);
+//   - the fast kernel needs K contiguous in both operands, 16-byte aligned bases and leading
+//     dimensions, and K a whole number of 128-byte slabs; otherwise the masked kernel gathers
+//     the offending operand element by element.
+//
+// Data movement per workgroup and K slab of 128 bytes per row:
+//   fast kernel:   global --global_load_lds_dwordx4 (no registers)--> LDS[buf^1]   (next slab)
+//   masked kernel: global --> registers --ds_write_b128--> LDS[buf^1]               (next slab)
+//   LDS[buf] --ds_read_b128--> MFMA operand registers --> v_mfma_f32_32x32x16       (this slab)
+// LDS rows are 128 bytes (eight 16-byte chunks); chunk c of row r lives at chunk position
+// c ^ swz(r).
+#pragma once
+#include "common.hpp"
+
+namespace gl {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
+
+constexpr int ROW_BYTES = 128;            // bytes of K per LDS row and per slab
+constexpr int CHUNKS = ROW_BYTES / 16;    // 16-byte chunks per row
+
+// XOR mask of row r.  Within any aligned group of 8 rows the masks are a permutation of 0..7, and
+// within any aligned group of 16 rows the even rows and the odd rows each get 8 different masks, so
+// a column of chunks read by consecutive rows is spread over all banks whether the LDS serves 8
+// lanes over 32 banks or 16 lanes over 64 banks per cycle.
+__device__ __forceinline__ int swz(int row) { return ((row >> 1) & 7) ^ ((row & 1) << 2); }
+
+// One 32x32 MFMA step on a 16-byte operand chunk per lane.  For 2-byte types the chunk is one
+// K=16 instruction; for e4m3 it is two K=16 instructions on its low and high halves.  Which k a
+// lane's bytes stand for is irrelevant as long as A and B agree, and both come through here.
+template <typename IN>
+__device__ __forceinline__ void mfma_chunk(const u32x4_t& a, const u32x4_t& b, f32x16_t& c)
+{
+    if constexpr (IN::ID == GEMM_BF16) {
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+    } else if constexpr (IN::ID == GEMM_F16) {
+        c = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+    } else {
+        const long alo = (long)(((uint64_t)a.y << 32) | a.x), ahi = (long)(((uint64_t)a.w << 32) | a.z);
+        const long blo = (long)(((uint64_t)b.y << 32) | b.x), bhi = (long)(((uint64_t)b.w << 32) | b.z);
+        c = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(alo, blo, c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(ahi, bhi, c, 0, 0, 0);
+    }
+}
+
+// Workgroup id -> (tile_m, tile_n).  Hardware hands consecutive workgroup ids to the 8 XCDs in
+// turn; ids are first regrouped so that each XCD (own L2) works on one contiguous run of tiles,
+// then tiles are walked in bands of GROUP_M tile-rows so that a run reuses few A rows and B columns.
+template <int GROUP_M>
+__device__ __forceinline__ void tile_of(int pid, int total, int tiles_m, int tiles_n, int& tm, int& tn)
+{
+    constexpr int XCD = 8;
+    const int x = pid % XCD, local = pid / XCD;
+    const int base = total / XCD, rem = total % XCD;
+    const int id = x * base + (x < rem ? x : rem) + local;
+    const int width = GROUP_M * tiles_n;
+    const int g = id / width, first = g * GROUP_M;
+    const int gsz = (tiles_m - first) < GROUP_M ? (tiles_m - first) : GROUP_M;
+    tm = first + (id % width) % gsz;
+    tn = (id % width) / gsz;
+}
+
+// Epilogue shared by both kernels.  A 32x32 accumulator tile keeps, in register r of lane l, the
+// element at row 8*(r/4) + 4*(l/32) + r%4 and column l%32.  The output type is resolved once,
+// outside the fully unrolled tile loops, so that every accumulator index is a compile-time constant.
+template <int OUT, int TMI, int TNI>
+__device__ __forceinline__ void store_tiles_as(const Args& a, int64_t b, const f32x16_t (&acc)[TMI][TNI],
+                                               int64_t row0, int64_t col0, int lane, float sc)
+{
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    char* C = (char*)a.C + (b * a.stride_c) * (OUT == GEMM_F32 ? 4 : 2);
+#pragma unroll
+    for (int i = 0; i < TMI; ++i)
+#pragma unroll
+        for (int j = 0; j < TNI; ++j) {
+            const int64_t gj = col0 + j * 32 + lrow;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t gi = row0 + i * 32 + 8 * (r / 4) + 4 * lhalf + (r % 4);
+                if (gi < a.M && gj < a.N) {
+                    const float v = acc[i][j][r] * sc;
+                    const int64_t idx = gi * a.ldc + gj;
+                    if constexpr (OUT == GEMM_F32) ((float*)C)[idx] = v;
+                    else if constexpr (OUT == GEMM_BF16) ((uint16_t*)C)[idx] = encode_bf16(v);
+                    else ((uint16_t*)C)[idx] = encode_f16(v);
+                }
+            }
+        }
+}
+
+template <int TMI, int TNI>
+__device__ __forceinline__ void store_tiles(const Args& a, int64_t b, const f32x16_t (&acc)[TMI][TNI],
+                                            int64_t row0, int64_t col0, int lane)
+{
+    const float sc = batch_scale(a, b);
+    if (a.out_dtype == GEMM_F32) store_tiles_as<GEMM_F32>(a, b, acc, row0, col0, lane, sc);
+    else if (a.out_dtype == GEMM_BF16) store_tiles_as<GEMM_BF16>(a, b, acc, row0, col0, lane, sc);
+    else store_tiles_as<GEMM_F16>(a, b, acc, row0, col0, lane, sc);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Fast kernel: both operands K-contiguous and 16-byte aligned, K a whole number of 128-byte slabs.
+// ------------------------------------------------------------------------------------------------
+template <typename IN, int BM_, int BN_, int WM_, int WN_, int WAVES_PER_SIMD_, int GROUP_M_ = 8>
+struct FastCfg {
+    using In = IN;
+    static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, GROUP_M = GROUP_M_;
+    static constexpr int WAVES_PER_SIMD = WAVES_PER_SIMD_;
+    static constexpr int T = WM * WN * 64;
+    static constexpr int TMI = BM / WM / 32, TNI = BN / WN / 32;
+    static constexpr int LDS_BYTES = 2 * (BM + BN) * ROW_BYTES;
+    static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0, "wave tiles are made of 32x32 MFMA tiles");
+};
+
+template <typename CFG>
+__global__ __launch_bounds__(CFG::T) __attribute__((amdgpu_waves_per_eu(CFG::WAVES_PER_SIMD, CFG::WAVES_PER_SIMD)))
+void k4_mfma_fast(Args a, int tiles_m, int tiles_n)
+{
+    using IN = typename CFG::In;
+    constexpr int BM = CFG::BM, BN = CFG::BN, WN = CFG::WN, T = CFG::T, NW = T / 64;
+    constexpr int TMI = CFG::TMI, TNI = CFG::TNI;
+    constexpr int KE = ROW_BYTES / IN::BYTES;        // K elements per slab
+    constexpr int V = 16 / IN::BYTES;                // K elements per chunk
+    constexpr int LA = BM / 8 / NW, LB = BN / 8 / NW; // direct loads per wave per slab (8 rows each)
+    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0 && NW % 2 == 0, "row octets must divide over the waves");
+    // Two separately declared buffers, each [A rows | B rows][128 bytes]: distinct objects let the
+    // compiler see that a direct load into one never aliases a fragment read from the other, so it
+    // does not wait for the loads before the reads.
+    constexpr int BUF_BYTES = (BM + BN) * ROW_BYTES;
+    __shared__ __attribute__((aligned(1024))) char lds0[BUF_BYTES];
+    __shared__ __attribute__((aligned(1024))) char lds1[BUF_BYTES];
+
+    const int t = threadIdx.x, lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const int64_t b = blockIdx.y;
+    int tm, tn;
+    tile_of<CFG::GROUP_M>(blockIdx.x, tiles_m * tiles_n, tiles_m, tiles_n, tm, tn);
+    const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
+
+    // ---- global -> LDS, without passing through registers -------------------------------------
+    // One wave-wide 16-byte load fills 8 consecutive LDS rows (lane L lands at byte 16*L of the
+    // 1 KiB block), so lane L must fetch, for row L/8, the chunk whose swizzled position is L%8.
+    // Wave w owns row octets w, w + NW, ...; NW is even, so all its octets share one parity and the
+    // lane's chunk index is the same for every one of them.
+    const int orow = lane >> 3;                                  // row inside the octet
+    const int gchunk = (lane & 7) ^ swz(orow + 8 * (wave & 1));  // chunk this lane fetches
+    const char* A = (const char*)a.A + (b * a.stride_a) * IN::BYTES;
+    const char* B = (const char*)a.B + (b * a.stride_b) * IN::BYTES;
+    const char* pa[LA];
+    const char* pb[LB];
+#pragma unroll
+    for (int n = 0; n < LA; ++n) {
+        const int64_t r = m0 + (wave + n * NW) * 8 + orow;       // rows past M are clamped: their products
+        pa[n] = A + ((r < a.M ? r : a.M - 1) * a.a_si + gchunk * V) * IN::BYTES;   // are never stored
+    }
+#pragma unroll
+    for (int n = 0; n < LB; ++n) {
+        const int64_t r = n0 + (wave + n * NW) * 8 + orow;
+        pb[n] = B + ((r < a.N ? r : a.N - 1) * a.b_sj + gchunk * V) * IN::BYTES;
+    }
+    using gptr = const __attribute__((address_space(1))) void*;
+    using lptr = __attribute__((address_space(3))) void*;
+    auto issue = [&](int64_t s, char* buf) __attribute__((always_inline)) {
+        const int64_t koff = s * ROW_BYTES;
+        char* base = buf + wave * 1024;
+#pragma unroll
+        for (int n = 0; n < LA; ++n)
+            __builtin_amdgcn_global_load_lds((gptr)(pa[n] + koff), (lptr)(base + n * NW * 1024), 16, 0, 0);
+#pragma unroll
+        for (int n = 0; n < LB; ++n)
+            __builtin_amdgcn_global_load_lds((gptr)(pb[n] + koff), (lptr)(base + BM * ROW_BYTES + n * NW * 1024), 16, 0, 0);
+    };
+
+    // ---- LDS read side: lane reads row (lane % 32) of each 32-row block, chunk 2*ks + lane/32 ---
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    const int rd_mask = lhalf ^ swz(lrow);
+    const int rd_a = (wm * (BM / CFG::WM) + lrow) * ROW_BYTES;
+    const int rd_b = (BM + wn * (BN / WN) + lrow) * ROW_BYTES;
+
+    f32x16_t acc[TMI][TNI];
+#pragma unroll
+    for (int i = 0; i < TMI; ++i)
+#pragma unroll
+        for (int j = 0; j < TNI; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    // Fragment reads run one k-step ahead of the MFMAs that consume them; the scheduling barrier
+    // keeps the compiler from hoisting every read of the slab to the top (which would need four
+    // times the fragment registers).
+    auto compute = [&](const char* base) __attribute__((always_inline)) {
+        u32x4_t fa[2][TMI], fb[2][TNI];
+        auto read = [&](int ks, int slot) __attribute__((always_inline)) {
+            const int pos = ((2 * ks) ^ rd_mask) << 4;
+#pragma unroll
+            for (int i = 0; i < TMI; ++i) fa[slot][i] = *(const u32x4_t*)(base + rd_a + i * 32 * ROW_BYTES + pos);
+#pragma unroll
+            for (int j = 0; j < TNI; ++j) fb[slot][j] = *(const u32x4_t*)(base + rd_b + j * 32 * ROW_BYTES + pos);
+        };
+        read(0, 0);
+#pragma unroll
+        for (int ks = 0; ks < CHUNKS / 2; ++ks) {
+            if (ks + 1 < CHUNKS / 2) read(ks + 1, (ks + 1) & 1);
+#pragma unroll
+            for (int i = 0; i < TMI; ++i)
+#pragma unroll
+                for (int j = 0; j < TNI; ++j) mfma_chunk<IN>(fa[ks & 1][i], fb[ks & 1][j], acc[i][j]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    // All of this wave's direct loads have landed in LDS; then every wave's have.
+    auto landed = [&]() __attribute__((always_inline)) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+    };
+
+    const int64_t nslab = a.K / KE;                  // K is a whole number of slabs
+    // Even slabs live in buffer 0, odd slabs in buffer 1.  The barrier that ends a step also
+    // guarantees that nobody still reads the buffer the next step's loads overwrite.  The loop
+    // walks whole pairs of slabs so that it has a single exit; an odd last slab is peeled.
+    if (nslab > 0) issue(0, lds0);
+    landed();
+    const int64_t npairs = nslab / 2;
+    for (int64_t p = 0; p < npairs; ++p) {
+        issue(2 * p + 1, lds1);
+        compute(lds0);
+        landed();
+        if (2 * p + 2 < nslab) issue(2 * p + 2, lds0);
+        compute(lds1);
+        landed();
+    }
+    if (nslab & 1) compute(lds0);
+
+    store_tiles<TMI, TNI>(a, b, acc, m0 + wm * (BM / CFG::WM), n0 + wn * (BN / WN), lane);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Masked kernel: any layout, any alignment, any K.  An operand whose 16-byte loads are legal
+// (bit in vec_mask) is still fetched by chunks; any other operand, and every chunk that crosses
+// the end of K, is gathered element by element under a mask.
+// ------------------------------------------------------------------------------------------------
+struct TileSrc {
+    const char* base;   // operand base for this batch item (bytes)
+    int64_t sr, sk;     // element strides along rows and along K
+    int64_t rows;       // logical rows (M for A, N for B)
+    int64_t r0;         // first row of the workgroup tile
+    bool vec;           // 16-byte loads along K are legal
+};
+
+template <typename IN, int BR, int THREADS, int NCH>
+__device__ __forceinline__ void fetch_tile(const TileSrc& x, int64_t k0, int64_t K, int t, u32x4_t (&R)[NCH])
+{
+    using raw = typename IN::raw;
+    constexpr int V = 16 / IN::BYTES;
+    static_assert(BR * CHUNKS == NCH * THREADS, "tile must divide evenly over the threads");
+    const bool kcontig = x.sk == 1;
+#pragma unroll
+    for (int n = 0; n < NCH; ++n) {
+        const int q = t + n * THREADS;
+        // along K first when K is contiguous (8 lanes cover one 128-byte row), along rows otherwise
+        const int c = kcontig ? q % CHUNKS : q / BR;
+        const int r = kcontig ? q / CHUNKS : q % BR;
+        const int64_t gr = x.r0 + r, gk = k0 + (int64_t)c * V;
+        u32x4_t w = {0, 0, 0, 0};
+        if (gr < x.rows && gk < K) {
+            const raw* p = (const raw*)x.base + gr * x.sr + gk * x.sk;
+            if (x.vec && gk + V <= K) {
+                w = *(const u32x4_t*)p;
+            } else {
+                raw tmp[V];
+#pragma unroll
+                for (int e = 0; e < V; ++e) tmp[e] = (gk + e < K) ? p[e * x.sk] : (raw)0;
+                __builtin_memcpy(&w, tmp, 16);
+            }
+        }
+        R[n] = w;
+    }
+}
+
+template <int BR, int THREADS, int NCH>
+__device__ __forceinline__ void commit_tile(bool kcontig, int t, const u32x4_t (&R)[NCH], char* lds)
+{
+#pragma unroll
+    for (int n = 0; n < NCH; ++n) {
+        const int q = t + n * THREADS;
+        const int c = kcontig ? q % CHUNKS : q / BR;
+        const int r = kcontig ? q / CHUNKS : q % BR;
+        *(u32x4_t*)(lds + r * ROW_BYTES + ((c ^ swz(r)) << 4)) = R[n];
+    }
+}
+
+template <typename IN, int BM, int BN, int WM, int WN>
+__global__ __launch_bounds__(WM* WN * 64) void k4_mfma_masked(Args a, int vec_mask, int tiles_m, int tiles_n)
+{
+    constexpr int T = WM * WN * 64;
+    constexpr int KE = ROW_BYTES / IN::BYTES;
+    constexpr int TMI = BM / WM / 32, TNI = BN / WN / 32;
+    constexpr int NCA = BM * CHUNKS / T, NCB = BN * CHUNKS / T;
+    __shared__ __attribute__((aligned(16))) char As[2][BM * ROW_BYTES];
+    __shared__ __attribute__((aligned(16))) char Bs[2][BN * ROW_BYTES];
+
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int64_t b = blockIdx.y;
+    int tm, tn;
+    tile_of<8>(blockIdx.x, tiles_m * tiles_n, tiles_m, tiles_n, tm, tn);
+
+    TileSrc sa{(const char*)a.A + b * a.stride_a * IN::BYTES, a.a_si, a.a_sk, a.M, (int64_t)tm * BM, (vec_mask & 1) != 0};
+    TileSrc sb{(const char*)a.B + b * a.stride_b * IN::BYTES, a.b_sj, a.b_sk, a.N, (int64_t)tn * BN, (vec_mask & 2) != 0};
+    const bool kca = a.a_sk == 1, kcb = a.b_sk == 1;
+
+    f32x16_t acc[TMI][TNI];
+#pragma unroll
+    for (int i = 0; i < TMI; ++i)
+#pragma unroll
+        for (int j = 0; j < TNI; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    u32x4_t ra[NCA], rb[NCB];
+    const int64_t nslab = (a.K + KE - 1) / KE;
+    if (nslab > 0) {
+        fetch_tile<IN, BM, T>(sa, 0, a.K, t, ra);
+        fetch_tile<IN, BN, T>(sb, 0, a.K, t, rb);
+        commit_tile<BM, T>(kca, t, ra, As[0]);
+        commit_tile<BN, T>(kcb, t, rb, Bs[0]);
+    }
+    __syncthreads();
+
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    int cur = 0;
+    for (int64_t s = 0; s < nslab; ++s) {
+        const bool more = s + 1 < nslab;
+        if (more) {
+            fetch_tile<IN, BM, T>(sa, (s + 1) * KE, a.K, t, ra);
+            fetch_tile<IN, BN, T>(sb, (s + 1) * KE, a.K, t, rb);
+        }
+        const char* Ac = As[cur] + (wm * (BM / WM)) * ROW_BYTES;
+        const char* Bc = Bs[cur] + (wn * (BN / WN)) * ROW_BYTES;
+#pragma unroll
+        for (int ks = 0; ks < CHUNKS / 2; ++ks) {
+            const int c = 2 * ks + lhalf;
+            u32x4_t fa[TMI], fb[TNI];
+#pragma unroll
+            for (int i = 0; i < TMI; ++i) {
+                const int r = i * 32 + lrow;
+                fa[i] = *(const u32x4_t*)(Ac + r * ROW_BYTES + ((c ^ swz(r)) << 4));
+            }
+#pragma unroll
+            for (int j = 0; j < TNI; ++j) {
+                const int r = j * 32 + lrow;
+                fb[j] = *(const u32x4_t*)(Bc + r * ROW_BYTES + ((c ^ swz(r)) << 4));
+            }
+#pragma unroll
+            for (int i = 0; i < TMI; ++i)
+#pragma unroll
+                for (int j = 0; j < TNI; ++j) mfma_chunk<IN>(fa[i], fb[j], acc[i][j]);
+        }
+        if (more) {
+            commit_tile<BM, T>(kca, t, ra, As[cur ^ 1]);
+            commit_tile<BN, T>(kcb, t, rb, Bs[cur ^ 1]);
+        }
+        __syncthreads();
+        cur ^= 1;
+    }
+    store_tiles<TMI, TNI>(a, b, acc, sa.r0 + wm * (BM / WM), sb.r0 + wn * (BN / WN), lane);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Streaming kernel for M <= 16 (decode-like shapes): the product is bound by reading B once from
+// HBM, so B is never staged in LDS.  A workgroup owns 16*NB columns of C; its WAVES waves split K,
+// each streaming its share of B with 16-byte loads straight into the B operand of
+// v_mfma_f32_16x16x32 while A (M x K, cache resident) supplies the other operand; partial sums
+// meet in LDS.  Needs: A row-major, B column-major, 16-byte aligned, K a multiple of 8.
+// ------------------------------------------------------------------------------------------------
+template <typename IN>
+__device__ __forceinline__ void mfma16(const u32x4_t& a, const u32x4_t& b, f32x4_t& c)
+{
+    if constexpr (IN::ID == GEMM_BF16)
+        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+    else
+        c = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+}
+
+template <typename IN, int WAVES_, int NB_, int UNROLL_>
+struct SkinnyCfg {
+    using In = IN;
+    static constexpr int WAVES = WAVES_, NB = NB_, UNROLL = UNROLL_, COLS = 16 * NB_;
+    static constexpr int LDS_BYTES = 4 * WAVES * 16 * (COLS + 1);
+};
+
+template <typename CFG>
+__global__ __launch_bounds__(CFG::WAVES * 64) void k4_skinny(Args a)
+{
+    using IN = typename CFG::In;
+    constexpr int WAVES = CFG::WAVES, NB = CFG::NB, UNROLL = CFG::UNROLL, COLS = CFG::COLS;
+    __shared__ float part[WAVES][16][COLS + 1];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int l16 = lane & 15, lq = lane >> 4;          // operand row/column and 8-element k group
+    const int64_t b = blockIdx.y;
+    const int64_t j0 = (int64_t)blockIdx.x * COLS;
+    const uint16_t* A = (const uint16_t*)a.A + b * a.stride_a;
+    const uint16_t* B = (const uint16_t*)a.B + b * a.stride_b;
+
+    // K is cut into WAVES contiguous ranges, each a multiple of 32
+    const int64_t ksteps = (a.K + 31) / 32;
+    const int64_t per = (ksteps + WAVES - 1) / WAVES;
+    const int64_t kbeg = wave * per * 32;
+    const int64_t kend = (kbeg + per * 32 < a.K) ? kbeg + per * 32 : a.K;
+
+    const bool arow = l16 < a.M;
+    const uint16_t* ap = A + (int64_t)(arow ? l16 : 0) * a.a_si + lq * 8;
+    const uint16_t* bp[NB];
+    bool bcol[NB];
+#pragma unroll
+    for (int n = 0; n < NB; ++n) {
+        const int64_t j = j0 + n * 16 + l16;
+        bcol[n] = j < a.N;
+        bp[n] = B + (bcol[n] ? j : 0) * a.b_sj + lq * 8;
+    }
+
+    f32x4_t acc[NB];
+#pragma unroll
+    for (int n = 0; n < NB; ++n) acc[n] = f32x4_t{0, 0, 0, 0};
+
+    const u32x4_t zero = {0, 0, 0, 0};
+    for (int64_t k = kbeg; k < kend; k += 32 * UNROLL) {
+        u32x4_t fa[UNROLL], fb[UNROLL][NB];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int64_t kk = k + u * 32 + lq * 8;      // this lane's 8 elements; K % 8 == 0
+            const bool in = kk < kend;
+            fa[u] = (in && arow) ? *(const u32x4_t*)(ap + k + u * 32) : zero;
+#pragma unroll
+            for (int n = 0; n < NB; ++n)
+                fb[u][n] = (in && bcol[n]) ? __builtin_nontemporal_load((const u32x4_t*)(bp[n] + k + u * 32)) : zero;
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u)
+#pragma unroll
+            for (int n = 0; n < NB; ++n) mfma16<IN>(fa[u], fb[u][n], acc[n]);
+    }
+
+    // 16x16 accumulator: register r of lane l holds row 4*(l/16) + r, column l%16
+#pragma unroll
+    for (int n = 0; n < NB; ++n)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) part[wave][4 * lq + r][n * 16 + l16] = acc[n][r];
+    __syncthreads();
+    const float sc = batch_scale(a, b);
+    for (int o = t; o < 16 * COLS; o += WAVES * 64) {
+        const int i = o / COLS, j = o % COLS;
+        float v = 0.0f;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) v += part[w][i][j];
+        if (i < a.M && j0 + j < a.N) store_out(a.C, b * a.stride_c + (int64_t)i * a.ldc + j0 + j, v * sc, a.out_dtype);
+    }
+}
+
+}  // namespace gl

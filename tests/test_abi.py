@@ -115,13 +115,13 @@ def test_query_reports_paths_and_conditions_for_the_five_workloads():
                            batch=c.batch)
         return gemm.gemm_query(v, d, A, B)
     assert q(2, "C1").path == "vec16" and q(2, "C1").violated == 0
-    r = q(4, "C2"); assert r.path == "mfma32-vec16" and r.violated == 0 and (r.bm, r.bn, r.bk) == (256, 256, 64)
+    r = q(4, "C2"); assert r.path == "mfma32-direct-to-lds" and r.violated == 0 and (r.bm, r.bn, r.bk) == (256, 256, 64)
     assert {"TILE_DIV_M", "TILE_DIV_N", "TILE_DIV_K"} <= set(gemm.Query.names(r.holds)) and r.grid == 1024
     r = q(2, "C3"); assert r.path == "elementwise-masked" and set(gemm.Query.names(r.violated)) == {"LD16_A", "LD16_B"}
     r = q(4, "C3"); assert "elementwise" in r.path and "K_CONTIG_B" in gemm.Query.names(r.violated)
     assert "TILE_DIV_M" not in gemm.Query.names(r.holds)
     r = q(4, "C4"); assert r.path.startswith("mfma16-stream") and "SMALL_M" in gemm.Query.names(r.holds)
-    r = q(4, "C5"); assert r.path == "mfma32-vec16" and r.bk == 128 and r.grid == 64 * 16
+    r = q(4, "C5"); assert r.path == "mfma32-direct-to-lds" and r.bk == 128 and r.grid == 64 * 16
     # a misaligned base pointer breaks ALIGN16 for that operand only
     r = q(3, "C2", A=0x1002, B=0x2000)
     assert r.path == "elementwise-masked(A)+vec16(B)" and gemm.Query.names(r.violated) == ["ALIGN16_A"]
