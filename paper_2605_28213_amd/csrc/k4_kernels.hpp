@@ -16,6 +16,8 @@
 // LDS rows are 128 bytes (eight 16-byte chunks); chunk c of row r lives at chunk position
 // c ^ swz(r).
 #pragma once
+#include <type_traits>
+
 #include "common.hpp"
 
 namespace gl {
@@ -109,8 +111,79 @@ __device__ __forceinline__ void store_tiles(const Args& a, int64_t b, const f32x
 }
 
 // ------------------------------------------------------------------------------------------------
-// Fast kernel: both operands K-contiguous and 16-byte aligned, K a whole number of 128-byte slabs.
+// Epilogue of the fast kernel.  The fast kernel feeds the B fragment as the first MFMA operand and
+// the A fragment as the second, so a 32x32 accumulator tile keeps, in register r of lane l, the
+// element at row (of C) l%32 and column 8*(r/4) + 4*(l/32) + r%4: four consecutive columns per
+// register quad.  Each wave rounds its accumulators to the output type, parks one 32-row block at a
+// time in a private LDS area (row pitch padded by 16 bytes) and writes it out again row by row, so
+// that global stores are 16 bytes per lane and whole 128-byte lines per row.
 // ------------------------------------------------------------------------------------------------
+template <int OUT, int TMI, int TNI>
+__device__ __forceinline__ void store_tiles_staged(const Args& a, int64_t b, const f32x16_t (&acc)[TMI][TNI],
+                                                   int64_t row0, int64_t col0, int lane, char* stage, bool vec_ok)
+{
+    constexpr int OB = OUT == GEMM_F32 ? 4 : 2;            // bytes per output element
+    constexpr int ROWB = TNI * 32 * OB, PITCH = ROWB + 16; // bytes per staged row
+    constexpr int CPR = ROWB / 16, PASSES = 32 * CPR / 64; // 16-byte chunks per row; read passes per block
+    constexpr int EPC = 16 / OB;                           // elements per chunk
+    const float sc = batch_scale(a, b);
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    char* C = (char*)a.C + (b * a.stride_c) * OB;
+#pragma unroll
+    for (int i = 0; i < TMI; ++i) {
+#pragma unroll
+        for (int j = 0; j < TNI; ++j)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const float v0 = acc[i][j][4 * g] * sc, v1 = acc[i][j][4 * g + 1] * sc;
+                const float v2 = acc[i][j][4 * g + 2] * sc, v3 = acc[i][j][4 * g + 3] * sc;
+                char* dst = stage + lrow * PITCH + (j * 32 + 8 * g + 4 * lhalf) * OB;
+                if constexpr (OUT == GEMM_F32) {
+                    *(f32x4_t*)dst = f32x4_t{v0, v1, v2, v3};
+                } else if constexpr (OUT == GEMM_BF16) {
+                    typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
+                    *(bf16x4_t*)dst = bf16x4_t{(__bf16)v0, (__bf16)v1, (__bf16)v2, (__bf16)v3};
+                } else {
+                    typedef __attribute__((ext_vector_type(4))) _Float16 f16x4_t;
+                    *(f16x4_t*)dst = f16x4_t{(_Float16)v0, (_Float16)v1, (_Float16)v2, (_Float16)v3};
+                }
+            }
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+            const int q = lane + 64 * p, r = q / CPR, c = q % CPR;
+            const u32x4_t w = *(const u32x4_t*)(stage + r * PITCH + c * 16);
+            const int64_t gi = row0 + i * 32 + r, gj = col0 + c * EPC;
+            if (gi < a.M) {
+                char* out = C + (gi * a.ldc + gj) * OB;
+                if (vec_ok && gj + EPC <= a.N) {
+                    *(u32x4_t*)out = w;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < EPC; ++e)
+                        if (gj + e < a.N) {
+                            if constexpr (OB == 4) ((uint32_t*)out)[e] = w[e];
+                            else ((uint16_t*)out)[e] = (uint16_t)(w[e / 2] >> (16 * (e & 1)));
+                        }
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Fast kernel: both operands K-contiguous and 16-byte aligned, K a whole number of 128-byte slabs.
+//
+// Software pipeline, per workgroup and slab s (4 k-steps of 32 bytes of K each; `cur` = LDS buffer
+// s%2, `nxt` the other one):
+//   k-steps 0..2:  MFMAs of the step, interleaved with the fragment reads of the next step
+//   k-step 3:      wait until this wave's loads of slab s+1 have landed and its reads of `cur` have
+//                  returned; barrier; then, interleaved with the step's MFMAs: fragment reads of
+//                  k-step 0 of slab s+1 from `nxt`, and the direct-to-LDS loads of slab s+2 into `cur`
+// so there is one barrier per slab, it sits in the shadow of MFMAs already issued, and no fragment
+// read is ever issued later than a full k-step before its use.
+// ------------------------------------------------------------------------------------------------
+enum { FAST_VEC_C = 1 };   // kernel flag: 16-byte stores to C are legal (base and ldc 16-byte aligned)
+
 template <typename IN, int BM_, int BN_, int WM_, int WN_, int WAVES_PER_SIMD_, int GROUP_M_ = 8>
 struct FastCfg {
     using In = IN;
@@ -120,17 +193,22 @@ struct FastCfg {
     static constexpr int TMI = BM / WM / 32, TNI = BN / WN / 32;
     static constexpr int LDS_BYTES = 2 * (BM + BN) * ROW_BYTES;
     static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0, "wave tiles are made of 32x32 MFMA tiles");
+    // the epilogue parks 32 rows of fp32 per wave, half of the waves in each LDS buffer
+    static_assert((WM * WN / 2) * 32 * (TNI * 32 * 4 + 16) <= (BM + BN) * ROW_BYTES, "epilogue staging must fit");
 };
+
+#define GL_SCHED_GROUP(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
 
 template <typename CFG>
 __global__ __launch_bounds__(CFG::T) __attribute__((amdgpu_waves_per_eu(CFG::WAVES_PER_SIMD, CFG::WAVES_PER_SIMD)))
-void k4_mfma_fast(Args a, int tiles_m, int tiles_n)
+void k4_mfma_fast(Args a, int tiles_m, int tiles_n, int flags)
 {
     using IN = typename CFG::In;
     constexpr int BM = CFG::BM, BN = CFG::BN, WN = CFG::WN, T = CFG::T, NW = T / 64;
     constexpr int TMI = CFG::TMI, TNI = CFG::TNI;
     constexpr int KE = ROW_BYTES / IN::BYTES;        // K elements per slab
     constexpr int V = 16 / IN::BYTES;                // K elements per chunk
+    constexpr int NK = CHUNKS / 2;                   // k-steps per slab
     constexpr int LA = BM / 8 / NW, LB = BN / 8 / NW; // direct loads per wave per slab (8 rows each)
     static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0 && NW % 2 == 0, "row octets must divide over the waves");
     // Two separately declared buffers, each [A rows | B rows][128 bytes]: distinct objects let the
@@ -196,53 +274,83 @@ void k4_mfma_fast(Args a, int tiles_m, int tiles_n)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    // Fragment reads run one k-step ahead of the MFMAs that consume them; the scheduling barrier
-    // keeps the compiler from hoisting every read of the slab to the top (which would need four
-    // times the fragment registers).
-    auto compute = [&](const char* base) __attribute__((always_inline)) {
-        u32x4_t fa[2][TMI], fb[2][TNI];
-        auto read = [&](int ks, int slot) __attribute__((always_inline)) {
-            const int pos = ((2 * ks) ^ rd_mask) << 4;
+    u32x4_t fa[2][TMI], fb[2][TNI];                  // two fragment slots: the step in use, the step in flight
+    auto read = [&](const char* base, int ks, int slot) __attribute__((always_inline)) {
+        const int pos = ((2 * ks) ^ rd_mask) << 4;
 #pragma unroll
-            for (int i = 0; i < TMI; ++i) fa[slot][i] = *(const u32x4_t*)(base + rd_a + i * 32 * ROW_BYTES + pos);
+        for (int i = 0; i < TMI; ++i) fa[slot][i] = *(const u32x4_t*)(base + rd_a + i * 32 * ROW_BYTES + pos);
 #pragma unroll
-            for (int j = 0; j < TNI; ++j) fb[slot][j] = *(const u32x4_t*)(base + rd_b + j * 32 * ROW_BYTES + pos);
-        };
-        read(0, 0);
+        for (int j = 0; j < TNI; ++j) fb[slot][j] = *(const u32x4_t*)(base + rd_b + j * 32 * ROW_BYTES + pos);
+    };
+    auto mfmas = [&](int slot) __attribute__((always_inline)) {
 #pragma unroll
-        for (int ks = 0; ks < CHUNKS / 2; ++ks) {
-            if (ks + 1 < CHUNKS / 2) read(ks + 1, (ks + 1) & 1);
+        for (int i = 0; i < TMI; ++i)
 #pragma unroll
-            for (int i = 0; i < TMI; ++i)
+            for (int j = 0; j < TNI; ++j) mfma_chunk<IN>(fb[slot][j], fa[slot][i], acc[i][j]);   // B first: see the epilogue
+    };
+    constexpr int NMF = TMI * TNI * (IN::BYTES == 1 ? 2 : 1);   // MFMA instructions per k-step
+    constexpr int NRD = TMI + TNI;                               // fragment reads per k-step
+    constexpr int NLD = LA + LB;                                 // direct loads per slab
+    static_assert(NMF > NRD, "the schedule hangs one read on each of the first MFMAs of a step");
+
+    const int64_t nslab = a.K / KE;                  // K is a whole number of slabs
+    // `full` = every prefetch of this slab is in range, so the body is free of branches and the
+    // requested interleaving can be realised by the instruction scheduler.
+    auto slab = [&](auto full, int64_t s, char* cur, char* nxt) __attribute__((always_inline)) {
+        constexpr bool FULL = decltype(full)::value;
 #pragma unroll
-                for (int j = 0; j < TNI; ++j) mfma_chunk<IN>(fa[ks & 1][i], fb[ks & 1][j], acc[i][j]);
+        for (int ks = 0; ks < NK; ++ks) {
+            if (ks + 1 < NK) {
+                read(cur, ks + 1, (ks + 1) & 1);
+                mfmas(ks & 1);
+#pragma unroll
+                for (int n = 0; n < NRD; ++n) { GL_SCHED_GROUP(0x008, 1); GL_SCHED_GROUP(0x100, 1); }
+                GL_SCHED_GROUP(0x008, NMF - NRD);
+            } else {
+                asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+                __syncthreads();
+                if (FULL || s + 1 < nslab) read(nxt, 0, 0);
+                if (FULL || s + 2 < nslab) issue(s + 2, cur);
+                mfmas(ks & 1);
+                if constexpr (FULL) {
+                    constexpr int REST = NMF - NRD, PER = (NLD + REST - 1) / REST;
+#pragma unroll
+                    for (int n = 0; n < NRD; ++n) { GL_SCHED_GROUP(0x008, 1); GL_SCHED_GROUP(0x100, 1); }
+#pragma unroll
+                    for (int n = 0; n < REST; ++n) { GL_SCHED_GROUP(0x008, 1); GL_SCHED_GROUP(0x020, PER); }
+                }
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
     };
-    // All of this wave's direct loads have landed in LDS; then every wave's have.
-    auto landed = [&]() __attribute__((always_inline)) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-    };
 
-    const int64_t nslab = a.K / KE;                  // K is a whole number of slabs
-    // Even slabs live in buffer 0, odd slabs in buffer 1.  The barrier that ends a step also
-    // guarantees that nobody still reads the buffer the next step's loads overwrite.  The loop
-    // walks whole pairs of slabs so that it has a single exit; an odd last slab is peeled.
     if (nslab > 0) issue(0, lds0);
-    landed();
-    const int64_t npairs = nslab / 2;
-    for (int64_t p = 0; p < npairs; ++p) {
-        issue(2 * p + 1, lds1);
-        compute(lds0);
-        landed();
-        if (2 * p + 2 < nslab) issue(2 * p + 2, lds0);
-        compute(lds1);
-        landed();
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (nslab > 1) issue(1, lds1);
+    if (nslab > 0) read(lds0, 0, 0);
+    using yes = std::integral_constant<bool, true>;
+    using no = std::integral_constant<bool, false>;
+    int64_t s = 0;
+    for (; s + 3 < nslab; s += 2) {                  // steady state: slabs s and s+1, both with s+2 in range
+        slab(yes{}, s, lds0, lds1);
+        slab(yes{}, s + 1, lds1, lds0);
     }
-    if (nslab & 1) compute(lds0);
+    for (; s + 1 < nslab; s += 2) {
+        slab(no{}, s, lds0, lds1);
+        slab(no{}, s + 1, lds1, lds0);
+    }
+    if (s < nslab) slab(no{}, s, lds0, lds1);
 
-    store_tiles<TMI, TNI>(a, b, acc, m0 + wm * (BM / CFG::WM), n0 + wn * (BN / WN), lane);
+    // After the barrier of the last slab nobody reads LDS any more: the buffers can hold the
+    // epilogue's staging areas, one per wave, half of the waves in each buffer.
+    constexpr int STAGE = 32 * (TNI * 32 * 4 + 16);
+    char* stage = (wave < NW / 2 ? lds0 : lds1) + (wave % (NW / 2)) * STAGE;
+    const int64_t row0 = m0 + wm * (BM / CFG::WM), col0 = n0 + wn * (BN / WN);
+    const bool vec_ok = (flags & FAST_VEC_C) != 0;
+    if (a.out_dtype == GEMM_F32) store_tiles_staged<GEMM_F32, TMI, TNI>(a, b, acc, row0, col0, lane, stage, vec_ok);
+    else if (a.out_dtype == GEMM_BF16) store_tiles_staged<GEMM_BF16, TMI, TNI>(a, b, acc, row0, col0, lane, stage, vec_ok);
+    else store_tiles_staged<GEMM_F16, TMI, TNI>(a, b, acc, row0, col0, lane, stage, vec_ok);
 }
 
 // ------------------------------------------------------------------------------------------------
