@@ -144,8 +144,9 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
         const bool va = (holds & (vecA | GEMM_COND_K_CONTIG_A)) == (vecA | GEMM_COND_K_CONTIG_A);
         const bool vb = (holds & (vecB | GEMM_COND_K_CONTIG_B)) == (vecB | GEMM_COND_K_CONTIG_B);
         const int64_t kvec = 16 / es;
+        // the streaming kernel addresses a strip of columns with 32-bit byte offsets: ldb is bounded
         const bool skinny = (holds & GEMM_COND_SMALL_M) && va && vb && d->K % kvec == 0 && d->K > 0 &&
-                            (d->in_dtype == GEMM_BF16 || d->in_dtype == GEMM_F16);
+                            (d->in_dtype == GEMM_BF16 || d->in_dtype == GEMM_F16) && d->ldb <= ((int64_t)1 << 24);
         const bool kdiv = d->K % (128 / es) == 0;   // whole 128-byte slabs: the direct-to-LDS kernel masks nothing along K
         if (skinny) {
             p.path = MFMA_SKINNY;

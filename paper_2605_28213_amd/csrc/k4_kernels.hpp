@@ -485,13 +485,6 @@ __global__ __launch_bounds__(WM* WN * 64) void k4_mfma_masked(Args a, int vec_ma
     store_tiles<TMI, TNI>(a, b, acc, sa.r0 + wm * (BM / WM), sb.r0 + wn * (BN / WN), lane);
 }
 
-// ------------------------------------------------------------------------------------------------
-// Streaming kernel for M <= 16 (decode-like shapes): the product is bound by reading B once from
-// HBM, so B is never staged in LDS.  A workgroup owns 16*NB columns of C; its WAVES waves split K,
-// each streaming its share of B with 16-byte loads straight into the B operand of
-// v_mfma_f32_16x16x32 while A (M x K, cache resident) supplies the other operand; partial sums
-// meet in LDS.  Needs: A row-major, B column-major, 16-byte aligned, K a multiple of 8.
-// ------------------------------------------------------------------------------------------------
 template <typename IN>
 __device__ __forceinline__ void mfma16(const u32x4_t& a, const u32x4_t& b, f32x4_t& c)
 {
@@ -501,77 +494,162 @@ __device__ __forceinline__ void mfma16(const u32x4_t& a, const u32x4_t& b, f32x4
         c = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
 }
 
-template <typename IN, int WAVES_, int NB_, int UNROLL_>
-struct SkinnyCfg {
+// ------------------------------------------------------------------------------------------------
+// Streaming kernel for M <= 16 (decode-like shapes): the product is bound by reading B once from
+// HBM.  A workgroup owns a strip of 16*NB columns of C; its WAVES waves split K, partial sums meet
+// in LDS at the end.  Needs: A row-major, B column-major, 16-byte aligned, K a multiple of 8.
+//
+// The B operand of v_mfma_f32_16x16x32 wants, per instruction, 16 columns x 64 bytes of K; fetched
+// that way every wave instruction opens 16 separate 64-byte streams 2*ldb bytes apart, and HBM
+// delivers about half of what it gives to contiguous reads.  Here a wave instead fetches, per load
+// instruction, 64/LPC columns' worth of LPC*16 contiguous bytes (LPC = lanes per column = TK/8),
+// parks the registers in a wave-private LDS tile of NB*16 rows (one per column) x TK*2 bytes, and
+// reads the MFMA operand layout back from there.  Chunk q (16 bytes) of row c is kept at chunk
+// position q ^ (c % 16): writes (16 consecutive q of one row) and operand reads (16 rows at one q)
+// are both bank-conflict free.  The tile is private to the wave and LDS serves a wave's requests in
+// order, so the main loop has no barrier: waves only meet for the final sum over the K split.
+//
+// Per wave and tile: NB*TK/32 loads of B stay in flight in registers while the previous tile is
+// multiplied; A (M <= 16 rows, cache resident) is fetched straight into the other MFMA operand.
+// ------------------------------------------------------------------------------------------------
+template <typename IN, int WAVES_, int NB_, int TK_>
+struct StreamCfg {
     using In = IN;
-    static constexpr int WAVES = WAVES_, NB = NB_, UNROLL = UNROLL_, COLS = 16 * NB_;
-    static constexpr int LDS_BYTES = 4 * WAVES * 16 * (COLS + 1);
+    static constexpr int WAVES = WAVES_, NB = NB_, TK = TK_, COLS = 16 * NB_;
+    static constexpr int LPC = TK / 8;                     // lanes (16-byte chunks) per column per tile
+    static constexpr int CPL = 64 / LPC;                   // columns covered by one load instruction
+    static constexpr int NLD = COLS / CPL;                 // B loads per tile per lane
+    static constexpr int KS = TK / 32;                     // MFMA k-steps per tile
+    static constexpr int TILE_BYTES = COLS * TK * 2;
+    static constexpr int LDS_BYTES = WAVES * TILE_BYTES;
+    static_assert(LPC >= 16 && LPC <= 64 && (LPC & (LPC - 1)) == 0, "a column's run is 16..64 lanes wide");
+    static_assert(WAVES * 16 * (COLS + 1) * 4 <= LDS_BYTES, "the K-split partial sums reuse the tiles");
 };
 
 template <typename CFG>
-__global__ __launch_bounds__(CFG::WAVES * 64) void k4_skinny(Args a)
+__global__ __launch_bounds__(CFG::WAVES * 64) void k4_stream(Args a)
 {
     using IN = typename CFG::In;
-    constexpr int WAVES = CFG::WAVES, NB = CFG::NB, UNROLL = CFG::UNROLL, COLS = CFG::COLS;
-    __shared__ float part[WAVES][16][COLS + 1];
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    const int l16 = lane & 15, lq = lane >> 4;          // operand row/column and 8-element k group
+    constexpr int WAVES = CFG::WAVES, NB = CFG::NB, TK = CFG::TK, COLS = CFG::COLS;
+    constexpr int LPC = CFG::LPC, CPL = CFG::CPL, NLD = CFG::NLD, KS = CFG::KS;
+    constexpr int ROWB = TK * 2;                            // bytes per LDS row
+    __shared__ __attribute__((aligned(16))) char lds[CFG::LDS_BYTES];
+    const int t = threadIdx.x, lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int l16 = lane & 15, lq = lane >> 4;
     const int64_t b = blockIdx.y;
     const int64_t j0 = (int64_t)blockIdx.x * COLS;
     const uint16_t* A = (const uint16_t*)a.A + b * a.stride_a;
     const uint16_t* B = (const uint16_t*)a.B + b * a.stride_b;
+    char* tile = lds + wave * CFG::TILE_BYTES;
 
-    // K is cut into WAVES contiguous ranges, each a multiple of 32
+    // K is cut into WAVES contiguous ranges, each a whole number of 32-element MFMA steps
     const int64_t ksteps = (a.K + 31) / 32;
     const int64_t per = (ksteps + WAVES - 1) / WAVES;
     const int64_t kbeg = wave * per * 32;
     const int64_t kend = (kbeg + per * 32 < a.K) ? kbeg + per * 32 : a.K;
 
-    const bool arow = l16 < a.M;
-    const uint16_t* ap = A + (int64_t)(arow ? l16 : 0) * a.a_si + lq * 8;
-    const uint16_t* bp[NB];
-    bool bcol[NB];
+    // load side: lane fetches chunk lc of column (n*CPL + lcol) of the strip; columns past N are
+    // clamped (their sums are never stored)
+    // (the host has checked that a strip's extent, COLS * ldb elements, fits 32-bit byte offsets)
+    const int lcol = lane / LPC, lc = lane % LPC;
+    const char* Bs = (const char*)(B + j0 * a.b_sj);       // wave-uniform base of the strip
+    uint32_t bo[NLD];
+    int wr[NLD];
 #pragma unroll
-    for (int n = 0; n < NB; ++n) {
-        const int64_t j = j0 + n * 16 + l16;
-        bcol[n] = j < a.N;
-        bp[n] = B + (bcol[n] ? j : 0) * a.b_sj + lq * 8;
+    for (int n = 0; n < NLD; ++n) {
+        const int c = n * CPL + lcol;
+        const int64_t cc = j0 + c < a.N ? c : a.N - 1 - j0;
+        bo[n] = (uint32_t)((cc * a.b_sj + lc * 8) * 2);
+        wr[n] = c * ROWB + ((lc ^ (c & 15)) << 4);
     }
+    // operand side: lane (l16, lq) holds, for k-step s, chunk 4s+lq of row l16 (A) / column l16 (B)
+    const uint16_t* ap = A + (int64_t)(l16 < a.M ? l16 : a.M - 1) * a.a_si + lq * 8;
+    const int rd = l16 * ROWB;
 
     f32x4_t acc[NB];
 #pragma unroll
     for (int n = 0; n < NB; ++n) acc[n] = f32x4_t{0, 0, 0, 0};
-
     const u32x4_t zero = {0, 0, 0, 0};
-    for (int64_t k = kbeg; k < kend; k += 32 * UNROLL) {
-        u32x4_t fa[UNROLL], fb[UNROLL][NB];
+    u32x4_t rb[NLD], ra[KS];
+
+    // `full`: the whole tile lies inside [kbeg, kend), no lane needs a mask
+    auto fetch = [&](auto full, int64_t k) __attribute__((always_inline)) {
+        constexpr bool FULL = decltype(full)::value;
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            const int64_t kk = k + u * 32 + lq * 8;      // this lane's 8 elements; K % 8 == 0
-            const bool in = kk < kend;
-            fa[u] = (in && arow) ? *(const u32x4_t*)(ap + k + u * 32) : zero;
-#pragma unroll
-            for (int n = 0; n < NB; ++n)
-                fb[u][n] = (in && bcol[n]) ? __builtin_nontemporal_load((const u32x4_t*)(bp[n] + k + u * 32)) : zero;
+        for (int n = 0; n < NLD; ++n) {
+            if (FULL || k + lc * 8 < kend) rb[n] = __builtin_nontemporal_load((const u32x4_t*)(Bs + k * 2 + bo[n]));
+            else rb[n] = zero;
         }
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u)
+        for (int s = 0; s < KS; ++s) {
+            if (FULL || k + s * 32 + lq * 8 < kend) ra[s] = *(const u32x4_t*)(ap + k + s * 32);
+            else ra[s] = zero;
+        }
+    };
+    auto park = [&]() __attribute__((always_inline)) {
 #pragma unroll
-            for (int n = 0; n < NB; ++n) mfma16<IN>(fa[u], fb[u][n], acc[n]);
+        for (int n = 0; n < NLD; ++n) *(u32x4_t*)(tile + wr[n]) = rb[n];
+    };
+    auto multiply = [&](const u32x4_t (&fa)[KS]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+#pragma unroll
+            for (int n = 0; n < NB; ++n) {
+                const u32x4_t fb = *(const u32x4_t*)(tile + n * 16 * ROWB + rd + (((4 * s + lq) ^ l16) << 4));
+                mfma16<IN>(fa[s], fb, acc[n]);
+            }
+    };
+    using yes = std::integral_constant<bool, true>;
+    using no = std::integral_constant<bool, false>;
+
+    // Tile i is parked and multiplied while the loads of tile i+1 are in flight.  The steady-state
+    // loop runs over whole tiles only and is free of branches; a ragged last tile is fetched under
+    // masks after it.
+    const int64_t span = kend > kbeg ? kend - kbeg : 0;
+    const int64_t nfull = span / TK;
+    const bool ragged = span % TK != 0;
+    int64_t k = kbeg;
+    if (nfull > 0) {
+        fetch(yes{}, k);
+        for (int64_t i = 1; i < nfull; ++i) {
+            u32x4_t fa[KS];
+#pragma unroll
+            for (int s = 0; s < KS; ++s) fa[s] = ra[s];
+            park();
+            k += TK;
+            fetch(yes{}, k);
+            multiply(fa);
+        }
+        u32x4_t fa[KS];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) fa[s] = ra[s];
+        park();
+        k += TK;
+        if (ragged) fetch(no{}, k);
+        multiply(fa);
+    } else if (ragged) {
+        fetch(no{}, k);
+    }
+    if (ragged) {
+        park();
+        multiply(ra);
     }
 
     // 16x16 accumulator: register r of lane l holds row 4*(l/16) + r, column l%16
+    __syncthreads();
+    float* part = (float*)lds;
 #pragma unroll
     for (int n = 0; n < NB; ++n)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) part[wave][4 * lq + r][n * 16 + l16] = acc[n][r];
+        for (int r = 0; r < 4; ++r) part[(wave * 16 + 4 * lq + r) * (COLS + 1) + n * 16 + l16] = acc[n][r];
     __syncthreads();
     const float sc = batch_scale(a, b);
     for (int o = t; o < 16 * COLS; o += WAVES * 64) {
         const int i = o / COLS, j = o % COLS;
         float v = 0.0f;
 #pragma unroll
-        for (int w = 0; w < WAVES; ++w) v += part[w][i][j];
+        for (int w = 0; w < WAVES; ++w) v += part[(w * 16 + i) * (COLS + 1) + j];
         if (i < a.M && j0 + j < a.N) store_out(a.C, b * a.stride_c + (int64_t)i * a.ldc + j0 + j, v * sc, a.out_dtype);
     }
 }

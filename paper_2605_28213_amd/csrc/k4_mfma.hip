@@ -6,7 +6,7 @@ namespace gl {
 
 // Frozen configurations ("templatize" + an offline sweep, paper Table 1 expression-level intents).
 template <typename IN> using FastK4 = FastCfg<IN, 256, 256, 2, 2, 1>;      // 4 waves, 1 per SIMD, 128x128 per wave
-template <typename IN> using SkinnyK4 = SkinnyCfg<IN, 4, 2, 4>;
+template <typename IN> using StreamK4 = StreamCfg<IN, 4, 2, 256>;           // 32 columns per workgroup, K split 4 ways, 512-byte runs
 constexpr int MASKED_BM = 128, MASKED_BN = 128, MASKED_WM = 2, MASKED_WN = 2;
 
 template <typename CFG>
@@ -32,10 +32,10 @@ static hipError_t launch_masked(const Args& a, int vec_mask)
 }
 
 template <typename CFG>
-static hipError_t launch_skinny(const Args& a)
+static hipError_t launch_stream(const Args& a)
 {
     dim3 grid((unsigned)((a.N + CFG::COLS - 1) / CFG::COLS), (unsigned)a.batch, 1), block(CFG::WAVES * 64, 1, 1);
-    hipLaunchKernelGGL(k4_skinny<CFG>, grid, block, 0, a.stream, a);
+    hipLaunchKernelGGL(k4_stream<CFG>, grid, block, 0, a.stream, a);
     return hipGetLastError();
 }
 
@@ -44,8 +44,8 @@ hipError_t launch_k4(int path, const Args& a)
 {
     const int kind = path & 0xFF, vec_mask = (path >> 8) & 3;
     if (kind == MFMA_SKINNY) {
-        if (a.in_dtype == GEMM_BF16) return launch_skinny<SkinnyK4<BF16>>(a);
-        if (a.in_dtype == GEMM_F16) return launch_skinny<SkinnyK4<F16>>(a);
+        if (a.in_dtype == GEMM_BF16) return launch_stream<StreamK4<BF16>>(a);
+        if (a.in_dtype == GEMM_F16) return launch_stream<StreamK4<F16>>(a);
         return hipErrorInvalidValue;
     }
     if (kind == MFMA_VEC16) {
@@ -69,8 +69,8 @@ Geometry geometry_k4(int path, const Args& a)
     const int kind = path & 0xFF;
     const int es = a.in_dtype == GEMM_FP8_E4M3 ? 1 : 2;
     if (kind == MFMA_SKINNY) {
-        using C = SkinnyK4<BF16>;
-        return Geometry{16, C::COLS, 32 * C::UNROLL, C::WAVES * 64, 1, C::LDS_BYTES, ((a.N + C::COLS - 1) / C::COLS) * a.batch};
+        using C = StreamK4<BF16>;
+        return Geometry{16, C::COLS, C::TK, C::WAVES * 64, 2, C::LDS_BYTES, ((a.N + C::COLS - 1) / C::COLS) * a.batch};
     }
     if (kind == MFMA_VEC16) {
         using C = FastK4<BF16>;

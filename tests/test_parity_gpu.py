@@ -117,6 +117,11 @@ def test_skinny_path_edges():
             assert gemm.gemm_query(4, d).path.startswith("mfma16-stream")
             check(4, inp)
             check(4, inp, out_dtype=gen.F32)
+    # batched, with a ragged last K tile in every wave's share of K and padded leading dimensions
+    cfg = gen.Config("skinny_batched", 13, 75, 1320, gen.BF16, gen.BF16, ROW, COL, "normal", std=0.02, batch=3,
+                     lda=1328, ldb=1336, ldc=80)
+    inp = gen.make_inputs(cfg, 5)
+    check(4, inp)
 
 
 def test_batched_strides_scales_and_padding_untouched():
