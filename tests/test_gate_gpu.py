@@ -1,0 +1,119 @@
+"""The validation gate over the whole lineage at the full benchmark sizes: every state K0..K4 on
+every workload C1..C5, three seeds each, in the launch configuration the benchmark times.
+
+Reference values come from the CPU oracle: the full product for C1, sampled outputs elsewhere
+(random points, first/last rows and columns, points around workgroup-tile corners), which the
+oracle evaluates one by one.  The ledger is written to gpurun_out/gate_ledger.jsonl and its table
+to gpurun_out/gate_table.txt.
+"""
+import json
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2605_28213_amd import gate, gemm
+from paper_2605_28213_amd import inputs as gen
+
+pytestmark = pytest.mark.gpu
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LEDGER = os.path.join(ROOT, "gpurun_out", "gate_ledger.jsonl")
+TABLE = os.path.join(ROOT, "gpurun_out", "gate_table.txt")
+_entries = []
+
+
+def sample_points(cfg, rng, n_random=3000):
+    M, N, nb = cfg.M, cfg.N, cfg.batch
+    pb = [rng.integers(0, nb, n_random)]
+    pi = [rng.integers(0, M, n_random)]
+    pj = [rng.integers(0, N, n_random)]
+    # last row / last column / first row of a random batch item: where tails and masks live
+    b = int(rng.integers(0, nb))
+    cols = rng.choice(N, size=min(N, 1024), replace=False)
+    rows = rng.choice(M, size=min(M, 1024), replace=False)
+    for i in (0, M - 1):
+        pb.append(np.full(cols.size, b)); pi.append(np.full(cols.size, i)); pj.append(cols)
+    for j in (0, N - 1):
+        pb.append(np.full(rows.size, b)); pi.append(rows); pj.append(np.full(rows.size, j))
+    # corners of 256 x 256 tiles
+    ti = np.array([t for t in (255, 256, 257, 2047, 2048, 4095, 4096) if t < M])
+    tj = np.array([t for t in (255, 256, 257, 2047, 2048, 4095, 4096) if t < N])
+    if ti.size and tj.size:
+        gi, gj = np.meshgrid(ti, tj, indexing="ij")
+        pb.append(np.full(gi.size, b)); pi.append(gi.ravel()); pj.append(gj.ravel())
+    return np.concatenate(pb), np.concatenate(pi), np.concatenate(pj)
+
+
+class OracleReference:
+    """Callable handed to the gate; caches the oracle's values per seed so that the five states of
+    one workload are compared against the same numbers."""
+
+    def __init__(self, cfg):
+        self.cfg, self.cache = cfg, {}
+
+    def __call__(self, inp):
+        if inp.seed in self.cache:
+            return self.cache[inp.seed]
+        c = self.cfg
+        if c.flops <= 1e9:
+            C_ref, D = oracle.gemm(c.in_dtype, c.layout_a, c.layout_b, c.M, c.N, c.K, inp.A, inp.lda, inp.B, inp.ldb,
+                                   batch=c.batch, stride_a=inp.stride_a, stride_b=inp.stride_b,
+                                   scale_a=inp.scale_a, scale_b=inp.scale_b)
+            ref = gate.Reference(C_ref, D)
+        else:
+            pts = sample_points(c, np.random.default_rng(100 + inp.seed))
+            C_ref, D = oracle.gemm_points(c.in_dtype, c.layout_a, c.layout_b, c.M, c.N, c.K, inp.A, inp.lda, inp.B,
+                                          inp.ldb, *pts, batch=c.batch, stride_a=inp.stride_a, stride_b=inp.stride_b,
+                                          scale_a=inp.scale_a, scale_b=inp.scale_b)
+            ref = gate.Reference(C_ref, D, pts)
+        self.cache[inp.seed] = ref
+        return ref
+
+
+@pytest.fixture(scope="module", autouse=True)
+def ledger_file():
+    os.makedirs(os.path.dirname(LEDGER), exist_ok=True)
+    if os.path.exists(LEDGER):
+        os.remove(LEDGER)
+    yield
+    with open(TABLE, "w") as f:
+        f.write(gate.format_table(_entries) + "\n\n" + json.dumps(gate.pass_rate(_entries)) + "\n")
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5"])
+def test_every_state_passes_the_gate(name):
+    cfg = gen.CONFIGS[name]
+    reference, cache = OracleReference(cfg), {}
+    for v in range(gemm.GEMM_VARIANT_COUNT):
+        print(f"[gate] {name} {gemm.gemm_variant_name(v)}", flush=True)
+        e = gate.run_gate(v, cfg, reference, inputs_cache=cache, ledger_path=LEDGER, time_budget_s=1.0)
+        _entries.append(e)
+        if v == gemm.GEMM_K4_MFMA and cfg.in_dtype == gen.F32:
+            # fp32 has no matrix instruction: the expert state refuses instead of substituting another state
+            assert e["verdict"].startswith("refused(precondition") and "DTYPE_HAS_MFMA" in e["verdict"]
+            continue
+        assert e["compile"]["ok"]
+        assert e["verdict"] == "passed", (name, e["variant_name"], e["verdict"], e.get("correctness"))
+        assert len(e["correctness"]) == 3 and all(s["all_outputs_finite"] for s in e["correctness"])
+        assert e["profile"]["launches"] >= 3
+    torch.cuda.empty_cache()
+
+
+def test_strict_mode_refuses_and_names_the_violated_conditions():
+    """The ragged fp16 workload violates the alignment conditions of K2..K4; under STRICT the gate
+    records a refusal with the condition names instead of running the masked path."""
+    cfg = gen.CONFIGS["C3_small"]
+    for v in (gemm.GEMM_K2_VECTORIZED, gemm.GEMM_K3_PIPELINED, gemm.GEMM_K4_MFMA):
+        e = gate.run_gate(v, cfg, OracleReference(cfg), seeds=(0,), strict=True, ledger_path=LEDGER)
+        _entries.append(e)
+        assert e["verdict"].startswith("refused(precondition")
+        assert "LD16_A" in e["query"]["violated"] and "correctness" not in e
+
+
+def test_pass_rate_of_the_ledger():
+    pr = gate.pass_rate(_entries)
+    assert pr["attempted"] >= 5 * 3 * 4 and pr["passed"] == pr["attempted"]
+    assert len(pr["refused"]) >= 4
