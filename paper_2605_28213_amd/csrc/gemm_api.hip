@@ -148,11 +148,13 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
         const bool skinny = (holds & GEMM_COND_SMALL_M) && va && vb && d->K % kvec == 0 && d->K > 0 &&
                             (d->in_dtype == GEMM_BF16 || d->in_dtype == GEMM_F16) && d->ldb <= ((int64_t)1 << 24);
         const bool kdiv = d->K % (128 / es) == 0;   // whole 128-byte slabs: the direct-to-LDS kernel masks nothing along K
+        // that kernel addresses a 256-row tile with 32-bit byte offsets: rows are bounded to 4 MiB
+        const bool rows_fit = d->lda * es <= ((int64_t)1 << 22) && d->ldb * es <= ((int64_t)1 << 22);
         if (skinny) {
             p.path = MFMA_SKINNY;
             path = "mfma16-stream(small-M)";
             required &= ~(uint32_t)GEMM_COND_TILE_DIV_K;
-        } else if (va && vb && kdiv) {
+        } else if (va && vb && kdiv && rows_fit) {
             p.path = MFMA_VEC16 | (3 << 8);
             path = "mfma32-direct-to-lds";
         } else {

@@ -17,6 +17,7 @@
 // c ^ swz(r).
 #pragma once
 #include <type_traits>
+#include <utility>
 
 #include "common.hpp"
 
@@ -173,50 +174,106 @@ __device__ __forceinline__ void store_tiles_staged(const Args& a, int64_t b, con
 // ------------------------------------------------------------------------------------------------
 // Fast kernel: both operands K-contiguous and 16-byte aligned, K a whole number of 128-byte slabs.
 //
-// Software pipeline, per workgroup and slab s (4 k-steps of 32 bytes of K each; `cur` = LDS buffer
-// s%2, `nxt` the other one):
-//   k-steps 0..2:  MFMAs of the step, interleaved with the fragment reads of the next step
-//   k-step 3:      wait until this wave's loads of slab s+1 have landed and its reads of `cur` have
-//                  returned; barrier; then, interleaved with the step's MFMAs: fragment reads of
-//                  k-step 0 of slab s+1 from `nxt`, and the direct-to-LDS loads of slab s+2 into `cur`
-// so there is one barrier per slab, it sits in the shadow of MFMAs already issued, and no fragment
-// read is ever issued later than a full k-step before its use.
+// One workgroup = 4 waves (one per SIMD) on a 256x256 tile of C, each wave on a 128x128 quarter =
+// 4x4 accumulator tiles of 32x32.  K advances in slabs of 128 bytes per row.  LDS is a ring of five
+// 32 KB regions, each one operand slab (256 rows x 128 bytes); operand slab q (A of slab s: q = 2s,
+// B of slab s: q = 2s+1) lives in region q % 5, so that while slab s is multiplied its successor is
+// complete or landing and the slab after that is already being fetched:
+//
+//      region of      A_s    B_s    A_s+1   B_s+1   (fifth: held B_s-1, free since the last barrier)
+//      during slab s  read   read   landed  landing  receives A_s+2;   B_s+2 goes to A_s's region
+//                                                     once slab s has been read (after the barrier)
+//
+// Global -> LDS uses buffer loads that write LDS directly (no registers); one wave instruction
+// fills 8 consecutive LDS rows, and the lane -> global chunk assignment applies the swizzle.  The
+// loads of a slab are issued in four groups spread over the slab's k-steps, so the memory pipe sees
+// an even stream instead of a burst per slab.  Rows past the end of the matrix lie outside the
+// buffer resource and read as zero.
+//
+// Per slab there is one barrier; before it a wave waits until all but its youngest 8 loads (the
+// A_s+2 group) have landed and its own LDS reads have returned.  The barrier is a bare s_barrier: a
+// fence would drain the loads that are meant to stay in flight.  Fragment reads run one k-step ahead
+// of the MFMAs that use them, in two register slots.
+//
+// A k-step is 32 bytes of K per lane half for 2-byte types (one chunk per lane, v_mfma 32x32x16) and
+// 64 bytes for e4m3 (two chunks per lane, v_mfma_scale 32x32x64 with unit scales: the form that runs
+// at twice the 16-bit rate on gfx950; the 32x32x16 fp8 form runs at the 16-bit rate).
 // ------------------------------------------------------------------------------------------------
 enum { FAST_VEC_C = 1 };   // kernel flag: 16-byte stores to C are legal (base and ldc 16-byte aligned)
 
-template <typename IN, int BM_, int BN_, int WM_, int WN_, int WAVES_PER_SIMD_, int GROUP_M_ = 8>
-struct FastCfg {
-    using In = IN;
-    static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, GROUP_M = GROUP_M_;
-    static constexpr int WAVES_PER_SIMD = WAVES_PER_SIMD_;
-    static constexpr int T = WM * WN * 64;
-    static constexpr int TMI = BM / WM / 32, TNI = BN / WN / 32;
-    static constexpr int LDS_BYTES = 2 * (BM + BN) * ROW_BYTES;
-    static_assert(BM % (WM * 32) == 0 && BN % (WN * 32) == 0, "wave tiles are made of 32x32 MFMA tiles");
-    // the epilogue parks 32 rows of fp32 per wave, half of the waves in each LDS buffer
-    static_assert((WM * WN / 2) * 32 * (TNI * 32 * 4 + 16) <= (BM + BN) * ROW_BYTES, "epilogue staging must fit");
-};
+typedef __attribute__((ext_vector_type(8))) int i32x8_t;
+
+template <typename IN> struct Frag { static constexpr int CPS = IN::BYTES == 1 ? 2 : 1; u32x4_t c[CPS]; };
+
+// acc += a . b^T for one k-step; `a` supplies accumulator columns, `b` accumulator rows (see the
+// epilogue).  Which k a lane's bytes stand for is irrelevant as long as both operands agree.
+template <typename IN>
+__device__ __forceinline__ void mfma_step(const Frag<IN>& a, const Frag<IN>& b, f32x16_t& c)
+{
+    if constexpr (IN::ID == GEMM_BF16) {
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a.c[0]), __builtin_bit_cast(bf16x8_t, b.c[0]), c, 0, 0, 0);
+    } else if constexpr (IN::ID == GEMM_F16) {
+        c = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a.c[0]), __builtin_bit_cast(f16x8_t, b.c[0]), c, 0, 0, 0);
+    } else {
+        const i32x8_t av = {(int)a.c[0].x, (int)a.c[0].y, (int)a.c[0].z, (int)a.c[0].w, (int)a.c[1].x, (int)a.c[1].y, (int)a.c[1].z, (int)a.c[1].w};
+        const i32x8_t bv = {(int)b.c[0].x, (int)b.c[0].y, (int)b.c[0].z, (int)b.c[0].w, (int)b.c[1].x, (int)b.c[1].y, (int)b.c[1].z, (int)b.c[1].w};
+        // cbsz = blgp = 0 select e4m3 for both operands; scale exponents 127 (E8M0) = 2^0
+        c = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, bv, c, 0, 0, 0, 0x7F7F7F7F, 0, 0x7F7F7F7F);
+    }
+}
 
 #define GL_SCHED_GROUP(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
 
+// Requested issue order of one k-step: NMF MFMAs, an LDS read (0x100) behind each of the first NRD,
+// NLOADS direct loads (VMEM, 0x020) spread evenly over all of them.
+template <int NMF, int NRD, int NLOADS, int N = 0>
+__device__ __forceinline__ void sched_kstep()
+{
+    if constexpr (N < NMF) {
+        GL_SCHED_GROUP(0x008, 1);
+        if constexpr (N < NRD) GL_SCHED_GROUP(0x100, 1);
+        constexpr int L = ((N + 1) * NLOADS) / NMF - (N * NLOADS) / NMF;
+        if constexpr (L > 0) GL_SCHED_GROUP(0x020, L);
+        sched_kstep<NMF, NRD, NLOADS, N + 1>();
+    }
+}
+
+template <int... KS, typename F>
+__device__ __forceinline__ void for_each_step(std::integer_sequence<int, KS...>, F&& f)
+{
+    (f(std::integral_constant<int, KS>{}), ...);
+}
+
+template <typename IN, int GROUP_M_ = 8>
+struct FastCfg {
+    using In = IN;
+    static constexpr int BM = 256, BN = 256, WM = 2, WN = 2, GROUP_M = GROUP_M_;
+    static constexpr int T = WM * WN * 64;
+    static constexpr int TMI = BM / WM / 32, TNI = BN / WN / 32;
+    static constexpr int REGION = 256 * ROW_BYTES, REGIONS = 5;
+    static constexpr int LDS_BYTES = REGIONS * REGION;
+    // the epilogue parks 32 rows of fp32 per wave, one wave per region
+    static_assert(32 * (TNI * 32 * 4 + 16) <= REGION, "epilogue staging must fit a region");
+};
+
 template <typename CFG>
-__global__ __launch_bounds__(CFG::T) __attribute__((amdgpu_waves_per_eu(CFG::WAVES_PER_SIMD, CFG::WAVES_PER_SIMD)))
+__global__ __launch_bounds__(CFG::T) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void k4_mfma_fast(Args a, int tiles_m, int tiles_n, int flags)
 {
     using IN = typename CFG::In;
-    constexpr int BM = CFG::BM, BN = CFG::BN, WN = CFG::WN, T = CFG::T, NW = T / 64;
-    constexpr int TMI = CFG::TMI, TNI = CFG::TNI;
-    constexpr int KE = ROW_BYTES / IN::BYTES;        // K elements per slab
-    constexpr int V = 16 / IN::BYTES;                // K elements per chunk
-    constexpr int NK = CHUNKS / 2;                   // k-steps per slab
-    constexpr int LA = BM / 8 / NW, LB = BN / 8 / NW; // direct loads per wave per slab (8 rows each)
-    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0 && NW % 2 == 0, "row octets must divide over the waves");
-    // Two separately declared buffers, each [A rows | B rows][128 bytes]: distinct objects let the
-    // compiler see that a direct load into one never aliases a fragment read from the other, so it
-    // does not wait for the loads before the reads.
-    constexpr int BUF_BYTES = (BM + BN) * ROW_BYTES;
-    __shared__ __attribute__((aligned(1024))) char lds0[BUF_BYTES];
-    __shared__ __attribute__((aligned(1024))) char lds1[BUF_BYTES];
+    constexpr int BM = CFG::BM, BN = CFG::BN, WN = CFG::WN, NW = CFG::T / 64;
+    constexpr int TMI = CFG::TMI, TNI = CFG::TNI, REGION = CFG::REGION;
+    constexpr int KE = ROW_BYTES / IN::BYTES;            // K elements per slab
+    constexpr int V = 16 / IN::BYTES;                    // K elements per chunk
+    constexpr int CPS = Frag<IN>::CPS;                   // chunks per lane per k-step
+    constexpr int NK = CHUNKS / (2 * CPS);               // k-steps per slab
+    constexpr int LD = 256 / 8 / NW;                     // direct loads per wave per operand slab
+    static_assert(BM == 256 && BN == 256 && NW == 4 && LD % 2 == 0, "the ring schedule is written for this shape");
+    __shared__ __attribute__((aligned(1024))) char r0[REGION];
+    __shared__ __attribute__((aligned(1024))) char r1[REGION];
+    __shared__ __attribute__((aligned(1024))) char r2[REGION];
+    __shared__ __attribute__((aligned(1024))) char r3[REGION];
+    __shared__ __attribute__((aligned(1024))) char r4[REGION];
 
     const int t = threadIdx.x, lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -226,45 +283,46 @@ void k4_mfma_fast(Args a, int tiles_m, int tiles_n, int flags)
     tile_of<CFG::GROUP_M>(blockIdx.x, tiles_m * tiles_n, tiles_m, tiles_n, tm, tn);
     const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
 
-    // ---- global -> LDS, without passing through registers -------------------------------------
-    // One wave-wide 16-byte load fills 8 consecutive LDS rows (lane L lands at byte 16*L of the
-    // 1 KiB block), so lane L must fetch, for row L/8, the chunk whose swizzled position is L%8.
-    // Wave w owns row octets w, w + NW, ...; NW is even, so all its octets share one parity and the
-    // lane's chunk index is the same for every one of them.
-    const int orow = lane >> 3;                                  // row inside the octet
-    const int gchunk = (lane & 7) ^ swz(orow + 8 * (wave & 1));  // chunk this lane fetches
-    const char* A = (const char*)a.A + (b * a.stride_a) * IN::BYTES;
-    const char* B = (const char*)a.B + (b * a.stride_b) * IN::BYTES;
-    const char* pa[LA];
-    const char* pb[LB];
-#pragma unroll
-    for (int n = 0; n < LA; ++n) {
-        const int64_t r = m0 + (wave + n * NW) * 8 + orow;       // rows past M are clamped: their products
-        pa[n] = A + ((r < a.M ? r : a.M - 1) * a.a_si + gchunk * V) * IN::BYTES;   // are never stored
-    }
-#pragma unroll
-    for (int n = 0; n < LB; ++n) {
-        const int64_t r = n0 + (wave + n * NW) * 8 + orow;
-        pb[n] = B + ((r < a.N ? r : a.N - 1) * a.b_sj + gchunk * V) * IN::BYTES;
-    }
-    using gptr = const __attribute__((address_space(1))) void*;
+    // ---- global -> LDS ---------------------------------------------------------------------------
+    // One buffer resource per operand, based at the tile's first row and ending with the matrix.
+    // A wave-wide 16-byte load lands lane L at byte 16*L of a 1 KiB block = 8 LDS rows, so lane L
+    // fetches, for row L/8 of the octet, the chunk whose swizzled position is L%8.  Wave w owns row
+    // octets w, w+4, ...: all of one parity, so one per-lane offset serves every load; the octet and
+    // the slab enter through the scalar offset.  (The host has checked that a tile's extent fits 32
+    // bits of byte offset.)
+    const int orow = lane >> 3;
+    const int gchunk = (lane & 7) ^ swz(orow + 8 * (wave & 1));
+    const char* A = (const char*)a.A + (b * a.stride_a + m0 * a.a_si) * IN::BYTES;
+    const char* B = (const char*)a.B + (b * a.stride_b + n0 * a.b_sj) * IN::BYTES;
+    const int64_t bytes_a = ((a.M - 1 - m0) * a.a_si + a.K) * IN::BYTES, bytes_b = ((a.N - 1 - n0) * a.b_sj + a.K) * IN::BYTES;
+    constexpr int64_t CAP = 0xFFFFFFFFll;
+    constexpr int RSRC_FLAGS = 0x00020000;               // raw buffer, 32-bit data format
+    const __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc((void*)A, 0, (int)(uint32_t)(bytes_a < CAP ? bytes_a : CAP), RSRC_FLAGS);
+    const __amdgpu_buffer_rsrc_t rsrc_b = __builtin_amdgcn_make_buffer_rsrc((void*)B, 0, (int)(uint32_t)(bytes_b < CAP ? bytes_b : CAP), RSRC_FLAGS);
+    const int voff_a = (int)((orow * a.a_si + gchunk * V) * IN::BYTES);
+    const int voff_b = (int)((orow * a.b_sj + gchunk * V) * IN::BYTES);
+    const int oct_a = (int)(8 * a.a_si * IN::BYTES), oct_b = (int)(8 * a.b_sj * IN::BYTES);   // bytes per row octet
     using lptr = __attribute__((address_space(3))) void*;
-    auto issue = [&](int64_t s, char* buf) __attribute__((always_inline)) {
-        const int64_t koff = s * ROW_BYTES;
-        char* base = buf + wave * 1024;
+    // loads [lo, hi) of this wave's share of operand slab s into region `reg`
+    auto issue_a = [&](int64_t s, char* reg, int lo, int hi) __attribute__((always_inline)) {
+        const int k0 = (int)(s * ROW_BYTES);
 #pragma unroll
-        for (int n = 0; n < LA; ++n)
-            __builtin_amdgcn_global_load_lds((gptr)(pa[n] + koff), (lptr)(base + n * NW * 1024), 16, 0, 0);
+        for (int n = lo; n < hi; ++n)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, (lptr)(reg + (wave + n * NW) * 1024), 16, voff_a, k0 + (wave + n * NW) * oct_a, 0, 0);
+    };
+    auto issue_b = [&](int64_t s, char* reg, int lo, int hi) __attribute__((always_inline)) {
+        const int k0 = (int)(s * ROW_BYTES);
 #pragma unroll
-        for (int n = 0; n < LB; ++n)
-            __builtin_amdgcn_global_load_lds((gptr)(pb[n] + koff), (lptr)(base + BM * ROW_BYTES + n * NW * 1024), 16, 0, 0);
+        for (int n = lo; n < hi; ++n)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_b, (lptr)(reg + (wave + n * NW) * 1024), 16, voff_b, k0 + (wave + n * NW) * oct_b, 0, 0);
     };
 
-    // ---- LDS read side: lane reads row (lane % 32) of each 32-row block, chunk 2*ks + lane/32 ---
+    // ---- LDS -> registers: lane reads row (lane % 32) of each 32-row block, CPS chunks starting at
+    // chunk CPS * (2*ks + lane/32) ---------------------------------------------------------------
     const int lrow = lane & 31, lhalf = lane >> 5;
-    const int rd_mask = lhalf ^ swz(lrow);
+    const int rd_mask = (lhalf * CPS) ^ swz(lrow);
     const int rd_a = (wm * (BM / CFG::WM) + lrow) * ROW_BYTES;
-    const int rd_b = (BM + wn * (BN / WN) + lrow) * ROW_BYTES;
+    const int rd_b = (wn * (BN / WN) + lrow) * ROW_BYTES;
 
     f32x16_t acc[TMI][TNI];
 #pragma unroll
@@ -274,78 +332,105 @@ void k4_mfma_fast(Args a, int tiles_m, int tiles_n, int flags)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    u32x4_t fa[2][TMI], fb[2][TNI];                  // two fragment slots: the step in use, the step in flight
-    auto read = [&](const char* base, int ks, int slot) __attribute__((always_inline)) {
-        const int pos = ((2 * ks) ^ rd_mask) << 4;
+    Frag<IN> fa[2][TMI], fb[2][TNI];                 // two fragment slots: the step in use, the step in flight
+    auto read = [&](const char* ra, const char* rb, int ks, int slot) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < TMI; ++i) fa[slot][i] = *(const u32x4_t*)(base + rd_a + i * 32 * ROW_BYTES + pos);
+        for (int q = 0; q < CPS; ++q) {
+            const int pos = ((2 * CPS * ks + q) ^ rd_mask) << 4;
 #pragma unroll
-        for (int j = 0; j < TNI; ++j) fb[slot][j] = *(const u32x4_t*)(base + rd_b + j * 32 * ROW_BYTES + pos);
+            for (int j = 0; j < TNI; ++j) fb[slot][j].c[q] = *(const u32x4_t*)(rb + rd_b + j * 32 * ROW_BYTES + pos);
+#pragma unroll
+            for (int i = 0; i < TMI; ++i) fa[slot][i].c[q] = *(const u32x4_t*)(ra + rd_a + i * 32 * ROW_BYTES + pos);
+        }
     };
+    // B first: see the epilogue.  Columns are walked back and forth so that consecutive MFMAs share
+    // one operand.
     auto mfmas = [&](int slot) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < TMI; ++i)
 #pragma unroll
-            for (int j = 0; j < TNI; ++j) mfma_chunk<IN>(fb[slot][j], fa[slot][i], acc[i][j]);   // B first: see the epilogue
+            for (int jj = 0; jj < TNI; ++jj) {
+                const int j = (i & 1) ? TNI - 1 - jj : jj;
+                mfma_step<IN>(fb[slot][j], fa[slot][i], acc[i][j]);
+            }
     };
-    constexpr int NMF = TMI * TNI * (IN::BYTES == 1 ? 2 : 1);   // MFMA instructions per k-step
-    constexpr int NRD = TMI + TNI;                               // fragment reads per k-step
-    constexpr int NLD = LA + LB;                                 // direct loads per slab
-    static_assert(NMF > NRD, "the schedule hangs one read on each of the first MFMAs of a step");
+    constexpr int NMF = TMI * TNI;                   // MFMA instructions per k-step
+    constexpr int NRD = (TMI + TNI) * CPS;           // fragment reads per k-step
+    constexpr int HALF = LD / 2;                     // loads per issue group
+    // issue groups of a slab, in order: B_s+1 second half, A_s+2 first half, A_s+2 second half (before
+    // the barrier, spread over the first NK-1 k-steps), B_s+2 first half (after it, last k-step)
+    constexpr int GROUPS_PER_STEP = NK > 1 ? (3 + NK - 2) / (NK - 1) : 3;
+    static_assert(NK >= 2 && NRD <= NMF, "a k-step hangs at most one fragment read on each MFMA");
 
     const int64_t nslab = a.K / KE;                  // K is a whole number of slabs
-    // `full` = every prefetch of this slab is in range, so the body is free of branches and the
-    // requested interleaving can be realised by the instruction scheduler.
-    auto slab = [&](auto full, int64_t s, char* cur, char* nxt) __attribute__((always_inline)) {
+    auto kstep = [&](auto full, auto step, int64_t s, char* ra, char* rb, char* na, char* nb, char* fifth) __attribute__((always_inline)) {
         constexpr bool FULL = decltype(full)::value;
-#pragma unroll
-        for (int ks = 0; ks < NK; ++ks) {
-            if (ks + 1 < NK) {
-                read(cur, ks + 1, (ks + 1) & 1);
-                mfmas(ks & 1);
-#pragma unroll
-                for (int n = 0; n < NRD; ++n) { GL_SCHED_GROUP(0x008, 1); GL_SCHED_GROUP(0x100, 1); }
-                GL_SCHED_GROUP(0x008, NMF - NRD);
+        constexpr int ks = decltype(step)::value;
+        constexpr int G0 = ks * GROUPS_PER_STEP, G1 = (ks + 1) * GROUPS_PER_STEP < 3 ? (ks + 1) * GROUPS_PER_STEP : 3;
+        constexpr int NLOADS = ks + 1 < NK ? (G1 > G0 ? (G1 - G0) * HALF : 0) : HALF;
+        if constexpr (ks + 1 < NK) {
+            read(ra, rb, ks + 1, (ks + 1) & 1);
+            if constexpr (G0 <= 0 && 0 < G1) { if (FULL || s + 1 < nslab) issue_b(s + 1, nb, HALF, LD); }
+            if constexpr (G0 <= 1 && 1 < G1) { if (FULL || s + 2 < nslab) issue_a(s + 2, fifth, 0, HALF); }
+            if constexpr (G0 <= 2 && 2 < G1) { if (FULL || s + 2 < nslab) issue_a(s + 2, fifth, HALF, LD); }
+        } else {
+            // landed after this wait: A_s+1, B_s+1; possibly still in flight: the LD loads of A_s+2
+            if constexpr (FULL) {
+                static_assert(LD == 8, "the wait below counts the A_s+2 group");
+                asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
             } else {
                 asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-                __syncthreads();
-                if (FULL || s + 1 < nslab) read(nxt, 0, 0);
-                if (FULL || s + 2 < nslab) issue(s + 2, cur);
-                mfmas(ks & 1);
-                if constexpr (FULL) {
-                    constexpr int REST = NMF - NRD, PER = (NLD + REST - 1) / REST;
-#pragma unroll
-                    for (int n = 0; n < NRD; ++n) { GL_SCHED_GROUP(0x008, 1); GL_SCHED_GROUP(0x100, 1); }
-#pragma unroll
-                    for (int n = 0; n < REST; ++n) { GL_SCHED_GROUP(0x008, 1); GL_SCHED_GROUP(0x020, PER); }
-                }
             }
-            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            if (FULL || s + 1 < nslab) read(na, nb, 0, 0);
+            if (FULL || s + 2 < nslab) issue_b(s + 2, ra, 0, HALF);
         }
+        mfmas(ks & 1);
+        // one fragment read behind each of the first MFMAs, the direct loads spread over all of them
+        if constexpr (FULL) sched_kstep<NMF, NRD, NLOADS>();
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    // `full` = every prefetch of this slab is in range, so the body is free of branches and the
+    // requested interleaving can be realised by the instruction scheduler.
+    auto slab = [&](auto full, int64_t s, char* ra, char* rb, char* na, char* nb, char* fifth) __attribute__((always_inline)) {
+        for_each_step(std::make_integer_sequence<int, NK>{}, [&](auto step) __attribute__((always_inline)) {
+            kstep(full, step, s, ra, rb, na, nb, fifth);
+        });
     };
 
-    if (nslab > 0) issue(0, lds0);
+    // prologue: A_0, B_0, A_1 and the first half of B_1
+    if (nslab > 0) { issue_a(0, r0, 0, LD); issue_b(0, r1, 0, LD); }
+    if (nslab > 1) { issue_a(1, r2, 0, LD); issue_b(1, r3, 0, HALF); }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    if (nslab > 1) issue(1, lds1);
-    if (nslab > 0) read(lds0, 0, 0);
+    if (nslab > 0) read(r0, r1, 0, 0);
     using yes = std::integral_constant<bool, true>;
     using no = std::integral_constant<bool, false>;
     int64_t s = 0;
-    for (; s + 3 < nslab; s += 2) {                  // steady state: slabs s and s+1, both with s+2 in range
-        slab(yes{}, s, lds0, lds1);
-        slab(yes{}, s + 1, lds1, lds0);
+    // five slabs bring the ring back to its start
+    for (; s + 6 < nslab; s += 5) {
+        slab(yes{}, s, r0, r1, r2, r3, r4);
+        slab(yes{}, s + 1, r2, r3, r4, r0, r1);
+        slab(yes{}, s + 2, r4, r0, r1, r2, r3);
+        slab(yes{}, s + 3, r1, r2, r3, r4, r0);
+        slab(yes{}, s + 4, r3, r4, r0, r1, r2);
     }
-    for (; s + 1 < nslab; s += 2) {
-        slab(no{}, s, lds0, lds1);
-        slab(no{}, s + 1, lds1, lds0);
+    // tail: at most six slabs, region pointers rotate at run time, waits are conservative
+    {
+        auto reg = [&](int i) __attribute__((always_inline)) -> char* {
+            i %= 5;
+            return i == 0 ? r0 : i == 1 ? r1 : i == 2 ? r2 : i == 3 ? r3 : r4;
+        };
+        for (; s < nslab; ++s) {
+            const int u = (int)((2 * s) % 5);
+            slab(no{}, s, reg(u), reg(u + 1), reg(u + 2), reg(u + 3), reg(u + 4));
+        }
     }
-    if (s < nslab) slab(no{}, s, lds0, lds1);
 
-    // After the barrier of the last slab nobody reads LDS any more: the buffers can hold the
-    // epilogue's staging areas, one per wave, half of the waves in each buffer.
-    constexpr int STAGE = 32 * (TNI * 32 * 4 + 16);
-    char* stage = (wave < NW / 2 ? lds0 : lds1) + (wave % (NW / 2)) * STAGE;
+    // After the barrier of the last slab nobody reads operands from LDS any more and no load is in
+    // flight: the regions can hold the epilogue's staging areas, one wave per region.
+    char* stage = wave == 0 ? r0 : wave == 1 ? r1 : wave == 2 ? r2 : r3;
     const int64_t row0 = m0 + wm * (BM / CFG::WM), col0 = n0 + wn * (BN / WN);
     const bool vec_ok = (flags & FAST_VEC_C) != 0;
     if (a.out_dtype == GEMM_F32) store_tiles_staged<GEMM_F32, TMI, TNI>(a, b, acc, row0, col0, lane, stage, vec_ok);

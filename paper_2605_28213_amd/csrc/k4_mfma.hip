@@ -5,7 +5,7 @@
 namespace gl {
 
 // Frozen configurations ("templatize" + an offline sweep, paper Table 1 expression-level intents).
-template <typename IN> using FastK4 = FastCfg<IN, 256, 256, 2, 2, 1>;      // 4 waves, 1 per SIMD, 128x128 per wave
+template <typename IN> using FastK4 = FastCfg<IN>;                         // 256x256 tile, 4 waves, 128x128 per wave
 template <typename IN> using StreamK4 = StreamCfg<IN, 4, 2, 256>;           // 32 columns per workgroup, K split 4 ways, 512-byte runs
 constexpr int MASKED_BM = 128, MASKED_BN = 128, MASKED_WM = 2, MASKED_WN = 2;
 
@@ -75,7 +75,7 @@ Geometry geometry_k4(int path, const Args& a)
     if (kind == MFMA_VEC16) {
         using C = FastK4<BF16>;
         const int64_t g = ((a.M + C::BM - 1) / C::BM) * ((a.N + C::BN - 1) / C::BN) * a.batch;
-        return Geometry{C::BM, C::BN, ROW_BYTES / es, C::T, 2, C::LDS_BYTES, g};
+        return Geometry{C::BM, C::BN, ROW_BYTES / es, C::T, 2, C::LDS_BYTES, g};   // stages: slabs in flight beyond the one in use
     }
     const int64_t g = ((a.M + MASKED_BM - 1) / MASKED_BM) * ((a.N + MASKED_BN - 1) / MASKED_BN) * a.batch;
     return Geometry{MASKED_BM, MASKED_BN, ROW_BYTES / es, MASKED_WM * MASKED_WN * 64, 2, 2 * (MASKED_BM + MASKED_BN) * ROW_BYTES, g};
