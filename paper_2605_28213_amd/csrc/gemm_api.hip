@@ -75,7 +75,8 @@ bool grid_fits(int variant, const gemm_desc_t* d)
     if (variant == GEMM_K0_NAIVE) return (d->M + 15) / 16 <= lim;
     if (variant == GEMM_K1_LDS_TILED) return (d->M + 63) / 64 <= lim;
     if (variant == GEMM_K2_VECTORIZED || variant == GEMM_K3_PIPELINED) return (d->M + 127) / 128 <= lim;
-    return ((d->M + 255) / 256) * ((d->N + 255) / 256) < ((int64_t)1 << 31);
+    // K4: one-dimensional grid over (batch, tile); the smallest tile of its paths is 128 x 128
+    return ((d->M + 127) / 128) * ((d->N + 127) / 128) * d->batch < ((int64_t)1 << 31);
 }
 
 Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, const void* C, bool need_ptrs)

@@ -56,21 +56,27 @@ __device__ __forceinline__ void mfma_chunk(const u32x4_t& a, const u32x4_t& b, f
     }
 }
 
-// Workgroup id -> (tile_m, tile_n).  Hardware hands consecutive workgroup ids to the 8 XCDs in
-// turn; ids are first regrouped so that each XCD (own L2) works on one contiguous run of tiles,
-// then tiles are walked in bands of GROUP_M tile-rows so that a run reuses few A rows and B columns.
+// Workgroup id -> (batch item, tile_m, tile_n) on a one-dimensional grid of tiles_m*tiles_n*batch
+// workgroups.  Hardware hands consecutive workgroup ids to the 8 XCDs in turn; ids are first
+// regrouped so that each XCD (own L2) works on one contiguous run of the (batch, tile) sequence --
+// whole problems when there are at least 8 of them, so that every operand tile is fetched into one
+// L2 only -- then the tiles of a problem are walked in bands of GROUP_M tile-rows so that a run
+// reuses few A rows and B columns.
 template <int GROUP_M>
-__device__ __forceinline__ void tile_of(int pid, int total, int tiles_m, int tiles_n, int& tm, int& tn)
+__device__ __forceinline__ void tile_of(int pid, int total, int tiles_m, int tiles_n, int64_t& b, int& tm, int& tn)
 {
     constexpr int XCD = 8;
     const int x = pid % XCD, local = pid / XCD;
     const int base = total / XCD, rem = total % XCD;
-    const int id = x * base + (x < rem ? x : rem) + local;
+    const int flat = x * base + (x < rem ? x : rem) + local;
+    const int per = tiles_m * tiles_n;
+    b = __builtin_amdgcn_readfirstlane(flat / per);     // wave-uniform by construction: keep it scalar
+    const int id = flat % per;
     const int width = GROUP_M * tiles_n;
     const int g = id / width, first = g * GROUP_M;
     const int gsz = (tiles_m - first) < GROUP_M ? (tiles_m - first) : GROUP_M;
-    tm = first + (id % width) % gsz;
-    tn = (id % width) / gsz;
+    tm = __builtin_amdgcn_readfirstlane(first + (id % width) % gsz);
+    tn = __builtin_amdgcn_readfirstlane((id % width) / gsz);
 }
 
 // Epilogue shared by both kernels.  A 32x32 accumulator tile keeps, in register r of lane l, the
@@ -278,9 +284,9 @@ void k4_mfma_fast(Args a, int tiles_m, int tiles_n, int flags)
     const int t = threadIdx.x, lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int wm = wave / WN, wn = wave % WN;
-    const int64_t b = blockIdx.y;
+    int64_t b;
     int tm, tn;
-    tile_of<CFG::GROUP_M>(blockIdx.x, tiles_m * tiles_n, tiles_m, tiles_n, tm, tn);
+    tile_of<CFG::GROUP_M>(blockIdx.x, (int)gridDim.x, tiles_m, tiles_n, b, tm, tn);
     const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
 
     // ---- global -> LDS ---------------------------------------------------------------------------
@@ -505,9 +511,9 @@ __global__ __launch_bounds__(WM* WN * 64) void k4_mfma_masked(Args a, int vec_ma
 
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int wm = wave / WN, wn = wave % WN;
-    const int64_t b = blockIdx.y;
+    int64_t b;
     int tm, tn;
-    tile_of<8>(blockIdx.x, tiles_m * tiles_n, tiles_m, tiles_n, tm, tn);
+    tile_of<8>(blockIdx.x, (int)gridDim.x, tiles_m, tiles_n, b, tm, tn);
 
     TileSrc sa{(const char*)a.A + b * a.stride_a * IN::BYTES, a.a_si, a.a_sk, a.M, (int64_t)tm * BM, (vec_mask & 1) != 0};
     TileSrc sb{(const char*)a.B + b * a.stride_b * IN::BYTES, a.b_sj, a.b_sk, a.N, (int64_t)tn * BN, (vec_mask & 2) != 0};

@@ -14,7 +14,7 @@ static hipError_t launch_fast(const Args& a)
 {
     auto kern = k4_mfma_fast<CFG>;
     const int tiles_m = (int)((a.M + CFG::BM - 1) / CFG::BM), tiles_n = (int)((a.N + CFG::BN - 1) / CFG::BN);
-    dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)a.batch, 1), block(CFG::T, 1, 1);
+    dim3 grid((unsigned)((int64_t)tiles_m * tiles_n * a.batch), 1, 1), block(CFG::T, 1, 1);
     const int eo = a.out_dtype == GEMM_F32 ? 4 : 2;
     const bool vec_c = ((uintptr_t)a.C % 16 == 0) && (a.ldc * eo) % 16 == 0 && (a.batch <= 1 || (a.stride_c * eo) % 16 == 0);
     hipLaunchKernelGGL(kern, grid, block, 0, a.stream, a, tiles_m, tiles_n, vec_c ? (int)FAST_VEC_C : 0);
@@ -25,7 +25,7 @@ template <typename IN>
 static hipError_t launch_masked(const Args& a, int vec_mask)
 {
     const int tiles_m = (int)((a.M + MASKED_BM - 1) / MASKED_BM), tiles_n = (int)((a.N + MASKED_BN - 1) / MASKED_BN);
-    dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)a.batch, 1), block(MASKED_WM * MASKED_WN * 64, 1, 1);
+    dim3 grid((unsigned)((int64_t)tiles_m * tiles_n * a.batch), 1, 1), block(MASKED_WM * MASKED_WN * 64, 1, 1);
     hipLaunchKernelGGL((k4_mfma_masked<IN, MASKED_BM, MASKED_BN, MASKED_WM, MASKED_WN>), grid, block, 0, a.stream, a,
                        vec_mask, tiles_m, tiles_n);
     return hipGetLastError();
