@@ -44,7 +44,7 @@ typedef enum {
     GEMM_ERR_BAD_VARIANT = 2,       /* variant id outside [0, GEMM_VARIANT_COUNT) */
     GEMM_ERR_UNSUPPORTED_DTYPE = 3, /* in/out dtype pair the library does not implement */
     GEMM_ERR_PRECONDITION = 4,      /* a condition the variant relies on does not hold (see gemm_query) */
-    GEMM_ERR_WORKSPACE = 5,         /* workspace missing or smaller than gemm_query reports */
+    GEMM_ERR_WORKSPACE = 5,         /* workspace was lent but is smaller than gemm_query reports, or misaligned */
     GEMM_ERR_LAUNCH = 6             /* the HIP runtime refused the launch */
 } gemm_status_t;
 
@@ -99,7 +99,13 @@ typedef struct {
     const float *scale_a, *scale_b;  /* device: one fp32 per batch item each, or NULL (= 1).  The
                                         epilogue multiplies the fp32 accumulator by scale_a[b]*scale_b[b]
                                         before rounding to out_dtype (round to nearest even). */
-    void *workspace;                 /* device scratch; NULL allowed when gemm_query reports 0 bytes */
+    void *workspace;                 /* optional device scratch lent by the caller (16-byte aligned), or NULL.
+                                        Only K4 uses it: when its fast path's conditions fail and scratch of at
+                                        least gemm_query's workspace_bytes is lent, it packs both operands
+                                        (K contiguous, aligned, zero-padded K) and runs the fast kernel on the
+                                        copies; without scratch its masked kernel runs.  Scratch that is lent
+                                        but too small or misaligned is an error (GEMM_ERR_WORKSPACE), never a
+                                        silent slow path.  Contents after the call are unspecified. */
     size_t workspace_bytes;
     void *stream;                    /* hipStream_t; NULL = the default stream */
     uint32_t flags;                  /* GEMM_FLAG_* */
@@ -115,7 +121,7 @@ typedef struct {
     int32_t  stages;          /* LDS buffers in flight */
     int32_t  lds_bytes;       /* static + dynamic LDS per workgroup */
     int64_t  grid;            /* workgroups launched */
-    size_t   workspace_bytes; /* scratch the call needs */
+    size_t   workspace_bytes; /* scratch the packed path of K4 uses for this call (0: no path would use any) */
     char     path[64];        /* name of the code path gemm_run_ex would take */
 } gemm_query_t;
 

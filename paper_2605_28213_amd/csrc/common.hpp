@@ -80,7 +80,11 @@ __device__ __forceinline__ float batch_scale(const Args& a, int64_t b)
 // Each returns hipSuccess or the launch error.  `path` selects a code path that the caller
 // (gemm_api.hip) has already proven legal for these arguments.
 enum ValuPath { VALU_SCALAR = 0, VALU_VEC16 = 1 };
-enum MfmaPath { MFMA_ELEMENTWISE = 0, MFMA_VEC16 = 1, MFMA_SKINNY = 2 };
+enum MfmaPath { MFMA_ELEMENTWISE = 0, MFMA_VEC16 = 1, MFMA_SKINNY = 2, MFMA_PACKED = 3 };
+
+// Workspace of the packed K4 path: both operands rewritten as [rows][Kp], Kp = K rounded up to a slab.
+int64_t k4_packed_k(const Args& a);
+size_t k4_packed_workspace_bytes(const Args& a);
 
 hipError_t launch_k0(const Args& a);
 hipError_t launch_valu_tiled(int variant, int path, const Args& a);

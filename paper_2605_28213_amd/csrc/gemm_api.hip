@@ -117,6 +117,7 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
 
     const uint32_t vecA = GEMM_COND_ALIGN16_A | GEMM_COND_LD16_A, vecB = GEMM_COND_ALIGN16_B | GEMM_COND_LD16_B;
     uint32_t required = 0;
+    size_t pack_bytes = 0;     // K4 only: scratch of the packed path (used when lent, advertised otherwise)
     Geometry g{};
     const char* path = "";
     switch (variant) {
@@ -151,6 +152,8 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
         const bool kdiv = d->K % (128 / es) == 0;   // whole 128-byte slabs: the direct-to-LDS kernel masks nothing along K
         // that kernel addresses a 256-row tile with 32-bit byte offsets: rows are bounded to 4 MiB
         const bool rows_fit = d->lda * es <= ((int64_t)1 << 22) && d->ldb * es <= ((int64_t)1 << 22);
+        // packing both operands into lent scratch turns any layout/alignment/K into the fast kernel's case
+        const bool can_pack = (holds & GEMM_COND_DTYPE_HAS_MFMA) && d->K > 0 && k4_packed_k(a) * es <= ((int64_t)1 << 22);
         if (skinny) {
             p.path = MFMA_SKINNY;
             path = "mfma16-stream(small-M)";
@@ -158,7 +161,13 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
         } else if (va && vb && kdiv && rows_fit) {
             p.path = MFMA_VEC16 | (3 << 8);
             path = "mfma32-direct-to-lds";
+        } else if (can_pack && d->workspace != nullptr) {
+            // the caller lent scratch: repair the violated conditions by packing, then run the fast kernel
+            p.path = MFMA_PACKED;
+            path = "mfma32-packed+direct-to-lds";
+            pack_bytes = k4_packed_workspace_bytes(a);
         } else {
+            if (can_pack) pack_bytes = k4_packed_workspace_bytes(a);   // what lending scratch would buy
             p.path = MFMA_ELEMENTWISE | (((va ? 1 : 0) | (vb ? 2 : 0)) << 8);
             path = va && vb ? "mfma32-vec16-masked" : va ? "mfma32-vec16(A)+elementwise-masked(B)"
                             : vb ? "mfma32-elementwise-masked(A)+vec16(B)" : "mfma32-elementwise-masked";
@@ -179,13 +188,14 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
     q.bm = g.bm; q.bn = g.bn; q.bk = g.bk;
     q.threads = g.threads; q.stages = g.stages; q.lds_bytes = g.lds_bytes;
     q.grid = p.empty ? 0 : g.grid;
-    q.workspace_bytes = 0;
+    q.workspace_bytes = pack_bytes;
     strncpy(q.path, path, sizeof(q.path) - 1);
 
     const bool hard = (q.violated & GEMM_COND_DTYPE_HAS_MFMA) != 0;   // no slow path exists for this one
     if (hard || (q.violated && (d->flags & GEMM_FLAG_STRICT))) p.status = GEMM_ERR_PRECONDITION;
-    else if (q.workspace_bytes > 0 && (!d->workspace || d->workspace_bytes < q.workspace_bytes) && need_ptrs)
-        p.status = GEMM_ERR_WORKSPACE;
+    else if ((p.path & 0xFF) == MFMA_PACKED && variant == GEMM_K4_MFMA &&
+             (d->workspace_bytes < q.workspace_bytes || ((uintptr_t)d->workspace & 15u)))
+        p.status = GEMM_ERR_WORKSPACE;   // scratch was lent but is too small or misaligned: say so rather than run slow
     return p;
 }
 
@@ -233,7 +243,7 @@ int gemm_run_ex(int variant, const gemm_desc_t* d, const void* A, const void* B,
     case GEMM_K1_LDS_TILED:
     case GEMM_K2_VECTORIZED:
     case GEMM_K3_PIPELINED: e = launch_valu_tiled(variant, p.path, p.args); break;
-    default: e = launch_k4((p.path & 0xFF) == MFMA_SKINNY ? MFMA_SKINNY : p.path, p.args); break;
+    default: e = launch_k4(p.path, p.args); break;
     }
     return e == hipSuccess ? GEMM_OK : GEMM_ERR_LAUNCH;
 }

@@ -125,7 +125,7 @@ __device__ __forceinline__ void store_tiles(const Args& a, int64_t b, const f32x
 // time in a private LDS area (row pitch padded by 16 bytes) and writes it out again row by row, so
 // that global stores are 16 bytes per lane and whole 128-byte lines per row.
 // ------------------------------------------------------------------------------------------------
-template <int OUT, int TMI, int TNI>
+template <int OUT, bool INTERIOR, int TMI, int TNI>
 __device__ __forceinline__ void store_tiles_staged(const Args& a, int64_t b, const f32x16_t (&acc)[TMI][TNI],
                                                    int64_t row0, int64_t col0, int lane, char* stage, bool vec_ok)
 {
@@ -155,6 +155,22 @@ __device__ __forceinline__ void store_tiles_staged(const Args& a, int64_t b, con
                     *(f16x4_t*)dst = f16x4_t{(_Float16)v0, (_Float16)v1, (_Float16)v2, (_Float16)v3};
                 }
             }
+        if constexpr (INTERIOR) {
+            // the wave's whole sub-tile lies inside C and 16-byte stores are legal: no masks, all reads
+            // of the block in flight before the first store
+            u32x4_t w[PASSES];
+#pragma unroll
+            for (int p = 0; p < PASSES; ++p) {
+                const int q = lane + 64 * p;
+                w[p] = *(const u32x4_t*)(stage + (q / CPR) * PITCH + (q % CPR) * 16);
+            }
+#pragma unroll
+            for (int p = 0; p < PASSES; ++p) {
+                const int q = lane + 64 * p;
+                *(u32x4_t*)(C + ((row0 + i * 32 + q / CPR) * a.ldc + col0 + (q % CPR) * EPC) * OB) = w[p];
+            }
+            continue;
+        }
 #pragma unroll
         for (int p = 0; p < PASSES; ++p) {
             const int q = lane + 64 * p, r = q / CPR, c = q % CPR;
@@ -439,9 +455,15 @@ void k4_mfma_fast(Args a, int tiles_m, int tiles_n, int flags)
     char* stage = wave == 0 ? r0 : wave == 1 ? r1 : wave == 2 ? r2 : r3;
     const int64_t row0 = m0 + wm * (BM / CFG::WM), col0 = n0 + wn * (BN / WN);
     const bool vec_ok = (flags & FAST_VEC_C) != 0;
-    if (a.out_dtype == GEMM_F32) store_tiles_staged<GEMM_F32, TMI, TNI>(a, b, acc, row0, col0, lane, stage, vec_ok);
-    else if (a.out_dtype == GEMM_BF16) store_tiles_staged<GEMM_BF16, TMI, TNI>(a, b, acc, row0, col0, lane, stage, vec_ok);
-    else store_tiles_staged<GEMM_F16, TMI, TNI>(a, b, acc, row0, col0, lane, stage, vec_ok);
+    const bool interior = vec_ok && row0 + BM / CFG::WM <= a.M && col0 + BN / WN <= a.N;   // wave-uniform
+    auto store = [&](auto out) __attribute__((always_inline)) {
+        constexpr int OUT = decltype(out)::value;
+        if (interior) store_tiles_staged<OUT, true, TMI, TNI>(a, b, acc, row0, col0, lane, stage, vec_ok);
+        else store_tiles_staged<OUT, false, TMI, TNI>(a, b, acc, row0, col0, lane, stage, vec_ok);
+    };
+    if (a.out_dtype == GEMM_F32) store(std::integral_constant<int, GEMM_F32>{});
+    else if (a.out_dtype == GEMM_BF16) store(std::integral_constant<int, GEMM_BF16>{});
+    else store(std::integral_constant<int, GEMM_F16>{});
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -583,6 +605,40 @@ __device__ __forceinline__ void mfma16(const u32x4_t& a, const u32x4_t& b, f32x4
         c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
     else
         c = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Pack kernel: rewrites one operand as [rows][Kp] with K contiguous, rows 16-byte aligned and K
+// padded with zeros to a whole number of slabs (Kp), in caller-provided workspace.  It is what lets
+// the fast kernel run on operands that violate its conditions (odd leading dimensions, K strided,
+// ragged K): Table 1's "smem_transpose" applied ahead of the product.  A workgroup moves a tile of
+// 64 rows x 128 bytes of K through LDS: element reads along whichever axis is contiguous in the
+// source, 16-byte writes along K.
+// ------------------------------------------------------------------------------------------------
+template <typename IN>
+__global__ __launch_bounds__(256) void k4_pack(const typename IN::raw* __restrict__ src, int64_t s_r, int64_t s_k,
+                                               int64_t rows, int64_t K, int64_t Kp, typename IN::raw* __restrict__ dst,
+                                               int64_t src_batch, int64_t dst_batch)
+{
+    using raw = typename IN::raw;
+    constexpr int KE = ROW_BYTES / IN::BYTES, V = 16 / IN::BYTES, TR = 64;
+    constexpr int PITCH = KE + V;                       // elements; keeps rows 16-byte aligned, spreads banks
+    __shared__ __attribute__((aligned(16))) raw tile[TR * PITCH];
+    const int t = threadIdx.x;
+    const int64_t k0 = (int64_t)blockIdx.x * KE, r0 = (int64_t)blockIdx.y * TR;
+    src += (int64_t)blockIdx.z * src_batch;
+    dst += (int64_t)blockIdx.z * dst_batch;
+    const bool kcontig = s_k == 1;
+    for (int idx = t; idx < TR * KE; idx += 256) {
+        const int r = kcontig ? idx / KE : idx % TR, k = kcontig ? idx % KE : idx / TR;
+        const int64_t gr = r0 + r, gk = k0 + k;
+        tile[r * PITCH + k] = (gr < rows && gk < K) ? src[gr * s_r + gk * s_k] : (raw)0;
+    }
+    __syncthreads();
+    for (int idx = t; idx < TR * CHUNKS; idx += 256) {
+        const int r = idx / CHUNKS, c = idx % CHUNKS;
+        if (r0 + r < rows) *(u32x4_t*)(dst + (r0 + r) * Kp + k0 + c * V) = *(const u32x4_t*)(tile + r * PITCH + c * V);
+    }
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -39,10 +39,59 @@ static hipError_t launch_stream(const Args& a)
     return hipGetLastError();
 }
 
+static int elem_bytes(int dt) { return dt == GEMM_FP8_E4M3 ? 1 : 2; }
+
+int64_t k4_packed_k(const Args& a)
+{
+    const int64_t ke = ROW_BYTES / elem_bytes(a.in_dtype);
+    return (a.K + ke - 1) / ke * ke;
+}
+
+size_t k4_packed_workspace_bytes(const Args& a)
+{
+    return (size_t)(a.batch * (a.M + a.N) * k4_packed_k(a)) * elem_bytes(a.in_dtype);
+}
+
+// Packed path: both operands are rewritten K-contiguous, aligned and zero-padded along K in the
+// workspace ([batch][M][Kp] then [batch][N][Kp]), then the fast kernel runs on the copies.
+template <typename IN>
+static hipError_t launch_packed(const Args& a)
+{
+    using raw = typename IN::raw;
+    constexpr int KE = ROW_BYTES / IN::BYTES;
+    const int64_t Kp = k4_packed_k(a);
+    raw* pa = (raw*)a.workspace;
+    raw* pb = pa + a.batch * a.M * Kp;
+    dim3 block(256, 1, 1);
+    if (a.M > 0 && Kp > 0) {
+        dim3 ga((unsigned)(Kp / KE), (unsigned)((a.M + 63) / 64), (unsigned)a.batch);
+        hipLaunchKernelGGL(k4_pack<IN>, ga, block, 0, a.stream, (const raw*)a.A, a.a_si, a.a_sk, a.M, a.K, Kp, pa, a.stride_a, a.M * Kp);
+    }
+    if (a.N > 0 && Kp > 0) {
+        dim3 gb((unsigned)(Kp / KE), (unsigned)((a.N + 63) / 64), (unsigned)a.batch);
+        hipLaunchKernelGGL(k4_pack<IN>, gb, block, 0, a.stream, (const raw*)a.B, a.b_sj, a.b_sk, a.N, a.K, Kp, pb, a.stride_b, a.N * Kp);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    Args p = a;
+    p.A = pa; p.B = pb; p.K = Kp;
+    p.a_si = Kp; p.a_sk = 1; p.b_sj = Kp; p.b_sk = 1;
+    p.stride_a = a.M * Kp; p.stride_b = a.N * Kp;
+    return launch_fast<FastK4<IN>>(p);
+}
+
 // `path`: low byte = MfmaPath, next byte = bitmask of operands whose 16-byte loads are legal.
 hipError_t launch_k4(int path, const Args& a)
 {
     const int kind = path & 0xFF, vec_mask = (path >> 8) & 3;
+    if (kind == MFMA_PACKED) {
+        switch (a.in_dtype) {
+        case GEMM_BF16: return launch_packed<BF16>(a);
+        case GEMM_F16: return launch_packed<F16>(a);
+        case GEMM_FP8_E4M3: return launch_packed<E4M3>(a);
+        default: return hipErrorInvalidValue;
+        }
+    }
     if (kind == MFMA_SKINNY) {
         if (a.in_dtype == GEMM_BF16) return launch_stream<StreamK4<BF16>>(a);
         if (a.in_dtype == GEMM_F16) return launch_stream<StreamK4<F16>>(a);
@@ -72,7 +121,7 @@ Geometry geometry_k4(int path, const Args& a)
         using C = StreamK4<BF16>;
         return Geometry{16, C::COLS, C::TK, C::WAVES * 64, 2, C::LDS_BYTES, ((a.N + C::COLS - 1) / C::COLS) * a.batch};
     }
-    if (kind == MFMA_VEC16) {
+    if (kind == MFMA_VEC16 || kind == MFMA_PACKED) {
         using C = FastK4<BF16>;
         const int64_t g = ((a.M + C::BM - 1) / C::BM) * ((a.N + C::BN - 1) / C::BN) * a.batch;
         return Geometry{C::BM, C::BN, ROW_BYTES / es, C::T, 2, C::LDS_BYTES, g};   // stages: slabs in flight beyond the one in use

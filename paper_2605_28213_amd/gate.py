@@ -74,7 +74,7 @@ def _stats(ms: Sequence[float]) -> Dict[str, float]:
 def run_gate(variant: int, cfg: gen.Config, reference: Callable[[gen.Inputs], Reference], *,
              seeds: Iterable[int] = (0, 1, 2), warmup: int = 25, reps: int = 100, strict: bool = False,
              time_budget_s: float = 3.0, inputs_cache: Optional[Dict[int, gen.Inputs]] = None,
-             rebuild: bool = False, ledger_path: Optional[str] = None) -> dict:
+             rebuild: bool = False, lend_workspace: bool = True, ledger_path: Optional[str] = None) -> dict:
     """Run the gate for (variant, cfg) and return the ledger entry (also appended to ledger_path).
 
     `reference(inputs)` supplies the values C is compared against.  `reps` is cut down for states so
@@ -124,6 +124,13 @@ def run_gate(variant: int, cfg: gen.Config, reference: Callable[[gen.Inputs], Re
                            lda=inp.lda, ldb=inp.ldb, ldc=inp.ldc, batch=cfg.batch, stride_a=inp.stride_a,
                            stride_b=inp.stride_b, stride_c=inp.stride_c, scale_a=sa, scale_b=sb, stream=stream,
                            flags=flags)
+        # lend the scratch the state's packed path asks for (K4 on operands that break its fast path)
+        ws = None
+        if lend_workspace:
+            need = gemm.gemm_query(variant, d, dA, dB, dC).workspace_bytes
+            if need:
+                ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+                d.workspace, d.workspace_bytes = ws.data_ptr(), need
         torch.cuda.synchronize()            # uploads and the poison fill ran on another stream
         # ---- query (once) ------------------------------------------------------------------------
         if "query" not in entry:
@@ -131,7 +138,8 @@ def run_gate(variant: int, cfg: gen.Config, reference: Callable[[gen.Inputs], Re
             entry["query"] = {"status": gemm.gemm_status_string(q.status), "path": q.path,
                               "required": gemm.Query.names(q.required), "violated": gemm.Query.names(q.violated),
                               "holds": gemm.Query.names(q.holds), "tile": [q.bm, q.bn, q.bk], "threads": q.threads,
-                              "stages": q.stages, "lds_bytes": q.lds_bytes, "grid": q.grid}
+                              "stages": q.stages, "lds_bytes": q.lds_bytes, "grid": q.grid,
+                              "workspace_bytes": q.workspace_bytes, "workspace_lent": ws is not None}
             if q.status == gemm.GEMM_ERR_PRECONDITION:
                 entry["verdict"] = "refused(precondition: " + ",".join(gemm.Query.names(q.violated)) + ")"
                 return _finish(entry, ledger_path)
@@ -180,7 +188,7 @@ def run_gate(variant: int, cfg: gen.Config, reference: Callable[[gen.Inputs], Re
             med = timing["median_us"] * 1e-6
             timing["TFLOP/s"] = cfg.flops / med / 1e12
             timing["GB/s"] = cfg.algorithmic_bytes / med / 1e9
-        del dA, dB, dC
+        del dA, dB, dC, ws
     entry["correctness"] = seed_results
     entry["profile"] = timing
     entry["verdict"] = verdict

@@ -30,10 +30,10 @@ def oracle_for(inp):
                        scale_a=inp.scale_a, scale_b=inp.scale_b)
 
 
-def check(variant, inp, ref=None, out_dtype=None):
+def check(variant, inp, ref=None, out_dtype=None, lend_workspace=False):
     c = inp.cfg
     C_ref, D = ref if ref is not None else oracle_for(inp)
-    rc, C, _ = util.run_config(variant, inp, out_dtype=out_dtype)
+    rc, C, _ = util.run_config(variant, inp, out_dtype=out_dtype, lend_workspace=lend_workspace)
     assert rc == gemm.GEMM_OK, gemm.gemm_status_string(rc)
     err = util.norm_err(C[:, :, : c.N], C_ref, D)
     assert err <= util.TOL[c.in_dtype], f"{gemm.gemm_variant_name(variant)} on {c.name}: normalised error {err:.3e}"
@@ -192,3 +192,40 @@ def test_launch_on_a_side_stream():
     s.synchronize()
     C = util.decode_out(dC, c.out_dtype).reshape(1, c.M, c.N)
     assert util.norm_err(C, C_ref, D) <= util.TOL[c.in_dtype]
+
+
+@pytest.mark.parametrize("dtype", [gen.BF16, gen.F16, gen.E4M3])
+@pytest.mark.parametrize("la,lb", [(ROW, ROW), (ROW, COL), (COL, ROW), (COL, COL)])
+def test_packed_path_with_lent_workspace(dtype, la, lb):
+    """K4 with scratch lent: operands that violate the fast path's conditions (odd leading dimensions,
+    K strided, ragged K) are packed and multiplied by the fast kernel; the query names that path."""
+    M, N, K = 300, 270, 203
+    cfg = gen.Config("packed", M, N, K, dtype, gen.BF16 if dtype == gen.E4M3 else dtype, la, lb, "uniform", batch=2,
+                     lda=(K if la == ROW else M) + 3, ldb=(N if lb == ROW else K) + 5, ldc=N + 1)
+    inp = gen.make_inputs(cfg, 11)
+    ref = oracle_for(inp)
+    d = gemm.make_desc(M, N, K, dtype, cfg.out_dtype, la, lb, lda=inp.lda, ldb=inp.ldb, ldc=inp.ldc, batch=2)
+    q = gemm.gemm_query(4, d)
+    assert q.workspace_bytes > 0 and q.path.startswith("mfma32-") and "packed" not in q.path
+    d.workspace, d.workspace_bytes = 256, q.workspace_bytes          # any non-null address: query only
+    assert gemm.gemm_query(4, d).path == "mfma32-packed+direct-to-lds"
+    check(4, inp, ref, lend_workspace=True)
+    check(4, inp, ref, out_dtype=gen.F32, lend_workspace=True)
+    check(4, inp, ref)                                               # and the masked path without scratch
+
+
+def test_lent_workspace_too_small_or_misaligned_is_refused():
+    cfg = gen.CONFIGS["C3_small"]
+    inp = gen.make_inputs(cfg, 0)
+    dA, dB = util.dev(inp.A), util.dev(inp.B)
+    dC = util.out_buffer(cfg.M * inp.ldc, cfg.out_dtype)
+    d = gemm.make_desc(cfg.M, cfg.N, cfg.K, cfg.in_dtype, cfg.out_dtype, cfg.layout_a, cfg.layout_b)
+    need = gemm.gemm_query(4, d).workspace_bytes
+    ws = torch.empty(need + 32, dtype=torch.uint8, device="cuda")
+    before = dC.clone()
+    d.workspace, d.workspace_bytes = ws.data_ptr(), need - 1
+    assert gemm.gemm_run_ex(4, d, dA, dB, dC) == gemm.GEMM_ERR_WORKSPACE
+    d.workspace, d.workspace_bytes = ws.data_ptr() + 2, need
+    assert gemm.gemm_run_ex(4, d, dA, dB, dC) == gemm.GEMM_ERR_WORKSPACE
+    torch.cuda.synchronize()
+    assert torch.equal(before, dC), "a refused call must leave C untouched"

@@ -52,8 +52,9 @@ def norm_err(C: np.ndarray, C_ref: np.ndarray, D: np.ndarray) -> float:
     return float(np.max(num[~zero] / D[~zero]))
 
 
-def run_config(variant: int, inp: gen.Inputs, *, out_dtype=None, flags: int = 0, dA=None, dB=None):
-    """Launch one variant on one generated workload; returns (status, C as (batch, M, ldc) fp64, raw buffer)."""
+def run_config(variant: int, inp: gen.Inputs, *, out_dtype=None, flags: int = 0, dA=None, dB=None, lend_workspace=False):
+    """Launch one variant on one generated workload; returns (status, C as (batch, M, ldc) fp64, raw buffer).
+    With lend_workspace the scratch gemm_query asks for is allocated and lent (K4's packed path)."""
     cfg = inp.cfg
     od = cfg.out_dtype if out_dtype is None else out_dtype
     dA = dev(inp.A) if dA is None else dA
@@ -65,6 +66,12 @@ def run_config(variant: int, inp: gen.Inputs, *, out_dtype=None, flags: int = 0,
                        lda=inp.lda, ldb=inp.ldb, ldc=inp.ldc, batch=cfg.batch,
                        stride_a=inp.stride_a, stride_b=inp.stride_b, stride_c=inp.stride_c,
                        scale_a=sa, scale_b=sb, flags=flags)
+    ws = None
+    if lend_workspace:
+        need = gemm.gemm_query(variant, d, dA, dB, dC).workspace_bytes
+        if need:
+            ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+            d.workspace, d.workspace_bytes = ws.data_ptr(), need
     rc = gemm.gemm_run_ex(variant, d, dA, dB, dC)
     torch.cuda.synchronize()
     C = decode_out(dC, od)
