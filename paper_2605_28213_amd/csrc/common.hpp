@@ -85,6 +85,8 @@ enum MfmaPath { MFMA_ELEMENTWISE = 0, MFMA_VEC16 = 1, MFMA_SKINNY = 2, MFMA_PACK
 // Workspace of the packed K4 path: both operands rewritten as [rows][Kp], Kp = K rounded up to a slab.
 int64_t k4_packed_k(const Args& a);
 size_t k4_packed_workspace_bytes(const Args& a);
+// True when the fast kernel's launcher hands a thin remainder of rows (M % 256 in 1..16) to the streaming kernel.
+bool k4_splits_m_tail(const Args& a);
 
 hipError_t launch_k0(const Args& a);
 hipError_t launch_valu_tiled(int variant, int path, const Args& a);

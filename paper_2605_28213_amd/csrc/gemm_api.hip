@@ -160,11 +160,11 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
             required &= ~(uint32_t)GEMM_COND_TILE_DIV_K;
         } else if (va && vb && kdiv && rows_fit) {
             p.path = MFMA_VEC16 | (3 << 8);
-            path = "mfma32-direct-to-lds";
+            path = k4_splits_m_tail(a) ? "mfma32-direct-to-lds+stream(M-tail)" : "mfma32-direct-to-lds";
         } else if (can_pack && d->workspace != nullptr) {
             // the caller lent scratch: repair the violated conditions by packing, then run the fast kernel
             p.path = MFMA_PACKED;
-            path = "mfma32-packed+direct-to-lds";
+            path = k4_splits_m_tail(a) ? "mfma32-packed+direct-to-lds+stream(M-tail)" : "mfma32-packed+direct-to-lds";
             pack_bytes = k4_packed_workspace_bytes(a);
         } else {
             if (can_pack) pack_bytes = k4_packed_workspace_bytes(a);   // what lending scratch would buy

@@ -39,6 +39,37 @@ static hipError_t launch_stream(const Args& a)
     return hipGetLastError();
 }
 
+// A thin remainder of rows (1..16 past the last whole 256-row tile) would cost a whole extra row of
+// workgroup tiles, on a large square-ish problem a second round of the machine for a few rows.  It
+// is split off and handed to the streaming kernel, which reads B once more but finishes in the time
+// of that read.  Applies to 2-byte types (the streaming kernel's) on operands the fast kernel accepts.
+bool k4_splits_m_tail(const Args& a)
+{
+    const int64_t rem = a.M % 256;
+    return a.in_dtype != GEMM_FP8_E4M3 && a.M > 256 && rem >= 1 && rem <= 16;
+}
+
+template <typename IN>
+static hipError_t launch_fast_split(const Args& a)
+{
+    if constexpr (IN::BYTES == 2) {
+        if (k4_splits_m_tail(a)) {
+            const int64_t rem = a.M % 256, top_rows = a.M - rem;
+            const int eo = a.out_dtype == GEMM_F32 ? 4 : 2;
+            Args top = a;
+            top.M = top_rows;
+            hipError_t e = launch_fast<FastK4<IN>>(top);
+            if (e != hipSuccess) return e;
+            Args bot = a;
+            bot.M = rem;
+            bot.A = (const char*)a.A + top_rows * a.a_si * IN::BYTES;
+            bot.C = (char*)a.C + top_rows * a.ldc * eo;
+            return launch_stream<StreamK4<IN>>(bot);
+        }
+    }
+    return launch_fast<FastK4<IN>>(a);
+}
+
 static int elem_bytes(int dt) { return dt == GEMM_FP8_E4M3 ? 1 : 2; }
 
 int64_t k4_packed_k(const Args& a)
@@ -77,7 +108,7 @@ static hipError_t launch_packed(const Args& a)
     p.A = pa; p.B = pb; p.K = Kp;
     p.a_si = Kp; p.a_sk = 1; p.b_sj = Kp; p.b_sk = 1;
     p.stride_a = a.M * Kp; p.stride_b = a.N * Kp;
-    return launch_fast<FastK4<IN>>(p);
+    return launch_fast_split<IN>(p);
 }
 
 // `path`: low byte = MfmaPath, next byte = bitmask of operands whose 16-byte loads are legal.
@@ -99,9 +130,9 @@ hipError_t launch_k4(int path, const Args& a)
     }
     if (kind == MFMA_VEC16) {
         switch (a.in_dtype) {
-        case GEMM_BF16: return launch_fast<FastK4<BF16>>(a);
-        case GEMM_F16: return launch_fast<FastK4<F16>>(a);
-        case GEMM_FP8_E4M3: return launch_fast<FastK4<E4M3>>(a);
+        case GEMM_BF16: return launch_fast_split<BF16>(a);
+        case GEMM_F16: return launch_fast_split<F16>(a);
+        case GEMM_FP8_E4M3: return launch_fast_split<E4M3>(a);
         default: return hipErrorInvalidValue;
         }
     }

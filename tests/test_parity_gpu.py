@@ -208,7 +208,7 @@ def test_packed_path_with_lent_workspace(dtype, la, lb):
     q = gemm.gemm_query(4, d)
     assert q.workspace_bytes > 0 and q.path.startswith("mfma32-") and "packed" not in q.path
     d.workspace, d.workspace_bytes = 256, q.workspace_bytes          # any non-null address: query only
-    assert gemm.gemm_query(4, d).path == "mfma32-packed+direct-to-lds"
+    assert gemm.gemm_query(4, d).path.startswith("mfma32-packed+direct-to-lds")
     check(4, inp, ref, lend_workspace=True)
     check(4, inp, ref, out_dtype=gen.F32, lend_workspace=True)
     check(4, inp, ref)                                               # and the masked path without scratch
@@ -229,3 +229,22 @@ def test_lent_workspace_too_small_or_misaligned_is_refused():
     assert gemm.gemm_run_ex(4, d, dA, dB, dC) == gemm.GEMM_ERR_WORKSPACE
     torch.cuda.synchronize()
     assert torch.equal(before, dC), "a refused call must leave C untouched"
+
+
+@pytest.mark.parametrize("dtype", [gen.BF16, gen.F16, gen.E4M3])
+@pytest.mark.parametrize("M", [256 + 3, 512 + 16, 256 + 17])
+def test_thin_row_remainder_goes_to_the_streaming_kernel(dtype, M):
+    """M a few rows past a whole number of 256-row tiles: the remainder (1..16 rows, 2-byte types) is
+    multiplied by the streaming kernel instead of a whole extra row of tiles; both parts must agree
+    with the oracle, in the aligned fast path and in the packed path."""
+    N, K = 300, 256
+    out = gen.BF16 if dtype == gen.E4M3 else dtype
+    cfg = gen.Config("mtail", M, N, K, dtype, out, ROW, COL, "normal", rsqrt_k=True, batch=2)
+    inp = gen.make_inputs(cfg, 6)
+    ref = oracle_for(inp)
+    d = gemm.make_desc(M, N, K, dtype, out, ROW, COL, batch=2)
+    split = dtype != gen.E4M3 and 1 <= M % 256 <= 16
+    assert gemm.gemm_query(4, d).path == ("mfma32-direct-to-lds+stream(M-tail)" if split else "mfma32-direct-to-lds")
+    check(4, inp, ref)
+    ragged = gen.Config("mtail_packed", M, N, K - 5, dtype, out, ROW, ROW, "normal", rsqrt_k=True)
+    check(4, gen.make_inputs(ragged, 7), lend_workspace=True)
