@@ -136,6 +136,50 @@ def main():
             lineage[gemm.gemm_variant_name(v)] = {"median_us": 1e3 * m, "TFLOP/s": cfg.flops / (m * 1e-3) / 1e12,
                                                   "path": gemm.gemm_query(v, d, *sets[0]).path, "launches": n}
         out["lineage"] = lineage
+    if not args.no_extras:
+        # ---- measured ceilings on this GPU, same session ------------------------------------------
+        # matrix pipe: register-resident loop of the expert kernel's instruction on the headline
+        # workload's own operand values (the clock the power limit allows depends on the data)
+        def event_times(fn, n, warm):
+            for _ in range(warm):
+                fn()
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+            for a, b in ev:
+                a.record(stream)
+                fn()
+                b.record(stream)
+            torch.cuda.synchronize()
+            return sorted(a.elapsed_time(b) for a, b in ev)
+
+        wgs, iters = 1024, 400
+        need = gemm.gemm_probe_mfma_operand_bytes(gemm.GEMM_BF16, wgs)
+        sink = torch.zeros(wgs * 256, dtype=torch.float32, device="cuda")
+        A0 = sets[0][0]
+        assert A0.numel() >= need
+        flops_box = []
+
+        def mfma_probe():
+            rc, fl = gemm.gemm_probe_mfma(gemm.GEMM_BF16, A0, need, wgs, iters, sink, sink.numel() * 4, stream)
+            assert rc == gemm.GEMM_OK
+            flops_box.append(fl)
+        tm = event_times(mfma_probe, 20, 10)
+        mf = flops_box[-1] / (tm[len(tm) // 2] * 1e-3) / 1e12
+        big = torch.empty(512 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+        s32 = torch.zeros(4, dtype=torch.int32, device="cuda")
+        torch.cuda.synchronize()
+        tr = event_times(lambda: gemm.gemm_probe_stream_read(big, big.numel(), s32, stream), 20, 5)
+        tc = event_times(lambda: gemm.gemm_probe_copy(dst, big, dst.numel(), stream), 20, 5)
+        rd = big.numel() / (tr[len(tr) // 2] * 1e-3) / 1e9
+        cp = 2 * dst.numel() / (tc[len(tc) // 2] * 1e-3) / 1e9
+        out["ceilings"] = {
+            "mfma_bf16_on_headline_operands": {"TFLOP/s": mf, "frac_of_peak": mf / PEAK["mfma_bf16"],
+                                               "what": f"{wgs} workgroups x 4 waves x {iters} x 32 v_mfma_f32_32x32x16_bf16, operands from A"},
+            "hbm_stream_read": {"GB/s": rd, "frac_of_peak": rd / PEAK["hbm_GBs"], "what": "512 MiB, 16-byte loads"},
+            "hbm_copy": {"GB/s": cp, "frac_of_peak": cp / PEAK["hbm_GBs"], "what": "256 MiB read + 256 MiB written"},
+        }
+        out["roofline"]["frac_of_measured_mfma_ceiling"] = out["roofline"]["achieved"] / mf
+        del big, dst, sink
     del sets, keep
     torch.cuda.empty_cache()
 
@@ -158,6 +202,8 @@ def main():
                      "GB/s": c.algorithmic_bytes / (ss["mean_us"] * 1e-6) / 1e9, "roofline": rl}
             if name == "C5":
                 entry["roofline_hbm"] = roofline_for(c, ss["mean_us"], "hbm")
+            if name == "C4" and "ceilings" in out:
+                rl["frac_of_measured_stream_read"] = rl["achieved"] / out["ceilings"]["hbm_stream_read"]["GB/s"]
             shapes[name] = entry
             del s2, keep2
             torch.cuda.empty_cache()

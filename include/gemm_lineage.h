@@ -147,6 +147,27 @@ int gemm_query(int variant, const gemm_desc_t *d, const void *A, const void *B, 
 /* gemm_default_desc: fills *d with the defaults gemm_run uses for (M, N, K, dtype). */
 int gemm_default_desc(gemm_desc_t *d, int64_t M, int64_t N, int64_t K, int dtype);
 
+/*
+ * Measurement probes (not part of the lineage, never used by gemm_run*).  The gate's profile leg
+ * (Sec. 3.1) reads a kernel's time against a ceiling; these three plain kernels measure, on the GPU at
+ * hand, the ceilings the published peaks only bound from above.  All pointers are device pointers,
+ * 16-byte aligned; byte counts are multiples of 16; launches are asynchronous on `stream`.
+ *   gemm_probe_copy         dst[0..bytes) = src[0..bytes): reads and writes exactly `bytes` each; the
+ *                           unit for calibrating HBM byte counters
+ *   gemm_probe_stream_read  reads src[0..bytes) once with 16-byte loads; sink: >= 4 bytes
+ *   gemm_probe_mfma         `workgroups` x 4 waves each issue iters x 32 matrix instructions of the
+ *                           expert kernel (bf16/fp16: 32x32x16; e4m3: scaled 32x32x64) on fragments
+ *                           read once from `operands` (>= gemm_probe_mfma_operand_bytes bytes, any
+ *                           finite values of the dtype); *flops receives the flop count of the launch;
+ *                           sink: workgroups*256 floats.  Errors: GEMM_ERR_BAD_ARG,
+ *                           GEMM_ERR_UNSUPPORTED_DTYPE (fp32), GEMM_ERR_LAUNCH.
+ */
+int gemm_probe_copy(void *dst, const void *src, size_t bytes, void *stream);
+int gemm_probe_stream_read(const void *src, size_t bytes, void *sink, void *stream);
+size_t gemm_probe_mfma_operand_bytes(int dtype, int workgroups);
+int gemm_probe_mfma(int dtype, const void *operands, size_t operand_bytes, int workgroups, int iters,
+                    void *sink, size_t sink_bytes, double *flops, void *stream);
+
 const char *gemm_status_string(int status);
 const char *gemm_variant_name(int variant);
 const char *gemm_variant_intent(int variant); /* Table 1 intent the transition into this state adds */

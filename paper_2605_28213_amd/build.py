@@ -15,7 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libgemm_lineage.so")
-SOURCES = ["gemm_api.hip", "k0_naive.hip", "k123_valu_tiled.hip", "k4_mfma.hip"]
+SOURCES = ["gemm_api.hip", "k0_naive.hip", "k123_valu_tiled.hip", "k4_mfma.hip", "probes.hip"]
 HEADERS = [os.path.join(CSRC, "common.hpp"), os.path.join(CSRC, "k4_kernels.hpp"),
            os.path.join(os.path.dirname(HERE), "include", "gemm_lineage.h")]
 # packed fp32 VALU forms (v_pk_*_f32) are switched off: the compiler must not form them for this target

@@ -78,6 +78,15 @@ def lib() -> ctypes.CDLL:
         L.gemm_cond_name.argtypes = [ctypes.c_uint32]
         L.gemm_variant_count.restype = ci
         L.gemm_abi_version.restype = ci
+        st = ctypes.c_size_t
+        L.gemm_probe_copy.restype = ci
+        L.gemm_probe_copy.argtypes = [vp, vp, st, vp]
+        L.gemm_probe_stream_read.restype = ci
+        L.gemm_probe_stream_read.argtypes = [vp, st, vp, vp]
+        L.gemm_probe_mfma_operand_bytes.restype = st
+        L.gemm_probe_mfma_operand_bytes.argtypes = [ci, ci]
+        L.gemm_probe_mfma.restype = ci
+        L.gemm_probe_mfma.argtypes = [ci, vp, st, ci, ci, vp, st, ctypes.POINTER(ctypes.c_double), vp]
         _lib = L
     return _lib
 
@@ -179,3 +188,28 @@ def gemm_variant_count() -> int:
 
 def gemm_abi_version() -> int:
     return int(lib().gemm_abi_version())
+
+
+def _stream_addr(stream: Any) -> Optional[int]:
+    return int(stream.cuda_stream) if hasattr(stream, "cuda_stream") else _addr(stream)
+
+
+def gemm_probe_copy(dst: Any, src: Any, nbytes: int, stream: Any = None) -> int:
+    return int(lib().gemm_probe_copy(_addr(dst), _addr(src), nbytes, _stream_addr(stream)))
+
+
+def gemm_probe_stream_read(src: Any, nbytes: int, sink: Any, stream: Any = None) -> int:
+    return int(lib().gemm_probe_stream_read(_addr(src), nbytes, _addr(sink), _stream_addr(stream)))
+
+
+def gemm_probe_mfma_operand_bytes(dtype: int, workgroups: int) -> int:
+    return int(lib().gemm_probe_mfma_operand_bytes(dtype, workgroups))
+
+
+def gemm_probe_mfma(dtype: int, operands: Any, operand_bytes: int, workgroups: int, iters: int, sink: Any,
+                    sink_bytes: int, stream: Any = None):
+    """Returns (status, flops of the launch)."""
+    fl = ctypes.c_double(0.0)
+    rc = int(lib().gemm_probe_mfma(dtype, _addr(operands), operand_bytes, workgroups, iters, _addr(sink), sink_bytes,
+                                   ctypes.byref(fl), _stream_addr(stream)))
+    return rc, fl.value
