@@ -1,0 +1,79 @@
+"""Code-generation guards for the expert kernels (host only: hipcc cross-compiles without a GPU).
+
+The hot loops of the K4 kernels rely on properties no functional test can see: accumulators that
+never leave their registers, buffer resources held in scalar registers (a resource the compiler
+believes to be lane-dependent is wrapped in a readfirstlane loop around every load), no scratch.
+This test compiles the translation unit to assembly and checks the steady-state loop of the fast
+kernel and the register budget of every K4 kernel.
+"""
+import os
+import re
+import subprocess
+
+import pytest
+
+from paper_2605_28213_amd import build as gl_build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = os.path.join(ROOT, "paper_2605_28213_amd", "csrc", "k4_mfma.hip")
+
+
+@pytest.fixture(scope="module")
+def asm(tmp_path_factory):
+    out = tmp_path_factory.mktemp("asm") / "k4.s"
+    flags = [f for f in gl_build.FLAGS if f != "-fPIC"]
+    r = subprocess.run(["hipcc", *flags, "-S", "--cuda-device-only", SRC, "-o", str(out)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr[-2000:]
+    return out.read_text()
+
+
+def kernel_body(asm, mangled_prefix):
+    m = re.search(r"^(%s\w*):[^\n]*\n(.*?)s_endpgm" % re.escape(mangled_prefix), asm, flags=re.S | re.M)
+    assert m, f"kernel {mangled_prefix} not found"
+    return m.group(2)
+
+
+def metadata(asm, mangled_prefix):
+    for block in asm.split("  - .agpr_count:")[1:]:
+        name = re.search(r"\.name:\s+(\S+)", block).group(1)
+        if name.startswith(mangled_prefix):
+            get = lambda k: int(re.search(r"\.%s:\s+(\d+)" % k, block).group(1))
+            return {"agpr": int(block.split()[0]), "vgpr": get("vgpr_count"), "vgpr_spill": get("vgpr_spill_count"),
+                    "lds": get("group_segment_fixed_size"), "scratch": get("private_segment_fixed_size")}
+    raise AssertionError(mangled_prefix)
+
+
+def first_inner_loop(body):
+    lines = body.split("\n")
+    start = next(i for i, l in enumerate(lines) if "Inner Loop Header" in l)
+    end = next(i for i in range(start, len(lines)) if re.match(r"\s+s_cbranch_(vccz|vccnz|scc0|scc1)\s", lines[i]))
+    return [l.split()[0] for l in lines[start:end] if l.strip() and not l.strip().startswith((";", "."))]
+
+
+@pytest.mark.parametrize("dtype,mfma,per_slab", [("4BF16", "v_mfma_f32_32x32x16_bf16", 64), ("3F16", "v_mfma_f32_32x32x16_f16", 64),
+                                                 ("4E4M3", "v_mfma_scale_f32_32x32x64_f8f6f4", 32)])
+def test_fast_kernel_steady_state_loop(asm, dtype, mfma, per_slab):
+    prefix = "_ZN2gl12k4_mfma_fastINS_7FastCfgINS_" + dtype
+    ops = first_inner_loop(kernel_body(asm, prefix))
+    count = lambda name: sum(o == name for o in ops)
+    # five slabs per trip round the LDS ring; 16 direct loads per slab; fragment reads are 16-byte
+    assert count(mfma) == 5 * per_slab
+    assert count("buffer_load_dwordx4") == 5 * 16
+    assert count("ds_read_b128") == 5 * 32
+    assert count("s_barrier") == 5
+    # nothing but scalar bookkeeping besides: no accumulator moves, no lane-dependent resource
+    # (readfirstlane loop), no scratch, no LDS writes, no plain VALU work
+    for bad in ("v_accvgpr_read_b32", "v_accvgpr_write_b32", "v_readfirstlane_b32", "s_and_saveexec_b64",
+                "scratch_load_dword", "scratch_store_dword", "v_mov_b32_e32", "ds_write_b128"):
+        assert count(bad) == 0, bad
+    meta = metadata(asm, prefix)
+    assert meta["agpr"] == 256 and meta["lds"] == 160 * 1024
+    assert meta["vgpr_spill"] <= 32 and meta["scratch"] <= 160      # a few values parked outside the loop at most
+
+
+def test_stream_kernel_register_budget(asm):
+    for dtype in ("4BF16", "3F16"):
+        meta = metadata(asm, "_ZN2gl9k4_streamINS_9StreamCfgINS_" + dtype)
+        assert meta["vgpr_spill"] == 0 and meta["scratch"] == 0
+        assert meta["vgpr"] <= 256, "two waves per SIMD need at most 256 registers each"
+        assert meta["lds"] == 64 * 1024, "two workgroups per CU"
