@@ -158,8 +158,12 @@ __global__ __launch_bounds__(CFG::THREADS) void valu_tiled(Args a, int vec_mask)
 
     float ra[NRA], rb[NRB];
 
+    // Pipelined state: the k loop is unrolled by 2 only.  Fully unrolled, with the next slab's global
+    // loads in flight, the scheduler gathers all BK steps' LDS reads at the top of the block (~400
+    // registers, one wave per SIMD); two steps keep the reads next to their FMAs.
+    constexpr int KUNROLL = CFG::DBUF ? 2 : BK;
     auto compute = [&](int buf) {
-#pragma unroll
+#pragma unroll KUNROLL
         for (int kk = 0; kk < BK; ++kk) {
             float av[TM], bv[TN];
 #pragma unroll
