@@ -21,6 +21,22 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+# HBM-side bytes per launch of the headline kernel from the FETCH_SIZE / WRITE_SIZE counter runs
+# summarised in profiles/k4_mfma_fast_bf16_C2.md (scaled by the copy probe's factor).  The figure
+# belongs to one version of the kernel sources: when their digest differs it is reported as null.
+TRAFFIC_C2 = {"bytes": 1.801e9, "sources_sha256": "61bd9205f6979c928a93ad13e4c11a807de7ed8afe18d40c3570c21da81f3191"}
+KERNEL_SOURCES = ["csrc/common.hpp", "csrc/k4_kernels.hpp", "csrc/k4_mfma.hip"]
+
+
+def kernel_sources_digest():
+    import hashlib
+    h = hashlib.sha256()
+    for rel in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2605_28213_amd", rel), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
 PEAK = {"mfma_bf16": 2500.0, "mfma_f16": 2500.0, "mfma_fp8": 5000.0, "valu_f32": 157.3, "hbm_GBs": 8000.0}
 
 
@@ -125,6 +141,8 @@ def main():
         "launch_us": st,
         "roofline": roofline_for(cfg, st["mean_us"], "mfma"),
     }
+    if kernel_sources_digest() == TRAFFIC_C2["sources_sha256"]:
+        out["roofline"]["traffic"] = TRAFFIC_C2["bytes"]
 
     if not args.no_extras:
         # ---- the lineage on the headline workload (few launches for the slow early states) ---------
