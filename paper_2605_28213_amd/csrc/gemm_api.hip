@@ -146,9 +146,10 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
         const bool va = (holds & (vecA | GEMM_COND_K_CONTIG_A)) == (vecA | GEMM_COND_K_CONTIG_A);
         const bool vb = (holds & (vecB | GEMM_COND_K_CONTIG_B)) == (vecB | GEMM_COND_K_CONTIG_B);
         const int64_t kvec = 16 / es;
-        // the streaming kernel addresses a strip of columns with 32-bit byte offsets: ldb is bounded
+        // the streaming kernel addresses a strip of columns and the rows of A with 32-bit byte offsets
         const bool skinny = (holds & GEMM_COND_SMALL_M) && va && vb && d->K % kvec == 0 && d->K > 0 &&
-                            (d->in_dtype == GEMM_BF16 || d->in_dtype == GEMM_F16) && d->ldb <= ((int64_t)1 << 24);
+                            (d->in_dtype == GEMM_BF16 || d->in_dtype == GEMM_F16) && d->ldb <= ((int64_t)1 << 24) &&
+                            d->lda <= ((int64_t)1 << 24);
         const bool kdiv = d->K % (128 / es) == 0;   // whole 128-byte slabs: the direct-to-LDS kernel masks nothing along K
         // that kernel addresses a 256-row tile with 32-bit byte offsets: rows are bounded to 4 MiB
         const bool rows_fit = d->lda * es <= ((int64_t)1 << 22) && d->ldb * es <= ((int64_t)1 << 22);

@@ -598,15 +598,6 @@ __global__ __launch_bounds__(WM* WN * 64) void k4_mfma_masked(Args a, int vec_ma
     store_tiles<TMI, TNI>(a, b, acc, sa.r0 + wm * (BM / WM), sb.r0 + wn * (BN / WN), lane);
 }
 
-template <typename IN>
-__device__ __forceinline__ void mfma16(const u32x4_t& a, const u32x4_t& b, f32x4_t& c)
-{
-    if constexpr (IN::ID == GEMM_BF16)
-        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
-    else
-        c = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
-}
-
 // ------------------------------------------------------------------------------------------------
 // Pack kernel: rewrites one operand as [rows][Kp] with K contiguous, rows 16-byte aligned and K
 // padded with zeros to a whole number of slabs (Kp), in caller-provided workspace.  It is what lets
@@ -646,30 +637,43 @@ __global__ __launch_bounds__(256) void k4_pack(const typename IN::raw* __restric
 // HBM.  A workgroup owns a strip of 16*NB columns of C; its WAVES waves split K, partial sums meet
 // in LDS at the end.  Needs: A row-major, B column-major, 16-byte aligned, K a multiple of 8.
 //
-// The B operand of v_mfma_f32_16x16x32 wants, per instruction, 16 columns x 64 bytes of K; fetched
-// that way every wave instruction opens 16 separate 64-byte streams 2*ldb bytes apart, and HBM
+// The operands of v_mfma_f32_16x16x32 want, per instruction, 16 rows x 64 bytes of K; fetched that
+// way every wave instruction opens 16 separate 64-byte streams a leading dimension apart, and HBM
 // delivers about half of what it gives to contiguous reads.  Here a wave instead fetches, per load
-// instruction, 64/LPC columns' worth of LPC*16 contiguous bytes (LPC = lanes per column = TK/8),
-// parks the registers in a wave-private LDS tile of NB*16 rows (one per column) x TK*2 bytes, and
-// reads the MFMA operand layout back from there.  Chunk q (16 bytes) of row c is kept at chunk
-// position q ^ (c % 16): writes (16 consecutive q of one row) and operand reads (16 rows at one q)
-// are both bank-conflict free.  The tile is private to the wave and LDS serves a wave's requests in
-// order, so the main loop has no barrier: waves only meet for the final sum over the K split.
+// instruction, 64/LPC rows' worth of LPC*16 contiguous bytes (LPC = lanes per row = TK/8), parks
+// the registers of one group of 16 rows (16 columns of B, or the 16 rows of A) in a wave-private LDS
+// tile of 16 rows x TK*2 bytes, and reads the MFMA operand layout back from there.  Chunk q (16
+// bytes) of row c is kept at chunk position q ^ c: writes (LPC consecutive q of a row) and operand
+// reads (16 rows at one q) are both bank-conflict free.  The tiles are private to the wave and LDS
+// serves a wave's requests in order, so the main loop has no barrier: waves only meet for the final
+// sum over the K split.
 //
-// Per wave and tile: NB*TK/32 loads of B stay in flight in registers while the previous tile is
-// multiplied; A (M <= 16 rows, cache resident) is fetched straight into the other MFMA operand.
+// Per wave and K tile: the A group and the NB column groups are parked and multiplied one after the
+// other (LDS holds A and one column group: 2 * 16 * TK * 2 bytes per wave); as soon as a group's
+// registers are parked its loads for the next K tile are issued, so (NB+1)*TK/32 loads stay in
+// flight per lane while the MFMAs of the current tile run.
 // ------------------------------------------------------------------------------------------------
+template <typename IN>
+__device__ __forceinline__ void mfma16(const u32x4_t& a, const u32x4_t& b, f32x4_t& c)
+{
+    if constexpr (IN::ID == GEMM_BF16)
+        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+    else
+        c = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+}
+
 template <typename IN, int WAVES_, int NB_, int TK_>
 struct StreamCfg {
     using In = IN;
     static constexpr int WAVES = WAVES_, NB = NB_, TK = TK_, COLS = 16 * NB_;
-    static constexpr int LPC = TK / 8;                     // lanes (16-byte chunks) per column per tile
-    static constexpr int CPL = 64 / LPC;                   // columns covered by one load instruction
-    static constexpr int NLD = COLS / CPL;                 // B loads per tile per lane
+    static constexpr int LPC = TK / 8;                     // lanes (16-byte chunks) per row per tile
+    static constexpr int CPL = 64 / LPC;                   // rows covered by one load instruction
+    static constexpr int GLD = 16 / CPL;                   // loads per group of 16 rows per lane
     static constexpr int KS = TK / 32;                     // MFMA k-steps per tile
-    static constexpr int TILE_BYTES = COLS * TK * 2;
+    static constexpr int GROUP_BYTES = 16 * TK * 2;
+    static constexpr int TILE_BYTES = 2 * GROUP_BYTES;     // the A group and one group of B columns
     static constexpr int LDS_BYTES = WAVES * TILE_BYTES;
-    static_assert(LPC >= 16 && LPC <= 64 && (LPC & (LPC - 1)) == 0, "a column's run is 16..64 lanes wide");
+    static_assert(LPC >= 16 && LPC <= 64 && (LPC & (LPC - 1)) == 0, "a row's run is 16..64 lanes wide");
     static_assert(WAVES * 16 * (COLS + 1) * 4 <= LDS_BYTES, "the K-split partial sums reuse the tiles");
 };
 
@@ -678,7 +682,7 @@ __global__ __launch_bounds__(CFG::WAVES * 64) void k4_stream(Args a)
 {
     using IN = typename CFG::In;
     constexpr int WAVES = CFG::WAVES, NB = CFG::NB, TK = CFG::TK, COLS = CFG::COLS;
-    constexpr int LPC = CFG::LPC, CPL = CFG::CPL, NLD = CFG::NLD, KS = CFG::KS;
+    constexpr int LPC = CFG::LPC, CPL = CFG::CPL, GLD = CFG::GLD, KS = CFG::KS;
     constexpr int ROWB = TK * 2;                            // bytes per LDS row
     __shared__ __attribute__((aligned(16))) char lds[CFG::LDS_BYTES];
     const int t = threadIdx.x, lane = t & 63;
@@ -688,99 +692,120 @@ __global__ __launch_bounds__(CFG::WAVES * 64) void k4_stream(Args a)
     const int64_t j0 = (int64_t)blockIdx.x * COLS;
     const uint16_t* A = (const uint16_t*)a.A + b * a.stride_a;
     const uint16_t* B = (const uint16_t*)a.B + b * a.stride_b;
-    char* tile = lds + wave * CFG::TILE_BYTES;
+    char* tile_a = lds + wave * CFG::TILE_BYTES;
+    char* tile_b = tile_a + CFG::GROUP_BYTES;
 
-    // K is cut into WAVES contiguous ranges, each a whole number of 32-element MFMA steps
-    const int64_t ksteps = (a.K + 31) / 32;
-    const int64_t per = (ksteps + WAVES - 1) / WAVES;
-    const int64_t kbeg = wave * per * 32;
-    const int64_t kend = (kbeg + per * 32 < a.K) ? kbeg + per * 32 : a.K;
+    // K tiles are dealt to the waves in turn (wave w takes tiles w, w+WAVES, ...): the waves of a
+    // workgroup advance side by side, so that together they read WAVES*TK*2 contiguous bytes of every
+    // column at a time, which keeps HBM pages open longer than WAVES far-apart runs would.
+    const int64_t kend = a.K;
+    constexpr int64_t KSTRIDE = (int64_t)WAVES * TK;
 
-    // load side: lane fetches chunk lc of column (n*CPL + lcol) of the strip; columns past N are
-    // clamped (their sums are never stored)
-    // (the host has checked that a strip's extent, COLS * ldb elements, fits 32-bit byte offsets)
-    const int lcol = lane / LPC, lc = lane % LPC;
-    const char* Bs = (const char*)(B + j0 * a.b_sj);       // wave-uniform base of the strip
-    uint32_t bo[NLD];
-    int wr[NLD];
+    // load side: lane fetches chunk lc of row (n*CPL + lrow) of a group.  Rows of A past M and columns
+    // past N are clamped (their sums are never stored).  Offsets are 32-bit from wave-uniform bases
+    // (the host has checked that a strip's extent, COLS * ldb elements, fits).
+    const int lrow = lane / LPC, lc = lane % LPC;
+    const char* Bs = (const char*)(B + j0 * a.b_sj);
+    const char* As = (const char*)A;
+    uint32_t ao[GLD], bo[NB][GLD];
+    int wr[GLD];
 #pragma unroll
-    for (int n = 0; n < NLD; ++n) {
-        const int c = n * CPL + lcol;
-        const int64_t cc = j0 + c < a.N ? c : a.N - 1 - j0;
-        bo[n] = (uint32_t)((cc * a.b_sj + lc * 8) * 2);
-        wr[n] = c * ROWB + ((lc ^ (c & 15)) << 4);
+    for (int n = 0; n < GLD; ++n) {
+        const int c = n * CPL + lrow;                       // row inside a group, 0..15
+        wr[n] = c * ROWB + ((lc ^ c) << 4);
+        ao[n] = (uint32_t)(((int64_t)(c < a.M ? c : a.M - 1) * a.a_si + lc * 8) * 2);
+#pragma unroll
+        for (int g = 0; g < NB; ++g) {
+            const int64_t cc = j0 + g * 16 + c < a.N ? g * 16 + c : a.N - 1 - j0;
+            bo[g][n] = (uint32_t)((cc * a.b_sj + lc * 8) * 2);
+        }
     }
-    // operand side: lane (l16, lq) holds, for k-step s, chunk 4s+lq of row l16 (A) / column l16 (B)
-    const uint16_t* ap = A + (int64_t)(l16 < a.M ? l16 : a.M - 1) * a.a_si + lq * 8;
+    // operand side: lane (l16, lq) holds, for k-step s, chunk 4s+lq of row l16 of the group
     const int rd = l16 * ROWB;
 
     f32x4_t acc[NB];
 #pragma unroll
     for (int n = 0; n < NB; ++n) acc[n] = f32x4_t{0, 0, 0, 0};
     const u32x4_t zero = {0, 0, 0, 0};
-    u32x4_t rb[NLD], ra[KS];
+    u32x4_t ra[GLD], rb[NB][GLD];
 
-    // `full`: the whole tile lies inside [kbeg, kend), no lane needs a mask
-    auto fetch = [&](auto full, int64_t k) __attribute__((always_inline)) {
+    // `full`: the whole tile lies inside K, no lane needs a mask
+    auto fetch_a = [&](auto full, int64_t k) __attribute__((always_inline)) {
         constexpr bool FULL = decltype(full)::value;
 #pragma unroll
-        for (int n = 0; n < NLD; ++n) {
-            if (FULL || k + lc * 8 < kend) rb[n] = __builtin_nontemporal_load((const u32x4_t*)(Bs + k * 2 + bo[n]));
-            else rb[n] = zero;
-        }
+        for (int n = 0; n < GLD; ++n)
+            ra[n] = (FULL || k + lc * 8 < kend) ? *(const u32x4_t*)(As + k * 2 + ao[n]) : zero;
+    };
+    auto fetch_b = [&](auto full, int g, int64_t k) __attribute__((always_inline)) {
+        constexpr bool FULL = decltype(full)::value;
+#pragma unroll
+        for (int n = 0; n < GLD; ++n)
+            rb[g][n] = (FULL || k + lc * 8 < kend) ? __builtin_nontemporal_load((const u32x4_t*)(Bs + k * 2 + bo[g][n])) : zero;
+    };
+    auto park_a = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int n = 0; n < GLD; ++n) *(u32x4_t*)(tile_a + wr[n]) = ra[n];
+    };
+    auto park_b = [&](int g) __attribute__((always_inline)) {
+#pragma unroll
+        for (int n = 0; n < GLD; ++n) *(u32x4_t*)(tile_b + wr[n]) = rb[g][n];
+    };
+    auto multiply = [&](int g) __attribute__((always_inline)) {
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            if (FULL || k + s * 32 + lq * 8 < kend) ra[s] = *(const u32x4_t*)(ap + k + s * 32);
-            else ra[s] = zero;
+            const int pos = rd + (((4 * s + lq) ^ l16) << 4);
+            const u32x4_t fa = *(const u32x4_t*)(tile_a + pos);
+            const u32x4_t fb = *(const u32x4_t*)(tile_b + pos);
+            mfma16<IN>(fa, fb, acc[g]);
         }
-    };
-    auto park = [&]() __attribute__((always_inline)) {
-#pragma unroll
-        for (int n = 0; n < NLD; ++n) *(u32x4_t*)(tile + wr[n]) = rb[n];
-    };
-    auto multiply = [&](const u32x4_t (&fa)[KS]) __attribute__((always_inline)) {
-#pragma unroll
-        for (int s = 0; s < KS; ++s)
-#pragma unroll
-            for (int n = 0; n < NB; ++n) {
-                const u32x4_t fb = *(const u32x4_t*)(tile + n * 16 * ROWB + rd + (((4 * s + lq) ^ l16) << 4));
-                mfma16<IN>(fa[s], fb, acc[n]);
-            }
     };
     using yes = std::integral_constant<bool, true>;
     using no = std::integral_constant<bool, false>;
 
-    // Tile i is parked and multiplied while the loads of tile i+1 are in flight.  The steady-state
-    // loop runs over whole tiles only and is free of branches; a ragged last tile is fetched under
-    // masks after it.
-    const int64_t span = kend > kbeg ? kend - kbeg : 0;
-    const int64_t nfull = span / TK;
-    const bool ragged = span % TK != 0;
-    int64_t k = kbeg;
+    // The steady-state loop runs over whole tiles only and is free of branches; a ragged last tile
+    // is fetched under masks after it.
+    const int64_t tiles = (a.K + TK - 1) / TK;                 // all K tiles, the last one possibly ragged
+    const int64_t whole = a.K / TK;                            // tiles without a mask
+    const int64_t mine = tiles > wave ? (tiles - wave + WAVES - 1) / WAVES : 0;
+    const int64_t nfull = whole > wave ? (whole - wave + WAVES - 1) / WAVES : 0;
+    const bool ragged = mine > nfull;                          // this wave owns the ragged tile
+    int64_t k = (int64_t)wave * TK;
     if (nfull > 0) {
-        fetch(yes{}, k);
+        fetch_a(yes{}, k);
+#pragma unroll
+        for (int g = 0; g < NB; ++g) fetch_b(yes{}, g, k);
         for (int64_t i = 1; i < nfull; ++i) {
-            u32x4_t fa[KS];
+            k += KSTRIDE;
+            park_a();
+            fetch_a(yes{}, k);
 #pragma unroll
-            for (int s = 0; s < KS; ++s) fa[s] = ra[s];
-            park();
-            k += TK;
-            fetch(yes{}, k);
-            multiply(fa);
+            for (int g = 0; g < NB; ++g) {
+                park_b(g);
+                fetch_b(yes{}, g, k);
+                multiply(g);
+            }
         }
-        u32x4_t fa[KS];
+        k += KSTRIDE;
+        park_a();
+        if (ragged) fetch_a(no{}, k);
 #pragma unroll
-        for (int s = 0; s < KS; ++s) fa[s] = ra[s];
-        park();
-        k += TK;
-        if (ragged) fetch(no{}, k);
-        multiply(fa);
+        for (int g = 0; g < NB; ++g) {
+            park_b(g);
+            if (ragged) fetch_b(no{}, g, k);
+            multiply(g);
+        }
     } else if (ragged) {
-        fetch(no{}, k);
+        fetch_a(no{}, k);
+#pragma unroll
+        for (int g = 0; g < NB; ++g) fetch_b(no{}, g, k);
     }
     if (ragged) {
-        park();
-        multiply(ra);
+        park_a();
+#pragma unroll
+        for (int g = 0; g < NB; ++g) {
+            park_b(g);
+            multiply(g);
+        }
     }
 
     // 16x16 accumulator: register r of lane l holds row 4*(l/16) + r, column l%16

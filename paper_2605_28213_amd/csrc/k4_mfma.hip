@@ -6,7 +6,7 @@ namespace gl {
 
 // Frozen configurations ("templatize" + an offline sweep, paper Table 1 expression-level intents).
 template <typename IN> using FastK4 = FastCfg<IN>;                         // 256x256 tile, 4 waves, 128x128 per wave
-template <typename IN> using StreamK4 = StreamCfg<IN, 4, 2, 256>;           // 32 columns per workgroup, K split 4 ways, 512-byte runs
+template <typename IN> using StreamK4 = StreamCfg<IN, 2, 2, 256>;           // 32 columns per workgroup, 2 waves taking K tiles in turn, 512-byte runs
 constexpr int MASKED_BM = 128, MASKED_BN = 128, MASKED_WM = 2, MASKED_WN = 2;
 
 template <typename CFG>
