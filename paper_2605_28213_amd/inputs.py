@@ -192,6 +192,12 @@ CONFIGS: Dict[str, Config] = {
     "C3": Config("C3", 4099, 4093, 4097, F16, F16, ROW_MAJOR, ROW_MAJOR, "uniform"),
     "C4": Config("C4", 16, 16384, 16384, BF16, BF16, ROW_MAJOR, COL_MAJOR, "normal", std=0.02),
     "C5": Config("C5", 1024, 1024, 1024, E4M3, BF16, ROW_MAJOR, COL_MAJOR, "normal", batch=64, scaled=True),
+    # the paper's own GEMM shape (Sec. 4.1, workload table) and the held-out GEMM-family shapes of its
+    # App. D that are plain (batched) products; bf16, same layouts and value recipe as C2
+    "P4096": Config("P4096", 4096, 4096, 4096, BF16, BF16, ROW_MAJOR, COL_MAJOR, "normal", rsqrt_k=True),
+    "P2048": Config("P2048", 2048, 2048, 2048, BF16, BF16, ROW_MAJOR, COL_MAJOR, "normal", rsqrt_k=True),
+    "PBMM16": Config("PBMM16", 2048, 2048, 2048, BF16, BF16, ROW_MAJOR, COL_MAJOR, "normal", rsqrt_k=True, batch=16),
+    "PBMM32": Config("PBMM32", 1024, 1024, 1024, BF16, BF16, ROW_MAJOR, COL_MAJOR, "normal", rsqrt_k=True, batch=32),
     # reduced-size counterparts: same dtype / layout / distribution / raggedness
     "C2_small": Config("C2_small", 512, 768, 640, BF16, BF16, ROW_MAJOR, COL_MAJOR, "normal", rsqrt_k=True),
     "C3_small": Config("C3_small", 387, 301, 259, F16, F16, ROW_MAJOR, ROW_MAJOR, "uniform"),

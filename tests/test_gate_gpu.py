@@ -102,6 +102,21 @@ def test_every_state_passes_the_gate(name):
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("name", ["P4096", "P2048", "PBMM16", "PBMM32"])
+def test_paper_shapes_pass_the_gate(name):
+    """The paper's own GEMM shape and its held-out plain and batched GEMM shapes (bf16): the expert
+    state at three seeds, the earlier states at one."""
+    cfg = gen.CONFIGS[name]
+    reference, cache = OracleReference(cfg), {}
+    for v in reversed(range(gemm.GEMM_VARIANT_COUNT)):
+        print(f"[gate] {name} {gemm.gemm_variant_name(v)}", flush=True)
+        seeds = (0, 1, 2) if v == gemm.GEMM_K4_MFMA else (0,)
+        e = gate.run_gate(v, cfg, reference, seeds=seeds, inputs_cache=cache, ledger_path=LEDGER, time_budget_s=0.5)
+        _entries.append(e)
+        assert e["verdict"] == "passed", (name, e["variant_name"], e["verdict"], e.get("correctness"))
+    torch.cuda.empty_cache()
+
+
 def test_strict_mode_refuses_and_names_the_violated_conditions():
     """The ragged fp16 workload violates the alignment conditions of K2..K4; under STRICT the gate
     records a refusal with the condition names instead of running the masked path."""
