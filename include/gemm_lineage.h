@@ -86,7 +86,13 @@ enum {
 };
 
 enum {
-    GEMM_FLAG_STRICT = 1u << 0  /* refuse (GEMM_ERR_PRECONDITION) instead of taking a variant's slow path */
+    GEMM_FLAG_STRICT = 1u << 0, /* refuse (GEMM_ERR_PRECONDITION) instead of taking a variant's slow path */
+    /* Validated simplifications of the expert state (Sec. 3.2, guided deoptimisation: a backward step
+     * removes or weakens one optimisation and must still pass the gate).  Only K4's fast kernel has them;
+     * on any other variant or path they are refused with GEMM_ERR_BAD_ARG.  Same result, slower: the
+     * latency difference is the evidence for what the optimisation buys. */
+    GEMM_FLAG_DEOPT_NO_SWIZZLE = 1u << 1, /* LDS operand rows unswizzled: fragment reads conflict on banks */
+    GEMM_FLAG_DEOPT_NO_OVERLAP = 1u << 2  /* loads waited for at once: nothing in flight under the MFMAs */
 };
 
 typedef struct {

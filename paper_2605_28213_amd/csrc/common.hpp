@@ -27,6 +27,7 @@ struct Args {
     int64_t ldc;
     int64_t stride_a, stride_b, stride_c;
     int32_t in_dtype, out_dtype;
+    uint32_t flags;      // GEMM_FLAG_DEOPT_* bits (host side only: they select an instantiation)
     hipStream_t stream;
 };
 

@@ -266,9 +266,17 @@ __device__ __forceinline__ void for_each_step(std::integer_sequence<int, KS...>,
     (f(std::integral_constant<int, KS>{}), ...);
 }
 
-template <typename IN, int GROUP_M_ = 8>
+// SWIZZLE and OVERLAP are on in the expert state.  Switching one off gives a validated simplification
+// of it (paper Sec. 3.2: a backward step removes or weakens one optimisation and must still pass the
+// gate); the latency it costs is the evidence for what that optimisation buys on this hardware.
+//   SWIZZLE = false: LDS rows keep their chunks in order; a wave's operand read then hits the same
+//                    banks from all 32 rows
+//   OVERLAP = false: every group of direct loads is waited for right after it is issued, so no load is
+//                    in flight while MFMAs issue
+template <typename IN, int GROUP_M_ = 8, bool SWIZZLE_ = true, bool OVERLAP_ = true>
 struct FastCfg {
     using In = IN;
+    static constexpr bool SWIZZLE = SWIZZLE_, OVERLAP = OVERLAP_;
     static constexpr int BM = 256, BN = 256, WM = 2, WN = 2, GROUP_M = GROUP_M_;
     static constexpr int T = WM * WN * 64;
     static constexpr int TMI = BM / WM / 32, TNI = BN / WN / 32;
@@ -313,7 +321,7 @@ void k4_mfma_fast(Args a, int tiles_m, int tiles_n, int flags)
     // the slab enter through the scalar offset.  (The host has checked that a tile's extent fits 32
     // bits of byte offset.)
     const int orow = lane >> 3;
-    const int gchunk = (lane & 7) ^ swz(orow + 8 * (wave & 1));
+    const int gchunk = (lane & 7) ^ (CFG::SWIZZLE ? swz(orow + 8 * (wave & 1)) : 0);
     const char* A = (const char*)a.A + (b * a.stride_a + m0 * a.a_si) * IN::BYTES;
     const char* B = (const char*)a.B + (b * a.stride_b + n0 * a.b_sj) * IN::BYTES;
     const int64_t bytes_a = ((a.M - 1 - m0) * a.a_si + a.K) * IN::BYTES, bytes_b = ((a.N - 1 - n0) * a.b_sj + a.K) * IN::BYTES;
@@ -342,7 +350,7 @@ void k4_mfma_fast(Args a, int tiles_m, int tiles_n, int flags)
     // ---- LDS -> registers: lane reads row (lane % 32) of each 32-row block, CPS chunks starting at
     // chunk CPS * (2*ks + lane/32) ---------------------------------------------------------------
     const int lrow = lane & 31, lhalf = lane >> 5;
-    const int rd_mask = (lhalf * CPS) ^ swz(lrow);
+    const int rd_mask = (lhalf * CPS) ^ (CFG::SWIZZLE ? swz(lrow) : 0);
     const int rd_a = (wm * (BM / CFG::WM) + lrow) * ROW_BYTES;
     const int rd_b = (wn * (BN / WN) + lrow) * ROW_BYTES;
 
@@ -408,9 +416,10 @@ void k4_mfma_fast(Args a, int tiles_m, int tiles_n, int flags)
             if (FULL || s + 1 < nslab) read(na, nb, 0, 0);
             if (FULL || s + 2 < nslab) issue_b(s + 2, ra, 0, HALF);
         }
+        if constexpr (!CFG::OVERLAP) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         mfmas(ks & 1);
         // one fragment read behind each of the first MFMAs, the direct loads spread over all of them
-        if constexpr (FULL) sched_kstep<NMF, NRD, NLOADS>();
+        if constexpr (FULL && CFG::OVERLAP) sched_kstep<NMF, NRD, NLOADS>();
         __builtin_amdgcn_sched_barrier(0);
     };
     // `full` = every prefetch of this slab is in range, so the body is free of branches and the

@@ -39,6 +39,17 @@ static hipError_t launch_stream(const Args& a)
     return hipGetLastError();
 }
 
+// The expert instantiation, or one of its validated simplifications when the caller asks for it.
+template <typename IN>
+static hipError_t launch_fast_any(const Args& a)
+{
+    const bool noswz = a.flags & GEMM_FLAG_DEOPT_NO_SWIZZLE, noovl = a.flags & GEMM_FLAG_DEOPT_NO_OVERLAP;
+    if (noswz && noovl) return launch_fast<FastCfg<IN, 8, false, false>>(a);
+    if (noswz) return launch_fast<FastCfg<IN, 8, false, true>>(a);
+    if (noovl) return launch_fast<FastCfg<IN, 8, true, false>>(a);
+    return launch_fast<FastK4<IN>>(a);
+}
+
 // A thin remainder of rows (1..16 past the last whole 256-row tile) would cost a whole extra row of
 // workgroup tiles, on a large square-ish problem a second round of the machine for a few rows.  It
 // is split off and handed to the streaming kernel, which reads B once more but finishes in the time
@@ -58,7 +69,7 @@ static hipError_t launch_fast_split(const Args& a)
             const int eo = a.out_dtype == GEMM_F32 ? 4 : 2;
             Args top = a;
             top.M = top_rows;
-            hipError_t e = launch_fast<FastK4<IN>>(top);
+            hipError_t e = launch_fast_any<IN>(top);
             if (e != hipSuccess) return e;
             Args bot = a;
             bot.M = rem;
@@ -67,7 +78,7 @@ static hipError_t launch_fast_split(const Args& a)
             return launch_stream<StreamK4<IN>>(bot);
         }
     }
-    return launch_fast<FastK4<IN>>(a);
+    return launch_fast_any<IN>(a);
 }
 
 static int elem_bytes(int dt) { return dt == GEMM_FP8_E4M3 ? 1 : 2; }

@@ -74,11 +74,13 @@ def _stats(ms: Sequence[float]) -> Dict[str, float]:
 def run_gate(variant: int, cfg: gen.Config, reference: Callable[[gen.Inputs], Reference], *,
              seeds: Iterable[int] = (0, 1, 2), warmup: int = 25, reps: int = 100, strict: bool = False,
              time_budget_s: float = 3.0, inputs_cache: Optional[Dict[int, gen.Inputs]] = None,
-             rebuild: bool = False, lend_workspace: bool = True, ledger_path: Optional[str] = None) -> dict:
+             rebuild: bool = False, lend_workspace: bool = True, extra_flags: int = 0,
+             ledger_path: Optional[str] = None) -> dict:
     """Run the gate for (variant, cfg) and return the ledger entry (also appended to ledger_path).
 
     `reference(inputs)` supplies the values C is compared against.  `reps` is cut down for states so
     slow that 100 launches would exceed `time_budget_s` (the entry records the number used).
+    `extra_flags` are GEMM_FLAG_DEOPT_* bits: the gate applied to a simplification of the expert state.
     `rebuild` recompiles stale objects first; otherwise the compile leg only builds when no library
     is present and records that the existing one loaded.
     """
@@ -88,7 +90,7 @@ def run_gate(variant: int, cfg: gen.Config, reference: Callable[[gen.Inputs], Re
 
     entry: dict = {"variant": variant, "workload": cfg.name, "time": time.time(),
                    "shape": [cfg.M, cfg.N, cfg.K, cfg.batch], "in_dtype": gen.DTYPE_NAMES[cfg.in_dtype],
-                   "strict": strict}
+                   "strict": strict, "flags": extra_flags}
     # ---- compile ---------------------------------------------------------------------------------
     try:
         prebuilt = os.path.exists(gemm.LIB_PATH) and not rebuild
@@ -105,7 +107,7 @@ def run_gate(variant: int, cfg: gen.Config, reference: Callable[[gen.Inputs], Re
     if not torch.cuda.is_available():
         raise RuntimeError("the gate's correctness and profile legs need a GPU")
     stream = torch.cuda.Stream()
-    flags = gemm.GEMM_FLAG_STRICT if strict else 0
+    flags = (gemm.GEMM_FLAG_STRICT if strict else 0) | extra_flags
     tol = TOLERANCE[cfg.in_dtype]
     seed_results: List[dict] = []
     timing = None

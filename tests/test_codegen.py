@@ -53,7 +53,7 @@ def first_inner_loop(body):
 @pytest.mark.parametrize("dtype,mfma,per_slab", [("4BF16", "v_mfma_f32_32x32x16_bf16", 64), ("3F16", "v_mfma_f32_32x32x16_f16", 64),
                                                  ("4E4M3", "v_mfma_scale_f32_32x32x64_f8f6f4", 32)])
 def test_fast_kernel_steady_state_loop(asm, dtype, mfma, per_slab):
-    prefix = "_ZN2gl12k4_mfma_fastINS_7FastCfgINS_" + dtype
+    prefix = "_ZN2gl12k4_mfma_fastINS_7FastCfgINS_" + dtype + "ELi8ELb1ELb1E"      # the expert instantiation
     ops = first_inner_loop(kernel_body(asm, prefix))
     count = lambda name: sum(o == name for o in ops)
     # five slabs per trip round the LDS ring; 16 direct loads per slab; fragment reads are 16-byte

@@ -117,6 +117,28 @@ def test_paper_shapes_pass_the_gate(name):
     torch.cuda.empty_cache()
 
 
+def test_simplifications_of_the_expert_state_pass_and_cost_time():
+    """Guided deoptimisation on the expert kernel: with the LDS swizzle removed, or with loads no longer
+    overlapping the MFMAs, the kernel still passes the gate on the headline workload and is slower;
+    the ledger keeps the latency each optimisation buys."""
+    cfg = gen.CONFIGS["C2"]
+    reference, cache = OracleReference(cfg), {}
+    base = gate.run_gate(gemm.GEMM_K4_MFMA, cfg, reference, seeds=(0,), inputs_cache=cache, ledger_path=LEDGER)
+    assert base["verdict"] == "passed"
+    for flags, tag in ((gemm.GEMM_FLAG_DEOPT_NO_SWIZZLE, "-noswz"), (gemm.GEMM_FLAG_DEOPT_NO_OVERLAP, "-noovl"),
+                       (gemm.GEMM_FLAG_DEOPT_NO_SWIZZLE | gemm.GEMM_FLAG_DEOPT_NO_OVERLAP, "-noswz-noovl")):
+        e = gate.run_gate(gemm.GEMM_K4_MFMA, cfg, reference, seeds=(0,), inputs_cache=cache, extra_flags=flags,
+                          ledger_path=LEDGER, time_budget_s=1.0)
+        e["variant_name"] = "K4_mfma" + tag
+        _entries.append(e)
+        assert e["verdict"] == "passed" and e["query"]["path"].endswith(tag), e
+        assert e["profile"]["median_us"] > 1.05 * base["profile"]["median_us"], (tag, e["profile"], base["profile"])
+    # the switches belong to K4's fast kernel: any other state refuses them
+    d = gemm.make_desc(512, 512, 512, gen.BF16, gen.BF16, gen.ROW_MAJOR, gen.COL_MAJOR, flags=gemm.GEMM_FLAG_DEOPT_NO_SWIZZLE)
+    assert gemm.gemm_query(gemm.GEMM_K3_PIPELINED, d).status == gemm.GEMM_ERR_BAD_ARG
+    torch.cuda.empty_cache()
+
+
 def test_strict_mode_refuses_and_names_the_violated_conditions():
     """The ragged fp16 workload violates the alignment conditions of K2..K4; under STRICT the gate
     records a refusal with the condition names instead of running the masked path."""

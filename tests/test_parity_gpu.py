@@ -248,3 +248,19 @@ def test_thin_row_remainder_goes_to_the_streaming_kernel(dtype, M):
     check(4, inp, ref)
     ragged = gen.Config("mtail_packed", M, N, K - 5, dtype, out, ROW, ROW, "normal", rsqrt_k=True)
     check(4, gen.make_inputs(ragged, 7), lend_workspace=True)
+
+
+@pytest.mark.parametrize("flags", [gemm.GEMM_FLAG_DEOPT_NO_SWIZZLE, gemm.GEMM_FLAG_DEOPT_NO_OVERLAP,
+                                   gemm.GEMM_FLAG_DEOPT_NO_SWIZZLE | gemm.GEMM_FLAG_DEOPT_NO_OVERLAP])
+@pytest.mark.parametrize("dtype", [gen.BF16, gen.E4M3])
+def test_simplified_expert_states_compute_the_same_product(flags, dtype):
+    """The validated simplifications of the fast kernel (no LDS swizzle, no load/MFMA overlap) on a ragged
+    multi-tile shape with enough slabs to go round the LDS ring."""
+    M, N, K = 300, 520, 1024
+    cfg = gen.Config("deopt", M, N, K, dtype, gen.BF16, ROW, COL, "normal", rsqrt_k=True, batch=2)
+    inp = gen.make_inputs(cfg, 12)
+    c = inp.cfg
+    C_ref, D = oracle_for(inp)
+    rc, C, _ = util.run_config(4, inp, flags=flags)
+    assert rc == gemm.GEMM_OK
+    assert util.norm_err(C[:, :, :N], C_ref, D) <= util.TOL[dtype]
