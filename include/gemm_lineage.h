@@ -92,7 +92,12 @@ enum {
      * on any other variant or path they are refused with GEMM_ERR_BAD_ARG.  Same result, slower: the
      * latency difference is the evidence for what the optimisation buys. */
     GEMM_FLAG_DEOPT_NO_SWIZZLE = 1u << 1, /* LDS operand rows unswizzled: fragment reads conflict on banks */
-    GEMM_FLAG_DEOPT_NO_OVERLAP = 1u << 2  /* loads waited for at once: nothing in flight under the MFMAs */
+    GEMM_FLAG_DEOPT_NO_OVERLAP = 1u << 2, /* loads waited for at once: nothing in flight under the MFMAs */
+    /* Tile override for K4's fast kernel (Table 1 "autotune": the sweep that froze the default choice
+     * needs both).  Default: 256 x 256 tiles, 128 x 128 when 256-tiles would not fill the CUs once.
+     * At most one of the two; refused with GEMM_ERR_BAD_ARG on other variants or paths. */
+    GEMM_FLAG_TILE_256 = 1u << 3,
+    GEMM_FLAG_TILE_128 = 1u << 4
 };
 
 typedef struct {

@@ -88,6 +88,8 @@ int64_t k4_packed_k(const Args& a);
 size_t k4_packed_workspace_bytes(const Args& a);
 // True when the fast kernel's launcher hands a thin remainder of rows (M % 256 in 1..16) to the streaming kernel.
 bool k4_splits_m_tail(const Args& a);
+// True when the fast kernel runs with 128 x 128 workgroup tiles instead of 256 x 256.
+bool k4_small_tiles(const Args& a);
 
 hipError_t launch_k0(const Args& a);
 hipError_t launch_valu_tiled(int variant, int path, const Args& a);

@@ -55,7 +55,9 @@ int validate(int variant, const gemm_desc_t* d, const void* A, const void* B, co
     if ((d->layout_a != GEMM_ROW_MAJOR && d->layout_a != GEMM_COL_MAJOR) ||
         (d->layout_b != GEMM_ROW_MAJOR && d->layout_b != GEMM_COL_MAJOR))
         return GEMM_ERR_BAD_ARG;
-    if (d->flags & ~(uint32_t)(GEMM_FLAG_STRICT | GEMM_FLAG_DEOPT_NO_SWIZZLE | GEMM_FLAG_DEOPT_NO_OVERLAP)) return GEMM_ERR_BAD_ARG;
+    constexpr uint32_t K4_FLAGS = GEMM_FLAG_DEOPT_NO_SWIZZLE | GEMM_FLAG_DEOPT_NO_OVERLAP | GEMM_FLAG_TILE_256 | GEMM_FLAG_TILE_128;
+    if (d->flags & ~(uint32_t)(GEMM_FLAG_STRICT | K4_FLAGS)) return GEMM_ERR_BAD_ARG;
+    if ((d->flags & GEMM_FLAG_TILE_256) && (d->flags & GEMM_FLAG_TILE_128)) return GEMM_ERR_BAD_ARG;
     const int64_t min_lda = d->layout_a == GEMM_ROW_MAJOR ? d->K : d->M;
     const int64_t min_ldb = d->layout_b == GEMM_ROW_MAJOR ? d->N : d->K;
     if (d->lda < 1 || d->ldb < 1 || d->ldc < 1) return GEMM_ERR_BAD_ARG;
@@ -99,7 +101,7 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
     a.ldc = d->ldc;
     a.stride_a = d->stride_a; a.stride_b = d->stride_b; a.stride_c = d->stride_c;
     a.in_dtype = d->in_dtype; a.out_dtype = d->out_dtype;
-    a.flags = d->flags & (GEMM_FLAG_DEOPT_NO_SWIZZLE | GEMM_FLAG_DEOPT_NO_OVERLAP);
+    a.flags = d->flags & (GEMM_FLAG_DEOPT_NO_SWIZZLE | GEMM_FLAG_DEOPT_NO_OVERLAP | GEMM_FLAG_TILE_256 | GEMM_FLAG_TILE_128);
     a.stream = (hipStream_t)d->stream;
     p.empty = d->M == 0 || d->N == 0;
 
@@ -194,7 +196,7 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
     q.workspace_bytes = pack_bytes;
     strncpy(q.path, path, sizeof(q.path) - 1);
 
-    if (a.flags) {   // simplifications exist for K4's fast kernel only (also when it runs on packed operands)
+    if (a.flags) {   // simplifications and tile overrides exist for K4's fast kernel only (also on packed operands)
         const int kind = p.path & 0xFF;
         if (variant != GEMM_K4_MFMA || (kind != MFMA_VEC16 && kind != MFMA_PACKED)) { p.status = GEMM_ERR_BAD_ARG; return p; }
         const size_t n = strlen(q.path);

@@ -196,6 +196,7 @@ __device__ __forceinline__ void store_tiles_staged(const Args& a, int64_t b, con
 // ------------------------------------------------------------------------------------------------
 // Fast kernel: both operands K-contiguous and 16-byte aligned, K a whole number of 128-byte slabs.
 //
+// (Sizes below are those of the 256-tile configuration.)
 // One workgroup = 4 waves (one per SIMD) on a 256x256 tile of C, each wave on a 128x128 quarter =
 // 4x4 accumulator tiles of 32x32.  K advances in slabs of 128 bytes per row.  LDS is a ring of five
 // 32 KB regions, each one operand slab (256 rows x 128 bytes); operand slab q (A of slab s: q = 2s,
@@ -246,14 +247,17 @@ __device__ __forceinline__ void mfma_step(const Frag<IN>& a, const Frag<IN>& b, 
 
 #define GL_SCHED_GROUP(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
 
-// Requested issue order of one k-step: NMF MFMAs, an LDS read (0x100) behind each of the first NRD,
-// NLOADS direct loads (VMEM, 0x020) spread evenly over all of them.
+// Requested issue order of one k-step: NMF MFMAs, the NRD LDS reads (0x100) behind the first of them
+// (one each, or more where there are more reads than MFMAs), NLOADS direct loads (VMEM, 0x020) spread
+// evenly over all of them.
 template <int NMF, int NRD, int NLOADS, int N = 0>
 __device__ __forceinline__ void sched_kstep()
 {
     if constexpr (N < NMF) {
+        constexpr int RPM = (NRD + NMF - 1) / NMF;
+        constexpr int R = NRD - N * RPM >= RPM ? RPM : (NRD - N * RPM > 0 ? NRD - N * RPM : 0);
         GL_SCHED_GROUP(0x008, 1);
-        if constexpr (N < NRD) GL_SCHED_GROUP(0x100, 1);
+        if constexpr (R > 0) GL_SCHED_GROUP(0x100, R);
         constexpr int L = ((N + 1) * NLOADS) / NMF - (N * NLOADS) / NMF;
         if constexpr (L > 0) GL_SCHED_GROUP(0x020, L);
         sched_kstep<NMF, NRD, NLOADS, N + 1>();
@@ -273,21 +277,28 @@ __device__ __forceinline__ void for_each_step(std::integer_sequence<int, KS...>,
 //                    banks from all 32 rows
 //   OVERLAP = false: every group of direct loads is waited for right after it is issued, so no load is
 //                    in flight while MFMAs issue
-template <typename IN, int GROUP_M_ = 8, bool SWIZZLE_ = true, bool OVERLAP_ = true>
+//
+// TILE is the side of the square workgroup tile: 256 (one workgroup per CU, 128x128 per wave, all of
+// LDS: the compute-bound shape) or 128 (64x64 per wave, half the LDS, two workgroups per CU that cover
+// each other's prologue, epilogue and memory waits: for short K, or when 256-tiles would leave CUs idle).
+template <typename IN, int TILE_ = 256, int GROUP_M_ = 8, bool SWIZZLE_ = true, bool OVERLAP_ = true, int PRE_ = 0>
 struct FastCfg {
     using In = IN;
     static constexpr bool SWIZZLE = SWIZZLE_, OVERLAP = OVERLAP_;
-    static constexpr int BM = 256, BN = 256, WM = 2, WN = 2, GROUP_M = GROUP_M_;
+    static constexpr int PRE_BARRIER_MFMAS = PRE_;
+    static constexpr int BM = TILE_, BN = TILE_, WM = 2, WN = 2, GROUP_M = GROUP_M_;
     static constexpr int T = WM * WN * 64;
     static constexpr int TMI = BM / WM / 32, TNI = BN / WN / 32;
-    static constexpr int REGION = 256 * ROW_BYTES, REGIONS = 5;
+    static constexpr int REGION = TILE_ * ROW_BYTES, REGIONS = 5;
     static constexpr int LDS_BYTES = REGIONS * REGION;
+    static constexpr int WAVES_PER_SIMD = TILE_ == 256 ? 1 : 2;
+    static_assert(TILE_ == 256 || TILE_ == 128, "square tiles of 256 or 128");
     // the epilogue parks 32 rows of fp32 per wave, one wave per region
     static_assert(32 * (TNI * 32 * 4 + 16) <= REGION, "epilogue staging must fit a region");
 };
 
 template <typename CFG>
-__global__ __launch_bounds__(CFG::T) __attribute__((amdgpu_waves_per_eu(1, 1)))
+__global__ __launch_bounds__(CFG::T) __attribute__((amdgpu_waves_per_eu(CFG::WAVES_PER_SIMD, CFG::WAVES_PER_SIMD)))
 void k4_mfma_fast(Args a, int tiles_m, int tiles_n, int flags)
 {
     using IN = typename CFG::In;
@@ -297,8 +308,8 @@ void k4_mfma_fast(Args a, int tiles_m, int tiles_n, int flags)
     constexpr int V = 16 / IN::BYTES;                    // K elements per chunk
     constexpr int CPS = Frag<IN>::CPS;                   // chunks per lane per k-step
     constexpr int NK = CHUNKS / (2 * CPS);               // k-steps per slab
-    constexpr int LD = 256 / 8 / NW;                     // direct loads per wave per operand slab
-    static_assert(BM == 256 && BN == 256 && NW == 4 && LD % 2 == 0, "the ring schedule is written for this shape");
+    constexpr int LD = BM / 8 / NW;                      // direct loads per wave per operand slab
+    static_assert(BM == BN && NW == 4 && LD % 2 == 0, "the ring schedule is written for square tiles and four waves");
     __shared__ __attribute__((aligned(1024))) char r0[REGION];
     __shared__ __attribute__((aligned(1024))) char r1[REGION];
     __shared__ __attribute__((aligned(1024))) char r2[REGION];
@@ -375,13 +386,13 @@ void k4_mfma_fast(Args a, int tiles_m, int tiles_n, int flags)
     };
     // B first: see the epilogue.  Columns are walked back and forth so that consecutive MFMAs share
     // one operand.
-    auto mfmas = [&](int slot) __attribute__((always_inline)) {
+    auto mfmas = [&](int slot, int lo, int hi) __attribute__((always_inline)) {    // MFMAs lo..hi-1 of a k-step
 #pragma unroll
         for (int i = 0; i < TMI; ++i)
 #pragma unroll
             for (int jj = 0; jj < TNI; ++jj) {
                 const int j = (i & 1) ? TNI - 1 - jj : jj;
-                mfma_step<IN>(fb[slot][j], fa[slot][i], acc[i][j]);
+                if (i * TNI + jj >= lo && i * TNI + jj < hi) mfma_step<IN>(fb[slot][j], fa[slot][i], acc[i][j]);
             }
     };
     constexpr int NMF = TMI * TNI;                   // MFMA instructions per k-step
@@ -390,7 +401,7 @@ void k4_mfma_fast(Args a, int tiles_m, int tiles_n, int flags)
     // issue groups of a slab, in order: B_s+1 second half, A_s+2 first half, A_s+2 second half (before
     // the barrier, spread over the first NK-1 k-steps), B_s+2 first half (after it, last k-step)
     constexpr int GROUPS_PER_STEP = NK > 1 ? (3 + NK - 2) / (NK - 1) : 3;
-    static_assert(NK >= 2 && NRD <= NMF, "a k-step hangs at most one fragment read on each MFMA");
+    static_assert(NK >= 2, "the barrier k-step is not the one that prefetches");
 
     const int64_t nslab = a.K / KE;                  // K is a whole number of slabs
     auto kstep = [&](auto full, auto step, int64_t s, char* ra, char* rb, char* na, char* nb, char* fifth) __attribute__((always_inline)) {
@@ -398,16 +409,24 @@ void k4_mfma_fast(Args a, int tiles_m, int tiles_n, int flags)
         constexpr int ks = decltype(step)::value;
         constexpr int G0 = ks * GROUPS_PER_STEP, G1 = (ks + 1) * GROUPS_PER_STEP < 3 ? (ks + 1) * GROUPS_PER_STEP : 3;
         constexpr int NLOADS = ks + 1 < NK ? (G1 > G0 ? (G1 - G0) * HALF : 0) : HALF;
+        constexpr int PRE = (ks + 1 == NK && FULL && CFG::OVERLAP) ? CFG::PRE_BARRIER_MFMAS : 0;
         if constexpr (ks + 1 < NK) {
             read(ra, rb, ks + 1, (ks + 1) & 1);
             if constexpr (G0 <= 0 && 0 < G1) { if (FULL || s + 1 < nslab) issue_b(s + 1, nb, HALF, LD); }
             if constexpr (G0 <= 1 && 1 < G1) { if (FULL || s + 2 < nslab) issue_a(s + 2, fifth, 0, HALF); }
             if constexpr (G0 <= 2 && 2 < G1) { if (FULL || s + 2 < nslab) issue_a(s + 2, fifth, HALF, LD); }
         } else {
+            // The slab's last k-step holds the barrier.  Its first PRE MFMAs (operands already in
+            // registers) are issued ahead of it, so the matrix pipe has work while the waves meet.
+            if constexpr (PRE > 0) {
+                mfmas(ks & 1, 0, PRE);
+                __builtin_amdgcn_sched_barrier(0);
+            }
             // landed after this wait: A_s+1, B_s+1; possibly still in flight: the LD loads of A_s+2
             if constexpr (FULL) {
-                static_assert(LD == 8, "the wait below counts the A_s+2 group");
-                asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
+                static_assert(LD == 8 || LD == 4, "the wait below counts the LD loads of the A_s+2 group");
+                if constexpr (LD == 8) asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
+                else asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)" ::: "memory");
             } else {
                 asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
             }
@@ -417,9 +436,9 @@ void k4_mfma_fast(Args a, int tiles_m, int tiles_n, int flags)
             if (FULL || s + 2 < nslab) issue_b(s + 2, ra, 0, HALF);
         }
         if constexpr (!CFG::OVERLAP) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        mfmas(ks & 1);
+        mfmas(ks & 1, PRE, NMF);
         // one fragment read behind each of the first MFMAs, the direct loads spread over all of them
-        if constexpr (FULL && CFG::OVERLAP) sched_kstep<NMF, NRD, NLOADS>();
+        if constexpr (FULL && CFG::OVERLAP) sched_kstep<NMF - PRE, NRD, NLOADS>();
         __builtin_amdgcn_sched_barrier(0);
     };
     // `full` = every prefetch of this slab is in range, so the body is free of branches and the

@@ -5,7 +5,8 @@
 namespace gl {
 
 // Frozen configurations ("templatize" + an offline sweep, paper Table 1 expression-level intents).
-template <typename IN> using FastK4 = FastCfg<IN>;                         // 256x256 tile, 4 waves, 128x128 per wave
+template <typename IN> using FastK4 = FastCfg<IN, 256>;                    // 256x256 tile, 4 waves, 128x128 per wave, one workgroup per CU
+template <typename IN> using FastK4Small = FastCfg<IN, 128>;               // 128x128 tile, 4 waves, 64x64 per wave, two workgroups per CU
 template <typename IN> using StreamK4 = StreamCfg<IN, 2, 2, 256>;           // 32 columns per workgroup, 2 waves taking K tiles in turn, 512-byte runs
 constexpr int MASKED_BM = 128, MASKED_BN = 128, MASKED_WM = 2, MASKED_WN = 2;
 
@@ -39,14 +40,27 @@ static hipError_t launch_stream(const Args& a)
     return hipGetLastError();
 }
 
+// Tile choice of the fast kernel ("templatize" + a measured sweep, Table 1's expression-level intents):
+// 128-tiles when 256-tiles would not fill the 256 CUs once (2048^3 bf16: 43 us -> 25 us).  Where the
+// machine is full they lose to 256-tiles even for short K (64 x 1024^3 e4m3: 108 us -> 131 us; 64x64 per
+// wave reads LDS twice as often per MFMA and needs twice the L2 traffic).
+bool k4_small_tiles(const Args& a)
+{
+    if (a.flags & GEMM_FLAG_TILE_128) return true;
+    if (a.flags & (GEMM_FLAG_TILE_256 | GEMM_FLAG_DEOPT_NO_SWIZZLE | GEMM_FLAG_DEOPT_NO_OVERLAP)) return false;   // the simplified states are 256-tile ones
+    const int64_t t256 = ((a.M + 255) / 256) * ((a.N + 255) / 256) * a.batch;
+    return t256 < 256;
+}
+
 // The expert instantiation, or one of its validated simplifications when the caller asks for it.
 template <typename IN>
 static hipError_t launch_fast_any(const Args& a)
 {
     const bool noswz = a.flags & GEMM_FLAG_DEOPT_NO_SWIZZLE, noovl = a.flags & GEMM_FLAG_DEOPT_NO_OVERLAP;
-    if (noswz && noovl) return launch_fast<FastCfg<IN, 8, false, false>>(a);
-    if (noswz) return launch_fast<FastCfg<IN, 8, false, true>>(a);
-    if (noovl) return launch_fast<FastCfg<IN, 8, true, false>>(a);
+    if (noswz && noovl) return launch_fast<FastCfg<IN, 256, 8, false, false>>(a);
+    if (noswz) return launch_fast<FastCfg<IN, 256, 8, false, true>>(a);
+    if (noovl) return launch_fast<FastCfg<IN, 256, 8, true, false>>(a);
+    if (k4_small_tiles(a)) return launch_fast<FastK4Small<IN>>(a);
     return launch_fast<FastK4<IN>>(a);
 }
 
@@ -164,9 +178,11 @@ Geometry geometry_k4(int path, const Args& a)
         return Geometry{16, C::COLS, C::TK, C::WAVES * 64, 2, C::LDS_BYTES, ((a.N + C::COLS - 1) / C::COLS) * a.batch};
     }
     if (kind == MFMA_VEC16 || kind == MFMA_PACKED) {
-        using C = FastK4<BF16>;
-        const int64_t g = ((a.M + C::BM - 1) / C::BM) * ((a.N + C::BN - 1) / C::BN) * a.batch;
-        return Geometry{C::BM, C::BN, ROW_BYTES / es, C::T, 2, C::LDS_BYTES, g};   // stages: slabs in flight beyond the one in use
+        const bool small = k4_small_tiles(a);
+        const int bt = small ? FastK4Small<BF16>::BM : FastK4<BF16>::BM;
+        const int64_t g = ((a.M + bt - 1) / bt) * ((a.N + bt - 1) / bt) * a.batch;
+        // stages: slabs in flight beyond the one in use
+        return Geometry{bt, bt, ROW_BYTES / es, 256, 2, small ? FastK4Small<BF16>::LDS_BYTES : FastK4<BF16>::LDS_BYTES, g};
     }
     const int64_t g = ((a.M + MASKED_BM - 1) / MASKED_BM) * ((a.N + MASKED_BN - 1) / MASKED_BN) * a.batch;
     return Geometry{MASKED_BM, MASKED_BN, ROW_BYTES / es, MASKED_WM * MASKED_WN * 64, 2, 2 * (MASKED_BM + MASKED_BN) * ROW_BYTES, g};

@@ -81,7 +81,15 @@ def test_argument_errors_return_codes_without_launching(variant):
     d = gemm.make_desc(64, 64, 64, 7, 1, 0, 1); cases.append((d, gemm.GEMM_ERR_UNSUPPORTED_DTYPE))
     d = gemm.make_desc(64, 64, 64, gemm.GEMM_F32, gemm.GEMM_BF16, 0, 0); cases.append((d, gemm.GEMM_ERR_UNSUPPORTED_DTYPE))
     d = gemm.make_desc(64, 64, 64, 1, 1, 0, 1, batch=2, stride_c=100); cases.append((d, gemm.GEMM_ERR_BAD_ARG))
-    d = gemm.make_desc(64, 64, 64, 1, 1, 0, 1, flags=8); cases.append((d, gemm.GEMM_ERR_BAD_ARG))
+    d = gemm.make_desc(64, 64, 64, 1, 1, 0, 1, flags=1 << 20); cases.append((d, gemm.GEMM_ERR_BAD_ARG))
+    d = gemm.make_desc(64, 64, 64, 1, 1, 0, 1, flags=gemm.GEMM_FLAG_TILE_256 | gemm.GEMM_FLAG_TILE_128)
+    cases.append((d, gemm.GEMM_ERR_BAD_ARG))
+    if variant != gemm.GEMM_K4_MFMA:                       # K4-only switches on another state
+        for f in (gemm.GEMM_FLAG_TILE_128, gemm.GEMM_FLAG_DEOPT_NO_SWIZZLE, gemm.GEMM_FLAG_DEOPT_NO_OVERLAP):
+            cases.append((gemm.make_desc(64, 64, 64, 1, 1, 0, 1, flags=f), gemm.GEMM_ERR_BAD_ARG))
+    else:                                                  # ... and on a K4 path other than the fast kernel
+        cases.append((gemm.make_desc(16, 64, 64, 1, 1, 0, 1, flags=gemm.GEMM_FLAG_TILE_128), gemm.GEMM_ERR_BAD_ARG))
+        cases.append((gemm.make_desc(64, 64, 60, 1, 1, 0, 1, flags=gemm.GEMM_FLAG_DEOPT_NO_SWIZZLE), gemm.GEMM_ERR_BAD_ARG))
     d = gemm.make_desc(64, 64, 64, 1, 1, 0, 1); d.reserved = 1; cases.append((d, gemm.GEMM_ERR_BAD_ARG))
     for d, want in cases:
         assert gemm.gemm_run_ex(variant, d, fake, fake, fake) == want

@@ -53,7 +53,7 @@ def first_inner_loop(body):
 @pytest.mark.parametrize("dtype,mfma,per_slab", [("4BF16", "v_mfma_f32_32x32x16_bf16", 64), ("3F16", "v_mfma_f32_32x32x16_f16", 64),
                                                  ("4E4M3", "v_mfma_scale_f32_32x32x64_f8f6f4", 32)])
 def test_fast_kernel_steady_state_loop(asm, dtype, mfma, per_slab):
-    prefix = "_ZN2gl12k4_mfma_fastINS_7FastCfgINS_" + dtype + "ELi8ELb1ELb1E"      # the expert instantiation
+    prefix = "_ZN2gl12k4_mfma_fastINS_7FastCfgINS_" + dtype + "ELi256ELi8ELb1ELb1ELi0E"      # the expert instantiation
     ops = first_inner_loop(kernel_body(asm, prefix))
     count = lambda name: sum(o == name for o in ops)
     # five slabs per trip round the LDS ring; 16 direct loads per slab; fragment reads are 16-byte
@@ -76,3 +76,10 @@ def test_stream_kernel_register_budget(asm):
         meta = metadata(asm, "_ZN2gl9k4_streamINS_9StreamCfgINS_" + dtype)
         assert meta["vgpr_spill"] == 0 and meta["scratch"] == 0
         assert meta["lds"] == 32 * 1024, "two waves, each the A group and one column group of 16 x 512 B"
+
+
+def test_small_tile_configuration_fits_two_workgroups_per_cu(asm):
+    for dtype in ("4BF16", "3F16", "4E4M3"):
+        meta = metadata(asm, "_ZN2gl12k4_mfma_fastINS_7FastCfgINS_" + dtype + "ELi128ELi8ELb1ELb1ELi0E")
+        assert meta["lds"] == 80 * 1024 and meta["agpr"] + meta["vgpr"] <= 512
+        assert meta["vgpr"] <= 256 and meta["vgpr_spill"] == 0, "two waves per SIMD need at most 256 registers each"

@@ -264,3 +264,22 @@ def test_simplified_expert_states_compute_the_same_product(flags, dtype):
     rc, C, _ = util.run_config(4, inp, flags=flags)
     assert rc == gemm.GEMM_OK
     assert util.norm_err(C[:, :, :N], C_ref, D) <= util.TOL[dtype]
+
+
+@pytest.mark.parametrize("tile_flag", [gemm.GEMM_FLAG_TILE_256, gemm.GEMM_FLAG_TILE_128])
+@pytest.mark.parametrize("dtype", [gen.BF16, gen.F16, gen.E4M3])
+def test_both_tile_configurations_on_ragged_shapes(tile_flag, dtype):
+    """The fast kernel with 256- and with 128-tiles forced, on shapes whose M and N end inside a tile
+    (rows past the end come from outside the buffer resource), with a batch, both output types, and
+    with K long enough to go round the LDS ring and to leave it through the tail loop."""
+    out = gen.BF16 if dtype == gen.E4M3 else dtype
+    for (M, N, K, nb) in [(300, 520, 1024, 2), (257, 129, 896, 1), (100, 700, 128, 3)]:
+        cfg = gen.Config("tiles", M, N, K, dtype, out, ROW, COL, "normal", rsqrt_k=True, batch=nb)
+        inp = gen.make_inputs(cfg, 13)
+        C_ref, D = oracle_for(inp)
+        for od in (out, gen.F32):
+            rc, C, _ = util.run_config(4, inp, flags=tile_flag, out_dtype=od)
+            assert rc == gemm.GEMM_OK
+            assert util.norm_err(C[:, :, :N], C_ref, D) <= util.TOL[dtype], (M, N, K, nb, od)
+    d = gemm.make_desc(300, 520, 1024, dtype, out, ROW, COL, flags=tile_flag)
+    assert gemm.gemm_query(4, d).bm == (256 if tile_flag == gemm.GEMM_FLAG_TILE_256 else 128)
