@@ -171,6 +171,25 @@ __device__ __forceinline__ void store_tiles_staged(const Args& a, int64_t b, con
             }
             continue;
         }
+        if (!vec_ok) {
+            // C rows are aligned to an element only: consecutive lanes store consecutive elements of
+            // one row, so that a store instruction still covers whole lines
+            constexpr int RW = TNI * 32;                                   // columns of the block
+            for (int r = 0; r < 32; ++r) {
+                const int64_t gi = row0 + i * 32 + r;
+                if (gi >= a.M) break;
+#pragma unroll
+                for (int h = 0; h < (RW + 63) / 64; ++h) {
+                    const int c = h * 64 + lane;
+                    const int64_t gj = col0 + c;
+                    if (c < RW && gj < a.N) {
+                        if constexpr (OB == 4) ((uint32_t*)C)[gi * a.ldc + gj] = *(const uint32_t*)(stage + r * PITCH + c * 4);
+                        else ((uint16_t*)C)[gi * a.ldc + gj] = *(const uint16_t*)(stage + r * PITCH + c * 2);
+                    }
+                }
+            }
+            continue;
+        }
 #pragma unroll
         for (int p = 0; p < PASSES; ++p) {
             const int q = lane + 64 * p, r = q / CPR, c = q % CPR;
@@ -627,36 +646,88 @@ __global__ __launch_bounds__(WM* WN * 64) void k4_mfma_masked(Args a, int vec_ma
 }
 
 // ------------------------------------------------------------------------------------------------
-// Pack kernel: rewrites one operand as [rows][Kp] with K contiguous, rows 16-byte aligned and K
-// padded with zeros to a whole number of slabs (Kp), in caller-provided workspace.  It is what lets
-// the fast kernel run on operands that violate its conditions (odd leading dimensions, K strided,
-// ragged K): Table 1's "smem_transpose" applied ahead of the product.  A workgroup moves a tile of
-// 64 rows x 128 bytes of K through LDS: element reads along whichever axis is contiguous in the
-// source, 16-byte writes along K.
+// Pack kernels: rewrite one operand as [rows][Kp] with K contiguous, rows 16-byte aligned and K
+// padded with zeros to a whole number of slabs (Kp), in caller-provided workspace.  They are what
+// lets the fast kernel run on operands that violate its conditions (odd leading dimensions, K
+// strided, ragged K): Table 1's "smem_transpose" applied ahead of the product.
+//
+// Source rows are aligned to their element size only, so nothing wider than an element can be
+// loaded at an element's own address.  Both kernels instead load the aligned dwords that contain the
+// elements they need (a dword that holds at least one valid byte lies inside the allocation) and
+// shift: by bytes within a register pair when K is contiguous (k4_pack_rows), by whole elements
+// into an LDS tile when the source is contiguous along the other axis (k4_pack_transpose).
 // ------------------------------------------------------------------------------------------------
+
+// K contiguous in the source.  One thread makes one 16-byte chunk of the packed row.
 template <typename IN>
-__global__ __launch_bounds__(256) void k4_pack(const typename IN::raw* __restrict__ src, int64_t s_r, int64_t s_k,
-                                               int64_t rows, int64_t K, int64_t Kp, typename IN::raw* __restrict__ dst,
-                                               int64_t src_batch, int64_t dst_batch)
+__global__ __launch_bounds__(256) void k4_pack_rows(const char* __restrict__ src, int64_t row_bytes, int64_t rows, int64_t K,
+                                                    int64_t Kp, char* __restrict__ dst, int64_t src_batch_bytes, int64_t dst_batch_bytes)
+{
+    constexpr int BYTES = IN::BYTES, V = 16 / BYTES;
+    const int64_t chunks = Kp / V;
+    const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (id >= rows * chunks) return;
+    const int64_t r = id / chunks, c = id % chunks;
+    src += (int64_t)blockIdx.y * src_batch_bytes + r * row_bytes;
+    const uintptr_t row = (uintptr_t)src, end = row + (uintptr_t)(K * BYTES);   // valid bytes of this row: [row, end)
+    const uintptr_t p = row + (uintptr_t)(c * 16);
+    const uintptr_t base = p & ~(uintptr_t)3;
+    const uint32_t sh = (uint32_t)(p & 3);
+    uint32_t d[5];
+#pragma unroll
+    for (int i = 0; i < 5; ++i) d[i] = (base + 4 * i < end && (i < 4 || sh != 0)) ? *(const uint32_t*)(base + 4 * i) : 0u;
+    u32x4_t out;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        uint32_t w = __builtin_amdgcn_alignbyte(d[i + 1], d[i], sh);          // bytes p+4i .. p+4i+3
+        const int64_t left = (int64_t)(end - p) - 4 * i;                      // valid bytes from here on
+        if (left <= 0) w = 0;
+        else if (left < 4) w &= (1u << (8 * left)) - 1u;
+        out[i] = w;
+    }
+    *(u32x4_t*)(dst + (int64_t)blockIdx.y * dst_batch_bytes + (r * Kp + c * V) * BYTES) = out;
+}
+
+// K strided in the source (elements of one k are contiguous along the rows that become the packed
+// rows).  A workgroup transposes a tile of 64 rows x 128 bytes of K through LDS.
+template <typename IN>
+__global__ __launch_bounds__(256) void k4_pack_transpose(const char* __restrict__ src, int64_t k_bytes, int64_t rows, int64_t K,
+                                                         int64_t Kp, char* __restrict__ dst, int64_t src_batch_bytes,
+                                                         int64_t dst_batch_bytes)
 {
     using raw = typename IN::raw;
-    constexpr int KE = ROW_BYTES / IN::BYTES, V = 16 / IN::BYTES, TR = 64;
+    constexpr int BYTES = IN::BYTES, KE = ROW_BYTES / BYTES, V = 16 / BYTES, TR = 64, EPD = 4 / BYTES;
     constexpr int PITCH = KE + V;                       // elements; keeps rows 16-byte aligned, spreads banks
     __shared__ __attribute__((aligned(16))) raw tile[TR * PITCH];
-    const int t = threadIdx.x;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int64_t k0 = (int64_t)blockIdx.x * KE, r0 = (int64_t)blockIdx.y * TR;
-    src += (int64_t)blockIdx.z * src_batch;
-    dst += (int64_t)blockIdx.z * dst_batch;
-    const bool kcontig = s_k == 1;
-    for (int idx = t; idx < TR * KE; idx += 256) {
-        const int r = kcontig ? idx / KE : idx % TR, k = kcontig ? idx % KE : idx / TR;
-        const int64_t gr = r0 + r, gk = k0 + k;
-        tile[r * PITCH + k] = (gr < rows && gk < K) ? src[gr * s_r + gk * s_k] : (raw)0;
+    src += (int64_t)blockIdx.z * src_batch_bytes;
+    dst += (int64_t)blockIdx.z * dst_batch_bytes;
+    for (int i = t; i < TR * PITCH * BYTES / 16; i += 256) ((u32x4_t*)tile)[i] = u32x4_t{0, 0, 0, 0};
+    __syncthreads();
+    // source line of k: elements r0 .. r0+TR-1 are contiguous; lane l loads the l-th aligned dword of
+    // the span and drops its elements into column kk of the tile
+    const int nvalid = (int)((rows - r0) < TR ? (rows - r0) : TR);
+    for (int kk = wave; kk < KE; kk += 4) {
+        if (k0 + kk >= K) break;
+        const uintptr_t first = (uintptr_t)(src + (k0 + kk) * k_bytes + r0 * BYTES);
+        const uintptr_t end = first + (uintptr_t)(nvalid * BYTES);
+        const uintptr_t base = first & ~(uintptr_t)3;
+        const uintptr_t q = base + 4 * (uintptr_t)lane;
+        if (q < end) {
+            const uint32_t w = *(const uint32_t*)q;
+#pragma unroll
+            for (int e = 0; e < EPD; ++e) {
+                const int64_t n = ((int64_t)(q - first)) / BYTES + e;          // row inside the tile (may be -1 .. )
+                const uintptr_t at = q + (uintptr_t)(e * BYTES);
+                if (at >= first && at < end) tile[n * PITCH + kk] = (raw)(w >> (8 * BYTES * e));
+            }
+        }
     }
     __syncthreads();
     for (int idx = t; idx < TR * CHUNKS; idx += 256) {
         const int r = idx / CHUNKS, c = idx % CHUNKS;
-        if (r0 + r < rows) *(u32x4_t*)(dst + (r0 + r) * Kp + k0 + c * V) = *(const u32x4_t*)(tile + r * PITCH + c * V);
+        if (r0 + r < rows) *(u32x4_t*)(dst + ((r0 + r) * Kp + k0 + c * V) * BYTES) = *(const u32x4_t*)(tile + r * PITCH + c * V);
     }
 }
 

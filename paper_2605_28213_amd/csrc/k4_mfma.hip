@@ -118,15 +118,23 @@ static hipError_t launch_packed(const Args& a)
     const int64_t Kp = k4_packed_k(a);
     raw* pa = (raw*)a.workspace;
     raw* pb = pa + a.batch * a.M * Kp;
-    dim3 block(256, 1, 1);
-    if (a.M > 0 && Kp > 0) {
-        dim3 ga((unsigned)(Kp / KE), (unsigned)((a.M + 63) / 64), (unsigned)a.batch);
-        hipLaunchKernelGGL(k4_pack<IN>, ga, block, 0, a.stream, (const raw*)a.A, a.a_si, a.a_sk, a.M, a.K, Kp, pa, a.stride_a, a.M * Kp);
-    }
-    if (a.N > 0 && Kp > 0) {
-        dim3 gb((unsigned)(Kp / KE), (unsigned)((a.N + 63) / 64), (unsigned)a.batch);
-        hipLaunchKernelGGL(k4_pack<IN>, gb, block, 0, a.stream, (const raw*)a.B, a.b_sj, a.b_sk, a.N, a.K, Kp, pb, a.stride_b, a.N * Kp);
-    }
+    // one operand: `rows` logical rows (M or N), element strides sr along rows and sk along K
+    auto pack = [&](const void* src, int64_t sr, int64_t sk, int64_t rows, int64_t src_batch, raw* dst) {
+        if (rows <= 0 || Kp <= 0) return;
+        const int64_t dst_batch_bytes = rows * Kp * IN::BYTES, src_batch_bytes = src_batch * IN::BYTES;
+        if (sk == 1) {
+            const int64_t threads = rows * (Kp / (16 / IN::BYTES));
+            dim3 g((unsigned)((threads + 255) / 256), (unsigned)a.batch, 1);
+            hipLaunchKernelGGL(k4_pack_rows<IN>, g, dim3(256), 0, a.stream, (const char*)src, sr * IN::BYTES, rows, a.K, Kp,
+                               (char*)dst, src_batch_bytes, dst_batch_bytes);
+        } else {   // sr == 1: row- or column-major storage leaves no other case
+            dim3 g((unsigned)(Kp / KE), (unsigned)((rows + 63) / 64), (unsigned)a.batch);
+            hipLaunchKernelGGL(k4_pack_transpose<IN>, g, dim3(256), 0, a.stream, (const char*)src, sk * IN::BYTES, rows, a.K, Kp,
+                               (char*)dst, src_batch_bytes, dst_batch_bytes);
+        }
+    };
+    pack(a.A, a.a_si, a.a_sk, a.M, a.stride_a, pa);
+    pack(a.B, a.b_sj, a.b_sk, a.N, a.stride_b, pb);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     Args p = a;
