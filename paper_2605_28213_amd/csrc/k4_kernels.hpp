@@ -708,19 +708,32 @@ __global__ __launch_bounds__(256) void k4_pack_transpose(const char* __restrict_
     // source line of k: elements r0 .. r0+TR-1 are contiguous; lane l loads the l-th aligned dword of
     // the span and drops its elements into column kk of the tile
     const int nvalid = (int)((rows - r0) < TR ? (rows - r0) : TR);
-    for (int kk = wave; kk < KE; kk += 4) {
-        if (k0 + kk >= K) break;
-        const uintptr_t first = (uintptr_t)(src + (k0 + kk) * k_bytes + r0 * BYTES);
-        const uintptr_t end = first + (uintptr_t)(nvalid * BYTES);
-        const uintptr_t base = first & ~(uintptr_t)3;
-        const uintptr_t q = base + 4 * (uintptr_t)lane;
-        if (q < end) {
-            const uint32_t w = *(const uint32_t*)q;
+    constexpr int LINES = KE / 4;                       // k lines per wave: wave w takes k = w, w+4, ...
+    constexpr int BATCH = 8;                            // loads in flight per lane
+    static_assert(LINES % BATCH == 0, "the k lines of a wave come in whole batches");
+    const uintptr_t line0 = (uintptr_t)(src + r0 * BYTES);
+    for (int i0 = 0; i0 < LINES; i0 += BATCH) {
+        uint32_t w[BATCH];
 #pragma unroll
-            for (int e = 0; e < EPD; ++e) {
-                const int64_t n = ((int64_t)(q - first)) / BYTES + e;          // row inside the tile (may be -1 .. )
-                const uintptr_t at = q + (uintptr_t)(e * BYTES);
-                if (at >= first && at < end) tile[n * PITCH + kk] = (raw)(w >> (8 * BYTES * e));
+        for (int i = 0; i < BATCH; ++i) {
+            const int64_t k = k0 + wave + 4 * (i0 + i);
+            const uintptr_t first = line0 + (uintptr_t)(k * k_bytes), end = first + (uintptr_t)(nvalid * BYTES);
+            const uintptr_t q = (first & ~(uintptr_t)3) + 4 * (uintptr_t)lane;
+            w[i] = (k < K && q < end) ? *(const uint32_t*)q : 0u;
+        }
+#pragma unroll
+        for (int i = 0; i < BATCH; ++i) {
+            const int kk = wave + 4 * (i0 + i);
+            const int64_t k = k0 + kk;
+            const uintptr_t first = line0 + (uintptr_t)(k * k_bytes), end = first + (uintptr_t)(nvalid * BYTES);
+            const uintptr_t q = (first & ~(uintptr_t)3) + 4 * (uintptr_t)lane;
+            if (k < K && q < end) {
+#pragma unroll
+                for (int e = 0; e < EPD; ++e) {
+                    const int64_t n = ((int64_t)(q - first)) / BYTES + e;      // row inside the tile (-1 for a byte before it)
+                    const uintptr_t at = q + (uintptr_t)(e * BYTES);
+                    if (at >= first && at < end) tile[n * PITCH + kk] = (raw)(w[i] >> (8 * BYTES * e));
+                }
             }
         }
     }
