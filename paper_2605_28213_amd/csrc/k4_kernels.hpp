@@ -423,17 +423,20 @@ void k4_mfma_fast(Args a, int tiles_m, int tiles_n, int flags)
     static_assert(NK >= 2, "the barrier k-step is not the one that prefetches");
 
     const int64_t nslab = a.K / KE;                  // K is a whole number of slabs
-    auto kstep = [&](auto full, auto step, int64_t s, char* ra, char* rb, char* na, char* nb, char* fifth) __attribute__((always_inline)) {
-        constexpr bool FULL = decltype(full)::value;
+    // `first`: slab 0 in the branch-free form; its pre-barrier loads were issued by the prologue.  In the
+    // branching form the same holds for s == 0.
+    auto kstep = [&](auto full, auto first, auto step, int64_t s, char* ra, char* rb, char* na, char* nb, char* fifth) __attribute__((always_inline)) {
+        constexpr bool FULL = decltype(full)::value, FIRST = decltype(first)::value;
         constexpr int ks = decltype(step)::value;
-        constexpr int G0 = ks * GROUPS_PER_STEP, G1 = (ks + 1) * GROUPS_PER_STEP < 3 ? (ks + 1) * GROUPS_PER_STEP : 3;
+        constexpr int G0 = FIRST ? 3 : ks * GROUPS_PER_STEP;
+        constexpr int G1 = FIRST ? 3 : ((ks + 1) * GROUPS_PER_STEP < 3 ? (ks + 1) * GROUPS_PER_STEP : 3);
         constexpr int NLOADS = ks + 1 < NK ? (G1 > G0 ? (G1 - G0) * HALF : 0) : HALF;
         constexpr int PRE = (ks + 1 == NK && FULL && CFG::OVERLAP) ? CFG::PRE_BARRIER_MFMAS : 0;
         if constexpr (ks + 1 < NK) {
             read(ra, rb, ks + 1, (ks + 1) & 1);
-            if constexpr (G0 <= 0 && 0 < G1) { if (FULL || s + 1 < nslab) issue_b(s + 1, nb, HALF, LD); }
-            if constexpr (G0 <= 1 && 1 < G1) { if (FULL || s + 2 < nslab) issue_a(s + 2, fifth, 0, HALF); }
-            if constexpr (G0 <= 2 && 2 < G1) { if (FULL || s + 2 < nslab) issue_a(s + 2, fifth, HALF, LD); }
+            if constexpr (G0 <= 0 && 0 < G1) { if (FULL || (s > 0 && s + 1 < nslab)) issue_b(s + 1, nb, HALF, LD); }
+            if constexpr (G0 <= 1 && 1 < G1) { if (FULL || (s > 0 && s + 2 < nslab)) issue_a(s + 2, fifth, 0, HALF); }
+            if constexpr (G0 <= 2 && 2 < G1) { if (FULL || (s > 0 && s + 2 < nslab)) issue_a(s + 2, fifth, HALF, LD); }
         } else {
             // The slab's last k-step holds the barrier.  Its first PRE MFMAs (operands already in
             // registers) are issued ahead of it, so the matrix pipe has work while the waves meet.
@@ -462,28 +465,39 @@ void k4_mfma_fast(Args a, int tiles_m, int tiles_n, int flags)
     };
     // `full` = every prefetch of this slab is in range, so the body is free of branches and the
     // requested interleaving can be realised by the instruction scheduler.
-    auto slab = [&](auto full, int64_t s, char* ra, char* rb, char* na, char* nb, char* fifth) __attribute__((always_inline)) {
+    using yes = std::integral_constant<bool, true>;
+    using no = std::integral_constant<bool, false>;
+    auto slab = [&](auto full, auto first, int64_t s, char* ra, char* rb, char* na, char* nb, char* fifth) __attribute__((always_inline)) {
         for_each_step(std::make_integer_sequence<int, NK>{}, [&](auto step) __attribute__((always_inline)) {
-            kstep(full, step, s, ra, rb, na, nb, fifth);
+            kstep(full, first, step, s, ra, rb, na, nb, fifth);
         });
     };
 
-    // prologue: A_0, B_0, A_1 and the first half of B_1
+    // Prologue: fill the whole ring at once (A_0, B_0, A_1, B_1, A_2: all five regions), then wait for
+    // slab 0 only; the rest lands while slab 0 is multiplied.  Slab 0 then issues no pre-barrier loads,
+    // and its barrier wait finds the same picture as in the steady state (youngest LD loads = A_2).
     if (nslab > 0) { issue_a(0, r0, 0, LD); issue_b(0, r1, 0, LD); }
-    if (nslab > 1) { issue_a(1, r2, 0, LD); issue_b(1, r3, 0, HALF); }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
+    if (nslab > 1) { issue_a(1, r2, 0, LD); issue_b(1, r3, 0, LD); }
+    if (nslab > 2) issue_a(2, r4, 0, LD);
+    static_assert(LD == 8 || LD == 4, "the waits below count loads");
+    if (nslab > 2) { if constexpr (LD == 8) asm volatile("s_waitcnt vmcnt(24)" ::: "memory"); else asm volatile("s_waitcnt vmcnt(12)" ::: "memory"); }
+    else if (nslab > 1) { if constexpr (LD == 8) asm volatile("s_waitcnt vmcnt(16)" ::: "memory"); else asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); }
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
     if (nslab > 0) read(r0, r1, 0, 0);
-    using yes = std::integral_constant<bool, true>;
-    using no = std::integral_constant<bool, false>;
     int64_t s = 0;
-    // five slabs bring the ring back to its start
+    if (nslab > 6) {
+        slab(yes{}, yes{}, 0, r0, r1, r2, r3, r4);
+        s = 1;
+    }
+    // five slabs bring the ring back to where it was
     for (; s + 6 < nslab; s += 5) {
-        slab(yes{}, s, r0, r1, r2, r3, r4);
-        slab(yes{}, s + 1, r2, r3, r4, r0, r1);
-        slab(yes{}, s + 2, r4, r0, r1, r2, r3);
-        slab(yes{}, s + 3, r1, r2, r3, r4, r0);
-        slab(yes{}, s + 4, r3, r4, r0, r1, r2);
+        slab(yes{}, no{}, s, r2, r3, r4, r0, r1);
+        slab(yes{}, no{}, s + 1, r4, r0, r1, r2, r3);
+        slab(yes{}, no{}, s + 2, r1, r2, r3, r4, r0);
+        slab(yes{}, no{}, s + 3, r3, r4, r0, r1, r2);
+        slab(yes{}, no{}, s + 4, r0, r1, r2, r3, r4);
     }
     // tail: at most six slabs, region pointers rotate at run time, waits are conservative
     {
@@ -493,7 +507,7 @@ void k4_mfma_fast(Args a, int tiles_m, int tiles_n, int flags)
         };
         for (; s < nslab; ++s) {
             const int u = (int)((2 * s) % 5);
-            slab(no{}, s, reg(u), reg(u + 1), reg(u + 2), reg(u + 3), reg(u + 4));
+            slab(no{}, no{}, s, reg(u), reg(u + 1), reg(u + 2), reg(u + 3), reg(u + 4));
         }
     }
 
