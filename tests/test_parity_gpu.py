@@ -283,3 +283,38 @@ def test_both_tile_configurations_on_ragged_shapes(tile_flag, dtype):
             assert util.norm_err(C[:, :, :N], C_ref, D) <= util.TOL[dtype], (M, N, K, nb, od)
     d = gemm.make_desc(300, 520, 1024, dtype, out, ROW, COL, flags=tile_flag)
     assert gemm.gemm_query(4, d).bm == (256 if tile_flag == gemm.GEMM_FLAG_TILE_256 else 128)
+
+
+def test_launches_are_capturable_and_replayable_in_a_hip_graph():
+    """The library allocates nothing and only launches kernels on the given stream, so a sequence of
+    calls can be captured into a HIP graph.  Three different states and shapes are captured once and
+    replayed several times with eager work in between; every replay must reproduce the eager result
+    bit for bit."""
+    stream = torch.cuda.Stream()
+    jobs = []
+    for variant, name in ((gemm.GEMM_K4_MFMA, "C2_small"), (gemm.GEMM_K4_MFMA, "C4_small"), (gemm.GEMM_K1_LDS_TILED, "C1")):
+        cfg = gen.CONFIGS[name]
+        inp = gen.make_inputs(cfg, 5)
+        dA, dB = util.dev(inp.A), util.dev(inp.B)
+        dC = util.out_buffer(cfg.batch * inp.stride_c, cfg.out_dtype)
+        d = gemm.make_desc(cfg.M, cfg.N, cfg.K, cfg.in_dtype, cfg.out_dtype, cfg.layout_a, cfg.layout_b, lda=inp.lda,
+                           ldb=inp.ldb, ldc=inp.ldc, stream=stream)
+        jobs.append((variant, d, dA, dB, dC))
+    torch.cuda.synchronize()
+    with torch.cuda.stream(stream):
+        for variant, d, dA, dB, dC in jobs:
+            assert gemm.gemm_run_ex(variant, d, dA, dB, dC) == gemm.GEMM_OK
+    stream.synchronize()
+    eager = [dC.clone() for *_, dC in jobs]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        for variant, d, dA, dB, dC in jobs:
+            assert gemm.gemm_run_ex(variant, d, dA, dB, dC) == gemm.GEMM_OK
+    for replay in range(3):
+        for *_, dC in jobs:
+            dC.fill_(0xFF)                                   # eager work between replays (a fill kernel)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for want, (*_, dC) in zip(eager, jobs):
+            assert torch.equal(want, dC), f"replay {replay} differs from the eager result"
