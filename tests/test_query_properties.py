@@ -1,0 +1,94 @@
+"""Property tests of the host-side planner (gemm_query never launches, so no GPU is needed).
+
+For arbitrary valid descriptors: the condition masks are consistent, STRICT turns exactly the calls
+with violated conditions into refusals, the reported scratch follows the packed layout, tile and
+simplification switches are accepted only where they mean something, and the launch geometry covers
+the problem.
+"""
+import math
+
+from hypothesis import given, settings, strategies as st
+
+from paper_2605_28213_amd import gemm
+
+DT = st.sampled_from([gemm.GEMM_F32, gemm.GEMM_BF16, gemm.GEMM_F16, gemm.GEMM_FP8_E4M3])
+LAYOUT = st.sampled_from([gemm.GEMM_ROW_MAJOR, gemm.GEMM_COL_MAJOR])
+ES = {gemm.GEMM_F32: 4, gemm.GEMM_BF16: 2, gemm.GEMM_F16: 2, gemm.GEMM_FP8_E4M3: 1}
+
+
+@st.composite
+def descriptors(draw):
+    M, N, K = draw(st.integers(1, 5000)), draw(st.integers(1, 5000)), draw(st.integers(1, 5000))
+    dt = draw(DT)
+    la, lb = draw(LAYOUT), draw(LAYOUT)
+    out = gemm.GEMM_BF16 if dt == gemm.GEMM_FP8_E4M3 else dt
+    pad = draw(st.sampled_from([0, 0, 1, 3, 8, 16]))
+    lda = (K if la == gemm.GEMM_ROW_MAJOR else M) + pad
+    ldb = (N if lb == gemm.GEMM_ROW_MAJOR else K) + pad
+    return dict(M=M, N=N, K=K, dt=dt, out=out, la=la, lb=lb, lda=lda, ldb=ldb, ldc=N + pad, batch=draw(st.integers(1, 4)))
+
+
+def make(p, **kw):
+    return gemm.make_desc(p["M"], p["N"], p["K"], p["dt"], p["out"], p["la"], p["lb"], lda=p["lda"], ldb=p["ldb"],
+                          ldc=p["ldc"], batch=p["batch"], **kw)
+
+
+@settings(max_examples=300, deadline=None)
+@given(descriptors(), st.integers(0, 4))
+def test_masks_status_and_geometry_are_consistent(p, variant):
+    q = gemm.gemm_query(variant, make(p))
+    assert q.status in (gemm.GEMM_OK, gemm.GEMM_ERR_PRECONDITION)
+    assert q.violated == q.required & ~q.holds
+    no_mfma = variant == gemm.GEMM_K4_MFMA and p["dt"] == gemm.GEMM_F32
+    assert (q.status == gemm.GEMM_ERR_PRECONDITION) == no_mfma          # every other violation has a slow path
+    strict = gemm.gemm_query(variant, make(p, flags=gemm.GEMM_FLAG_STRICT))
+    assert (strict.status == gemm.GEMM_ERR_PRECONDITION) == (q.violated != 0)
+    assert strict.path == q.path and strict.violated == q.violated
+    if q.status == gemm.GEMM_OK:
+        assert q.path and q.threads in (64, 128, 256) and q.grid >= 1
+        if q.bm and q.bn and "stream" not in q.path:
+            assert q.grid >= math.ceil(p["M"] / q.bm) * math.ceil(p["N"] / q.bn) * p["batch"] or "M-tail" in q.path
+        assert q.lds_bytes <= 160 * 1024
+
+
+@settings(max_examples=300, deadline=None)
+@given(descriptors())
+def test_expert_state_paths_and_scratch(p):
+    if p["dt"] == gemm.GEMM_F32:
+        return
+    es = ES[p["dt"]]
+    q = gemm.gemm_query(gemm.GEMM_K4_MFMA, make(p))
+    fast_ok = (p["la"] == gemm.GEMM_ROW_MAJOR and p["lb"] == gemm.GEMM_COL_MAJOR and (p["lda"] * es) % 16 == 0
+               and (p["ldb"] * es) % 16 == 0 and (p["batch"] == 1 or ((p["M"] * p["lda"] * es) % 16 == 0 and (p["N"] * p["ldb"] * es) % 16 == 0)))
+    kvec, kslab = 16 // es, 128 // es
+    if fast_ok and p["M"] <= 16 and p["K"] % kvec == 0 and es == 2:
+        assert q.path == "mfma16-stream(small-M)" and q.workspace_bytes == 0
+    elif fast_ok and p["K"] % kslab == 0:
+        assert q.path.startswith("mfma32-direct-to-lds") and q.workspace_bytes == 0 and q.violated == 0
+    else:
+        kp = math.ceil(p["K"] / kslab) * kslab
+        assert q.path.startswith("mfma32-") and "packed" not in q.path
+        assert q.workspace_bytes == p["batch"] * (p["M"] + p["N"]) * kp * es
+        lent = gemm.gemm_query(gemm.GEMM_K4_MFMA, make(p, workspace=4096, workspace_bytes=q.workspace_bytes))
+        assert lent.status == gemm.GEMM_OK and lent.path.startswith("mfma32-packed+direct-to-lds")
+        small = gemm.gemm_query(gemm.GEMM_K4_MFMA, make(p, workspace=4096, workspace_bytes=q.workspace_bytes - 1))
+        assert small.status == gemm.GEMM_ERR_WORKSPACE
+        odd = gemm.gemm_query(gemm.GEMM_K4_MFMA, make(p, workspace=4100, workspace_bytes=q.workspace_bytes))
+        assert odd.status == gemm.GEMM_ERR_WORKSPACE
+
+
+@settings(max_examples=200, deadline=None)
+@given(descriptors(), st.integers(0, 4), st.sampled_from([gemm.GEMM_FLAG_TILE_128, gemm.GEMM_FLAG_TILE_256,
+                                                         gemm.GEMM_FLAG_DEOPT_NO_SWIZZLE, gemm.GEMM_FLAG_DEOPT_NO_OVERLAP]))
+def test_expert_only_switches_are_refused_elsewhere(p, variant, flag):
+    plain = gemm.gemm_query(variant, make(p))
+    q = gemm.gemm_query(variant, make(p, flags=flag))
+    on_fast_kernel = variant == gemm.GEMM_K4_MFMA and plain.status == gemm.GEMM_OK and plain.path.startswith("mfma32-direct-to-lds")
+    if on_fast_kernel:
+        assert q.status == gemm.GEMM_OK
+        if flag == gemm.GEMM_FLAG_TILE_128:
+            assert (q.bm, q.bn) == (128, 128)
+        if flag in (gemm.GEMM_FLAG_TILE_256, gemm.GEMM_FLAG_DEOPT_NO_SWIZZLE, gemm.GEMM_FLAG_DEOPT_NO_OVERLAP):
+            assert (q.bm, q.bn) == (256, 256)
+    elif plain.status == gemm.GEMM_OK:
+        assert q.status == gemm.GEMM_ERR_BAD_ARG
