@@ -81,15 +81,16 @@ def main():
             sets.append((A, B, C))
         sa = torch.from_numpy(inp.scale_a).cuda() if inp.scale_a is not None else None
         sb = torch.from_numpy(inp.scale_b).cuda() if inp.scale_b is not None else None
+        bias = torch.from_numpy(inp.bias).cuda() if inp.bias is not None else None
         d = gemm.make_desc(cfg.M, cfg.N, cfg.K, cfg.in_dtype, cfg.out_dtype, cfg.layout_a, cfg.layout_b,
                            lda=inp.lda, ldb=inp.ldb, ldc=inp.ldc, batch=cfg.batch, stride_a=inp.stride_a,
-                           stride_b=inp.stride_b, stride_c=inp.stride_c, scale_a=sa, scale_b=sb, stream=stream)
+                           stride_b=inp.stride_b, stride_c=inp.stride_c, scale_a=sa, scale_b=sb, bias=bias, stream=stream)
         # lend the scratch K4's packed path asks for (only the ragged fp16 workload needs any)
         need = gemm.gemm_query(gemm.GEMM_K4_MFMA, d, *sets[0]).workspace_bytes if cfg.in_dtype != gen.F32 else 0
         ws = torch.empty(need, dtype=torch.uint8, device="cuda") if need else None
         if ws is not None:
             d.workspace, d.workspace_bytes = ws.data_ptr(), need
-        return inp, sets, d, (sa, sb, ws)
+        return inp, sets, d, (sa, sb, bias, ws)
 
     def timed(variant, sets, d, steps, warmup):
         """Returns (wall seconds for `steps` launches, list of per-launch ms from HIP events)."""
@@ -212,9 +213,10 @@ def main():
         paper_ms = {"P4096": ("KLineage CUDA, H100 PCIe / RTX PRO 6000, App. A", (0.3130, 0.3681)),
                     "P2048": ("TileLang +cfg, RTX PRO 6000, App. D", (0.074,)),
                     "PBMM16": ("TileLang +cfg, RTX PRO 6000, App. D", (0.703,)),
-                    "PBMM32": ("TileLang +cfg, RTX PRO 6000, App. D", (0.226,))}
+                    "PBMM32": ("TileLang +cfg, RTX PRO 6000, App. D", (0.226,)),
+                    "PADDMM": ("TileLang +cfg, RTX PRO 6000, App. D", (0.375,))}
         for name, bound in (("C1", "alu"), ("C3", "mfma"), ("C4", "hbm"), ("C5", "mfma"), ("P4096", "mfma"),
-                            ("P2048", "mfma"), ("PBMM16", "mfma"), ("PBMM32", "mfma")):
+                            ("P2048", "mfma"), ("PBMM16", "mfma"), ("PBMM32", "mfma"), ("PADDMM", "mfma")):
             c = gen.CONFIGS[name]
             v = gemm.GEMM_K3_PIPELINED if name == "C1" else gemm.GEMM_K4_MFMA
             _, s2, d2, keep2 = device_sets(c)

@@ -110,6 +110,9 @@ typedef struct {
     const float *scale_a, *scale_b;  /* device: one fp32 per batch item each, or NULL (= 1).  The
                                         epilogue multiplies the fp32 accumulator by scale_a[b]*scale_b[b]
                                         before rounding to out_dtype (round to nearest even). */
+    const float *bias;               /* device: N fp32 values or NULL.  C[b,i,j] = round(s_b * acc + bias[j]):
+                                        the "AddMM" shape of the paper's held-out GEMM family (App. D),
+                                        fused into every state's epilogue; shared by all batch items. */
     void *workspace;                 /* optional device scratch lent by the caller (16-byte aligned), or NULL.
                                         Only K4 uses it: when its fast path's conditions fail and scratch of at
                                         least gemm_query's workspace_bytes is lent, it packs both operands
@@ -180,6 +183,8 @@ int gemm_probe_mfma(int dtype, const void *operands, size_t operand_bytes, int w
                     void *sink, size_t sink_bytes, double *flops, void *stream);
 
 const char *gemm_status_string(int status);
+/* The HIP runtime's message for the calling thread's most recent GEMM_ERR_LAUNCH ("no error" if none). */
+const char *gemm_last_launch_error(void);
 const char *gemm_variant_name(int variant);
 const char *gemm_variant_intent(int variant); /* Table 1 intent the transition into this state adds */
 const char *gemm_cond_name(uint32_t single_bit);

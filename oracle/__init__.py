@@ -100,9 +100,13 @@ def _check_storage(dtype: int, a: np.ndarray, name: str) -> np.ndarray:
 def gemm(dtype: int, layout_a: int, layout_b: int, M: int, N: int, K: int,
          A: np.ndarray, lda: int, B: np.ndarray, ldb: int, *, batch: int = 1,
          stride_a: int = 0, stride_b: int = 0,
-         scale_a: Optional[np.ndarray] = None, scale_b: Optional[np.ndarray] = None
-         ) -> Tuple[np.ndarray, np.ndarray]:
-    """Full oracle product.  Returns (C_ref, D), each fp64 of shape (batch, M, N)."""
+         scale_a: Optional[np.ndarray] = None, scale_b: Optional[np.ndarray] = None,
+         bias: Optional[np.ndarray] = None) -> Tuple[np.ndarray, np.ndarray]:
+    """Full oracle product.  Returns (C_ref, D), each fp64 of shape (batch, M, N).
+
+    With `bias` (N fp32 values, the AddMM shape of the paper's App. D): C_ref[b,i,j] += bias[j] and
+    D[b,i,j] += |bias[j]|, both in fp64, so that the acceptance metric stays a bound relative to the
+    magnitude of the terms summed."""
     lib = _load()
     A = _check_storage(dtype, A, "A")
     B = _check_storage(dtype, B, "B")
@@ -117,6 +121,10 @@ def gemm(dtype: int, layout_a: int, layout_b: int, M: int, N: int, K: int,
                          _ptr(scale_a), _ptr(scale_b), _ptr(C), _ptr(D), max(N, 1), M * N)
     if rc != 0:
         raise ValueError(f"oracle_gemm rejected its arguments (code {rc})")
+    if bias is not None:
+        bias64 = np.asarray(bias, dtype=np.float32).astype(np.float64).reshape(1, 1, N)
+        C += bias64
+        D += np.abs(bias64)
     return C, D
 
 
@@ -124,9 +132,10 @@ def gemm_points(dtype: int, layout_a: int, layout_b: int, M: int, N: int, K: int
                 A: np.ndarray, lda: int, B: np.ndarray, ldb: int,
                 pb: np.ndarray, pi: np.ndarray, pj: np.ndarray, *, batch: int = 1,
                 stride_a: int = 0, stride_b: int = 0,
-                scale_a: Optional[np.ndarray] = None, scale_b: Optional[np.ndarray] = None
-                ) -> Tuple[np.ndarray, np.ndarray]:
-    """Oracle values at selected (batch, i, j) points.  Returns (C_ref, D), each fp64 of shape (n,)."""
+                scale_a: Optional[np.ndarray] = None, scale_b: Optional[np.ndarray] = None,
+                bias: Optional[np.ndarray] = None) -> Tuple[np.ndarray, np.ndarray]:
+    """Oracle values at selected (batch, i, j) points.  Returns (C_ref, D), each fp64 of shape (n,).
+    `bias` as in gemm()."""
     lib = _load()
     A = _check_storage(dtype, A, "A")
     B = _check_storage(dtype, B, "B")
@@ -148,4 +157,8 @@ def gemm_points(dtype: int, layout_a: int, layout_b: int, M: int, N: int, K: int
                                 _ptr(C), _ptr(D))
     if rc != 0:
         raise ValueError(f"oracle_gemm_points rejected its arguments (code {rc})")
+    if bias is not None:
+        bias64 = np.asarray(bias, dtype=np.float32).astype(np.float64)[pj]
+        C += bias64
+        D += np.abs(bias64)
     return C, D

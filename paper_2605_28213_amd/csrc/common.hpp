@@ -20,6 +20,7 @@ struct Args {
     void* C;
     const float* scale_a;
     const float* scale_b;
+    const float* bias;
     void* workspace;
     int64_t M, N, K, batch;
     int64_t a_si, a_sk;  // A(i,k) at i*a_si + k*a_sk

@@ -14,7 +14,8 @@ using namespace gl;
 
 namespace {
 
-constexpr int ABI_VERSION = 1;
+constexpr int ABI_VERSION = 2;
+thread_local hipError_t last_launch_error = hipSuccess;   // of the calling thread's most recent GEMM_ERR_LAUNCH
 
 bool dtype_pair_supported(int in, int out)
 {
@@ -91,7 +92,7 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
 
     Args& a = p.args;
     a.A = A; a.B = B; a.C = (void*)C;
-    a.scale_a = d->scale_a; a.scale_b = d->scale_b;
+    a.scale_a = d->scale_a; a.scale_b = d->scale_b; a.bias = d->bias;
     a.workspace = d->workspace;
     a.M = d->M; a.N = d->N; a.K = d->K; a.batch = d->batch;
     a.a_si = d->layout_a == GEMM_ROW_MAJOR ? d->lda : 1;
@@ -249,6 +250,7 @@ int gemm_run_ex(int variant, const gemm_desc_t* d, const void* A, const void* B,
     Plan p = make_plan(variant, d, A, B, C, /*need_ptrs=*/true);
     if (p.status != GEMM_OK) return p.status;
     if (p.empty) return GEMM_OK;
+    (void)hipGetLastError();   // the thread's last-error slot may hold someone else's stale error: GEMM_ERR_LAUNCH must mean this launch
     hipError_t e;
     switch (variant) {
     case GEMM_K0_NAIVE: e = launch_k0(p.args); break;
@@ -257,8 +259,11 @@ int gemm_run_ex(int variant, const gemm_desc_t* d, const void* A, const void* B,
     case GEMM_K3_PIPELINED: e = launch_valu_tiled(variant, p.path, p.args); break;
     default: e = launch_k4(p.path, p.args); break;
     }
+    if (e != hipSuccess) last_launch_error = e;
     return e == hipSuccess ? GEMM_OK : GEMM_ERR_LAUNCH;
 }
+
+const char* gemm_last_launch_error(void) { return hipGetErrorString(last_launch_error); }
 
 int gemm_run(int variant, int64_t M, int64_t N, int64_t K, int dtype, const void* A, const void* B, void* C)
 {

@@ -18,7 +18,7 @@ __global__ __launch_bounds__(K0_TX* K0_TY) void k0_naive(Args a)
     float acc = 0.0f;
     for (int64_t k = 0; k < a.K; ++k)
         acc = __builtin_fmaf(decode<IN>(A[k * a.a_sk]), decode<IN>(B[k * a.b_sk]), acc);
-    store_out(a.C, b * a.stride_c + i * a.ldc + j, acc * batch_scale(a, b), a.out_dtype);
+    store_out(a.C, b * a.stride_c + i * a.ldc + j, acc * batch_scale(a, b) + (a.bias ? a.bias[j] : 0.0f), a.out_dtype);
 }
 
 Geometry geometry_k0(const Args& a)

@@ -227,7 +227,7 @@ __global__ __launch_bounds__(CFG::THREADS) void valu_tiled(Args a, int vec_mask)
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int64_t gj = ob.r0 + (j / 4) * (BN / CN) + tx * 4 + (j % 4);
-            if (gj < a.N) store_out(a.C, b * a.stride_c + gi * a.ldc + gj, acc[i][j] * s, a.out_dtype);
+            if (gj < a.N) store_out(a.C, b * a.stride_c + gi * a.ldc + gj, acc[i][j] * s + (a.bias ? a.bias[gj] : 0.0f), a.out_dtype);
         }
     }
 }

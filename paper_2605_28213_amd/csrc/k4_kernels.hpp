@@ -97,7 +97,7 @@ __device__ __forceinline__ void store_tiles_as(const Args& a, int64_t b, const f
             for (int r = 0; r < 16; ++r) {
                 const int64_t gi = row0 + i * 32 + 8 * (r / 4) + 4 * lhalf + (r % 4);
                 if (gi < a.M && gj < a.N) {
-                    const float v = acc[i][j][r] * sc;
+                    const float v = acc[i][j][r] * sc + (a.bias ? a.bias[gj] : 0.0f);
                     const int64_t idx = gi * a.ldc + gj;
                     if constexpr (OUT == GEMM_F32) ((float*)C)[idx] = v;
                     else if constexpr (OUT == GEMM_BF16) ((uint16_t*)C)[idx] = encode_bf16(v);
@@ -136,14 +136,28 @@ __device__ __forceinline__ void store_tiles_staged(const Args& a, int64_t b, con
     const float sc = batch_scale(a, b);
     const int lrow = lane & 31, lhalf = lane >> 5;
     char* C = (char*)a.C + (b * a.stride_c) * OB;
+    // bias of the four columns a lane holds per (column tile, register quad), the same for every row block
+    f32x4_t bv[TNI][4];
+#pragma unroll
+    for (int j = 0; j < TNI; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            bv[j][g] = f32x4_t{0, 0, 0, 0};
+            if (a.bias) {
+                const int64_t gj = col0 + j * 32 + 8 * g + 4 * lhalf;
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (INTERIOR || gj + c < a.N) bv[j][g][c] = a.bias[gj + c];
+            }
+        }
 #pragma unroll
     for (int i = 0; i < TMI; ++i) {
 #pragma unroll
         for (int j = 0; j < TNI; ++j)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const float v0 = acc[i][j][4 * g] * sc, v1 = acc[i][j][4 * g + 1] * sc;
-                const float v2 = acc[i][j][4 * g + 2] * sc, v3 = acc[i][j][4 * g + 3] * sc;
+                const float v0 = acc[i][j][4 * g] * sc + bv[j][g][0], v1 = acc[i][j][4 * g + 1] * sc + bv[j][g][1];
+                const float v2 = acc[i][j][4 * g + 2] * sc + bv[j][g][2], v3 = acc[i][j][4 * g + 3] * sc + bv[j][g][3];
                 char* dst = stage + lrow * PITCH + (j * 32 + 8 * g + 4 * lhalf) * OB;
                 if constexpr (OUT == GEMM_F32) {
                     *(f32x4_t*)dst = f32x4_t{v0, v1, v2, v3};
@@ -948,7 +962,8 @@ __global__ __launch_bounds__(CFG::WAVES * 64) void k4_stream(Args a)
         float v = 0.0f;
 #pragma unroll
         for (int w = 0; w < WAVES; ++w) v += part[(w * 16 + i) * (COLS + 1) + j];
-        if (i < a.M && j0 + j < a.N) store_out(a.C, b * a.stride_c + (int64_t)i * a.ldc + j0 + j, v * sc, a.out_dtype);
+        if (i < a.M && j0 + j < a.N)
+            store_out(a.C, b * a.stride_c + (int64_t)i * a.ldc + j0 + j, v * sc + (a.bias ? a.bias[j0 + j] : 0.0f), a.out_dtype);
     }
 }
 

@@ -98,6 +98,7 @@ extern "C" {
 int gemm_probe_copy(void* dst, const void* src, size_t bytes, void* stream)
 {
     if (!dst || !src || bytes == 0 || bytes % 16 || ((uintptr_t)dst & 15u) || ((uintptr_t)src & 15u)) return GEMM_ERR_BAD_ARG;
+    (void)hipGetLastError();
     hipLaunchKernelGGL(probe_copy, dim3(4096), dim3(256), 0, (hipStream_t)stream, (u32x4_t*)dst, (const u32x4_t*)src, bytes / 16);
     return hipGetLastError() == hipSuccess ? GEMM_OK : GEMM_ERR_LAUNCH;
 }
@@ -105,6 +106,7 @@ int gemm_probe_copy(void* dst, const void* src, size_t bytes, void* stream)
 int gemm_probe_stream_read(const void* src, size_t bytes, void* sink, void* stream)
 {
     if (!src || !sink || bytes == 0 || bytes % 16 || ((uintptr_t)src & 15u)) return GEMM_ERR_BAD_ARG;
+    (void)hipGetLastError();
     hipLaunchKernelGGL(probe_stream_read, dim3(4096), dim3(256), 0, (hipStream_t)stream, (const u32x4_t*)src, bytes / 16, (uint32_t*)sink);
     return hipGetLastError() == hipSuccess ? GEMM_OK : GEMM_ERR_LAUNCH;
 }
@@ -125,6 +127,7 @@ int gemm_probe_mfma(int dtype, const void* operands, size_t operand_bytes, int w
     const double per_mfma = dtype == GEMM_FP8_E4M3 ? 2.0 * 32 * 32 * 64 : 2.0 * 32 * 32 * 16;
     if (flops) *flops = (double)workgroups * 4 * iters * 2 * 16 * per_mfma;
     dim3 grid((unsigned)workgroups), block(256);
+    (void)hipGetLastError();
     hipStream_t st = (hipStream_t)stream;
     if (dtype == GEMM_BF16) hipLaunchKernelGGL(probe_mfma<BF16>, grid, block, 0, st, (const char*)operands, iters, (float*)sink);
     else if (dtype == GEMM_F16) hipLaunchKernelGGL(probe_mfma<F16>, grid, block, 0, st, (const char*)operands, iters, (float*)sink);

@@ -120,11 +120,12 @@ def run_gate(variant: int, cfg: gen.Config, reference: Callable[[gen.Inputs], Re
         dB = torch.from_numpy(np.ascontiguousarray(inp.B).reshape(-1).view(np.uint8)).cuda()
         sa = torch.from_numpy(inp.scale_a).cuda() if inp.scale_a is not None else None
         sb = torch.from_numpy(inp.scale_b).cuda() if inp.scale_b is not None else None
+        bias = torch.from_numpy(inp.bias).cuda() if inp.bias is not None else None
         n_out = max(1, cfg.batch * inp.stride_c)
         dC = torch.full((n_out * _OUT_BYTES[cfg.out_dtype],), 0xFF, dtype=torch.uint8, device="cuda")
         d = gemm.make_desc(cfg.M, cfg.N, cfg.K, cfg.in_dtype, cfg.out_dtype, cfg.layout_a, cfg.layout_b,
                            lda=inp.lda, ldb=inp.ldb, ldc=inp.ldc, batch=cfg.batch, stride_a=inp.stride_a,
-                           stride_b=inp.stride_b, stride_c=inp.stride_c, scale_a=sa, scale_b=sb, stream=stream,
+                           stride_b=inp.stride_b, stride_c=inp.stride_c, scale_a=sa, scale_b=sb, bias=bias, stream=stream,
                            flags=flags)
         # lend the scratch the state's packed path asks for (K4 on operands that break its fast path)
         ws = None

@@ -36,7 +36,7 @@ class gemm_desc_t(ctypes.Structure):
                 ("layout_a", ctypes.c_int32), ("layout_b", ctypes.c_int32),
                 ("lda", ctypes.c_int64), ("ldb", ctypes.c_int64), ("ldc", ctypes.c_int64),
                 ("stride_a", ctypes.c_int64), ("stride_b", ctypes.c_int64), ("stride_c", ctypes.c_int64),
-                ("scale_a", ctypes.c_void_p), ("scale_b", ctypes.c_void_p),
+                ("scale_a", ctypes.c_void_p), ("scale_b", ctypes.c_void_p), ("bias", ctypes.c_void_p),
                 ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
                 ("stream", ctypes.c_void_p), ("flags", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
 
@@ -63,6 +63,14 @@ def lib() -> ctypes.CDLL:
             raise GemmLibraryMissing(
                 f"{LIB_PATH} not found: build it with `python -m paper_2605_28213_amd.build` "
                 "(there is no CPU fallback for the GEMM lineage)")
+        # PyTorch ships its own copy of the HIP runtime.  If this library were loaded first it would
+        # pull in the system's copy, PyTorch would then load its own, and the second runtime in a
+        # process cannot open the GPU ("no ROCm-capable device is detected" on the first launch).
+        # Importing torch first makes its runtime the one both sides use.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = ctypes.CDLL(LIB_PATH)
         i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
         L.gemm_run.restype = ci
@@ -76,6 +84,8 @@ def lib() -> ctypes.CDLL:
         for name in ("gemm_status_string", "gemm_variant_name", "gemm_variant_intent"):
             getattr(L, name).restype = ctypes.c_char_p
             getattr(L, name).argtypes = [ci]
+        L.gemm_last_launch_error.restype = ctypes.c_char_p
+        L.gemm_last_launch_error.argtypes = []
         L.gemm_cond_name.restype = ctypes.c_char_p
         L.gemm_cond_name.argtypes = [ctypes.c_uint32]
         L.gemm_variant_count.restype = ci
@@ -113,7 +123,7 @@ def gemm_default_desc(M: int, N: int, K: int, dtype: int) -> gemm_desc_t:
 
 def make_desc(M: int, N: int, K: int, in_dtype: int, out_dtype: int, layout_a: int, layout_b: int, *,
               lda: int = 0, ldb: int = 0, ldc: int = 0, batch: int = 1, stride_a: int = -1, stride_b: int = -1,
-              stride_c: int = -1, scale_a: Any = None, scale_b: Any = None, stream: Any = None,
+              stride_c: int = -1, scale_a: Any = None, scale_b: Any = None, bias: Any = None, stream: Any = None,
               workspace: Any = None, workspace_bytes: int = 0, flags: int = 0) -> gemm_desc_t:
     """Fill a descriptor; tight leading dimensions and batch strides unless given."""
     d = gemm_desc_t()
@@ -125,7 +135,7 @@ def make_desc(M: int, N: int, K: int, in_dtype: int, out_dtype: int, layout_a: i
     d.stride_a = stride_a if stride_a >= 0 else (M if layout_a == GEMM_ROW_MAJOR else K) * d.lda
     d.stride_b = stride_b if stride_b >= 0 else (K if layout_b == GEMM_ROW_MAJOR else N) * d.ldb
     d.stride_c = stride_c if stride_c >= 0 else M * d.ldc
-    d.scale_a, d.scale_b = _addr(scale_a), _addr(scale_b)
+    d.scale_a, d.scale_b, d.bias = _addr(scale_a), _addr(scale_b), _addr(bias)
     d.workspace, d.workspace_bytes = _addr(workspace), workspace_bytes
     d.stream = _addr(stream) if not hasattr(stream, "cuda_stream") else int(stream.cuda_stream)
     d.flags, d.reserved = flags, 0
@@ -215,3 +225,7 @@ def gemm_probe_mfma(dtype: int, operands: Any, operand_bytes: int, workgroups: i
     rc = int(lib().gemm_probe_mfma(dtype, _addr(operands), operand_bytes, workgroups, iters, _addr(sink), sink_bytes,
                                    ctypes.byref(fl), _stream_addr(stream)))
     return rc, fl.value
+
+
+def gemm_last_launch_error() -> str:
+    return lib().gemm_last_launch_error().decode()

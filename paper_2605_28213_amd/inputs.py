@@ -163,6 +163,7 @@ class Config:
     rsqrt_k: bool = False
     batch: int = 1
     scaled: bool = False      # per-problem scale_a[b], scale_b[b] ~ U[0.5, 2]
+    biased: bool = False      # bias[j] ~ N(0, 1), fp32, added in the epilogue (AddMM)
     lda: int = 0              # 0 = tight
     ldb: int = 0
     ldc: int = 0
@@ -198,6 +199,7 @@ CONFIGS: Dict[str, Config] = {
     "P2048": Config("P2048", 2048, 2048, 2048, BF16, BF16, ROW_MAJOR, COL_MAJOR, "normal", rsqrt_k=True),
     "PBMM16": Config("PBMM16", 2048, 2048, 2048, BF16, BF16, ROW_MAJOR, COL_MAJOR, "normal", rsqrt_k=True, batch=16),
     "PBMM32": Config("PBMM32", 1024, 1024, 1024, BF16, BF16, ROW_MAJOR, COL_MAJOR, "normal", rsqrt_k=True, batch=32),
+    "PADDMM": Config("PADDMM", 4096, 4096, 4096, BF16, BF16, ROW_MAJOR, COL_MAJOR, "normal", rsqrt_k=True, biased=True),
     # reduced-size counterparts: same dtype / layout / distribution / raggedness
     "C2_small": Config("C2_small", 512, 768, 640, BF16, BF16, ROW_MAJOR, COL_MAJOR, "normal", rsqrt_k=True),
     "C3_small": Config("C3_small", 387, 301, 259, F16, F16, ROW_MAJOR, ROW_MAJOR, "uniform"),
@@ -205,7 +207,7 @@ CONFIGS: Dict[str, Config] = {
     "C5_small": Config("C5_small", 256, 256, 256, E4M3, BF16, ROW_MAJOR, COL_MAJOR, "normal", batch=3, scaled=True),
 }
 
-TENSOR_A, TENSOR_B, TENSOR_SCALE_A, TENSOR_SCALE_B = 1, 2, 3, 4
+TENSOR_A, TENSOR_B, TENSOR_SCALE_A, TENSOR_SCALE_B, TENSOR_BIAS = 1, 2, 3, 4, 5
 
 
 def _draw(cfg: Config, seed: int, tensor: int, count: int) -> np.ndarray:
@@ -232,6 +234,7 @@ class Inputs:
     stride_c: int
     scale_a: Optional[np.ndarray] = None    # fp32, one per batch item
     scale_b: Optional[np.ndarray] = None
+    bias: Optional[np.ndarray] = None       # fp32, N values
     meta: dict = field(default_factory=dict)
 
 
@@ -247,4 +250,5 @@ def make_inputs(cfg: Config, seed: int) -> Inputs:
     if cfg.scaled:
         sa = uniform_range(seed, TENSOR_SCALE_A, cfg.batch, 0.5, 2.0)
         sb = uniform_range(seed, TENSOR_SCALE_B, cfg.batch, 0.5, 2.0)
-    return Inputs(cfg, seed, A, B, lda, ldb, ldc, stride_a, stride_b, stride_c, sa, sb)
+    bias = normal(seed, TENSOR_BIAS, cfg.N, 1.0).astype(np.float32) if cfg.biased else None
+    return Inputs(cfg, seed, A, B, lda, ldb, ldc, stride_a, stride_b, stride_c, sa, sb, bias)

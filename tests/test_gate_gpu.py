@@ -61,13 +61,13 @@ class OracleReference:
         if c.flops <= 1e9:
             C_ref, D = oracle.gemm(c.in_dtype, c.layout_a, c.layout_b, c.M, c.N, c.K, inp.A, inp.lda, inp.B, inp.ldb,
                                    batch=c.batch, stride_a=inp.stride_a, stride_b=inp.stride_b,
-                                   scale_a=inp.scale_a, scale_b=inp.scale_b)
+                                   scale_a=inp.scale_a, scale_b=inp.scale_b, bias=inp.bias)
             ref = gate.Reference(C_ref, D)
         else:
             pts = sample_points(c, np.random.default_rng(100 + inp.seed))
             C_ref, D = oracle.gemm_points(c.in_dtype, c.layout_a, c.layout_b, c.M, c.N, c.K, inp.A, inp.lda, inp.B,
                                           inp.ldb, *pts, batch=c.batch, stride_a=inp.stride_a, stride_b=inp.stride_b,
-                                          scale_a=inp.scale_a, scale_b=inp.scale_b)
+                                          scale_a=inp.scale_a, scale_b=inp.scale_b, bias=inp.bias)
             ref = gate.Reference(C_ref, D, pts)
         self.cache[inp.seed] = ref
         return ref
@@ -102,10 +102,10 @@ def test_every_state_passes_the_gate(name):
     torch.cuda.empty_cache()
 
 
-@pytest.mark.parametrize("name", ["P4096", "P2048", "PBMM16", "PBMM32"])
+@pytest.mark.parametrize("name", ["P4096", "P2048", "PBMM16", "PBMM32", "PADDMM"])
 def test_paper_shapes_pass_the_gate(name):
-    """The paper's own GEMM shape and its held-out plain and batched GEMM shapes (bf16): the expert
-    state at three seeds, the earlier states at one."""
+    """The paper's own GEMM shape and its held-out plain, batched and bias-added GEMM shapes (bf16):
+    the expert state at three seeds, the earlier states at one."""
     cfg = gen.CONFIGS[name]
     reference, cache = OracleReference(cfg), {}
     for v in reversed(range(gemm.GEMM_VARIANT_COUNT)):

@@ -308,3 +308,21 @@ def test_output_rounding_probe_fits_tolerance(oracle):
     back = oracle.decode(F16, stored)
     assert back[0] == 4096.0
     assert abs(back[0] - C[0, 0]) / D[0, 0] == pytest.approx(1 / 4097) and 1 / 4097 < 1e-2
+
+
+def test_bias_term_closed_forms(oracle):
+    """With A = 0 the result is the bias alone, exactly, and D = |bias|; with all-ones operands
+    C = K + bias[j] exactly; the point form agrees with the full form; the bias is shared by a batch."""
+    M, N, K, nb = 5, 7, 9, 2
+    bias = (np.arange(N, dtype=np.float32) - 3.0) * 0.25
+    zero = np.zeros(nb * M * K, dtype=np.float32)
+    ones_a, ones_b = np.ones(nb * M * K, dtype=np.float32), np.ones(nb * K * N, dtype=np.float32)
+    C, D = oracle.gemm(oracle.F32, 0, 0, M, N, K, zero, K, ones_b, N, batch=nb, stride_a=M * K, stride_b=K * N, bias=bias)
+    assert np.array_equal(C, np.broadcast_to(bias.astype(np.float64), (nb, M, N))) and np.array_equal(D, np.abs(C))
+    C, D = oracle.gemm(oracle.F32, 0, 0, M, N, K, ones_a, K, ones_b, N, batch=nb, stride_a=M * K, stride_b=K * N, bias=bias)
+    assert np.array_equal(C, K + np.broadcast_to(bias.astype(np.float64), (nb, M, N)))
+    assert np.array_equal(D, K + np.abs(np.broadcast_to(bias.astype(np.float64), (nb, M, N))))
+    pb, pi, pj = np.array([0, 1, 1]), np.array([0, 4, 2]), np.array([6, 0, 3])
+    Cp, Dp = oracle.gemm_points(oracle.F32, 0, 0, M, N, K, ones_a, K, ones_b, N, pb, pi, pj, batch=nb, stride_a=M * K,
+                                stride_b=K * N, bias=bias)
+    assert np.array_equal(Cp, C[pb, pi, pj]) and np.array_equal(Dp, D[pb, pi, pj])

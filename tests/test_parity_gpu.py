@@ -27,7 +27,7 @@ def oracle_for(inp):
     c = inp.cfg
     return oracle.gemm(c.in_dtype, c.layout_a, c.layout_b, c.M, c.N, c.K, inp.A, inp.lda, inp.B, inp.ldb,
                        batch=c.batch, stride_a=inp.stride_a, stride_b=inp.stride_b,
-                       scale_a=inp.scale_a, scale_b=inp.scale_b)
+                       scale_a=inp.scale_a, scale_b=inp.scale_b, bias=inp.bias)
 
 
 def check(variant, inp, ref=None, out_dtype=None, lend_workspace=False):
@@ -318,3 +318,25 @@ def test_launches_are_capturable_and_replayable_in_a_hip_graph():
         torch.cuda.synchronize()
         for want, (*_, dC) in zip(eager, jobs):
             assert torch.equal(want, dC), f"replay {replay} differs from the eager result"
+
+
+@pytest.mark.parametrize("dtype", [gen.F32, gen.BF16, gen.F16, gen.E4M3])
+def test_bias_is_added_before_the_rounding_in_every_state(dtype):
+    """AddMM: C = round(s * A.B + bias[j]).  Every state, ragged multi-tile shapes in the aligned and
+    in the masked / packed paths, a batch (the bias is shared), the streaming path, both tile sizes."""
+    out = gen.BF16 if dtype == gen.E4M3 else dtype
+    shapes = [(300, 270, 256, 2, ROW, COL, 0), (130, 70, 203, 1, ROW, ROW, 3), (9, 100, 264, 2, ROW, COL, 0)]
+    for (M, N, K, nb, la, lb, pad) in shapes:
+        cfg = gen.Config("addmm", M, N, K, dtype, out, la, lb, "normal", rsqrt_k=True, batch=nb, scaled=dtype == gen.E4M3,
+                         biased=True, lda=(K if la == ROW else M) + pad, ldb=(N if lb == ROW else K) + pad, ldc=N + pad)
+        inp = gen.make_inputs(cfg, 21)
+        ref = oracle_for(inp)
+        assert np.max(np.abs(ref[0])) > 1.0                         # the bias dominates: a dropped bias cannot pass
+        for v in variants_for(dtype):
+            check(v, inp, ref)
+        if dtype != gen.F32:
+            check(4, inp, ref, lend_workspace=True)
+            if la == ROW and lb == COL and pad == 0 and M > 16:
+                for flag in (gemm.GEMM_FLAG_TILE_256, gemm.GEMM_FLAG_TILE_128):
+                    rc, C, _ = util.run_config(4, inp, flags=flag)
+                    assert rc == gemm.GEMM_OK and util.norm_err(C[:, :, :N], ref[0], ref[1]) <= util.TOL[dtype]

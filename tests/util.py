@@ -61,11 +61,12 @@ def run_config(variant: int, inp: gen.Inputs, *, out_dtype=None, flags: int = 0,
     dB = dev(inp.B) if dB is None else dB
     sa = torch.from_numpy(inp.scale_a).cuda() if inp.scale_a is not None else None
     sb = torch.from_numpy(inp.scale_b).cuda() if inp.scale_b is not None else None
+    bias = torch.from_numpy(inp.bias).cuda() if inp.bias is not None else None
     dC = out_buffer(cfg.batch * inp.stride_c, od)
     d = gemm.make_desc(cfg.M, cfg.N, cfg.K, cfg.in_dtype, od, cfg.layout_a, cfg.layout_b,
                        lda=inp.lda, ldb=inp.ldb, ldc=inp.ldc, batch=cfg.batch,
                        stride_a=inp.stride_a, stride_b=inp.stride_b, stride_c=inp.stride_c,
-                       scale_a=sa, scale_b=sb, flags=flags)
+                       scale_a=sa, scale_b=sb, bias=bias, flags=flags)
     ws = None
     if lend_workspace:
         need = gemm.gemm_query(variant, d, dA, dB, dC).workspace_bytes
