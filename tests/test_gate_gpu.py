@@ -139,6 +139,21 @@ def test_simplifications_of_the_expert_state_pass_and_cost_time():
     torch.cuda.empty_cache()
 
 
+def test_frozen_tile_rule_agrees_with_the_sweep():
+    """The default tile choice of the fast kernel must be the faster of the two configurations (within
+    noise) on the workloads where they differ most, and the sweep table is kept with the gate's output."""
+    from paper_2605_28213_amd import tune
+    lines = []
+    for name in ("C5", "P2048", "PBMM32"):
+        r = tune.sweep(gen.CONFIGS[name], reps=30)
+        best = min(r["tile256"]["median_us"], r["tile128"]["median_us"])
+        lines.append(f"{name}: " + json.dumps({k: round(v["median_us"], 1) for k, v in r.items()}))
+        assert r["default"]["median_us"] <= 1.08 * best, (name, r)
+    with open(os.path.join(ROOT, "gpurun_out", "tile_sweep.txt"), "w") as f:
+        f.write("\n".join(lines) + "\n")
+    torch.cuda.empty_cache()
+
+
 def test_strict_mode_refuses_and_names_the_violated_conditions():
     """The ragged fp16 workload violates the alignment conditions of K2..K4; under STRICT the gate
     records a refusal with the condition names instead of running the masked path."""
