@@ -802,10 +802,10 @@ __device__ __forceinline__ void mfma16(const u32x4_t& a, const u32x4_t& b, f32x4
         c = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
 }
 
-template <typename IN, int WAVES_, int NB_, int TK_>
+template <typename IN, int WAVES_, int NB_, int TK_, int ROT_ = 0>
 struct StreamCfg {
     using In = IN;
-    static constexpr int WAVES = WAVES_, NB = NB_, TK = TK_, COLS = 16 * NB_;
+    static constexpr int WAVES = WAVES_, NB = NB_, TK = TK_, COLS = 16 * NB_, ROT = ROT_;
     static constexpr int LPC = TK / 8;                     // lanes (16-byte chunks) per row per tile
     static constexpr int CPL = 64 / LPC;                   // rows covered by one load instruction
     static constexpr int GLD = 16 / CPL;                   // loads per group of 16 rows per lane
@@ -909,13 +909,19 @@ __global__ __launch_bounds__(CFG::WAVES * 64) void k4_stream(Args a)
     const int64_t mine = tiles > wave ? (tiles - wave + WAVES - 1) / WAVES : 0;
     const int64_t nfull = whole > wave ? (whole - wave + WAVES - 1) / WAVES : 0;
     const bool ragged = mine > nfull;                          // this wave owns the ragged tile
+    // The whole tiles are walked from a start that differs from one workgroup to the next and wraps
+    // round (sums commute): at any moment the workgroups then read different offsets inside their
+    // columns instead of all the same one, a leading dimension apart.
+    const int64_t kwrap = ((int64_t)wave + WAVES * nfull) * TK; // this wave's first tile past the whole ones
     int64_t k = (int64_t)wave * TK;
+    if (CFG::ROT && nfull > 0) k += ((int64_t)blockIdx.x * CFG::ROT % nfull) * KSTRIDE;
     if (nfull > 0) {
         fetch_a(yes{}, k);
 #pragma unroll
         for (int g = 0; g < NB; ++g) fetch_b(yes{}, g, k);
         for (int64_t i = 1; i < nfull; ++i) {
             k += KSTRIDE;
+            if (CFG::ROT && k >= kwrap) k -= nfull * KSTRIDE;
             park_a();
             fetch_a(yes{}, k);
 #pragma unroll
@@ -925,7 +931,7 @@ __global__ __launch_bounds__(CFG::WAVES * 64) void k4_stream(Args a)
                 multiply(g);
             }
         }
-        k += KSTRIDE;
+        k = kwrap;
         park_a();
         if (ragged) fetch_a(no{}, k);
 #pragma unroll

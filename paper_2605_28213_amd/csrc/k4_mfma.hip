@@ -7,7 +7,8 @@ namespace gl {
 // Frozen configurations ("templatize" + an offline sweep, paper Table 1 expression-level intents).
 template <typename IN> using FastK4 = FastCfg<IN, 256>;                    // 256x256 tile, 4 waves, 128x128 per wave, one workgroup per CU
 template <typename IN> using FastK4Small = FastCfg<IN, 128>;               // 128x128 tile, 4 waves, 64x64 per wave, two workgroups per CU
-template <typename IN> using StreamK4 = StreamCfg<IN, 2, 2, 256>;           // 32 columns per workgroup, 2 waves taking K tiles in turn, 512-byte runs
+template <typename IN> using StreamK4 = StreamCfg<IN, 1, 1, 256, 19>;      // 16 columns per one-wave workgroup, 512-byte runs, K walk rotated by 19 tiles per workgroup
+template <typename IN> using StreamK4Deep = StreamCfg<IN, 4, 1, 256, 19>;  // the same with 4 waves taking K tiles in turn, for strips too few to fill the chip
 constexpr int MASKED_BM = 128, MASKED_BN = 128, MASKED_WM = 2, MASKED_WN = 2;
 
 template <typename CFG>
@@ -33,11 +34,22 @@ static hipError_t launch_masked(const Args& a, int vec_mask)
 }
 
 template <typename CFG>
-static hipError_t launch_stream(const Args& a)
+static hipError_t launch_stream_cfg(const Args& a)
 {
     dim3 grid((unsigned)((a.N + CFG::COLS - 1) / CFG::COLS), (unsigned)a.batch, 1), block(CFG::WAVES * 64, 1, 1);
     hipLaunchKernelGGL(k4_stream<CFG>, grid, block, 0, a.stream, a);
     return hipGetLastError();
+}
+
+// One wave per strip of 16 columns when that gives every CU work (bf16 16 x 16384 x 16384: 1024 strips,
+// 78 us against 85 us for two-wave workgroups of 32 columns: waves that share no barrier drift apart and
+// spread over the memory channels); with fewer strips than CUs, 4 waves split each strip's K.
+static bool stream_deep(const Args& a) { return ((a.N + 15) / 16) * a.batch < 256; }
+
+template <typename IN>
+static hipError_t launch_stream(const Args& a)
+{
+    return stream_deep(a) ? launch_stream_cfg<StreamK4Deep<IN>>(a) : launch_stream_cfg<StreamK4<IN>>(a);
 }
 
 // Tile choice of the fast kernel ("templatize" + a measured sweep, Table 1's expression-level intents):
@@ -89,7 +101,7 @@ static hipError_t launch_fast_split(const Args& a)
             bot.M = rem;
             bot.A = (const char*)a.A + top_rows * a.a_si * IN::BYTES;
             bot.C = (char*)a.C + top_rows * a.ldc * eo;
-            return launch_stream<StreamK4<IN>>(bot);
+            return launch_stream<IN>(bot);
         }
     }
     return launch_fast_any<IN>(a);
@@ -157,8 +169,8 @@ hipError_t launch_k4(int path, const Args& a)
         }
     }
     if (kind == MFMA_SKINNY) {
-        if (a.in_dtype == GEMM_BF16) return launch_stream<StreamK4<BF16>>(a);
-        if (a.in_dtype == GEMM_F16) return launch_stream<StreamK4<F16>>(a);
+        if (a.in_dtype == GEMM_BF16) return launch_stream<BF16>(a);
+        if (a.in_dtype == GEMM_F16) return launch_stream<F16>(a);
         return hipErrorInvalidValue;
     }
     if (kind == MFMA_VEC16) {
@@ -183,7 +195,10 @@ Geometry geometry_k4(int path, const Args& a)
     const int es = a.in_dtype == GEMM_FP8_E4M3 ? 1 : 2;
     if (kind == MFMA_SKINNY) {
         using C = StreamK4<BF16>;
-        return Geometry{16, C::COLS, C::TK, C::WAVES * 64, 2, C::LDS_BYTES, ((a.N + C::COLS - 1) / C::COLS) * a.batch};
+        using D = StreamK4Deep<BF16>;
+        const int64_t g = ((a.N + C::COLS - 1) / C::COLS) * a.batch;
+        if (stream_deep(a)) return Geometry{16, D::COLS, D::TK, D::WAVES * 64, 2, D::LDS_BYTES, g};
+        return Geometry{16, C::COLS, C::TK, C::WAVES * 64, 2, C::LDS_BYTES, g};
     }
     if (kind == MFMA_VEC16 || kind == MFMA_PACKED) {
         const bool small = k4_small_tiles(a);

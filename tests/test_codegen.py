@@ -73,9 +73,10 @@ def test_fast_kernel_steady_state_loop(asm, dtype, mfma, per_slab):
 
 def test_stream_kernel_register_budget(asm):
     for dtype in ("4BF16", "3F16"):
-        meta = metadata(asm, "_ZN2gl9k4_streamINS_9StreamCfgINS_" + dtype)
-        assert meta["vgpr_spill"] == 0 and meta["scratch"] == 0
-        assert meta["lds"] == 32 * 1024, "two waves, each the A group and one column group of 16 x 512 B"
+        for waves in (1, 4):
+            meta = metadata(asm, "_ZN2gl9k4_streamINS_9StreamCfgINS_%sELi%dELi1ELi256ELi19E" % (dtype, waves))
+            assert meta["vgpr_spill"] == 0 and meta["scratch"] == 0
+            assert meta["lds"] == waves * 16 * 1024, "per wave the A group and one column group of 16 x 512 B"
 
 
 def test_small_tile_configuration_fits_two_workgroups_per_cu(asm):
