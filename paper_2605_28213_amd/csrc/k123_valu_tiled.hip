@@ -29,6 +29,15 @@ struct ValuCfg {
 using CfgK1 = ValuCfg<64, 64, 16, 4, 4, false, false>;
 using CfgK2 = ValuCfg<128, 128, 16, 8, 8, true, false>;
 using CfgK3 = ValuCfg<128, 128, 16, 8, 8, true, true>;
+// The same two states with 64 x 64 tiles, for problems whose 128 x 128 tiles would leave most CUs idle
+// (fp32 256^3: 4 workgroups; 66 us with them against 24 us for K1's 16 workgroups).
+using CfgK2Small = ValuCfg<64, 64, 16, 4, 4, true, false>;
+using CfgK3Small = ValuCfg<64, 64, 16, 4, 4, true, true>;
+
+static bool valu_small_tiles(const Args& a)
+{
+    return ((a.M + CfgK2::BM - 1) / CfgK2::BM) * ((a.N + CfgK2::BN - 1) / CfgK2::BN) * a.batch < 256;
+}
 
 // One operand's view of the current tile: `rows` is its M (for A) or N (for B) extent.
 struct Operand {
@@ -258,8 +267,8 @@ hipError_t launch_valu_tiled(int variant, int path, const Args& a)
 {
     switch (variant) {
     case GEMM_K1_LDS_TILED: return launch_cfg<CfgK1>(a, 0);
-    case GEMM_K2_VECTORIZED: return launch_cfg<CfgK2>(a, path);
-    case GEMM_K3_PIPELINED: return launch_cfg<CfgK3>(a, path);
+    case GEMM_K2_VECTORIZED: return valu_small_tiles(a) ? launch_cfg<CfgK2Small>(a, path) : launch_cfg<CfgK2>(a, path);
+    case GEMM_K3_PIPELINED: return valu_small_tiles(a) ? launch_cfg<CfgK3Small>(a, path) : launch_cfg<CfgK3>(a, path);
     default: return hipErrorInvalidValue;
     }
 }
@@ -268,8 +277,8 @@ Geometry geometry_valu_tiled(int variant, int, const Args& a)
 {
     switch (variant) {
     case GEMM_K1_LDS_TILED: return geometry_cfg<CfgK1>(a);
-    case GEMM_K2_VECTORIZED: return geometry_cfg<CfgK2>(a);
-    default: return geometry_cfg<CfgK3>(a);
+    case GEMM_K2_VECTORIZED: return valu_small_tiles(a) ? geometry_cfg<CfgK2Small>(a) : geometry_cfg<CfgK2>(a);
+    default: return valu_small_tiles(a) ? geometry_cfg<CfgK3Small>(a) : geometry_cfg<CfgK3>(a);
     }
 }
 
