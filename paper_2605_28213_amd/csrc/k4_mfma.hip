@@ -44,7 +44,7 @@ static hipError_t launch_stream_cfg(const Args& a)
 // One wave per strip of 16 columns when that gives every CU work (bf16 16 x 16384 x 16384: 1024 strips,
 // 78 us against 85 us for two-wave workgroups of 32 columns: waves that share no barrier drift apart and
 // spread over the memory channels); with fewer strips than CUs, 4 waves split each strip's K.
-static bool stream_deep(const Args& a) { return ((a.N + 15) / 16) * a.batch < 256; }
+static bool stream_deep(const Args& a) { return ((a.N + 15) / 16) * a.batch < 512; }
 
 template <typename IN>
 static hipError_t launch_stream(const Args& a)
