@@ -3,8 +3,9 @@ every workload C1..C5, three seeds each, in the launch configuration the benchma
 
 Reference values come from the CPU oracle: the full product for C1, sampled outputs elsewhere
 (random points, first/last rows and columns, points around workgroup-tile corners), which the
-oracle evaluates one by one.  The ledger is written to gpurun_out/gate_ledger.jsonl and its table
-to gpurun_out/gate_table.txt.
+oracle evaluates one by one.  The ledger (gate_ledger.jsonl), its table (gate_table.txt) and the tile
+sweep (tile_sweep.txt) are written to the directory GEMM_GATE_OUT names, by default gate_out/ at the
+repository root.
 """
 import json
 import os
@@ -20,8 +21,9 @@ from paper_2605_28213_amd import inputs as gen
 pytestmark = pytest.mark.gpu
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-LEDGER = os.path.join(ROOT, "gpurun_out", "gate_ledger.jsonl")
-TABLE = os.path.join(ROOT, "gpurun_out", "gate_table.txt")
+OUT_DIR = os.environ.get("GEMM_GATE_OUT") or os.path.join(ROOT, "gate_out")
+LEDGER = os.path.join(OUT_DIR, "gate_ledger.jsonl")
+TABLE = os.path.join(OUT_DIR, "gate_table.txt")
 _entries = []
 
 
@@ -149,7 +151,7 @@ def test_frozen_tile_rule_agrees_with_the_sweep():
         best = min(r["tile256"]["median_us"], r["tile128"]["median_us"])
         lines.append(f"{name}: " + json.dumps({k: round(v["median_us"], 1) for k, v in r.items()}))
         assert r["default"]["median_us"] <= 1.25 * best, (name, r)   # a sanity bound: where the rule matters the gap is 1.7x
-    with open(os.path.join(ROOT, "gpurun_out", "tile_sweep.txt"), "w") as f:
+    with open(os.path.join(OUT_DIR, "tile_sweep.txt"), "w") as f:
         f.write("\n".join(lines) + "\n")
     torch.cuda.empty_cache()
 
