@@ -1,10 +1,10 @@
-"""CPU oracle for the GEMM lineage -- TEST INFRASTRUCTURE ONLY.
+"""CPU oracle for the GEMM lineage and its convolution transfer -- TEST INFRASTRUCTURE ONLY.
 
-ctypes wrapper around ``gemm_oracle.c`` (plain C, fp64 accumulation).  Only the
+ctypes wrapper around ``gemm_oracle.c`` and ``conv_oracle.c`` (plain C, fp64 accumulation).  Only the
 test-suite, the smoke check and the benchmark's CPU-baseline leg may import this
 package; the GPU library never does, and this package never imports the GPU
-library.  See the header of ``gemm_oracle.c`` for the definition it implements
-and for the list of pins that hold it in place.
+library.  See the headers of the two C files for the definitions they implement
+and for the lists of pins that hold them in place.
 
 Arrays are numpy; integer-coded dtypes are passed as their raw bit patterns
 (``uint16`` for bf16/fp16, ``uint8`` for e4m3, ``float32`` for fp32).
@@ -23,6 +23,7 @@ ROW_MAJOR, COL_MAJOR = 0, 1
 
 _DIR = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_DIR, "gemm_oracle.c")
+_SRC_CONV = os.path.join(_DIR, "conv_oracle.c")
 _LIB = os.path.join(_DIR, "libgemm_oracle.so")
 
 _NP_STORAGE = {F32: np.float32, BF16: np.uint16, F16: np.uint16, E4M3: np.uint8}
@@ -32,9 +33,10 @@ _lib = None
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (no fast-math: fp64 semantics are the point)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_CONV))
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
         cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-fno-fast-math",
-               "-ffp-contract=off", "-o", _LIB, _SRC, "-lm"]
+               "-ffp-contract=off", "-o", _LIB, _SRC, _SRC_CONV, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -52,6 +54,13 @@ def _bind(path: str):
     lib.oracle_gemm_points.argtypes = ([ctypes.c_int] * 3 + [i64] * 4 + [vp, i64, i64, vp, i64, i64]
                                        + [vp, vp, i64, vp, vp, vp, vp, vp])
     lib.oracle_num_threads.restype = ctypes.c_int
+    if hasattr(lib, "oracle_conv2d"):                   # absent from a library built from gemm_oracle.c alone
+        lib.oracle_conv2d_output_size.restype = None
+        lib.oracle_conv2d_output_size.argtypes = [i64] * 8 + [vp, vp]
+        lib.oracle_conv2d.restype = ctypes.c_int
+        lib.oracle_conv2d.argtypes = [ctypes.c_int] + [i64] * 11 + [vp, vp, vp, vp]
+        lib.oracle_conv2d_points.restype = ctypes.c_int
+        lib.oracle_conv2d_points.argtypes = [ctypes.c_int] + [i64] * 11 + [vp, vp, i64, vp, vp, vp, vp, vp, vp]
     return lib
 
 
@@ -162,3 +171,66 @@ def gemm_points(dtype: int, layout_a: int, layout_b: int, M: int, N: int, K: int
         C += bias64
         D += np.abs(bias64)
     return C, D
+
+
+def conv2d_output_size(H: int, W: int, R: int, S: int, stride: Tuple[int, int], pad: Tuple[int, int]) -> Tuple[int, int]:
+    """(P, Q) as the C oracle defines them (one definition: the buffers below are sized by it)."""
+    P, Q = ctypes.c_int64(0), ctypes.c_int64(0)
+    _load().oracle_conv2d_output_size(H, W, R, S, stride[0], stride[1], pad[0], pad[1], ctypes.byref(P), ctypes.byref(Q))
+    return int(P.value), int(Q.value)
+
+
+def conv2d(dtype: int, x: np.ndarray, w: np.ndarray, *, stride: Tuple[int, int] = (1, 1),
+           pad: Tuple[int, int] = (0, 0), bias: Optional[np.ndarray] = None) -> Tuple[np.ndarray, np.ndarray]:
+    """Oracle convolution layer.  x: (N, H, W, C) stored codes, w: (F, R, S, C) stored codes.
+    Returns (y_ref, D), each fp64 of shape (N, P, Q, F).  With `bias` (F fp32 values):
+    y_ref[..., f] += bias[f] and D[..., f] += |bias[f]| in fp64."""
+    lib = _load()
+    x = _check_storage(dtype, x, "x")
+    w = _check_storage(dtype, w, "w")
+    N, H, W, C = x.shape
+    F, R, S, C2 = w.shape
+    if C2 != C:
+        raise ValueError("x and w disagree on the number of channels")
+    if min(stride) < 1 or min(pad) < 0 or H + 2 * pad[0] < R or W + 2 * pad[1] < S:
+        raise ValueError("oracle conv2d: stride, padding or filter size out of range")
+    P, Q = conv2d_output_size(H, W, R, S, stride, pad)
+    y = np.zeros((N, max(P, 0), max(Q, 0), F), dtype=np.float64)
+    d = np.zeros_like(y)
+    rc = lib.oracle_conv2d(dtype, N, H, W, C, F, R, S, stride[0], stride[1], pad[0], pad[1],
+                           _ptr(x), _ptr(w), _ptr(y), _ptr(d))
+    if rc != 0:
+        raise ValueError(f"oracle_conv2d rejected its arguments (code {rc})")
+    if bias is not None:
+        b64 = np.asarray(bias, dtype=np.float32).astype(np.float64).reshape(1, 1, 1, F)
+        y += b64
+        d += np.abs(b64)
+    return y, d
+
+
+def conv2d_points(dtype: int, x: np.ndarray, w: np.ndarray, pn: np.ndarray, pp: np.ndarray, pq: np.ndarray,
+                  pf: np.ndarray, *, stride: Tuple[int, int] = (1, 1), pad: Tuple[int, int] = (0, 0),
+                  bias: Optional[np.ndarray] = None) -> Tuple[np.ndarray, np.ndarray]:
+    """Oracle values at selected outputs (n, p, q, f).  Returns (y_ref, D), each fp64 of shape (npts,)."""
+    lib = _load()
+    x = _check_storage(dtype, x, "x")
+    w = _check_storage(dtype, w, "w")
+    N, H, W, C = x.shape
+    F, R, S, C2 = w.shape
+    if C2 != C:
+        raise ValueError("x and w disagree on the number of channels")
+    idx = [np.ascontiguousarray(a, dtype=np.int64) for a in (pn, pp, pq, pf)]
+    n = idx[0].size
+    if any(a.size != n for a in idx):
+        raise ValueError("point index arrays differ in length")
+    y = np.zeros(n, dtype=np.float64)
+    d = np.zeros(n, dtype=np.float64)
+    rc = lib.oracle_conv2d_points(dtype, N, H, W, C, F, R, S, stride[0], stride[1], pad[0], pad[1],
+                                  _ptr(x), _ptr(w), n, *[_ptr(a) for a in idx], _ptr(y), _ptr(d))
+    if rc != 0:
+        raise ValueError(f"oracle_conv2d_points rejected its arguments (code {rc})")
+    if bias is not None:
+        b64 = np.asarray(bias, dtype=np.float32).astype(np.float64)[idx[3]]
+        y += b64
+        d += np.abs(b64)
+    return y, d

@@ -1,8 +1,9 @@
 """Mutation check of the oracle's pins (CPU only).
 
-Each case plants one plausible mistake in a copy of ``gemm_oracle.c`` (a dropped term, a
-wrong sign, a transposed operand, an off-by-one, a wrong bias), builds it, swaps it in for
-the real library and requires that at least one pin in ``test_oracle_pins`` fails.
+Each case plants one plausible mistake in a copy of ``gemm_oracle.c`` or ``conv_oracle.c`` (a
+dropped term, a wrong sign, a transposed operand, an off-by-one, a wrong bias, a flipped filter),
+builds it, swaps it in for the real library and requires that at least one pin in
+``test_oracle_pins`` / ``test_conv_oracle_pins`` fails.
 """
 import os
 import subprocess
@@ -10,6 +11,7 @@ import subprocess
 import pytest
 
 import oracle as oracle_mod
+from tests import test_conv_oracle_pins as conv_pins
 from tests import test_oracle_pins as pins
 
 SRC = os.path.join(os.path.dirname(oracle_mod.__file__), "gemm_oracle.c")
@@ -78,4 +80,67 @@ def test_planted_mistake_is_caught(name, tmp_path, monkeypatch):
 
 def test_unmutated_oracle_passes_the_same_selection():
     for fn, kw in _pins_that_apply():
+        fn(oracle_mod, **kw)
+
+
+# ---------------------------------------------------------------- convolution oracle
+CONV_SRC = os.path.join(os.path.dirname(oracle_mod.__file__), "conv_oracle.c")
+
+CONV_MUTATIONS = {
+    "filter_flipped": ("wd[((f * R + r) * S + s) * C + c]", "wd[((f * R + (R - 1 - r)) * S + (S - 1 - s)) * C + c]"),
+    "padding_sign": ("const int64_t h = p * sh - ph + r;", "const int64_t h = p * sh + ph - r;"),
+    "padding_off_by_one": ("const int64_t ww = q * sw - pw + s;", "const int64_t ww = q * sw - pw + s + 1;"),
+    "taps_swapped": ("const int64_t h = p * sh - ph + r;", "const int64_t h = p * sh - ph + (r * S) / R;"),
+    "stride_dropped": ("const int64_t ww = q * sw - pw + s;", "const int64_t ww = q - pw + s;"),
+    "image_transposed": ("xd[((n * H + h) * W + ww) * C + c]", "xd[((n * W + ww) * H + h) * C + c]"),
+    "border_replicated": ("if (h < 0 || h >= H || ww < 0 || ww >= W) continue;",
+                          "if (h < 0 || h >= H || ww < 0 || ww >= W) { for (int64_t c = 0; c < C; ++c) { acc += wd[((f * R + r) * S + s) * C + c]; } continue; }"),
+    "mag_without_abs": ("mag += fabs(pr);", "mag += pr;"),
+    "last_channel_dropped": ("for (int64_t c = 0; c < C; ++c) {\n                const double pr", "for (int64_t c = 0; c + 1 < C; ++c) {\n                const double pr"),
+    "width_from_height_stride": ("*Q = conv_out(W, pad_w, S, stride_w);", "*Q = conv_out(W, pad_w, S, stride_h);"),
+    "output_size_rounds_up": ("return (extent + 2 * pad - filt) / stride + 1;", "return (extent + 2 * pad - filt + stride - 1) / stride + 1;"),
+    "batch_index_dropped": ("xd[((n * H + h) * W + ww) * C + c]", "xd[((0 * H + h) * W + ww) * C + c]"),
+}
+
+
+def _conv_pins_that_apply():
+    calls = [
+        (conv_pins.test_centre_tap_identity_filter_returns_the_input, {"dt": pins.F32}),
+        (conv_pins.test_all_ones_counts_the_taps_inside_the_image, {"dt": pins.F16}),
+        (conv_pins.test_output_size_strides_and_paddings, {}),
+        (conv_pins.test_one_by_one_filter_is_a_matrix_product, {"dt": pins.BF16}),
+        (conv_pins.test_integer_valued_against_scipy_correlate2d, {}),
+        (conv_pins.test_exact_rational_brute_force, {"dt": pins.F16}),
+        (conv_pins.test_linearity_and_channel_order, {}),
+    ]
+    for r, s_ in [(0, 0), (2, 1)]:
+        calls.append((conv_pins.test_single_tap_shifts_the_image_without_flipping_the_filter, {"r": r, "s": s_}))
+    for geom in [((2, 2), (1, 1), 3, 3), ((1, 2), (0, 2), 3, 2)]:
+        calls.append((conv_pins.test_integer_valued_against_torch_fp64_conv2d, {"dt": pins.F32, "geom": geom}))
+    return calls
+
+
+@pytest.mark.parametrize("name", sorted(CONV_MUTATIONS))
+def test_planted_conv_mistake_is_caught(name, tmp_path, monkeypatch):
+    old, new = CONV_MUTATIONS[name]
+    text = open(CONV_SRC).read()
+    assert text.count(old) >= 1, f"mutation site for {name} not found; update the table"
+    mutated = tmp_path / "mutant_conv.c"
+    mutated.write_text(text.replace(old, new, 1))
+    so = tmp_path / "libmutant_conv.so"
+    subprocess.run(["gcc", "-O1", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-o", str(so), SRC, str(mutated), "-lm"],
+                   check=True)
+    oracle_mod._load()
+    monkeypatch.setattr(oracle_mod, "_lib", oracle_mod._bind(str(so)))
+    caught = []
+    for fn, kw in _conv_pins_that_apply():
+        try:
+            fn(oracle_mod, **kw)
+        except (AssertionError, ValueError):
+            caught.append(fn.__name__)
+    assert caught, f"mutation {name!r} survived every pin"
+
+
+def test_unmutated_conv_oracle_passes_the_same_selection():
+    for fn, kw in _conv_pins_that_apply():
         fn(oracle_mod, **kw)
