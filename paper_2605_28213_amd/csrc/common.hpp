@@ -13,6 +13,17 @@
 
 namespace gl {
 
+// Geometry of a convolution layer lowered to a matrix product (rows = output pixels n,p,q; columns =
+// filters; K = taps x channels in the order r, s, c).  Only K4's gathering instantiation reads it.
+struct ConvGeom {
+    int32_t H, W, C;              // input height, width, channels
+    int32_t P, Q;                 // output height, width
+    int32_t S;                    // filter width (taps per filter row)
+    int32_t stride_h, stride_w, pad_h, pad_w;
+    int32_t slabs_per_tap;        // C * element size / 128
+    uint32_t x_bytes;             // extent of the activations: the gather's buffer resource ends here
+};
+
 // Launch arguments, passed to kernels by value.  Strides are in elements.
 struct Args {
     const void* A;
@@ -30,6 +41,7 @@ struct Args {
     int32_t in_dtype, out_dtype;
     uint32_t flags;      // GEMM_FLAG_DEOPT_* bits (host side only: they select an instantiation)
     hipStream_t stream;
+    ConvGeom conv;       // all zero for a plain matrix product
 };
 
 // ---- storage formats ------------------------------------------------------------------------
@@ -95,11 +107,15 @@ bool k4_small_tiles(const Args& a);
 hipError_t launch_k0(const Args& a);
 hipError_t launch_valu_tiled(int variant, int path, const Args& a);
 hipError_t launch_k4(int path, const Args& a);
+// K4's fast kernel with A gathered from the activations of a convolution layer (a.conv); a.A = x,
+// a.B = filters (F rows of K contiguous elements), 2-byte or 1-byte types, whole slabs per tap.
+hipError_t launch_k4_conv(const Args& a);
 
 // Geometry reported by gemm_query (kept next to the kernels that define it).
 struct Geometry { int bm, bn, bk, threads, stages, lds_bytes; int64_t grid; };
 Geometry geometry_k0(const Args& a);
 Geometry geometry_valu_tiled(int variant, int path, const Args& a);
 Geometry geometry_k4(int path, const Args& a);
+Geometry geometry_k4_conv(const Args& a);
 
 }  // namespace gl

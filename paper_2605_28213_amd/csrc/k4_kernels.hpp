@@ -314,10 +314,14 @@ __device__ __forceinline__ void for_each_step(std::integer_sequence<int, KS...>,
 // TILE is the side of the square workgroup tile: 256 (one workgroup per CU, 128x128 per wave, all of
 // LDS: the compute-bound shape) or 128 (64x64 per wave, half the LDS, two workgroups per CU that cover
 // each other's prologue, epilogue and memory waits: for short K, or when 256-tiles would leave CUs idle).
-template <typename IN, int TILE_ = 256, int GROUP_M_ = 8, bool SWIZZLE_ = true, bool OVERLAP_ = true, int PRE_ = 0>
+//
+// CONV: the A operand is gathered from the activations of a convolution layer (ConvGeom): row m is
+// output pixel (n, p, q), K slab s is one tap's run of 128 bytes of channels.  Everything after the
+// loads (LDS layout, ring, MFMAs, epilogue) is the matrix product's.
+template <typename IN, int TILE_ = 256, int GROUP_M_ = 8, bool SWIZZLE_ = true, bool OVERLAP_ = true, int PRE_ = 0, bool CONV_ = false>
 struct FastCfg {
     using In = IN;
-    static constexpr bool SWIZZLE = SWIZZLE_, OVERLAP = OVERLAP_;
+    static constexpr bool SWIZZLE = SWIZZLE_, OVERLAP = OVERLAP_, CONV = CONV_;
     static constexpr int PRE_BARRIER_MFMAS = PRE_;
     static constexpr int BM = TILE_, BN = TILE_, WM = 2, WN = 2, GROUP_M = GROUP_M_;
     static constexpr int T = WM * WN * 64;
@@ -366,9 +370,10 @@ void k4_mfma_fast(Args a, int tiles_m, int tiles_n, int flags)
     // bits of byte offset.)
     const int orow = lane >> 3;
     const int gchunk = (lane & 7) ^ (CFG::SWIZZLE ? swz(orow + 8 * (wave & 1)) : 0);
-    const char* A = (const char*)a.A + (b * a.stride_a + m0 * a.a_si) * IN::BYTES;
+    const char* A = CFG::CONV ? (const char*)a.A : (const char*)a.A + (b * a.stride_a + m0 * a.a_si) * IN::BYTES;
     const char* B = (const char*)a.B + (b * a.stride_b + n0 * a.b_sj) * IN::BYTES;
-    const int64_t bytes_a = ((a.M - 1 - m0) * a.a_si + a.K) * IN::BYTES, bytes_b = ((a.N - 1 - n0) * a.b_sj + a.K) * IN::BYTES;
+    const int64_t bytes_a = CFG::CONV ? (int64_t)a.conv.x_bytes : ((a.M - 1 - m0) * a.a_si + a.K) * IN::BYTES;
+    const int64_t bytes_b = ((a.N - 1 - n0) * a.b_sj + a.K) * IN::BYTES;
     constexpr int64_t CAP = 0xFFFFFFFFll;
     constexpr int RSRC_FLAGS = 0x00020000;               // raw buffer, 32-bit data format
     const __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc((void*)A, 0, (int)(uint32_t)(bytes_a < CAP ? bytes_a : CAP), RSRC_FLAGS);
@@ -377,12 +382,48 @@ void k4_mfma_fast(Args a, int tiles_m, int tiles_n, int flags)
     const int voff_b = (int)((orow * a.b_sj + gchunk * V) * IN::BYTES);
     const int oct_a = (int)(8 * a.a_si * IN::BYTES), oct_b = (int)(8 * a.b_sj * IN::BYTES);   // bytes per row octet
     using lptr = __attribute__((address_space(3))) void*;
+    // Gather (CONV): per load of this wave (row octet wave + n*NW, row orow of it) the lane keeps the
+    // byte offset of its output pixel's window origin (channel chunk included; the origin may lie in
+    // the padding, a tap's offset is only added when the tap is inside the image) and the origin's
+    // input coordinates.  Rows past M get coordinates that fail every tap's range test.
+    constexpr int NCONV = CFG::CONV ? LD : 1;
+    constexpr int OUT_OF_RANGE = (int)0x80000000;          // as an unsigned offset: past any x below 2 GiB
+    int conv_base[NCONV], conv_h[NCONV], conv_w[NCONV];
+    if constexpr (CFG::CONV) {
+        const ConvGeom& g = a.conv;
+#pragma unroll
+        for (int n = 0; n < LD; ++n) {
+            const int64_t m = m0 + 8 * (wave + n * NW) + orow;
+            const bool in = m < a.M;
+            const int mm = in ? (int)m : 0;
+            const int img = mm / (g.P * g.Q), rem = mm - img * (g.P * g.Q);
+            const int p = rem / g.Q, q = rem - p * g.Q;
+            const int h0 = p * g.stride_h - g.pad_h;
+            conv_h[n] = in ? h0 : -(1 << 24);
+            conv_w[n] = q * g.stride_w - g.pad_w;
+            conv_base[n] = (((img * g.H + h0) * g.W + conv_w[n]) * g.C + gchunk * V) * IN::BYTES;
+        }
+    }
     // loads [lo, hi) of this wave's share of operand slab s into region `reg`
     auto issue_a = [&](int64_t s, char* reg, int lo, int hi) __attribute__((always_inline)) {
-        const int k0 = (int)(s * ROW_BYTES);
+        if constexpr (CFG::CONV) {
+            const ConvGeom& g = a.conv;
+            const int tap = (int)s / g.slabs_per_tap, cb = (int)s - tap * g.slabs_per_tap;
+            const int r = tap / g.S, sx = tap - r * g.S;
+            const int delta = (r * g.W + sx) * g.C * IN::BYTES + cb * ROW_BYTES;
 #pragma unroll
-        for (int n = lo; n < hi; ++n)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, (lptr)(reg + (wave + n * NW) * 1024), 16, voff_a, k0 + (wave + n * NW) * oct_a, 0, 0);
+            for (int n = lo; n < hi; ++n) {
+                const bool inside = (unsigned)(conv_h[n] + r) < (unsigned)g.H && (unsigned)(conv_w[n] + sx) < (unsigned)g.W;
+                // (a named value: with the select written as the builtin's argument the host pass drops the kernel's stub)
+                const int voff = inside ? conv_base[n] + delta : OUT_OF_RANGE;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, (lptr)(reg + (wave + n * NW) * 1024), 16, voff, 0, 0, 0);
+            }
+        } else {
+            const int k0 = (int)(s * ROW_BYTES);
+#pragma unroll
+            for (int n = lo; n < hi; ++n)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_a, (lptr)(reg + (wave + n * NW) * 1024), 16, voff_a, k0 + (wave + n * NW) * oct_a, 0, 0);
+        }
     };
     auto issue_b = [&](int64_t s, char* reg, int lo, int hi) __attribute__((always_inline)) {
         const int k0 = (int)(s * ROW_BYTES);

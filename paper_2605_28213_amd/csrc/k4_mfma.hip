@@ -189,6 +189,28 @@ hipError_t launch_k4(int path, const Args& a)
     }
 }
 
+// Convolution layer on the fast kernel: 128 x 128 tiles (the layer sizes this is built for have 64-256
+// filters; 64 x 64 per wave leaves the registers the gather's per-lane pixel state needs).
+template <typename IN> using ConvK4 = FastCfg<IN, 128, 8, true, true, 0, true>;
+
+hipError_t launch_k4_conv(const Args& a)
+{
+    switch (a.in_dtype) {
+    case GEMM_BF16: return launch_fast<ConvK4<BF16>>(a);
+    case GEMM_F16: return launch_fast<ConvK4<F16>>(a);
+    case GEMM_FP8_E4M3: return launch_fast<ConvK4<E4M3>>(a);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+Geometry geometry_k4_conv(const Args& a)
+{
+    using C = ConvK4<BF16>;
+    const int es = a.in_dtype == GEMM_FP8_E4M3 ? 1 : 2;
+    const int64_t g = ((a.M + C::BM - 1) / C::BM) * ((a.N + C::BN - 1) / C::BN);
+    return Geometry{C::BM, C::BN, ROW_BYTES / es, C::T, 2, C::LDS_BYTES, g};
+}
+
 Geometry geometry_k4(int path, const Args& a)
 {
     const int kind = path & 0xFF;

@@ -252,3 +252,85 @@ def make_inputs(cfg: Config, seed: int) -> Inputs:
         sb = uniform_range(seed, TENSOR_SCALE_B, cfg.batch, 0.5, 2.0)
     bias = normal(seed, TENSOR_BIAS, cfg.N, 1.0).astype(np.float32) if cfg.biased else None
     return Inputs(cfg, seed, A, B, lda, ldb, ldc, stride_a, stride_b, stride_c, sa, sb, bias)
+
+
+# ----------------------------------------------------------------------------
+# convolution layer (paper Sec. 4.1, workload table: Conv2d)
+# ----------------------------------------------------------------------------
+@dataclass(frozen=True)
+class ConvConfig:
+    """x: N x H x W x C, w: F x R x S x C, y: N x P x Q x F; all dense, channels fastest.
+
+    The paper gives the sizes and the dtype and no value distribution: activations are drawn uniform
+    in [-1, 1], filters normal with standard deviation 1/sqrt(R*S*C) (outputs of order 1), the bias
+    (where present) standard normal in fp32."""
+    name: str
+    N: int
+    H: int
+    W: int
+    C: int
+    F: int
+    R: int
+    S: int
+    in_dtype: int
+    out_dtype: int
+    stride: Tuple[int, int] = (1, 1)
+    pad: Tuple[int, int] = (1, 1)
+    biased: bool = False
+
+    @property
+    def P(self) -> int:
+        return (self.H + 2 * self.pad[0] - self.R) // self.stride[0] + 1
+
+    @property
+    def Q(self) -> int:
+        return (self.W + 2 * self.pad[1] - self.S) // self.stride[1] + 1
+
+    @property
+    def flops(self) -> float:
+        """2 x multiply-adds of the layer lowered to a matrix product (taps in the padding counted)."""
+        return 2.0 * self.N * self.P * self.Q * self.F * self.R * self.S * self.C
+
+    @property
+    def algorithmic_bytes(self) -> int:
+        """x and w read once, y written once, at storage width."""
+        return ((self.N * self.H * self.W * self.C + self.F * self.R * self.S * self.C) * ELEM_BYTES[self.in_dtype]
+                + self.N * self.P * self.Q * self.F * ELEM_BYTES[self.out_dtype])
+
+
+CONV_CONFIGS: Dict[str, ConvConfig] = {
+    # the paper's layer
+    "CONV": ConvConfig("CONV", 8, 56, 56, 64, 128, 3, 3, F16, F16),
+    # reduced and ragged counterparts: odd image sizes, strides, paddings, partial tiles in both directions
+    "CONV_small": ConvConfig("CONV_small", 2, 13, 11, 64, 40, 3, 3, F16, F16),
+    "CONV_stride2": ConvConfig("CONV_stride2", 3, 17, 15, 128, 136, 3, 3, BF16, BF16, stride=(2, 2), pad=(1, 1), biased=True),
+    "CONV_5x3": ConvConfig("CONV_5x3", 1, 20, 9, 64, 24, 5, 3, F16, F32, stride=(1, 2), pad=(2, 0)),
+    "CONV_1x1": ConvConfig("CONV_1x1", 2, 9, 9, 192, 130, 1, 1, BF16, BF16, pad=(0, 0)),
+    "CONV_fp8": ConvConfig("CONV_fp8", 2, 10, 12, 128, 72, 3, 3, E4M3, BF16),
+    # channels that are not whole 128-byte slabs: the implicit state refuses, im2col pads K
+    "CONV_c24": ConvConfig("CONV_c24", 2, 12, 10, 24, 20, 3, 3, F16, F16),
+    "CONV_c3": ConvConfig("CONV_c3", 1, 16, 16, 3, 8, 7, 7, BF16, BF16, stride=(2, 2), pad=(3, 3)),
+}
+
+TENSOR_X, TENSOR_W, TENSOR_CONV_BIAS = 11, 12, 13
+
+
+@dataclass
+class ConvInputs:
+    cfg: ConvConfig
+    seed: int
+    x: np.ndarray                       # raw storage, shape (N, H, W, C)
+    w: np.ndarray                       # raw storage, shape (F, R, S, C)
+    bias: Optional[np.ndarray] = None   # fp32, F values
+
+
+def make_conv_inputs(cfg: ConvConfig, seed: int) -> ConvInputs:
+    nx, nw = cfg.N * cfg.H * cfg.W * cfg.C, cfg.F * cfg.R * cfg.S * cfg.C
+    xv = uniform_pm1(seed, TENSOR_X, nx)
+    wv = normal(seed, TENSOR_W, nw, 1.0 / math.sqrt(cfg.R * cfg.S * cfg.C))
+    if cfg.in_dtype == E4M3:
+        wv = wv * 16.0      # keep the filters clear of e4m3's subnormal range; the metric is scale-invariant
+    x = quantise(cfg.in_dtype, xv).reshape(cfg.N, cfg.H, cfg.W, cfg.C)
+    w = quantise(cfg.in_dtype, wv).reshape(cfg.F, cfg.R, cfg.S, cfg.C)
+    bias = normal(seed, TENSOR_CONV_BIAS, cfg.F, 1.0).astype(np.float32) if cfg.biased else None
+    return ConvInputs(cfg, seed, x, w, bias)

@@ -53,7 +53,7 @@ def first_inner_loop(body):
 @pytest.mark.parametrize("dtype,mfma,per_slab", [("4BF16", "v_mfma_f32_32x32x16_bf16", 64), ("3F16", "v_mfma_f32_32x32x16_f16", 64),
                                                  ("4E4M3", "v_mfma_scale_f32_32x32x64_f8f6f4", 32)])
 def test_fast_kernel_steady_state_loop(asm, dtype, mfma, per_slab):
-    prefix = "_ZN2gl12k4_mfma_fastINS_7FastCfgINS_" + dtype + "ELi256ELi8ELb1ELb1ELi0E"      # the expert instantiation
+    prefix = "_ZN2gl12k4_mfma_fastINS_7FastCfgINS_" + dtype + "ELi256ELi8ELb1ELb1ELi0ELb0E"      # the expert instantiation
     ops = first_inner_loop(kernel_body(asm, prefix))
     count = lambda name: sum(o == name for o in ops)
     # five slabs per trip round the LDS ring; 16 direct loads per slab; fragment reads are 16-byte
@@ -81,6 +81,15 @@ def test_stream_kernel_register_budget(asm):
 
 def test_small_tile_configuration_fits_two_workgroups_per_cu(asm):
     for dtype in ("4BF16", "3F16", "4E4M3"):
-        meta = metadata(asm, "_ZN2gl12k4_mfma_fastINS_7FastCfgINS_" + dtype + "ELi128ELi8ELb1ELb1ELi0E")
+        meta = metadata(asm, "_ZN2gl12k4_mfma_fastINS_7FastCfgINS_" + dtype + "ELi128ELi8ELb1ELb1ELi0ELb0E")
         assert meta["lds"] == 80 * 1024 and meta["agpr"] + meta["vgpr"] <= 512
         assert meta["vgpr"] <= 256 and meta["vgpr_spill"] == 0, "two waves per SIMD need at most 256 registers each"
+
+
+def test_gathering_instantiation_keeps_two_workgroups_per_cu(asm):
+    """The convolution form of the fast kernel: same budget as the 128-tile matrix product."""
+    for dtype in ("4BF16", "3F16", "4E4M3"):
+        meta = metadata(asm, "_ZN2gl12k4_mfma_fastINS_7FastCfgINS_" + dtype + "ELi128ELi8ELb1ELb1ELi0ELb1E")
+        assert meta["lds"] == 80 * 1024 and meta["vgpr"] <= 256 and meta["vgpr_spill"] == 0 and meta["scratch"] == 0
+        body = kernel_body(asm, "_ZN2gl12k4_mfma_fastINS_7FastCfgINS_" + dtype + "ELi128ELi8ELb1ELb1ELi0ELb1E")
+        assert "v_readfirstlane_b32" not in first_inner_loop(body), "the activations' buffer resource must stay scalar"
