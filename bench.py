@@ -9,7 +9,8 @@ three copies so that no launch finds its inputs in the Infinity Cache left by it
 
 The same JSON line carries, under "shapes", the expert state on the other four workloads (each
 against its own roofline: HBM for the M=16 shape) and, under "lineage", every state K0..K4 on the
-headline workload; under "cpu_baseline" the CPU oracle timed on a slab of rows of the same product.
+headline workload; under "conv2d" the paper's convolution layer on the same expert kernel; under
+"cpu_baseline" the CPU oracle timed on a slab of rows of the same product.
 """
 import argparse
 import json
@@ -241,6 +242,40 @@ def main():
             del s2, keep2
             torch.cuda.empty_cache()
         out["shapes"] = shapes
+
+        # ---- the paper's Conv2d layer (Sec. 4.1 workload table) on the lineage's expert state -----------
+        from paper_2605_28213_amd import conv
+        cc = gen.CONV_CONFIGS["CONV"]
+        ci = gen.make_conv_inputs(cc, 0)
+        to_dev = lambda a: torch.from_numpy(a.reshape(-1).view(np.uint8).copy()).cuda()
+        xs = [to_dev(ci.x) for _ in range(NSETS)]
+        wd = to_dev(ci.w)
+        yd = torch.empty(cc.N * cc.P * cc.Q * cc.F * gen.ELEM_BYTES[cc.out_dtype], dtype=torch.uint8, device="cuda")
+        layer = {}
+        for v in (conv.CONV_C1_IM2COL_MFMA, conv.CONV_C2_IMPLICIT_MFMA):
+            dd = conv.make_desc(cc.N, cc.H, cc.W, cc.C, cc.F, cc.R, cc.S, cc.in_dtype, cc.out_dtype, stride=cc.stride,
+                                pad=cc.pad, stream=stream)
+            need = conv.conv2d_query(v, dd, xs[0], wd, yd).workspace_bytes
+            ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+            dd.workspace, dd.workspace_bytes = ws.data_ptr(), need
+            k = [0]
+            def launch():
+                rc = conv.conv2d_run(v, dd, xs[k[0] % NSETS], wd, yd)
+                k[0] += 1
+                if rc != gemm.GEMM_OK:
+                    raise RuntimeError(f"conv2d_run: {gemm.gemm_status_string(rc)}")
+            ss = stats(event_times(launch, 100, 25))
+            layer[conv.conv2d_variant_name(v)] = {
+                "path": conv.conv2d_query(v, dd, xs[0], wd, yd).path, "launch_us": ss,
+                "TFLOP/s": cc.flops / (ss["mean_us"] * 1e-6) / 1e12, "GB/s": cc.algorithmic_bytes / (ss["mean_us"] * 1e-6) / 1e9}
+            del ws
+        layer["workload"] = "fp16 N=8 H=W=56 C=64 F=128 3x3 stride 1 pad 1, NHWC, 3.70 GFLOP, 9.78 MB"
+        layer["paper_context"] = {"source": "KLineage CUDA / cuDNN, H100 PCIe and RTX PRO 6000, App. A",
+                                  "latency_ms": {"H100 KLineage": 0.0157, "H100 cuDNN": 0.0272, "RTX PRO 6000 KLineage": 0.0235,
+                                                 "RTX PRO 6000 cuDNN": 0.0253}}
+        out["conv2d"] = layer
+        del xs, wd, yd
+        torch.cuda.empty_cache()
 
     if not args.no_cpu:
         # ---- CPU oracle on a bounded sample of the headline workload ---------------------------------
