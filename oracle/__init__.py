@@ -1,6 +1,7 @@
 """CPU oracle for the GEMM lineage and its convolution transfer -- TEST INFRASTRUCTURE ONLY.
 
-ctypes wrapper around ``gemm_oracle.c`` and ``conv_oracle.c`` (plain C, fp64 accumulation).  Only the
+ctypes wrapper around ``gemm_oracle.c``, ``conv_oracle.c`` (plain C, fp64 accumulation) and
+``topk_oracle.c`` (rank counting).  Only the
 test-suite, the smoke check and the benchmark's CPU-baseline leg may import this
 package; the GPU library never does, and this package never imports the GPU
 library.  See the headers of the two C files for the definitions they implement
@@ -24,6 +25,7 @@ ROW_MAJOR, COL_MAJOR = 0, 1
 _DIR = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_DIR, "gemm_oracle.c")
 _SRC_CONV = os.path.join(_DIR, "conv_oracle.c")
+_SRC_TOPK = os.path.join(_DIR, "topk_oracle.c")
 _LIB = os.path.join(_DIR, "libgemm_oracle.so")
 
 _NP_STORAGE = {F32: np.float32, BF16: np.uint16, F16: np.uint16, E4M3: np.uint8}
@@ -33,10 +35,10 @@ _lib = None
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (no fast-math: fp64 semantics are the point)."""
-    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_CONV))
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_CONV), os.path.getmtime(_SRC_TOPK))
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
         cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-fno-fast-math",
-               "-ffp-contract=off", "-o", _LIB, _SRC, _SRC_CONV, "-lm"]
+               "-ffp-contract=off", "-o", _LIB, _SRC, _SRC_CONV, _SRC_TOPK, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -61,6 +63,9 @@ def _bind(path: str):
         lib.oracle_conv2d.argtypes = [ctypes.c_int] + [i64] * 11 + [vp, vp, vp, vp]
         lib.oracle_conv2d_points.restype = ctypes.c_int
         lib.oracle_conv2d_points.argtypes = [ctypes.c_int] + [i64] * 11 + [vp, vp, i64, vp, vp, vp, vp, vp, vp]
+    if hasattr(lib, "oracle_topk"):
+        lib.oracle_topk.restype = ctypes.c_int
+        lib.oracle_topk.argtypes = [i64, i64, i64, vp, i64, vp, vp]
     return lib
 
 
@@ -234,3 +239,20 @@ def conv2d_points(dtype: int, x: np.ndarray, w: np.ndarray, pn: np.ndarray, pp: 
         y += b64
         d += np.abs(b64)
     return y, d
+
+
+def topk(x: np.ndarray, k: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Oracle top-k of each row of a 2-D fp32 array (rows may be a strided view along axis 0).
+    Returns (idx int32, val fp32), each (batch, k): the k largest, ties towards lower indices,
+    listed in increasing index order."""
+    lib = _load()
+    if x.dtype != np.float32 or x.ndim != 2 or x.strides[1] != 4 or x.strides[0] % 4 != 0:
+        raise TypeError("oracle topk wants a 2-D fp32 array with contiguous rows")
+    batch, n = x.shape
+    ld = x.strides[0] // 4 if batch > 1 else max(n, 1)
+    idx = np.zeros((batch, k), dtype=np.int32)
+    val = np.zeros((batch, k), dtype=np.float32)
+    rc = lib.oracle_topk(batch, n, k, x.ctypes.data_as(ctypes.c_void_p), ld, _ptr(idx), _ptr(val))
+    if rc != 0:
+        raise ValueError(f"oracle_topk rejected its arguments (code {rc})")
+    return idx, val

@@ -1,7 +1,8 @@
-"""Seeded synthetic inputs for the GEMM lineage (shared by the GPU tests and the CPU oracle tests).
+"""Seeded synthetic inputs for the GEMM lineage, the convolution layer and the top-k selection built
+beside it (shared by the GPU tests and the CPU oracle tests).
 
-This module holds no GEMM arithmetic: it only draws numbers, quantises them to
-the storage format and describes the five benchmark workloads.  Neither the HIP
+This module holds none of their arithmetic: it only draws numbers, quantises them to
+the storage format and describes the benchmark workloads.  Neither the HIP
 library nor the oracle imports it; tests hand its arrays to both.
 
 Generator.  Element ``n`` (linear position in the stored buffer) of tensor ``t``

@@ -1,9 +1,9 @@
 """Mutation check of the oracle's pins (CPU only).
 
-Each case plants one plausible mistake in a copy of ``gemm_oracle.c`` or ``conv_oracle.c`` (a
+Each case plants one plausible mistake in a copy of ``gemm_oracle.c``, ``conv_oracle.c`` or ``topk_oracle.c`` (a
 dropped term, a wrong sign, a transposed operand, an off-by-one, a wrong bias, a flipped filter),
 builds it, swaps it in for the real library and requires that at least one pin in
-``test_oracle_pins`` / ``test_conv_oracle_pins`` fails.
+``test_oracle_pins`` / ``test_conv_oracle_pins`` / ``test_topk_oracle_pins`` fails.
 """
 import os
 import subprocess
@@ -13,6 +13,7 @@ import pytest
 import oracle as oracle_mod
 from tests import test_conv_oracle_pins as conv_pins
 from tests import test_oracle_pins as pins
+from tests import test_topk_oracle_pins as topk_pins
 
 SRC = os.path.join(os.path.dirname(oracle_mod.__file__), "gemm_oracle.c")
 
@@ -144,3 +145,46 @@ def test_planted_conv_mistake_is_caught(name, tmp_path, monkeypatch):
 def test_unmutated_conv_oracle_passes_the_same_selection():
     for fn, kw in _conv_pins_that_apply():
         fn(oracle_mod, **kw)
+
+
+# ---------------------------------------------------------------- top-k oracle
+TOPK_SRC = os.path.join(os.path.dirname(oracle_mod.__file__), "topk_oracle.c")
+
+TOPK_MUTATIONS = {
+    "smallest_instead_of_largest": ("if (row[j] > row[i] || (row[j] == row[i] && j < i)) ++rank;",
+                                    "if (row[j] < row[i] || (row[j] == row[i] && j < i)) ++rank;"),
+    "ties_to_higher_index": ("(row[j] == row[i] && j < i)", "(row[j] == row[i] && j > i)"),
+    "ties_all_selected": ("if (row[j] > row[i] || (row[j] == row[i] && j < i)) ++rank;", "if (row[j] > row[i]) ++rank;"),
+    "ties_count_twice": ("(row[j] == row[i] && j < i)", "(row[j] == row[i] && j != i)"),
+    "one_too_few": ("if (rank < k && out < k) {", "if (rank + 1 < k && out < k) {"),
+    "row_stride_dropped": ("const float *row = x + b * ld;", "const float *row = x + b * n;"),
+    "values_from_first_row": ("val[b * k + out] = row[i];", "val[b * k + out] = x[i];"),
+}
+
+
+def _topk_pins_that_apply():
+    return [(topk_pins.test_ramps_and_constant_rows, {}),
+            (topk_pins.test_edge_values_of_k_and_signed_zeros, {}),
+            (topk_pins.test_against_stable_argsort_and_torch_topk, {"n": 257, "k": 100}),
+            (topk_pins.test_exhaustive_short_rows_over_a_small_alphabet, {}),
+            (topk_pins.test_rows_are_independent_and_strided_rows_work, {})]
+
+
+@pytest.mark.parametrize("name", sorted(TOPK_MUTATIONS))
+def test_planted_topk_mistake_is_caught(name, tmp_path, monkeypatch):
+    old, new = TOPK_MUTATIONS[name]
+    text = open(TOPK_SRC).read()
+    assert text.count(old) >= 1, f"mutation site for {name} not found; update the table"
+    mutated = tmp_path / "mutant_topk.c"
+    mutated.write_text(text.replace(old, new, 1))
+    so = tmp_path / "libmutant_topk.so"
+    subprocess.run(["gcc", "-O1", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-o", str(so), SRC, str(mutated), "-lm"], check=True)
+    oracle_mod._load()
+    monkeypatch.setattr(oracle_mod, "_lib", oracle_mod._bind(str(so)))
+    caught = []
+    for fn, kw in _topk_pins_that_apply():
+        try:
+            fn(oracle_mod, **kw)
+        except (AssertionError, ValueError):
+            caught.append(fn.__name__)
+    assert caught, f"mutation {name!r} survived every pin"
