@@ -123,7 +123,8 @@ int oracle_conv2d(int dtype, int64_t N, int64_t H, int64_t W, int64_t C, int64_t
 {
     int rc = conv_check(dtype, N, H, W, C, F, R, S, stride_h, stride_w, pad_h, pad_w, x, w);
     if (rc != CONV_ORACLE_OK) return rc;
-    const int64_t P = conv_out(H, pad_h, R, stride_h), Q = conv_out(W, pad_w, S, stride_w);
+    int64_t P, Q;
+    oracle_conv2d_output_size(H, W, R, S, stride_h, stride_w, pad_h, pad_w, &P, &Q);
     if (N == 0 || F == 0) return CONV_ORACLE_OK;
     double *xd, *wd;
     rc = conv_decode_copies(dtype, N * H * W * C, F * R * S * C, x, w, &xd, &wd);
@@ -152,7 +153,8 @@ int oracle_conv2d_points(int dtype, int64_t N, int64_t H, int64_t W, int64_t C, 
 {
     int rc = conv_check(dtype, N, H, W, C, F, R, S, stride_h, stride_w, pad_h, pad_w, x, w);
     if (rc != CONV_ORACLE_OK) return rc;
-    const int64_t P = conv_out(H, pad_h, R, stride_h), Q = conv_out(W, pad_w, S, stride_w);
+    int64_t P, Q;
+    oracle_conv2d_output_size(H, W, R, S, stride_h, stride_w, pad_h, pad_w, &P, &Q);
     if (npts < 0 || (npts > 0 && (!pn || !pp || !pq || !pf))) return CONV_ORACLE_BAD_ARG;
     for (int64_t i = 0; i < npts; ++i)
         if (pn[i] < 0 || pn[i] >= N || pp[i] < 0 || pp[i] >= P || pq[i] < 0 || pq[i] >= Q || pf[i] < 0 || pf[i] >= F)
