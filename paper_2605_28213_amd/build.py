@@ -15,10 +15,11 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libgemm_lineage.so")
-SOURCES = ["gemm_api.hip", "conv_api.hip", "k0_naive.hip", "k123_valu_tiled.hip", "k4_mfma.hip", "probes.hip"]
+SOURCES = ["gemm_api.hip", "conv_api.hip", "topk.hip", "k0_naive.hip", "k123_valu_tiled.hip", "k4_mfma.hip", "probes.hip"]
 HEADERS = [os.path.join(CSRC, "common.hpp"), os.path.join(CSRC, "k4_kernels.hpp"),
            os.path.join(os.path.dirname(HERE), "include", "gemm_lineage.h"),
-           os.path.join(os.path.dirname(HERE), "include", "conv_lineage.h")]
+           os.path.join(os.path.dirname(HERE), "include", "conv_lineage.h"),
+           os.path.join(os.path.dirname(HERE), "include", "topk_lineage.h")]
 # packed fp32 VALU forms (v_pk_*_f32) are switched off: the compiler must not form them for this target
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -335,3 +335,47 @@ def make_conv_inputs(cfg: ConvConfig, seed: int) -> ConvInputs:
     w = quantise(cfg.in_dtype, wv).reshape(cfg.F, cfg.R, cfg.S, cfg.C)
     bias = normal(seed, TENSOR_CONV_BIAS, cfg.F, 1.0).astype(np.float32) if cfg.biased else None
     return ConvInputs(cfg, seed, x, w, bias)
+
+
+# ----------------------------------------------------------------------------
+# row-wise top-k (paper Sec. 4.1, workload table: Top-K)
+# ----------------------------------------------------------------------------
+@dataclass(frozen=True)
+class TopkConfig:
+    """x: batch rows of n fp32 values, ld elements apart.  The paper gives the shape only; values are
+    standard normal ("normal"), or standard normal rounded to multiples of 1/4 so that many elements tie,
+    also at the threshold ("ties")."""
+    name: str
+    batch: int
+    n: int
+    k: int
+    ld: int = 0               # 0 = tight
+    dist: str = "normal"
+
+    @property
+    def algorithmic_bytes(self) -> int:
+        """The rows read once, indices and values written once."""
+        return self.batch * (self.n * 4 + self.k * 8)
+
+
+TOPK_CONFIGS: Dict[str, TopkConfig] = {
+    "TOPK": TopkConfig("TOPK", 64, 4096, 512),                       # the paper's shape
+    "TOPK_ties": TopkConfig("TOPK_ties", 64, 4096, 512, dist="ties"),
+    "TOPK_small": TopkConfig("TOPK_small", 5, 1000, 37, ld=1004),
+    "TOPK_ragged": TopkConfig("TOPK_ragged", 3, 4099, 4000, ld=4100, dist="ties"),
+    "TOPK_wide": TopkConfig("TOPK_wide", 2, 16384, 2048, dist="ties"),
+    "TOPK_long": TopkConfig("TOPK_long", 2, 70001, 300),             # beyond what T0 and T2 hold: both refuse
+}
+
+TENSOR_TOPK = 21
+
+
+def make_topk_inputs(cfg: TopkConfig, seed: int) -> np.ndarray:
+    """Returns the (batch, ld) fp32 buffer; the row is its first n columns, the rest is padding (huge
+    values, which a kernel that read past n would select)."""
+    ld = cfg.ld or cfg.n
+    x = normal(seed, TENSOR_TOPK, cfg.batch * ld, 1.0).astype(np.float32).reshape(cfg.batch, ld)
+    if cfg.dist == "ties":
+        x = (np.round(x * 4.0) / 4.0).astype(np.float32)
+    x[:, cfg.n:] = 1.0e30
+    return x
