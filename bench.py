@@ -9,8 +9,8 @@ three copies so that no launch finds its inputs in the Infinity Cache left by it
 
 The same JSON line carries, under "shapes", the expert state on the other four workloads (each
 against its own roofline: HBM for the M=16 shape) and, under "lineage", every state K0..K4 on the
-headline workload; under "conv2d" the paper's convolution layer on the same expert kernel; under
-"cpu_baseline" the CPU oracle timed on a slab of rows of the same product.
+headline workload; under "conv2d" the paper's convolution layer on the same expert kernel and under
+"topk" its selection workload; under "cpu_baseline" the CPU oracle timed on a slab of rows of the same product.
 """
 import argparse
 import json
@@ -276,6 +276,31 @@ def main():
         out["conv2d"] = layer
         del xs, wd, yd
         torch.cuda.empty_cache()
+
+        # ---- the paper's Top-K shape (Sec. 4.1 workload table): batch 64, 4096 values, k = 512, fp32 ----
+        from paper_2605_28213_amd import topk
+        tc = gen.TOPK_CONFIGS["TOPK"]
+        txs = [torch.from_numpy(gen.make_topk_inputs(tc, 0)).cuda() for _ in range(NSETS)]
+        tidx = torch.empty(tc.batch * tc.k, dtype=torch.int32, device="cuda")
+        tval = torch.empty(tc.batch * tc.k, dtype=torch.float32, device="cuda")
+        td = topk.make_desc(tc.batch, tc.n, tc.k, stream=stream)
+        sel = {}
+        for v in (topk.TOPK_T1_RADIX_SELECT, topk.TOPK_T2_RESIDENT):
+            k = [0]
+            def launch_topk():
+                rc = topk.topk_run(v, td, txs[k[0] % NSETS], tidx, tval)
+                k[0] += 1
+                if rc != gemm.GEMM_OK:
+                    raise RuntimeError(f"topk_run: {gemm.gemm_status_string(rc)}")
+            ss = stats(event_times(launch_topk, 100, 25))
+            sel[topk.topk_variant_name(v)] = {"path": topk.topk_query(v, td, txs[0]).path, "launch_us": ss,
+                                              "GB/s": tc.algorithmic_bytes / (ss["mean_us"] * 1e-6) / 1e9}
+        sel["workload"] = "fp32 batch 64 x 4096, k = 512, indices + values out, 1.31 MB"
+        sel["paper_context"] = {"source": "KLineage CUDA / FlashInfer, H100 PCIe and RTX PRO 6000, App. A",
+                                "latency_ms": {"H100 KLineage": 0.0143, "H100 FlashInfer": 0.0160, "RTX PRO 6000 KLineage": 0.0131,
+                                               "RTX PRO 6000 FlashInfer": 0.0169}}
+        out["topk"] = sel
+        del txs, tidx, tval
 
     if not args.no_cpu:
         # ---- CPU oracle on a bounded sample of the headline workload ---------------------------------

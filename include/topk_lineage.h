@@ -41,7 +41,7 @@ typedef enum {
 
 enum {
     TOPK_COND_ROW_IN_LDS       = 1u << 0, /* n <= 65536: T0 keeps one "taken" byte per element in LDS */
-    TOPK_COND_ROW_IN_REGISTERS = 1u << 1, /* n <= 16384: T2 holds 16 keys per lane of a 256- or 1024-lane workgroup */
+    TOPK_COND_ROW_IN_REGISTERS = 1u << 1, /* n <= 16384: T2 holds 4 or 16 keys per lane of a 1024-lane workgroup */
     TOPK_COND_ALIGN16          = 1u << 2  /* x 16-byte aligned and ld a multiple of 4: T2 loads 16 bytes per lane */
 };
 

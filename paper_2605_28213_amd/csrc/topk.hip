@@ -226,7 +226,6 @@ __global__ __launch_bounds__(T) void topk_radix(TopkArgs a)
     }
 }
 
-using RadixStream = void (*)(TopkArgs);
 constexpr int RES_ITEMS = 16;
 
 struct Plan {
@@ -234,6 +233,7 @@ struct Plan {
     bool empty = false;
     TopkArgs a{};
     int threads = 0;
+    int items = 0;          // T2: keys per lane
     hipStream_t stream = nullptr;
     topk_query_t q{};
 };
@@ -269,8 +269,11 @@ Plan make_plan(int variant, const topk_desc_t* d, const float* x, const void* id
         break;
     default:
         required = TOPK_COND_ROW_IN_REGISTERS | TOPK_COND_ALIGN16;
-        p.threads = d->n <= 256 * RES_ITEMS ? 256 : 1024;
-        path = p.threads == 256 ? "radix-select(11+11+10, 16 keys/lane x 256)" : "radix-select(11+11+10, 16 keys/lane x 1024)";
+        // 1024 lanes per row: 64 rows keep a quarter of the CUs busy, so the work per lane is what counts
+        // (batch 64, n 4096, k 512: 15.5 us with 256 lanes x 16 keys, 10.2 us with 1024 lanes x 4 keys)
+        p.threads = 1024;
+        p.items = d->n <= 1024 * 4 ? 4 : RES_ITEMS;
+        path = p.items == 4 ? "radix-select(11+11+10, 4 keys/lane x 1024)" : "radix-select(11+11+10, 16 keys/lane x 1024)";
         q.passes = 4; q.lds_bytes = 2048 * 4 + 72;
         break;
     }
@@ -308,8 +311,8 @@ int topk_run(int variant, const topk_desc_t* d, const float* x, int32_t* idx, fl
         hipLaunchKernelGGL(topk_selection, grid, dim3(SEL_T), 0, p.stream, p.a);
     else if (variant == TOPK_T1_RADIX_SELECT)
         hipLaunchKernelGGL((topk_radix<256, 1, false, 4, 8, 8, 8, 8>), grid, dim3(256), 0, p.stream, p.a);
-    else if (p.threads == 256)
-        hipLaunchKernelGGL((topk_radix<256, RES_ITEMS, true, 3, 11, 11, 10, 0>), grid, dim3(256), 0, p.stream, p.a);
+    else if (p.items == 4)
+        hipLaunchKernelGGL((topk_radix<1024, 4, true, 3, 11, 11, 10, 0>), grid, dim3(1024), 0, p.stream, p.a);
     else
         hipLaunchKernelGGL((topk_radix<1024, RES_ITEMS, true, 3, 11, 11, 10, 0>), grid, dim3(1024), 0, p.stream, p.a);
     const hipError_t e = hipGetLastError();

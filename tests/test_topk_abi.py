@@ -54,9 +54,9 @@ def test_plans_and_refusals():
     d = topk.make_desc(64, 4096, 512)
     q0, q1, q2 = (topk.topk_query(v, d) for v in range(3))
     assert all(q.status == gemm.GEMM_OK and q.grid == 64 for q in (q0, q1, q2))
-    assert (q0.threads, q0.passes) == (256, 512) and (q1.threads, q1.passes) == (256, 5) and (q2.threads, q2.passes) == (256, 4)
-    assert "11+11+10" in q2.path and "x 256" in q2.path
-    assert "x 1024" in topk.topk_query(2, topk.make_desc(2, 4097, 5, ld=4100)).path
+    assert (q0.threads, q0.passes) == (256, 512) and (q1.threads, q1.passes) == (256, 5) and (q2.threads, q2.passes) == (1024, 4)
+    assert "11+11+10" in q2.path and "4 keys/lane" in q2.path
+    assert "16 keys/lane" in topk.topk_query(2, topk.make_desc(2, 4097, 5, ld=4100)).path
     big = topk.make_desc(2, 70001, 300)
     assert topk.Query.names(topk.topk_query(0, big).violated) == ["ROW_IN_LDS"]
     assert topk.topk_query(1, big).status == gemm.GEMM_OK
