@@ -1,0 +1,65 @@
+"""Seeded random GEMM calls against the oracle (GPU): shapes, layouts, leading dimensions, batch,
+scales, bias, output types and scratch lending drawn at random inside the documented limits, so that
+combinations no hand-written case names still get run.  The draw is fixed by its seed; every case runs
+K4 (whatever path its planner picks) and one earlier state.
+"""
+import numpy as np
+import pytest
+
+from paper_2605_28213_amd import gemm
+from paper_2605_28213_amd import inputs as gen
+from tests import util
+from tests.test_parity_gpu import oracle_for
+
+pytestmark = pytest.mark.gpu
+
+ROW, COL = gen.ROW_MAJOR, gen.COL_MAJOR
+
+
+def draw_case(rng, i):
+    dtype = int(rng.choice([gen.F32, gen.BF16, gen.F16, gen.E4M3], p=[0.1, 0.35, 0.3, 0.25]))
+    kind = rng.choice(["ragged", "aligned", "small_m", "thin_tail", "tiny"], p=[0.3, 0.3, 0.2, 0.1, 0.1])
+    la, lb = int(rng.choice([ROW, COL])), int(rng.choice([ROW, COL]))
+    batch = int(rng.choice([1, 1, 2, 3]))
+    if kind == "small_m":
+        M, N, K = int(rng.integers(1, 17)), int(rng.choice([40, 500, 8200])), int(rng.integers(1, 40)) * 8
+        la, lb = ROW, COL
+    elif kind == "thin_tail":
+        M, N, K = 256 * int(rng.integers(1, 3)) + int(rng.integers(1, 17)), int(rng.integers(100, 400)), int(rng.integers(60, 300))
+    elif kind == "tiny":
+        M, N, K = (int(rng.integers(0, 9)) for _ in range(3))
+    else:
+        M, N, K = int(rng.integers(1, 600)), int(rng.integers(1, 600)), int(rng.integers(1, 700))
+    es = gen.ELEM_BYTES[dtype]
+    if kind in ("aligned", "small_m"):
+        K = max(128 // es, K // (128 // es) * (128 // es)) if kind == "aligned" else K
+        la, lb = (ROW, COL) if rng.random() < 0.7 else (la, lb)
+        pad = lambda n: (n + 15) // 16 * 16
+    else:
+        pad = lambda n: n + int(rng.integers(0, 5))
+    out = int(rng.choice({gen.F32: [gen.F32], gen.BF16: [gen.BF16, gen.F32], gen.F16: [gen.F16, gen.F32], gen.E4M3: [gen.BF16, gen.F32]}[dtype]))
+    cfg = gen.Config(f"fuzz{i}", M, N, K, dtype, out, la, lb, str(rng.choice(["uniform", "normal"])),
+                     batch=batch, scaled=bool(rng.random() < 0.3), biased=bool(rng.random() < 0.3),
+                     lda=max(1, pad(K if la == ROW else M)), ldb=max(1, pad(N if lb == ROW else K)), ldc=max(1, pad(N)))
+    return cfg, bool(rng.random() < 0.6)
+
+
+CASES = [draw_case(np.random.default_rng(1000 + i), i) for i in range(48)]
+
+
+@pytest.mark.parametrize("i", range(len(CASES)))
+def test_random_case(i):
+    cfg, lend = CASES[i]
+    inp = gen.make_inputs(cfg, 100 + i)
+    C_ref, D = oracle_for(inp)
+    rng = np.random.default_rng(i)
+    variants = [gemm.GEMM_K4_MFMA, int(rng.integers(0, 4))] if cfg.in_dtype != gen.F32 else [int(rng.integers(0, 4)), int(rng.integers(0, 4))]
+    for v in variants:
+        rc, C, _ = util.run_config(v, inp, lend_workspace=lend)
+        q = gemm.gemm_query(v, gemm.make_desc(cfg.M, cfg.N, cfg.K, cfg.in_dtype, cfg.out_dtype, cfg.layout_a, cfg.layout_b,
+                                              lda=inp.lda, ldb=inp.ldb, ldc=inp.ldc, batch=cfg.batch))
+        assert rc == gemm.GEMM_OK, (cfg, gemm.gemm_variant_name(v), gemm.gemm_status_string(rc), gemm.gemm_last_launch_error())
+        if cfg.M * cfg.N == 0:
+            continue
+        err = util.norm_err(C[:, :, : cfg.N], C_ref, D)
+        assert err <= util.TOL[cfg.in_dtype], (cfg, gemm.gemm_variant_name(v), q.path, err)

@@ -2,7 +2,7 @@
 
 Sizes here are ones the oracle finishes in seconds while still spanning several workgroup tiles of
 every variant (the largest tile is 256 x 256 x 128 B of K) and ending in ragged tails.  Full-size
-workloads are covered by tests/test_full_size_gpu.py.
+workloads are covered by tests/test_gate_gpu.py.
 """
 import numpy as np
 import pytest
