@@ -758,14 +758,19 @@ __global__ __launch_bounds__(256) void k4_pack_rows(const char* __restrict__ src
 }
 
 // K strided in the source (elements of one k are contiguous along the rows that become the packed
-// rows).  A workgroup transposes a tile of 64 rows x 128 bytes of K through LDS.
+// rows).  A workgroup transposes a tile of PackRows<IN> rows x 128 bytes of K through LDS.  A tile's
+// rows span 248 bytes of a source line: with the line's misalignment at most 63 aligned dwords, one per
+// lane of a wave (a 64-row tile left half of the lanes idle and fetched twice the bytes it used).
+template <typename IN> constexpr int PackRows = 248 / IN::BYTES;
+
 template <typename IN>
 __global__ __launch_bounds__(256) void k4_pack_transpose(const char* __restrict__ src, int64_t k_bytes, int64_t rows, int64_t K,
                                                          int64_t Kp, char* __restrict__ dst, int64_t src_batch_bytes,
                                                          int64_t dst_batch_bytes)
 {
     using raw = typename IN::raw;
-    constexpr int BYTES = IN::BYTES, KE = ROW_BYTES / BYTES, V = 16 / BYTES, TR = 64, EPD = 4 / BYTES;
+    constexpr int BYTES = IN::BYTES, KE = ROW_BYTES / BYTES, V = 16 / BYTES, TR = PackRows<IN>, EPD = 4 / BYTES;
+    static_assert((TR * BYTES + 3 + 3) / 4 <= 64, "a line's span of a tile fits one dword per lane");
     constexpr int PITCH = KE + V;                       // elements; keeps rows 16-byte aligned, spreads banks
     __shared__ __attribute__((aligned(16))) raw tile[TR * PITCH];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;

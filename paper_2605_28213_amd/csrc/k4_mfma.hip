@@ -140,7 +140,7 @@ static hipError_t launch_packed(const Args& a)
             hipLaunchKernelGGL(k4_pack_rows<IN>, g, dim3(256), 0, a.stream, (const char*)src, sr * IN::BYTES, rows, a.K, Kp,
                                (char*)dst, src_batch_bytes, dst_batch_bytes);
         } else {   // sr == 1: row- or column-major storage leaves no other case
-            dim3 g((unsigned)(Kp / KE), (unsigned)((rows + 63) / 64), (unsigned)a.batch);
+            dim3 g((unsigned)(Kp / KE), (unsigned)((rows + PackRows<IN> - 1) / PackRows<IN>), (unsigned)a.batch);
             hipLaunchKernelGGL(k4_pack_transpose<IN>, g, dim3(256), 0, a.stream, (const char*)src, sk * IN::BYTES, rows, a.K, Kp,
                                (char*)dst, src_batch_bytes, dst_batch_bytes);
         }
