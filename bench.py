@@ -40,7 +40,7 @@ def kernel_sources_digest():
 
 PAPER_MM_8192_TFLOPS = 2.0 * 8192 ** 3 / 2.625e-3 / 1e12
 
-PEAK = {"mfma_bf16": 2500.0, "mfma_f16": 2500.0, "mfma_fp8": 5000.0, "valu_f32": 157.3, "hbm_GBs": 8000.0}
+PEAK = {"mfma_bf16": 2500.0, "mfma_f16": 2500.0, "mfma_fp8": 5000.0, "mfma_f32": 157.3, "hbm_GBs": 8000.0}
 
 
 def parse():
@@ -122,7 +122,7 @@ def main():
             ach = cfg.algorithmic_bytes / (mean_us * 1e-6) / 1e9
             return {"bound": "hbm", "achieved": ach, "peak": PEAK["hbm_GBs"], "unit": "GB/s",
                     "frac": ach / PEAK["hbm_GBs"], "traffic": None}
-        peak = PEAK["mfma_fp8"] if cfg.in_dtype == gen.E4M3 else PEAK["mfma_bf16"]
+        peak = PEAK["mfma_fp8"] if cfg.in_dtype == gen.E4M3 else PEAK["mfma_f32"] if cfg.in_dtype == gen.F32 else PEAK["mfma_bf16"]
         ach = cfg.flops / (mean_us * 1e-6) / 1e12
         return {"bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak, "traffic": None}
 
@@ -216,19 +216,14 @@ def main():
                     "PBMM16": ("TileLang +cfg, RTX PRO 6000, App. D", (0.703,)),
                     "PBMM32": ("TileLang +cfg, RTX PRO 6000, App. D", (0.226,)),
                     "PADDMM": ("TileLang +cfg, RTX PRO 6000, App. D", (0.375,))}
-        for name, bound in (("C1", "alu"), ("C3", "mfma"), ("C4", "hbm"), ("C5", "mfma"), ("P4096", "mfma"),
+        for name, bound in (("C1", "mfma"), ("C3", "mfma"), ("C4", "hbm"), ("C5", "mfma"), ("P4096", "mfma"),
                             ("P2048", "mfma"), ("PBMM16", "mfma"), ("PBMM32", "mfma"), ("PADDMM", "mfma")):
             c = gen.CONFIGS[name]
-            v = gemm.GEMM_K3_PIPELINED if name == "C1" else gemm.GEMM_K4_MFMA
+            v = gemm.GEMM_K4_MFMA
             _, s2, d2, keep2 = device_sets(c)
             _, sms = timed(v, s2, d2, 100, 25)
             ss = stats(sms)
-            if bound == "alu":
-                ach = c.flops / (ss["mean_us"] * 1e-6) / 1e12
-                rl = {"bound": "alu", "achieved": ach, "peak": PEAK["valu_f32"], "unit": "TFLOP/s",
-                      "frac": ach / PEAK["valu_f32"], "traffic": None}
-            else:
-                rl = roofline_for(c, ss["mean_us"], bound)
+            rl = roofline_for(c, ss["mean_us"], bound)
             entry = {"variant": gemm.gemm_variant_name(v), "path": gemm.gemm_query(v, d2, *s2[0]).path,
                      "launch_us": ss, "TFLOP/s": c.flops / (ss["mean_us"] * 1e-6) / 1e12,
                      "GB/s": c.algorithmic_bytes / (ss["mean_us"] * 1e-6) / 1e9, "roofline": rl}

@@ -61,7 +61,7 @@ typedef enum {
     GEMM_K1_LDS_TILED = 1,  /* + "tile / sm_stage": workgroup output tiles, K slabs staged through LDS */
     GEMM_K2_VECTORIZED = 2, /* + "vectorize_global": 16-byte global loads, element-masked tails */
     GEMM_K3_PIPELINED = 3,  /* + "pipeline": double-buffered LDS, next slab in flight during compute */
-    GEMM_K4_MFMA = 4,       /* + "mma" / "swizzle": wave64 MFMA, swizzled LDS operand layout */
+    GEMM_K4_MFMA = 4,       /* + "mma" / "swizzle": wave64 MFMA, swizzled LDS operand layout (fp32: its masked kernel only) */
     GEMM_VARIANT_COUNT = 5
 } gemm_variant_t;
 
@@ -80,7 +80,7 @@ enum {
     GEMM_COND_TILE_DIV_K     = 1u << 8,
     GEMM_COND_K_CONTIG_A     = 1u << 9,  /* A stored with K contiguous (row-major) */
     GEMM_COND_K_CONTIG_B     = 1u << 10, /* B stored with K contiguous (column-major) */
-    GEMM_COND_DTYPE_HAS_MFMA = 1u << 11, /* the input dtype has a matrix instruction on gfx950 */
+    GEMM_COND_DTYPE_HAS_MFMA = 1u << 11, /* the input dtype has a matrix instruction on gfx950 (all four do) */
     GEMM_COND_LDS_STAGED     = 1u << 12, /* operands pass through LDS (holds from K1 on) */
     GEMM_COND_SMALL_M        = 1u << 13  /* M <= 16: the streaming (bandwidth-bound) path applies */
 };

@@ -116,7 +116,7 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
     if ((d->ldc * eo) % 16 == 0) holds |= GEMM_COND_LD16_C;
     if (d->layout_a == GEMM_ROW_MAJOR) holds |= GEMM_COND_K_CONTIG_A;
     if (d->layout_b == GEMM_COL_MAJOR) holds |= GEMM_COND_K_CONTIG_B;
-    if (d->in_dtype != GEMM_F32) holds |= GEMM_COND_DTYPE_HAS_MFMA;
+    holds |= GEMM_COND_DTYPE_HAS_MFMA;   // all four input types have one on gfx950 (fp32: v_mfma_f32_32x32x2_f32)
     if (variant >= GEMM_K1_LDS_TILED) holds |= GEMM_COND_LDS_STAGED;
     if (d->M <= 16) holds |= GEMM_COND_SMALL_M;
 
@@ -155,16 +155,19 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
         const bool skinny = (holds & GEMM_COND_SMALL_M) && va && vb && d->K % kvec == 0 && d->K > 0 &&
                             (d->in_dtype == GEMM_BF16 || d->in_dtype == GEMM_F16) && d->ldb <= ((int64_t)1 << 24) &&
                             d->lda <= ((int64_t)1 << 24);
+        // fp32 has its matrix instruction in the masked kernel only: no direct-to-LDS, packed or streaming form
+        const bool f32 = d->in_dtype == GEMM_F32;
+        if (f32) required = GEMM_COND_DTYPE_HAS_MFMA | GEMM_COND_LDS_STAGED;
         const bool kdiv = d->K % (128 / es) == 0;   // whole 128-byte slabs: the direct-to-LDS kernel masks nothing along K
         // that kernel addresses a 256-row tile with 32-bit byte offsets: rows are bounded to 4 MiB
         const bool rows_fit = d->lda * es <= ((int64_t)1 << 22) && d->ldb * es <= ((int64_t)1 << 22);
         // packing both operands into lent scratch turns any layout/alignment/K into the fast kernel's case
-        const bool can_pack = (holds & GEMM_COND_DTYPE_HAS_MFMA) && d->K > 0 && k4_packed_k(a) * es <= ((int64_t)1 << 22);
+        const bool can_pack = !f32 && d->K > 0 && k4_packed_k(a) * es <= ((int64_t)1 << 22);
         if (skinny) {
             p.path = MFMA_SKINNY;
             path = "mfma16-stream(small-M)";
             required &= ~(uint32_t)GEMM_COND_TILE_DIV_K;
-        } else if (va && vb && kdiv && rows_fit) {
+        } else if (!f32 && va && vb && kdiv && rows_fit) {
             p.path = MFMA_VEC16 | (3 << 8);
             path = k4_splits_m_tail(a) ? "mfma32-direct-to-lds+stream(M-tail)" : "mfma32-direct-to-lds";
         } else if (can_pack && d->workspace != nullptr) {
@@ -178,8 +181,7 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
             path = va && vb ? "mfma32-vec16-masked" : va ? "mfma32-vec16(A)+elementwise-masked(B)"
                             : vb ? "mfma32-elementwise-masked(A)+vec16(B)" : "mfma32-elementwise-masked";
         }
-        if (holds & GEMM_COND_DTYPE_HAS_MFMA) g = geometry_k4(p.path & 0xFF, a);
-        else path = "refused(no matrix instruction for this dtype)";
+        g = geometry_k4(p.path & 0xFF, a);
         break;
     }
     }

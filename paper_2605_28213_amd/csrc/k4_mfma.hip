@@ -9,7 +9,7 @@ template <typename IN> using FastK4 = FastCfg<IN, 256>;                    // 25
 template <typename IN> using FastK4Small = FastCfg<IN, 128>;               // 128x128 tile, 4 waves, 64x64 per wave, two workgroups per CU
 template <typename IN> using StreamK4 = StreamCfg<IN, 1, 1, 256, 19>;      // 16 columns per one-wave workgroup, 512-byte runs, K walk rotated by 19 tiles per workgroup
 template <typename IN> using StreamK4Deep = StreamCfg<IN, 4, 1, 256, 19>;  // the same with 4 waves taking K tiles in turn, for strips too few to fill the chip
-constexpr int MASKED_BM = 128, MASKED_BN = 128, MASKED_WM = 2, MASKED_WN = 2;
+constexpr int MASKED_BM = 128, MASKED_BN = 128, MASKED_WM = 2, MASKED_WN = 2;   // (64 x 64 for small problems, see masked_tile)
 
 template <typename CFG>
 static hipError_t launch_fast(const Args& a)
@@ -23,14 +23,27 @@ static hipError_t launch_fast(const Args& a)
     return hipGetLastError();
 }
 
+// The masked kernel takes 64 x 64 tiles (one 32 x 32 accumulator tile per wave) when 128 x 128 tiles would
+// leave most CUs idle (fp32 256^3: 4 workgroups took 37 us).
+static int masked_tile(const Args& a)
+{
+    const int64_t t = ((a.M + MASKED_BM - 1) / MASKED_BM) * ((a.N + MASKED_BN - 1) / MASKED_BN) * a.batch;
+    return t < 256 ? 64 : MASKED_BM;
+}
+
+template <typename IN, int BT>
+static hipError_t launch_masked_tile(const Args& a, int vec_mask)
+{
+    const int tiles_m = (int)((a.M + BT - 1) / BT), tiles_n = (int)((a.N + BT - 1) / BT);
+    dim3 grid((unsigned)((int64_t)tiles_m * tiles_n * a.batch), 1, 1), block(MASKED_WM * MASKED_WN * 64, 1, 1);
+    hipLaunchKernelGGL((k4_mfma_masked<IN, BT, BT, MASKED_WM, MASKED_WN>), grid, block, 0, a.stream, a, vec_mask, tiles_m, tiles_n);
+    return hipGetLastError();
+}
+
 template <typename IN>
 static hipError_t launch_masked(const Args& a, int vec_mask)
 {
-    const int tiles_m = (int)((a.M + MASKED_BM - 1) / MASKED_BM), tiles_n = (int)((a.N + MASKED_BN - 1) / MASKED_BN);
-    dim3 grid((unsigned)((int64_t)tiles_m * tiles_n * a.batch), 1, 1), block(MASKED_WM * MASKED_WN * 64, 1, 1);
-    hipLaunchKernelGGL((k4_mfma_masked<IN, MASKED_BM, MASKED_BN, MASKED_WM, MASKED_WN>), grid, block, 0, a.stream, a,
-                       vec_mask, tiles_m, tiles_n);
-    return hipGetLastError();
+    return masked_tile(a) == 64 ? launch_masked_tile<IN, 64>(a, vec_mask) : launch_masked_tile<IN, MASKED_BM>(a, vec_mask);
 }
 
 template <typename CFG>
@@ -107,7 +120,7 @@ static hipError_t launch_fast_split(const Args& a)
     return launch_fast_any<IN>(a);
 }
 
-static int elem_bytes(int dt) { return dt == GEMM_FP8_E4M3 ? 1 : 2; }
+static int elem_bytes(int dt) { return dt == GEMM_FP8_E4M3 ? 1 : dt == GEMM_F32 ? 4 : 2; }
 
 int64_t k4_packed_k(const Args& a)
 {
@@ -182,6 +195,7 @@ hipError_t launch_k4(int path, const Args& a)
         }
     }
     switch (a.in_dtype) {
+    case GEMM_F32: return launch_masked<F32>(a, vec_mask);
     case GEMM_BF16: return launch_masked<BF16>(a, vec_mask);
     case GEMM_F16: return launch_masked<F16>(a, vec_mask);
     case GEMM_FP8_E4M3: return launch_masked<E4M3>(a, vec_mask);
@@ -206,7 +220,7 @@ hipError_t launch_k4_conv(const Args& a)
 Geometry geometry_k4_conv(const Args& a)
 {
     using C = ConvK4<BF16>;
-    const int es = a.in_dtype == GEMM_FP8_E4M3 ? 1 : 2;
+    const int es = elem_bytes(a.in_dtype);
     const int64_t g = ((a.M + C::BM - 1) / C::BM) * ((a.N + C::BN - 1) / C::BN);
     return Geometry{C::BM, C::BN, ROW_BYTES / es, C::T, 2, C::LDS_BYTES, g};
 }
@@ -214,7 +228,7 @@ Geometry geometry_k4_conv(const Args& a)
 Geometry geometry_k4(int path, const Args& a)
 {
     const int kind = path & 0xFF;
-    const int es = a.in_dtype == GEMM_FP8_E4M3 ? 1 : 2;
+    const int es = elem_bytes(a.in_dtype);
     if (kind == MFMA_SKINNY) {
         using C = StreamK4<BF16>;
         using D = StreamK4Deep<BF16>;
@@ -229,8 +243,9 @@ Geometry geometry_k4(int path, const Args& a)
         // stages: slabs in flight beyond the one in use
         return Geometry{bt, bt, ROW_BYTES / es, 256, 2, small ? FastK4Small<BF16>::LDS_BYTES : FastK4<BF16>::LDS_BYTES, g};
     }
-    const int64_t g = ((a.M + MASKED_BM - 1) / MASKED_BM) * ((a.N + MASKED_BN - 1) / MASKED_BN) * a.batch;
-    return Geometry{MASKED_BM, MASKED_BN, ROW_BYTES / es, MASKED_WM * MASKED_WN * 64, 2, 2 * (MASKED_BM + MASKED_BN) * ROW_BYTES, g};
+    const int bt = masked_tile(a);
+    const int64_t g = ((a.M + bt - 1) / bt) * ((a.N + bt - 1) / bt) * a.batch;
+    return Geometry{bt, bt, ROW_BYTES / es, MASKED_WM * MASKED_WN * 64, 2, 4 * bt * ROW_BYTES, g};
 }
 
 }  // namespace gl

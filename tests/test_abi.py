@@ -107,12 +107,15 @@ def test_bad_variant():
         assert gemm.gemm_run(v, 8, 8, 8, 0, 16, 16, 16) == gemm.GEMM_ERR_BAD_VARIANT
 
 
-def test_fp32_has_no_matrix_instruction_path():
+def test_fp32_runs_the_expert_state_on_its_masked_kernel_only():
     d = gemm.make_desc(256, 256, 256, gemm.GEMM_F32, gemm.GEMM_F32, 0, 0)
     q = gemm.gemm_query(gemm.GEMM_K4_MFMA, d)
-    assert q.status == gemm.GEMM_ERR_PRECONDITION and "DTYPE_HAS_MFMA" in gemm.Query.names(q.violated)
-    # refused before any launch, so a fake pointer is never touched
-    assert gemm.gemm_run_ex(gemm.GEMM_K4_MFMA, d, 0x1000, 0x1000, 0x1000) == gemm.GEMM_ERR_PRECONDITION
+    assert q.status == gemm.GEMM_OK and q.violated == 0 and "DTYPE_HAS_MFMA" in gemm.Query.names(q.holds)
+    assert "masked" in q.path and (q.bm, q.bn, q.bk) == (64, 64, 32) and q.workspace_bytes == 0      # 4 tiles of 128: small
+    strict = gemm.make_desc(256, 256, 256, gemm.GEMM_F32, gemm.GEMM_F32, 0, 0, flags=gemm.GEMM_FLAG_STRICT)
+    assert gemm.gemm_query(gemm.GEMM_K4_MFMA, strict).status == gemm.GEMM_OK      # it has no faster path to insist on
+    lent = gemm.make_desc(256, 256, 256, gemm.GEMM_F32, gemm.GEMM_F32, 0, 0, workspace=4096, workspace_bytes=1 << 30)
+    assert "packed" not in gemm.gemm_query(gemm.GEMM_K4_MFMA, lent).path
 
 
 def test_query_reports_paths_and_conditions_for_the_five_workloads():

@@ -93,10 +93,6 @@ def test_every_state_passes_the_gate(name):
         print(f"[gate] {name} {gemm.gemm_variant_name(v)}", flush=True)
         e = gate.run_gate(v, cfg, reference, inputs_cache=cache, ledger_path=LEDGER, time_budget_s=1.0)
         _entries.append(e)
-        if v == gemm.GEMM_K4_MFMA and cfg.in_dtype == gen.F32:
-            # fp32 has no matrix instruction: the expert state refuses instead of substituting another state
-            assert e["verdict"].startswith("refused(precondition") and "DTYPE_HAS_MFMA" in e["verdict"]
-            continue
         assert e["compile"]["ok"]
         assert e["verdict"] == "passed", (name, e["variant_name"], e["verdict"], e.get("correctness"))
         assert len(e["correctness"]) == 3 and all(s["all_outputs_finite"] for s in e["correctness"])
@@ -170,4 +166,4 @@ def test_strict_mode_refuses_and_names_the_violated_conditions():
 def test_pass_rate_of_the_ledger():
     pr = gate.pass_rate(_entries)
     assert pr["attempted"] >= 5 * 3 * 4 and pr["passed"] == pr["attempted"]
-    assert len(pr["refused"]) >= 4
+    assert len(pr["refused"]) >= 3

@@ -39,8 +39,7 @@ def test_masks_status_and_geometry_are_consistent(p, variant):
     q = gemm.gemm_query(variant, make(p))
     assert q.status in (gemm.GEMM_OK, gemm.GEMM_ERR_PRECONDITION)
     assert q.violated == q.required & ~q.holds
-    no_mfma = variant == gemm.GEMM_K4_MFMA and p["dt"] == gemm.GEMM_F32
-    assert (q.status == gemm.GEMM_ERR_PRECONDITION) == no_mfma          # every other violation has a slow path
+    assert q.status == gemm.GEMM_OK                                     # every violation has a slow path of the same state
     strict = gemm.gemm_query(variant, make(p, flags=gemm.GEMM_FLAG_STRICT))
     assert (strict.status == gemm.GEMM_ERR_PRECONDITION) == (q.violated != 0)
     assert strict.path == q.path and strict.violated == q.violated
@@ -54,10 +53,13 @@ def test_masks_status_and_geometry_are_consistent(p, variant):
 @settings(max_examples=300, deadline=None)
 @given(descriptors())
 def test_expert_state_paths_and_scratch(p):
-    if p["dt"] == gemm.GEMM_F32:
-        return
     es = ES[p["dt"]]
     q = gemm.gemm_query(gemm.GEMM_K4_MFMA, make(p))
+    if p["dt"] == gemm.GEMM_F32:
+        # fp32 runs its matrix instruction in the masked kernel only: no fast, packed or streaming form, no scratch
+        assert q.status == gemm.GEMM_OK and "masked" in q.path and q.workspace_bytes == 0 and q.violated == 0
+        assert (q.bm, q.bn) in ((128, 128), (64, 64)) and q.bk == 32
+        return
     fast_ok = (p["la"] == gemm.GEMM_ROW_MAJOR and p["lb"] == gemm.GEMM_COL_MAJOR and (p["lda"] * es) % 16 == 0
                and (p["ldb"] * es) % 16 == 0 and (p["batch"] == 1 or ((p["M"] * p["lda"] * es) % 16 == 0 and (p["N"] * p["ldb"] * es) % 16 == 0)))
     kvec, kslab = 16 // es, 128 // es
