@@ -50,7 +50,7 @@ enum {
     CONV_COND_ALIGN16_W      = 1u << 1,
     CONV_COND_ALIGN16_Y      = 1u << 2,
     CONV_COND_C_WHOLE_SLABS  = 1u << 3, /* C * element size is a multiple of 128 bytes: a K slab never straddles two taps */
-    CONV_COND_DTYPE_HAS_MFMA = 1u << 4, /* the input dtype has a matrix instruction on gfx950 (not fp32) */
+    CONV_COND_DTYPE_ON_FAST_KERNEL = 1u << 4, /* bf16, fp16 or e4m3: the types K4's direct-to-LDS kernel is built for (fp32 runs on C0 only) */
     CONV_COND_X_BELOW_2GIB   = 1u << 5, /* x spans less than 2^31 bytes: the gather uses 32-bit byte offsets */
     CONV_COND_SCRATCH_LENT   = 1u << 6  /* workspace of at least conv2d_query's workspace_bytes, 16-byte aligned */
 };

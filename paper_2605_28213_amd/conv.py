@@ -15,7 +15,7 @@ from .gemm import _addr, _stream_addr
 CONV_C0_DIRECT, CONV_C1_IM2COL_MFMA, CONV_C2_IMPLICIT_MFMA = 0, 1, 2
 CONV_VARIANT_COUNT = 3
 COND_BITS = {name: 1 << i for i, name in enumerate(
-    ["ALIGN16_X", "ALIGN16_W", "ALIGN16_Y", "C_WHOLE_SLABS", "DTYPE_HAS_MFMA", "X_BELOW_2GIB", "SCRATCH_LENT"])}
+    ["ALIGN16_X", "ALIGN16_W", "ALIGN16_Y", "C_WHOLE_SLABS", "DTYPE_ON_FAST_KERNEL", "X_BELOW_2GIB", "SCRATCH_LENT"])}
 
 
 class conv2d_desc_t(ctypes.Structure):

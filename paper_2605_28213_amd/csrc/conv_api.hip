@@ -171,7 +171,7 @@ Plan make_plan(int variant, const conv2d_desc_t* d, const void* x, const void* w
     if (!w || ((uintptr_t)w & 15u) == 0) holds |= CONV_COND_ALIGN16_W;
     if (!y || ((uintptr_t)y & 15u) == 0) holds |= CONV_COND_ALIGN16_Y;
     if ((d->C * es) % 128 == 0) holds |= CONV_COND_C_WHOLE_SLABS;
-    if (d->in_dtype != GEMM_F32) holds |= CONV_COND_DTYPE_HAS_MFMA;
+    if (d->in_dtype != GEMM_F32) holds |= CONV_COND_DTYPE_ON_FAST_KERNEL;
     if (x_bytes < ((int64_t)1 << 31)) holds |= CONV_COND_X_BELOW_2GIB;
 
     // the matrix product both MFMA states run: rows = output pixels, columns = filters
@@ -193,7 +193,7 @@ Plan make_plan(int variant, const conv2d_desc_t* d, const void* x, const void* w
         if (geo.grid >= ((int64_t)1 << 31)) return fail(GEMM_ERR_BAD_ARG);
         break;
     case CONV_C1_IM2COL_MFMA: {
-        required = CONV_COND_DTYPE_HAS_MFMA | CONV_COND_SCRATCH_LENT;
+        required = CONV_COND_DTYPE_ON_FAST_KERNEL | CONV_COND_SCRATCH_LENT;
         p.pad_w = Kp != K || !(holds & CONV_COND_ALIGN16_W);
         need = (size_t)(M * Kp * es) + (p.pad_w ? (size_t)(d->F * Kp * es) : 0);
         if (d->workspace && d->workspace_bytes >= need && ((uintptr_t)d->workspace & 15u) == 0) holds |= CONV_COND_SCRATCH_LENT;
@@ -201,18 +201,18 @@ Plan make_plan(int variant, const conv2d_desc_t* d, const void* x, const void* w
         g.B = p.pad_w ? (const void*)((const char*)d->workspace + M * Kp * es) : w;
         g.K = Kp; g.a_si = Kp; g.b_sj = Kp;
         path = p.pad_w ? "im2col+pad(w)+mfma32-direct-to-lds" : "im2col+mfma32-direct-to-lds";
-        if (holds & CONV_COND_DTYPE_HAS_MFMA) geo = geometry_k4(MFMA_VEC16, g);
+        if (holds & CONV_COND_DTYPE_ON_FAST_KERNEL) geo = geometry_k4(MFMA_VEC16, g);
         if ((M * (Kp / (16 / es)) + 255) / 256 >= ((int64_t)1 << 31)) return fail(GEMM_ERR_BAD_ARG);
         break;
     }
     default: {  // CONV_C2_IMPLICIT_MFMA
-        required = CONV_COND_DTYPE_HAS_MFMA | CONV_COND_C_WHOLE_SLABS | CONV_COND_ALIGN16_X | CONV_COND_ALIGN16_W | CONV_COND_X_BELOW_2GIB;
+        required = CONV_COND_DTYPE_ON_FAST_KERNEL | CONV_COND_C_WHOLE_SLABS | CONV_COND_ALIGN16_X | CONV_COND_ALIGN16_W | CONV_COND_X_BELOW_2GIB;
         g.A = x; g.B = w;
         g.K = K; g.a_si = 0; g.b_sj = K;
         g.conv = ConvGeom{(int32_t)d->H, (int32_t)d->W, (int32_t)d->C, (int32_t)P, (int32_t)Q, (int32_t)d->S,
                           d->stride_h, d->stride_w, d->pad_h, d->pad_w, (int32_t)(d->C * es / 128), (uint32_t)x_bytes};
         path = "implicit-gather+mfma32-direct-to-lds";
-        if (holds & CONV_COND_DTYPE_HAS_MFMA) geo = geometry_k4_conv(g);
+        if (holds & CONV_COND_DTYPE_ON_FAST_KERNEL) geo = geometry_k4_conv(g);
         break;
     }
     }
@@ -332,7 +332,7 @@ const char* conv2d_cond_name(uint32_t bit)
     case CONV_COND_ALIGN16_W: return "ALIGN16_W";
     case CONV_COND_ALIGN16_Y: return "ALIGN16_Y";
     case CONV_COND_C_WHOLE_SLABS: return "C_WHOLE_SLABS";
-    case CONV_COND_DTYPE_HAS_MFMA: return "DTYPE_HAS_MFMA";
+    case CONV_COND_DTYPE_ON_FAST_KERNEL: return "DTYPE_ON_FAST_KERNEL";
     case CONV_COND_X_BELOW_2GIB: return "X_BELOW_2GIB";
     case CONV_COND_SCRATCH_LENT: return "SCRATCH_LENT";
     default: return "?";

@@ -94,7 +94,7 @@ def test_implicit_state_refuses_what_it_cannot_gather():
     f32 = conv.make_desc(1, 8, 8, 64, 8, 3, 3, gen.F32, gen.F32, pad=(1, 1))
     for v in (1, 2):
         q = conv.conv2d_query(v, f32)
-        assert q.status == gemm.GEMM_ERR_PRECONDITION and "DTYPE_HAS_MFMA" in conv.Query.names(q.violated)
+        assert q.status == gemm.GEMM_ERR_PRECONDITION and "DTYPE_ON_FAST_KERNEL" in conv.Query.names(q.violated)
     assert conv.conv2d_query(0, f32).status == gemm.GEMM_OK
 
 
