@@ -53,9 +53,11 @@ __device__ __forceinline__ int block_scan(int v, int* wsum, int* total)
 
 // Ordered compaction shared by all states.  Each thread owns a contiguous run of elements [lo, hi) and
 // classifies element i through `cls(i)`: 2 = above the threshold, 1 = equal to it, 0 = below.  Selected
-// are all of class 2 and the first `take_equal` of class 1 in index order; they are written in index order.
-template <int T, typename CLS>
-__device__ __forceinline__ void compact(const TopkArgs& a, const float* row, int64_t lo, int64_t hi, int take_equal, int* wsum, CLS cls)
+// are all of class 2 and the first `take_equal` of class 1 in index order; they are written in index
+// order, values taken from `value(i)`.  Rows shorter than 65536 elements need one scan (both counts
+// packed into one word), longer ones two.
+template <int T, typename CLS, typename VAL>
+__device__ __forceinline__ void compact(const TopkArgs& a, int64_t lo, int64_t hi, int take_equal, int* wsum, CLS cls, VAL value)
 {
     int gt = 0, eq = 0;
     for (int64_t i = lo; i < hi; ++i) {
@@ -63,9 +65,15 @@ __device__ __forceinline__ void compact(const TopkArgs& a, const float* row, int
         gt += c == 2;
         eq += c == 1;
     }
-    int total;
-    int g = block_scan<T>(gt, wsum, &total) - gt;      // class-2 elements before this thread's run
-    int e = block_scan<T>(eq, wsum, &total) - eq;      // class-1 elements before it
+    int total, g, e;
+    if (a.n < 65536) {
+        const int both = block_scan<T>(gt | (eq << 16), wsum, &total) - (gt | (eq << 16));
+        g = both & 0xFFFF;                             // class-2 elements before this thread's run
+        e = (int)((uint32_t)both >> 16);               // class-1 elements before it
+    } else {
+        g = block_scan<T>(gt, wsum, &total) - gt;
+        e = block_scan<T>(eq, wsum, &total) - eq;
+    }
     int32_t* idx = a.idx + (int64_t)blockIdx.x * a.k;
     float* val = a.val + (int64_t)blockIdx.x * a.k;
     for (int64_t i = lo; i < hi; ++i) {
@@ -74,7 +82,7 @@ __device__ __forceinline__ void compact(const TopkArgs& a, const float* row, int
             const int64_t pos = g + (e < take_equal ? e : take_equal);
             if (pos < a.k) {                            // always true for NaN-free rows
                 idx[pos] = (int32_t)i;
-                val[pos] = row[i];
+                val[pos] = value(i);
             }
         }
         g += c == 2;
@@ -125,7 +133,7 @@ __global__ __launch_bounds__(SEL_T) void topk_selection(TopkArgs a)
     }
     const int64_t seg = (a.n + SEL_T - 1) / SEL_T;
     const int64_t lo = tid * seg < a.n ? tid * seg : a.n, hi = lo + seg < a.n ? lo + seg : a.n;
-    compact<SEL_T>(a, row, lo, hi, 0, wsum, [&](int64_t i) { return taken[i] ? 2 : 0; });
+    compact<SEL_T>(a, lo, hi, 0, wsum, [&](int64_t i) { return taken[i] ? 2 : 0; }, [&](int64_t i) { return row[i]; });
 }
 
 // ---- T1 / T2: radix select ----------------------------------------------------------------------
@@ -145,7 +153,10 @@ __global__ __launch_bounds__(T) void topk_radix(TopkArgs a)
     const int tid = threadIdx.x;
     const int64_t n = a.n;
 
-    uint32_t keys[RESIDENT ? ITEMS : 1];
+    // resident form: the thread's values as loaded (bit patterns; the key is three ALU operations away).
+    // Elements past n are held as the pattern whose key is 0, below every non-NaN key.
+    constexpr uint32_t PAD_BITS = 0xFFFFFFFFu;
+    uint32_t held[RESIDENT ? ITEMS : 1];
     if constexpr (RESIDENT) {
         static_assert(ITEMS % 4 == 0, "16-byte loads");
 #pragma unroll
@@ -153,10 +164,10 @@ __global__ __launch_bounds__(T) void topk_radix(TopkArgs a)
             const int64_t i = (int64_t)tid * ITEMS + j;
             if (i + 3 < n) {
                 const float4 v = *(const float4*)(row + i);
-                keys[j] = key_of(v.x); keys[j + 1] = key_of(v.y); keys[j + 2] = key_of(v.z); keys[j + 3] = key_of(v.w);
+                held[j] = __float_as_uint(v.x); held[j + 1] = __float_as_uint(v.y); held[j + 2] = __float_as_uint(v.z); held[j + 3] = __float_as_uint(v.w);
             } else {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) keys[j + e] = i + e < n ? key_of(row[i + e]) : 0u;   // 0: below every non-NaN key
+                for (int e = 0; e < 4; ++e) held[j + e] = i + e < n ? __float_as_uint(row[i + e]) : PAD_BITS;
             }
         }
     }
@@ -171,8 +182,10 @@ __global__ __launch_bounds__(T) void topk_radix(TopkArgs a)
         __syncthreads();
         if constexpr (RESIDENT) {
 #pragma unroll
-            for (int j = 0; j < ITEMS; ++j)
-                if ((keys[j] & mask) == prefix) atomicAdd(&hist[(keys[j] >> shift) & (nb - 1)], 1);
+            for (int j = 0; j < ITEMS; ++j) {
+                const uint32_t key = key_of(__uint_as_float(held[j]));
+                if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & (nb - 1)], 1);
+            }
         } else {
             for (int64_t i = tid; i < n; i += T) {
                 const uint32_t key = key_of(row[i]);
@@ -210,19 +223,21 @@ __global__ __launch_bounds__(T) void topk_radix(TopkArgs a)
     if constexpr (RESIDENT) {
         const int64_t lo = (int64_t)tid * ITEMS < n ? (int64_t)tid * ITEMS : n, hi = lo + ITEMS < n ? lo + ITEMS : n;
         const int64_t base = (int64_t)tid * ITEMS;
-        compact<T>(a, row, lo, hi, remaining, wsum, [&](int64_t i) {
-            uint32_t key = 0;
+        auto bits_of = [&](int64_t i) {
+            uint32_t b = PAD_BITS;
 #pragma unroll
-            for (int j = 0; j < ITEMS; ++j) key = (i - base == j) ? keys[j] : key;     // register select, no scratch
-            return key > thr ? 2 : key == thr ? 1 : 0;
-        });
+            for (int j = 0; j < ITEMS; ++j) b = (i - base == j) ? held[j] : b;       // register select, no scratch
+            return b;
+        };
+        compact<T>(a, lo, hi, remaining, wsum,
+                   [&](int64_t i) { const uint32_t key = key_of(__uint_as_float(bits_of(i))); return key > thr ? 2 : key == thr ? 1 : 0; },
+                   [&](int64_t i) { return __uint_as_float(bits_of(i)); });
     } else {
         const int64_t seg = (n + T - 1) / T;
         const int64_t lo = tid * seg < n ? tid * seg : n, hi = lo + seg < n ? lo + seg : n;
-        compact<T>(a, row, lo, hi, remaining, wsum, [&](int64_t i) {
-            const uint32_t key = key_of(row[i]);
-            return key > thr ? 2 : key == thr ? 1 : 0;
-        });
+        compact<T>(a, lo, hi, remaining, wsum,
+                   [&](int64_t i) { const uint32_t key = key_of(row[i]); return key > thr ? 2 : key == thr ? 1 : 0; },
+                   [&](int64_t i) { return row[i]; });
     }
 }
 

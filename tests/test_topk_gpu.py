@@ -84,6 +84,16 @@ def test_degenerate_values(variant):
         check(variant, x, n, k)
 
 
+def test_long_runs_of_equal_values_in_long_rows():
+    """More than 32767 elements equal to the threshold in a row shorter than 65536 (the compaction's
+    counts share one word there), and a row beyond 65536 (two scans)."""
+    for n, k in ((50000, 40000), (65535, 65000), (66000, 40000)):
+        x = np.full((2, n), 1.5, np.float32)
+        x[1, ::7] = 2.0
+        x[1, 5::11] = -3.0
+        check(1, x, n, k)
+
+
 def test_empty_calls_and_misaligned_rows():
     x = np.random.default_rng(0).standard_normal((2, 64)).astype(np.float32)
     for variant in range(3):
