@@ -90,6 +90,21 @@ __device__ __forceinline__ float batch_scale(const Args& a, int64_t b)
     return s;
 }
 
+// ---- host-side helpers shared by the entry points -------------------------------------------------
+inline int elem_size(int dt) { return dt == GEMM_F32 ? 4 : dt == GEMM_FP8_E4M3 ? 1 : 2; }
+
+// input / output type pairs the library implements (accumulation is always fp32)
+inline bool dtype_pair_supported(int in, int out)
+{
+    switch (in) {
+    case GEMM_F32: return out == GEMM_F32;
+    case GEMM_BF16: return out == GEMM_BF16 || out == GEMM_F32;
+    case GEMM_F16: return out == GEMM_F16 || out == GEMM_F32;
+    case GEMM_FP8_E4M3: return out == GEMM_BF16 || out == GEMM_F32;
+    default: return false;
+    }
+}
+
 // ---- host-side launchers, one per translation unit ---------------------------------------------
 // Each returns hipSuccess or the launch error.  `path` selects a code path that the caller
 // (gemm_api.hip) has already proven legal for these arguments.

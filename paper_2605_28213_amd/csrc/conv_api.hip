@@ -105,19 +105,6 @@ __global__ __launch_bounds__(256) void conv_pad_rows(const void* src, char* dst,
     *(uint4*)(dst + (f * Kp + k0) * IN::BYTES) = out;
 }
 
-int elem_size(int dt) { return dt == GEMM_F32 ? 4 : dt == GEMM_FP8_E4M3 ? 1 : 2; }
-
-bool dtype_pair_supported(int in, int out)
-{
-    switch (in) {
-    case GEMM_F32: return out == GEMM_F32;
-    case GEMM_BF16: return out == GEMM_BF16 || out == GEMM_F32;
-    case GEMM_F16: return out == GEMM_F16 || out == GEMM_F32;
-    case GEMM_FP8_E4M3: return out == GEMM_BF16 || out == GEMM_F32;
-    default: return false;
-    }
-}
-
 struct Plan {
     int status = GEMM_OK;
     bool empty = false;

@@ -17,19 +17,6 @@ namespace {
 constexpr int ABI_VERSION = 2;
 thread_local hipError_t last_launch_error = hipSuccess;   // of the calling thread's most recent GEMM_ERR_LAUNCH
 
-bool dtype_pair_supported(int in, int out)
-{
-    switch (in) {
-    case GEMM_F32: return out == GEMM_F32;
-    case GEMM_BF16: return out == GEMM_BF16 || out == GEMM_F32;
-    case GEMM_F16: return out == GEMM_F16 || out == GEMM_F32;
-    case GEMM_FP8_E4M3: return out == GEMM_BF16 || out == GEMM_F32;
-    default: return false;
-    }
-}
-
-int elem_size(int dt) { return dt == GEMM_F32 ? 4 : dt == GEMM_FP8_E4M3 ? 1 : 2; }
-
 bool aligned16(const void* p, int64_t batch, int64_t stride, int es)
 {
     if (p && ((uintptr_t)p & 15u)) return false;

@@ -120,17 +120,16 @@ static hipError_t launch_fast_split(const Args& a)
     return launch_fast_any<IN>(a);
 }
 
-static int elem_bytes(int dt) { return dt == GEMM_FP8_E4M3 ? 1 : dt == GEMM_F32 ? 4 : 2; }
 
 int64_t k4_packed_k(const Args& a)
 {
-    const int64_t ke = ROW_BYTES / elem_bytes(a.in_dtype);
+    const int64_t ke = ROW_BYTES / elem_size(a.in_dtype);
     return (a.K + ke - 1) / ke * ke;
 }
 
 size_t k4_packed_workspace_bytes(const Args& a)
 {
-    return (size_t)(a.batch * (a.M + a.N) * k4_packed_k(a)) * elem_bytes(a.in_dtype);
+    return (size_t)(a.batch * (a.M + a.N) * k4_packed_k(a)) * elem_size(a.in_dtype);
 }
 
 // Packed path: both operands are rewritten K-contiguous, aligned and zero-padded along K in the
@@ -220,7 +219,7 @@ hipError_t launch_k4_conv(const Args& a)
 Geometry geometry_k4_conv(const Args& a)
 {
     using C = ConvK4<BF16>;
-    const int es = elem_bytes(a.in_dtype);
+    const int es = elem_size(a.in_dtype);
     const int64_t g = ((a.M + C::BM - 1) / C::BM) * ((a.N + C::BN - 1) / C::BN);
     return Geometry{C::BM, C::BN, ROW_BYTES / es, C::T, 2, C::LDS_BYTES, g};
 }
@@ -228,7 +227,7 @@ Geometry geometry_k4_conv(const Args& a)
 Geometry geometry_k4(int path, const Args& a)
 {
     const int kind = path & 0xFF;
-    const int es = elem_bytes(a.in_dtype);
+    const int es = elem_size(a.in_dtype);
     if (kind == MFMA_SKINNY) {
         using C = StreamK4<BF16>;
         using D = StreamK4Deep<BF16>;
