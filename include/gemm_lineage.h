@@ -97,7 +97,14 @@ enum {
      * needs both).  Default: 256 x 256 tiles, 128 x 128 when 256-tiles would not fill the CUs once.
      * At most one of the two; refused with GEMM_ERR_BAD_ARG on other variants or paths. */
     GEMM_FLAG_TILE_256 = 1u << 3,
-    GEMM_FLAG_TILE_128 = 1u << 4
+    GEMM_FLAG_TILE_128 = 1u << 4,
+    /* Two more validated simplifications, so that the backward walk from the expert state (Sec. 3.2;
+     * the paper's deoptimisation traces remove "L2 raster", "swizzle", "vec. load" one at a time) has an
+     * edge for each of them. */
+    GEMM_FLAG_DEOPT_NO_RASTER = 1u << 5, /* K4's fast kernel only: workgroup i takes tile i in row-major order
+                                            instead of the XCD-aware banded walk */
+    GEMM_FLAG_DEOPT_NO_VECTOR = 1u << 6  /* K2 and K3 only: slabs fetched element by element (K3 with it is
+                                            "pipeline without vectorised loads", an order the lineage skips) */
 };
 
 typedef struct {

@@ -43,8 +43,9 @@ int validate(int variant, const gemm_desc_t* d, const void* A, const void* B, co
     if ((d->layout_a != GEMM_ROW_MAJOR && d->layout_a != GEMM_COL_MAJOR) ||
         (d->layout_b != GEMM_ROW_MAJOR && d->layout_b != GEMM_COL_MAJOR))
         return GEMM_ERR_BAD_ARG;
-    constexpr uint32_t K4_FLAGS = GEMM_FLAG_DEOPT_NO_SWIZZLE | GEMM_FLAG_DEOPT_NO_OVERLAP | GEMM_FLAG_TILE_256 | GEMM_FLAG_TILE_128;
-    if (d->flags & ~(uint32_t)(GEMM_FLAG_STRICT | K4_FLAGS)) return GEMM_ERR_BAD_ARG;
+    constexpr uint32_t K4_FLAGS = GEMM_FLAG_DEOPT_NO_SWIZZLE | GEMM_FLAG_DEOPT_NO_OVERLAP | GEMM_FLAG_TILE_256 | GEMM_FLAG_TILE_128 |
+                                  GEMM_FLAG_DEOPT_NO_RASTER;
+    if (d->flags & ~(uint32_t)(GEMM_FLAG_STRICT | K4_FLAGS | GEMM_FLAG_DEOPT_NO_VECTOR)) return GEMM_ERR_BAD_ARG;
     if ((d->flags & GEMM_FLAG_TILE_256) && (d->flags & GEMM_FLAG_TILE_128)) return GEMM_ERR_BAD_ARG;
     const int64_t min_lda = d->layout_a == GEMM_ROW_MAJOR ? d->K : d->M;
     const int64_t min_ldb = d->layout_b == GEMM_ROW_MAJOR ? d->N : d->K;
@@ -89,7 +90,7 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
     a.ldc = d->ldc;
     a.stride_a = d->stride_a; a.stride_b = d->stride_b; a.stride_c = d->stride_c;
     a.in_dtype = d->in_dtype; a.out_dtype = d->out_dtype;
-    a.flags = d->flags & (GEMM_FLAG_DEOPT_NO_SWIZZLE | GEMM_FLAG_DEOPT_NO_OVERLAP | GEMM_FLAG_TILE_256 | GEMM_FLAG_TILE_128);
+    a.flags = d->flags & ~(uint32_t)GEMM_FLAG_STRICT;
     a.stream = (hipStream_t)d->stream;
     p.empty = d->M == 0 || d->N == 0;
 
@@ -186,12 +187,19 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
     q.workspace_bytes = pack_bytes;
     strncpy(q.path, path, sizeof(q.path) - 1);
 
-    if (a.flags) {   // simplifications and tile overrides exist for K4's fast kernel only (also on packed operands)
+    if (a.flags & GEMM_FLAG_DEOPT_NO_VECTOR) {   // the vector-load simplification belongs to K2 and K3
+        if ((variant != GEMM_K2_VECTORIZED && variant != GEMM_K3_PIPELINED) || (a.flags & ~(uint32_t)GEMM_FLAG_DEOPT_NO_VECTOR)) {
+            p.status = GEMM_ERR_BAD_ARG;
+            return p;
+        }
+        p.path = 0;
+        strncpy(q.path, "elementwise-masked(-novec)", sizeof(q.path) - 1);
+    } else if (a.flags) {   // the other simplifications and the tile overrides exist for K4's fast kernel only (also on packed operands)
         const int kind = p.path & 0xFF;
         if (variant != GEMM_K4_MFMA || (kind != MFMA_VEC16 && kind != MFMA_PACKED)) { p.status = GEMM_ERR_BAD_ARG; return p; }
         const size_t n = strlen(q.path);
-        snprintf(q.path + n, sizeof(q.path) - n, "%s%s", (a.flags & GEMM_FLAG_DEOPT_NO_SWIZZLE) ? "-noswz" : "",
-                 (a.flags & GEMM_FLAG_DEOPT_NO_OVERLAP) ? "-noovl" : "");
+        snprintf(q.path + n, sizeof(q.path) - n, "%s%s%s", (a.flags & GEMM_FLAG_DEOPT_NO_SWIZZLE) ? "-noswz" : "",
+                 (a.flags & GEMM_FLAG_DEOPT_NO_OVERLAP) ? "-noovl" : "", (a.flags & GEMM_FLAG_DEOPT_NO_RASTER) ? "-noraster" : "");
     }
     const bool hard = (q.violated & GEMM_COND_DTYPE_HAS_MFMA) != 0;   // no slow path exists for this one
     if (hard || (q.violated && (d->flags & GEMM_FLAG_STRICT))) p.status = GEMM_ERR_PRECONDITION;

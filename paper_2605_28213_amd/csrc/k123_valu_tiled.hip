@@ -34,6 +34,12 @@ using CfgK3 = ValuCfg<128, 128, 16, 8, 8, true, true>;
 using CfgK2Small = ValuCfg<64, 64, 16, 4, 4, true, false>;
 using CfgK3Small = ValuCfg<64, 64, 16, 4, 4, true, true>;
 
+// K2 / K3 with the vectorised loads taken out again (a validated simplification: GEMM_FLAG_DEOPT_NO_VECTOR)
+using CfgK2NoVec = ValuCfg<128, 128, 16, 8, 8, false, false>;
+using CfgK3NoVec = ValuCfg<128, 128, 16, 8, 8, false, true>;
+using CfgK2SmallNoVec = ValuCfg<64, 64, 16, 4, 4, false, false>;
+using CfgK3SmallNoVec = ValuCfg<64, 64, 16, 4, 4, false, true>;
+
 static bool valu_small_tiles(const Args& a)
 {
     return ((a.M + CfgK2::BM - 1) / CfgK2::BM) * ((a.N + CfgK2::BN - 1) / CfgK2::BN) * a.batch < 256;
@@ -267,8 +273,12 @@ hipError_t launch_valu_tiled(int variant, int path, const Args& a)
 {
     switch (variant) {
     case GEMM_K1_LDS_TILED: return launch_cfg<CfgK1>(a, 0);
-    case GEMM_K2_VECTORIZED: return valu_small_tiles(a) ? launch_cfg<CfgK2Small>(a, path) : launch_cfg<CfgK2>(a, path);
-    case GEMM_K3_PIPELINED: return valu_small_tiles(a) ? launch_cfg<CfgK3Small>(a, path) : launch_cfg<CfgK3>(a, path);
+    case GEMM_K2_VECTORIZED:
+        if (a.flags & GEMM_FLAG_DEOPT_NO_VECTOR) return valu_small_tiles(a) ? launch_cfg<CfgK2SmallNoVec>(a, 0) : launch_cfg<CfgK2NoVec>(a, 0);
+        return valu_small_tiles(a) ? launch_cfg<CfgK2Small>(a, path) : launch_cfg<CfgK2>(a, path);
+    case GEMM_K3_PIPELINED:
+        if (a.flags & GEMM_FLAG_DEOPT_NO_VECTOR) return valu_small_tiles(a) ? launch_cfg<CfgK3SmallNoVec>(a, 0) : launch_cfg<CfgK3NoVec>(a, 0);
+        return valu_small_tiles(a) ? launch_cfg<CfgK3Small>(a, path) : launch_cfg<CfgK3>(a, path);
     default: return hipErrorInvalidValue;
     }
 }

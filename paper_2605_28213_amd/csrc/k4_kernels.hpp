@@ -260,7 +260,10 @@ __device__ __forceinline__ void store_tiles_staged(const Args& a, int64_t b, con
 // 64 bytes for e4m3 (two chunks per lane, v_mfma_scale 32x32x64 with unit scales: the form that runs
 // at twice the 16-bit rate on gfx950; the 32x32x16 fp8 form runs at the 16-bit rate).
 // ------------------------------------------------------------------------------------------------
-enum { FAST_VEC_C = 1 };   // kernel flag: 16-byte stores to C are legal (base and ldc 16-byte aligned)
+enum {
+    FAST_VEC_C = 1,          // kernel flag: 16-byte stores to C are legal (base and ldc 16-byte aligned)
+    FAST_PLAIN_RASTER = 2    // kernel flag: workgroup i takes tile i in row-major order (a validated simplification)
+};
 
 typedef __attribute__((ext_vector_type(8))) int i32x8_t;
 
@@ -363,7 +366,20 @@ void k4_mfma_fast(Args a, int tiles_m, int tiles_n, int flags)
     const int wm = wave / WN, wn = wave % WN;
     int64_t b;
     int tm, tn;
-    tile_of<CFG::GROUP_M>(blockIdx.x, (int)gridDim.x, tiles_m, tiles_n, b, tm, tn);
+    if (flags & FAST_PLAIN_RASTER) {
+        const int per = tiles_m * tiles_n, id = (int)blockIdx.x % per;
+        b = (int)blockIdx.x / per;
+        tm = id / tiles_n;
+        tn = id % tiles_n;
+    } else {
+        tile_of<CFG::GROUP_M>(blockIdx.x, (int)gridDim.x, tiles_m, tiles_n, b, tm, tn);
+    }
+    // Integer division runs on the vector unit and the two forms may be merged by a select: say once
+    // more, after the merge, that the coordinates are wave-uniform, or every buffer load below is
+    // wrapped in a loop over the lanes' "different" resources.
+    b = __builtin_amdgcn_readfirstlane((int)b);
+    tm = __builtin_amdgcn_readfirstlane(tm);
+    tn = __builtin_amdgcn_readfirstlane(tn);
     const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
 
     // ---- global -> LDS ---------------------------------------------------------------------------

@@ -19,7 +19,8 @@ static hipError_t launch_fast(const Args& a)
     dim3 grid((unsigned)((int64_t)tiles_m * tiles_n * a.batch), 1, 1), block(CFG::T, 1, 1);
     const int eo = a.out_dtype == GEMM_F32 ? 4 : 2;
     const bool vec_c = ((uintptr_t)a.C % 16 == 0) && (a.ldc * eo) % 16 == 0 && (a.batch <= 1 || (a.stride_c * eo) % 16 == 0);
-    hipLaunchKernelGGL(kern, grid, block, 0, a.stream, a, tiles_m, tiles_n, vec_c ? (int)FAST_VEC_C : 0);
+    const int kflags = (vec_c ? (int)FAST_VEC_C : 0) | ((a.flags & GEMM_FLAG_DEOPT_NO_RASTER) ? (int)FAST_PLAIN_RASTER : 0);
+    hipLaunchKernelGGL(kern, grid, block, 0, a.stream, a, tiles_m, tiles_n, kflags);
     return hipGetLastError();
 }
 
@@ -72,7 +73,7 @@ static hipError_t launch_stream(const Args& a)
 bool k4_small_tiles(const Args& a)
 {
     if (a.flags & GEMM_FLAG_TILE_128) return true;
-    if (a.flags & (GEMM_FLAG_TILE_256 | GEMM_FLAG_DEOPT_NO_SWIZZLE | GEMM_FLAG_DEOPT_NO_OVERLAP)) return false;   // the simplified states are 256-tile ones
+    if (a.flags & (GEMM_FLAG_TILE_256 | GEMM_FLAG_DEOPT_NO_SWIZZLE | GEMM_FLAG_DEOPT_NO_OVERLAP | GEMM_FLAG_DEOPT_NO_RASTER)) return false;   // the simplified states are 256-tile ones
     const int64_t t256 = ((a.M + 255) / 256) * ((a.N + 255) / 256) * a.batch;
     return t256 < 256;
 }

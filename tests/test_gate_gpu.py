@@ -137,6 +137,23 @@ def test_simplifications_of_the_expert_state_pass_and_cost_time():
     torch.cuda.empty_cache()
 
 
+def test_deoptimisation_trace_of_the_headline_workload():
+    """The backward walk from the expert state, one optimisation removed per edge, every state through
+    the gate (Sec. 3.2): all must pass, and the table is kept with the gate's output."""
+    from paper_2605_28213_amd import deopt
+    cfg = gen.CONFIGS["C2"]
+    entries = deopt.trace(cfg, OracleReference(cfg), seeds=(0,), ledger_path=LEDGER)
+    for e in entries:
+        e["variant_name"] = e["variant_name"] + " [" + e["deopt_label"] + "]"
+        _entries.append(e)
+        assert e["verdict"] == "passed", (e["deopt_label"], e["verdict"], e.get("correctness"))
+    with open(os.path.join(OUT_DIR, "deopt_trace.txt"), "w") as f:
+        f.write(deopt.format_trace(entries) + "\n")
+    med = {e["deopt_label"]: e["profile"]["median_us"] for e in entries}
+    assert med["- LDS staging (K0)"] > med["- MFMA (K3)"] > med["- load/MFMA overlap"] > med["expert (K4)"]
+    torch.cuda.empty_cache()
+
+
 def test_frozen_tile_rule_agrees_with_the_sweep():
     """The default tile choice of the fast kernel must be the faster of the two configurations (within
     noise) on the workloads where they differ most, and the sweep table is kept with the gate's output."""

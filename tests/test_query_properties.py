@@ -81,7 +81,8 @@ def test_expert_state_paths_and_scratch(p):
 
 @settings(max_examples=200, deadline=None)
 @given(descriptors(), st.integers(0, 4), st.sampled_from([gemm.GEMM_FLAG_TILE_128, gemm.GEMM_FLAG_TILE_256,
-                                                         gemm.GEMM_FLAG_DEOPT_NO_SWIZZLE, gemm.GEMM_FLAG_DEOPT_NO_OVERLAP]))
+                                                         gemm.GEMM_FLAG_DEOPT_NO_SWIZZLE, gemm.GEMM_FLAG_DEOPT_NO_OVERLAP,
+                                                         gemm.GEMM_FLAG_DEOPT_NO_RASTER]))
 def test_expert_only_switches_are_refused_elsewhere(p, variant, flag):
     plain = gemm.gemm_query(variant, make(p))
     q = gemm.gemm_query(variant, make(p, flags=flag))
@@ -90,7 +91,20 @@ def test_expert_only_switches_are_refused_elsewhere(p, variant, flag):
         assert q.status == gemm.GEMM_OK
         if flag == gemm.GEMM_FLAG_TILE_128:
             assert (q.bm, q.bn) == (128, 128)
-        if flag in (gemm.GEMM_FLAG_TILE_256, gemm.GEMM_FLAG_DEOPT_NO_SWIZZLE, gemm.GEMM_FLAG_DEOPT_NO_OVERLAP):
+        if flag in (gemm.GEMM_FLAG_TILE_256, gemm.GEMM_FLAG_DEOPT_NO_SWIZZLE, gemm.GEMM_FLAG_DEOPT_NO_OVERLAP,
+                    gemm.GEMM_FLAG_DEOPT_NO_RASTER):
             assert (q.bm, q.bn) == (256, 256)
     elif plain.status == gemm.GEMM_OK:
+        assert q.status == gemm.GEMM_ERR_BAD_ARG
+
+
+@settings(max_examples=150, deadline=None)
+@given(descriptors(), st.integers(0, 4))
+def test_vector_load_simplification_belongs_to_k2_and_k3(p, variant):
+    q = gemm.gemm_query(variant, make(p, flags=gemm.GEMM_FLAG_DEOPT_NO_VECTOR))
+    if variant in (gemm.GEMM_K2_VECTORIZED, gemm.GEMM_K3_PIPELINED):
+        assert q.status == gemm.GEMM_OK and q.path == "elementwise-masked(-novec)"
+        both = gemm.gemm_query(variant, make(p, flags=gemm.GEMM_FLAG_DEOPT_NO_VECTOR | gemm.GEMM_FLAG_DEOPT_NO_RASTER))
+        assert both.status == gemm.GEMM_ERR_BAD_ARG
+    else:
         assert q.status == gemm.GEMM_ERR_BAD_ARG
