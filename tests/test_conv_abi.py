@@ -117,3 +117,43 @@ def test_argument_validation():
     assert conv.conv2d_run(0, d, None, 256, 256) == gemm.GEMM_ERR_BAD_ARG
     dd = conv.conv2d_default_desc(8, 56, 56, 64, 128, 3, 3, gen.F16)
     assert (dd.pad_h, dd.pad_w, dd.stride_h, dd.stride_w, dd.out_dtype) == (1, 1, 1, 1, gen.F16)
+
+
+def test_planner_properties_over_random_layers():
+    """Seeded random geometries: output sizes agree with the oracle's definition, the lowered product's
+    sizes are N*P*Q x F x R*S*C, the implicit state's conditions are exactly the documented ones, and
+    im2col's scratch is the patch matrix (plus a padded copy of the filters when K is not whole slabs)."""
+    import numpy as np
+    import oracle
+    rng = np.random.default_rng(0)
+    es_of = {gen.F32: 4, gen.BF16: 2, gen.F16: 2, gen.E4M3: 1}
+    for _ in range(300):
+        dt = int(rng.choice([gen.F32, gen.BF16, gen.F16, gen.E4M3]))
+        out = gen.BF16 if dt == gen.E4M3 else dt
+        N, H, W = int(rng.integers(0, 5)), int(rng.integers(1, 40)), int(rng.integers(1, 40))
+        C, F = int(rng.choice([3, 24, 64, 96, 128, 192])), int(rng.integers(0, 300))
+        R, S = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+        st, pd = (int(rng.integers(1, 4)), int(rng.integers(1, 4))), (int(rng.integers(0, 3)), int(rng.integers(0, 3)))
+        d = conv.make_desc(N, H, W, C, F, R, S, dt, out, stride=st, pad=pd)
+        q = [conv.conv2d_query(v, d) for v in range(3)]
+        if H + 2 * pd[0] < R or W + 2 * pd[1] < S:
+            assert all(x.status == gemm.GEMM_ERR_BAD_ARG for x in q)
+            continue
+        P, Q = oracle.conv2d_output_size(H, W, R, S, st, pd)
+        es, K = es_of[dt], R * S * C
+        for x in q:
+            assert (x.P, x.Q, x.gemm_m, x.gemm_n, x.gemm_k) == (P, Q, N * P * Q, F, K)
+        assert q[0].status == gemm.GEMM_OK and q[0].workspace_bytes == 0
+        if dt == gen.F32:
+            assert q[1].status == q[2].status == gemm.GEMM_ERR_PRECONDITION
+            continue
+        kp = -(-K * es // 128) * 128 // es
+        want_ws = N * P * Q * kp * es + (F * kp * es if kp != K else 0)
+        assert q[1].workspace_bytes == want_ws and q[1].status == gemm.GEMM_ERR_WORKSPACE
+        ok2 = (C * es) % 128 == 0
+        assert (q[2].status == gemm.GEMM_OK) == ok2
+        if not ok2:
+            assert conv.Query.names(q[2].violated) == ["C_WHOLE_SLABS"]
+        else:
+            assert q[2].workspace_bytes == 0 and (q[2].bm, q[2].bn) == (128, 128)
+            assert q[2].grid == (0 if N * P * Q == 0 or F == 0 else -(-N * P * Q // 128) * -(-F // 128))

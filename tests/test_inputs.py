@@ -69,3 +69,28 @@ def test_make_inputs_shapes_and_scales():
     assert inp3.lda == 259 and inp3.ldb == 301 and inp3.ldc == 301 and inp3.scale_a is None
     again = gen.make_inputs(gen.CONFIGS["C3_small"], 2)
     np.testing.assert_array_equal(inp3.A, again.A)
+
+
+def test_conv_and_topk_workload_tables_and_generators():
+    c = gen.CONV_CONFIGS["CONV"]
+    assert (c.N, c.H, c.W, c.C, c.F, c.R, c.S, c.stride, c.pad, c.in_dtype) == (8, 56, 56, 64, 128, 3, 3, (1, 1), (1, 1), gen.F16)
+    assert (c.P, c.Q) == (56, 56) and c.flops == 2 * 8 * 56 * 56 * 128 * 576
+    assert c.algorithmic_bytes == (8 * 56 * 56 * 64 + 128 * 576 + 8 * 56 * 56 * 128) * 2
+    s2 = gen.CONV_CONFIGS["CONV_stride2"]
+    assert (s2.P, s2.Q) == (9, 8) and s2.biased
+    ci = gen.make_conv_inputs(gen.CONV_CONFIGS["CONV_small"], 3)
+    assert ci.x.shape == (2, 13, 11, 64) and ci.w.shape == (40, 3, 3, 64) and ci.x.dtype == np.uint16 and ci.bias is None
+    np.testing.assert_array_equal(ci.x, gen.make_conv_inputs(gen.CONV_CONFIGS["CONV_small"], 3).x)
+    assert not np.array_equal(ci.x, gen.make_conv_inputs(gen.CONV_CONFIGS["CONV_small"], 4).x)
+    f8 = gen.make_conv_inputs(gen.CONV_CONFIGS["CONV_fp8"], 0)
+    assert f8.x.dtype == np.uint8 and np.all((f8.w & 0x7F) != 0x7F)
+
+    t = gen.TOPK_CONFIGS["TOPK"]
+    assert (t.batch, t.n, t.k) == (64, 4096, 512) and t.algorithmic_bytes == 64 * (4096 * 4 + 512 * 8)
+    r = gen.TOPK_CONFIGS["TOPK_ragged"]
+    x = gen.make_topk_inputs(r, 1)
+    assert x.shape == (3, 4100) and x.dtype == np.float32 and np.all(x[:, r.n:] == np.float32(1e30))
+    assert np.all(x[:, : r.n] * 4 == np.round(x[:, : r.n] * 4))        # the tie-heavy variant: multiples of 1/4
+    counts = np.unique(x[0, : r.n], return_counts=True)[1]
+    assert counts.max() > 100                                           # many equal values
+    np.testing.assert_array_equal(x, gen.make_topk_inputs(r, 1))
