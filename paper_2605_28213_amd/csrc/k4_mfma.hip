@@ -73,7 +73,7 @@ static hipError_t launch_stream(const Args& a)
 bool k4_small_tiles(const Args& a)
 {
     if (a.flags & GEMM_FLAG_TILE_128) return true;
-    if (a.flags & (GEMM_FLAG_TILE_256 | GEMM_FLAG_DEOPT_NO_SWIZZLE | GEMM_FLAG_DEOPT_NO_OVERLAP | GEMM_FLAG_DEOPT_NO_RASTER)) return false;   // the simplified states are 256-tile ones
+    if (a.flags & (GEMM_FLAG_TILE_256 | GEMM_FLAG_DEOPT_NO_SWIZZLE | GEMM_FLAG_DEOPT_NO_OVERLAP)) return false;   // the instantiations without swizzle / overlap are 256-tile ones
     const int64_t t256 = ((a.M + 255) / 256) * ((a.N + 255) / 256) * a.batch;
     return t256 < 256;
 }

@@ -3,9 +3,10 @@ needs a templatized kernel; App. D notes that the tile configuration is what a h
 contributes beyond the idiom).
 
 The fast kernel of K4 exists in two tile configurations, 256 x 256 (one workgroup per CU) and
-128 x 128 (two per CU).  The library's default choice is a frozen rule (128-tiles when 256-tiles would
-not fill the CUs once); this module measures both configurations on a workload so that the rule can be
-checked against the hardware, and prints the table.
+128 x 128 (two per CU), each with the XCD-aware tile walk or a plain row-major one: four points.  The
+library's default choice is a frozen rule (128-tiles when 256-tiles would not fill the CUs once, always
+the XCD-aware walk); this module measures all points on a workload so that the rule can be checked
+against the hardware, and prints the table.
 
     python -m paper_2605_28213_amd.tune C2 C5 P2048
 """
@@ -20,7 +21,9 @@ import numpy as np
 from . import gemm
 from . import inputs as gen
 
-CHOICES = {"default": 0, "tile256": gemm.GEMM_FLAG_TILE_256, "tile128": gemm.GEMM_FLAG_TILE_128}
+CHOICES = {"default": 0, "tile256": gemm.GEMM_FLAG_TILE_256, "tile128": gemm.GEMM_FLAG_TILE_128,
+           "tile256-rowmajor": gemm.GEMM_FLAG_TILE_256 | gemm.GEMM_FLAG_DEOPT_NO_RASTER,
+           "tile128-rowmajor": gemm.GEMM_FLAG_TILE_128 | gemm.GEMM_FLAG_DEOPT_NO_RASTER}
 
 
 def sweep(cfg: gen.Config, *, seed: int = 0, warmup: int = 10, reps: int = 50) -> Dict[str, dict]:
@@ -61,14 +64,15 @@ def sweep(cfg: gen.Config, *, seed: int = 0, warmup: int = 10, reps: int = 50) -
 
 
 def report(names: Iterable[str]) -> str:
-    rows = ["workload   default tile  default us   tile256 us   tile128 us   best"]
+    points = [k for k in CHOICES if k != "default"]
+    rows = ["workload   default tile  default us   " + "   ".join("%-16s" % (p + " us") for p in points) + "   best"]
     for n in names:
         r = sweep(gen.CONFIGS[n])
         t = {k: v.get("median_us") for k, v in r.items()}
-        best = min((k for k in ("tile256", "tile128") if t.get(k)), key=lambda k: t[k], default="-")
+        best = min((k for k in points if t.get(k)), key=lambda k: t[k], default="-")
         fmt = lambda x: ("%.1f" % x) if x else "-"
-        rows.append("%-10s %-13s %-12s %-12s %-12s %s" % (n, "x".join(map(str, r["default"].get("tile", []))) or "-",
-                                                          fmt(t.get("default")), fmt(t.get("tile256")), fmt(t.get("tile128")), best))
+        rows.append("%-10s %-13s %-12s " % (n, "x".join(map(str, r["default"].get("tile", []))) or "-", fmt(t.get("default")))
+                    + "   ".join("%-16s" % fmt(t.get(p)) for p in points) + "   " + best)
     return "\n".join(rows)
 
 

@@ -282,6 +282,41 @@ def test_both_tile_configurations_on_ragged_shapes(tile_flag, dtype):
     assert gemm.gemm_query(4, d).bm == (256 if tile_flag == gemm.GEMM_FLAG_TILE_256 else 128)
 
 
+@pytest.mark.parametrize("tile_flag", [0, gemm.GEMM_FLAG_TILE_256, gemm.GEMM_FLAG_TILE_128])
+def test_row_major_tile_walk_computes_the_same_product(tile_flag):
+    """GEMM_FLAG_DEOPT_NO_RASTER: a different order of the same tiles, with either tile size, batched and ragged."""
+    for dtype, (M, N, K, nb) in ((gen.BF16, (700, 520, 512, 3)), (gen.E4M3, (257, 1100, 256, 2)), (gen.F16, (1024, 768, 128, 1))):
+        out = gen.BF16 if dtype == gen.E4M3 else dtype
+        cfg = gen.Config("walk", M, N, K, dtype, out, ROW, COL, "normal", rsqrt_k=True, batch=nb)
+        inp = gen.make_inputs(cfg, 17)
+        C_ref, D = oracle_for(inp)
+        flags = tile_flag | gemm.GEMM_FLAG_DEOPT_NO_RASTER
+        rc, C, _ = util.run_config(4, inp, flags=flags)
+        assert rc == gemm.GEMM_OK
+        assert util.norm_err(C[:, :, :N], C_ref, D) <= util.TOL[dtype], (dtype, M, N, K, nb)
+        q = gemm.gemm_query(4, gemm.make_desc(M, N, K, dtype, out, ROW, COL, batch=nb, flags=flags))
+        assert q.path.endswith("-noraster")
+
+
+@pytest.mark.parametrize("dtype", [gen.F32, gen.BF16, gen.F16, gen.E4M3])
+@pytest.mark.parametrize("la,lb", [(ROW, ROW), (ROW, COL), (COL, COL)])
+def test_vector_loads_removed_from_k2_and_k3(dtype, la, lb):
+    """GEMM_FLAG_DEOPT_NO_VECTOR: both states fetch element by element and still compute the product, on
+    aligned operands (where they would otherwise use 16-byte loads), large and small tile forms."""
+    out = gen.BF16 if dtype == gen.E4M3 else dtype
+    for (M, N, K) in ((300, 272, 208), (2100, 2064, 64)):
+        cfg = gen.Config("novec", M, N, K, dtype, out, la, lb, "uniform", lda=(K if la == ROW else M) + 16 - (K if la == ROW else M) % 16,
+                         ldb=(N if lb == ROW else K) + 16 - (N if lb == ROW else K) % 16)
+        inp = gen.make_inputs(cfg, 19)
+        C_ref, D = oracle_for(inp)
+        for v in (gemm.GEMM_K2_VECTORIZED, gemm.GEMM_K3_PIPELINED):
+            rc, C, _ = util.run_config(v, inp, flags=gemm.GEMM_FLAG_DEOPT_NO_VECTOR)
+            assert rc == gemm.GEMM_OK
+            assert util.norm_err(C[:, :, :N], C_ref, D) <= util.TOL[dtype], (v, dtype, M, N, K)
+    rc, _, raw = util.run_config(gemm.GEMM_K1_LDS_TILED, inp, flags=gemm.GEMM_FLAG_DEOPT_NO_VECTOR)
+    assert rc == gemm.GEMM_ERR_BAD_ARG and torch.all(raw == util.POISON)
+
+
 def test_launches_are_capturable_and_replayable_in_a_hip_graph():
     """The library allocates nothing and only launches kernels on the given stream, so a sequence of
     calls can be captured into a HIP graph.  Three different states and shapes are captured once and

@@ -91,9 +91,10 @@ def test_expert_only_switches_are_refused_elsewhere(p, variant, flag):
         assert q.status == gemm.GEMM_OK
         if flag == gemm.GEMM_FLAG_TILE_128:
             assert (q.bm, q.bn) == (128, 128)
-        if flag in (gemm.GEMM_FLAG_TILE_256, gemm.GEMM_FLAG_DEOPT_NO_SWIZZLE, gemm.GEMM_FLAG_DEOPT_NO_OVERLAP,
-                    gemm.GEMM_FLAG_DEOPT_NO_RASTER):
+        if flag in (gemm.GEMM_FLAG_TILE_256, gemm.GEMM_FLAG_DEOPT_NO_SWIZZLE, gemm.GEMM_FLAG_DEOPT_NO_OVERLAP):
             assert (q.bm, q.bn) == (256, 256)
+        if flag == gemm.GEMM_FLAG_DEOPT_NO_RASTER:
+            assert (q.bm, q.bn) == (plain.bm, plain.bn) and q.path.endswith("-noraster")     # the tile walk is independent of the tile
     elif plain.status == gemm.GEMM_OK:
         assert q.status == gemm.GEMM_ERR_BAD_ARG
 
