@@ -121,12 +121,16 @@ typedef struct {
                                         the "AddMM" shape of the paper's held-out GEMM family (App. D),
                                         fused into every state's epilogue; shared by all batch items. */
     void *workspace;                 /* optional device scratch lent by the caller (16-byte aligned), or NULL.
-                                        Only K4 uses it: when its fast path's conditions fail and scratch of at
-                                        least gemm_query's workspace_bytes is lent, it packs both operands
-                                        (K contiguous, aligned, zero-padded K) and runs the fast kernel on the
-                                        copies; without scratch its masked kernel runs.  Scratch that is lent
-                                        but too small or misaligned is an error (GEMM_ERR_WORKSPACE), never a
-                                        silent slow path.  Contents after the call are unspecified. */
+                                        Only K4 uses it, in two cases.  (1) Its fast path's conditions fail:
+                                        with scratch of at least gemm_query's workspace_bytes it packs both
+                                        operands (K contiguous, aligned, zero-padded K) and runs the fast
+                                        kernel on the copies; without scratch its masked kernel runs.  (2) The
+                                        fast path applies but the product has too few tiles to fill the chip
+                                        and a long K (batch 1, 17 or more rows): with scratch it splits K into
+                                        ranges that run side by side and adds their fp32 partial products in a
+                                        second pass; without scratch the unsplit kernel runs.  Scratch that is
+                                        lent but too small or misaligned is an error (GEMM_ERR_WORKSPACE), never
+                                        a silent slow path.  Contents after the call are unspecified. */
     size_t workspace_bytes;
     void *stream;                    /* hipStream_t; NULL = the default stream */
     uint32_t flags;                  /* GEMM_FLAG_* */
@@ -142,7 +146,7 @@ typedef struct {
     int32_t  stages;          /* LDS buffers in flight */
     int32_t  lds_bytes;       /* static + dynamic LDS per workgroup */
     int64_t  grid;            /* workgroups launched */
-    size_t   workspace_bytes; /* scratch the packed path of K4 uses for this call (0: no path would use any) */
+    size_t   workspace_bytes; /* scratch the packed or split-K path of K4 uses for this call (0: no path would use any) */
     char     path[64];        /* name of the code path gemm_run_ex would take */
 } gemm_query_t;
 

@@ -109,11 +109,15 @@ inline bool dtype_pair_supported(int in, int out)
 // Each returns hipSuccess or the launch error.  `path` selects a code path that the caller
 // (gemm_api.hip) has already proven legal for these arguments.
 enum ValuPath { VALU_SCALAR = 0, VALU_VEC16 = 1 };
-enum MfmaPath { MFMA_ELEMENTWISE = 0, MFMA_VEC16 = 1, MFMA_SKINNY = 2, MFMA_PACKED = 3 };
+enum MfmaPath { MFMA_ELEMENTWISE = 0, MFMA_VEC16 = 1, MFMA_SKINNY = 2, MFMA_PACKED = 3, MFMA_SPLITK = 4 };
 
 // Workspace of the packed K4 path: both operands rewritten as [rows][Kp], Kp = K rounded up to a slab.
 int64_t k4_packed_k(const Args& a);
 size_t k4_packed_workspace_bytes(const Args& a);
+// Split-K form of the fast kernel: how many K ranges a product with too few tiles to fill the chip
+// is cut into (1: not applicable), and the fp32 scratch the partial products need.
+int k4_splitk_factor(const Args& a);
+size_t k4_splitk_workspace_bytes(const Args& a, int splits);
 // True when the fast kernel's launcher hands a thin remainder of rows (M % 256 in 1..16) to the streaming kernel.
 bool k4_splits_m_tail(const Args& a);
 // True when the fast kernel runs with 128 x 128 workgroup tiles instead of 256 x 256.

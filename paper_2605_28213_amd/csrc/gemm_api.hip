@@ -110,7 +110,8 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
 
     const uint32_t vecA = GEMM_COND_ALIGN16_A | GEMM_COND_LD16_A, vecB = GEMM_COND_ALIGN16_B | GEMM_COND_LD16_B;
     uint32_t required = 0;
-    size_t pack_bytes = 0;     // K4 only: scratch of the packed path (used when lent, advertised otherwise)
+    size_t pack_bytes = 0;     // K4 only: scratch of the packed or split-K path (used when lent, advertised otherwise)
+    char splitk_path[64];
     Geometry g{};
     const char* path = "";
     switch (variant) {
@@ -158,6 +159,16 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
         } else if (!f32 && va && vb && kdiv && rows_fit) {
             p.path = MFMA_VEC16 | (3 << 8);
             path = k4_splits_m_tail(a) ? "mfma32-direct-to-lds+stream(M-tail)" : "mfma32-direct-to-lds";
+            // too few tiles for the chip and a long K: with scratch for the partial products, K is split
+            const int splits = k4_splitk_factor(a);
+            if (splits > 1) {
+                pack_bytes = k4_splitk_workspace_bytes(a, splits);
+                if (d->workspace != nullptr) {
+                    p.path = MFMA_SPLITK;
+                    snprintf(splitk_path, sizeof(splitk_path), "mfma32-direct-to-lds+splitK(%d)", splits);
+                    path = splitk_path;
+                }
+            }
         } else if (can_pack && d->workspace != nullptr) {
             // the caller lent scratch: repair the violated conditions by packing, then run the fast kernel
             p.path = MFMA_PACKED;
@@ -203,7 +214,7 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
     }
     const bool hard = (q.violated & GEMM_COND_DTYPE_HAS_MFMA) != 0;   // no slow path exists for this one
     if (hard || (q.violated && (d->flags & GEMM_FLAG_STRICT))) p.status = GEMM_ERR_PRECONDITION;
-    else if ((p.path & 0xFF) == MFMA_PACKED && variant == GEMM_K4_MFMA &&
+    else if (((p.path & 0xFF) == MFMA_PACKED || (p.path & 0xFF) == MFMA_SPLITK) && variant == GEMM_K4_MFMA &&
              (d->workspace_bytes < q.workspace_bytes || ((uintptr_t)d->workspace & 15u)))
         p.status = GEMM_ERR_WORKSPACE;   // scratch was lent but is too small or misaligned: say so rather than run slow
     return p;

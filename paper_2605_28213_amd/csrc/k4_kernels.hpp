@@ -840,6 +840,36 @@ __global__ __launch_bounds__(256) void k4_pack_transpose(const char* __restrict_
 }
 
 // ------------------------------------------------------------------------------------------------
+// Second pass of the split-K form: C = round(s * sum over the K ranges of the fp32 partial products
+// + bias).  Partials are [splits][M][N] dense; one thread per four consecutive columns.
+// ------------------------------------------------------------------------------------------------
+template <typename IN>   // (a template only so that the header can be included by several translation units)
+__global__ __launch_bounds__(256) void k4_splitk_reduce(Args a, const float* __restrict__ part, int splits)
+{
+    const int64_t quads = (a.N + 3) / 4;
+    const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (id >= a.M * quads) return;
+    const int64_t i = id / quads, j0 = (id % quads) * 4;
+    const float sc = batch_scale(a, 0);
+    const bool whole = j0 + 3 < a.N && (a.N % 4) == 0;         // the row's partials are 16-byte aligned
+    float v[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int s = 0; s < splits; ++s) {
+        const float* p = part + ((int64_t)s * a.M + i) * a.N + j0;
+        if (whole) {
+            const float4 w = *(const float4*)p;
+            v[0] += w.x; v[1] += w.y; v[2] += w.z; v[3] += w.w;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (j0 + e < a.N) v[e] += p[e];
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        if (j0 + e < a.N) store_out(a.C, i * a.ldc + j0 + e, v[e] * sc + (a.bias ? a.bias[j0 + e] : 0.0f), a.out_dtype);
+}
+
+// ------------------------------------------------------------------------------------------------
 // Streaming kernel for M <= 16 (decode-like shapes): the product is bound by reading B once from
 // HBM.  A workgroup owns a strip of 16*NB columns of C; its WAVES waves split K, partial sums meet
 // in LDS at the end.  Needs: A row-major, B column-major, 16-byte aligned, K a multiple of 8.

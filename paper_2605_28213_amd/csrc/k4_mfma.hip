@@ -121,6 +121,47 @@ static hipError_t launch_fast_split(const Args& a)
     return launch_fast_any<IN>(a);
 }
 
+// Split-K ("split-K / stream-K for small M" among Table 1's expression-level intents).  A product whose
+// tiles do not fill the 256 CUs once and whose K is long (decode-like shapes with 17..128 rows: bf16
+// 32 x 16384 x 16384 took 206 us on 128 workgroups) is cut along K into `splits` equal ranges that run
+// as the batch items of one launch of the fast kernel (batch strides = the K range), each writing fp32
+// partial products to caller-lent scratch; a second small kernel adds them, scales, adds the bias and
+// rounds once.  The factor: the largest divisor of the slab count that keeps at least 16 slabs per
+// range and at most about 512 workgroups, at most 8.
+int k4_splitk_factor(const Args& a)
+{
+    if (a.batch != 1 || a.flags != 0 || a.M <= 16 || k4_splits_m_tail(a)) return 1;
+    const int64_t ke = ROW_BYTES / elem_size(a.in_dtype);
+    if (a.K <= 0 || a.K % ke != 0) return 1;
+    const int64_t nslab = a.K / ke, tiles = ((a.M + 127) / 128) * ((a.N + 127) / 128);
+    if (tiles >= 256) return 1;
+    int best = 1;
+    for (int s = 2; s <= 8; ++s)
+        if (nslab % s == 0 && nslab / s >= 16 && tiles * s <= 640) best = s;
+    return best;
+}
+
+size_t k4_splitk_workspace_bytes(const Args& a, int splits) { return (size_t)splits * (size_t)(a.M * a.N) * 4; }
+
+template <typename IN>
+static hipError_t launch_splitk(const Args& a)
+{
+    const int splits = k4_splitk_factor(a);
+    Args p = a;
+    p.batch = splits;
+    p.K = a.K / splits;
+    p.stride_a = p.K;                       // K is contiguous in both operands: the next range starts K/splits elements on
+    p.stride_b = p.K;
+    p.C = a.workspace; p.ldc = a.N; p.stride_c = a.M * a.N;
+    p.out_dtype = GEMM_F32;
+    p.scale_a = p.scale_b = nullptr; p.bias = nullptr;
+    p.flags = k4_small_tiles(a) ? GEMM_FLAG_TILE_128 : GEMM_FLAG_TILE_256;   // the tile the product itself would get
+    hipError_t e = launch_fast_any<IN>(p);
+    if (e != hipSuccess) return e;
+    const int64_t threads = a.M * ((a.N + 3) / 4);
+    hipLaunchKernelGGL(k4_splitk_reduce<IN>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, a.stream, a, (const float*)a.workspace, splits);
+    return hipGetLastError();
+}
 
 int64_t k4_packed_k(const Args& a)
 {
@@ -181,6 +222,14 @@ hipError_t launch_k4(int path, const Args& a)
         default: return hipErrorInvalidValue;
         }
     }
+    if (kind == MFMA_SPLITK) {
+        switch (a.in_dtype) {
+        case GEMM_BF16: return launch_splitk<BF16>(a);
+        case GEMM_F16: return launch_splitk<F16>(a);
+        case GEMM_FP8_E4M3: return launch_splitk<E4M3>(a);
+        default: return hipErrorInvalidValue;
+        }
+    }
     if (kind == MFMA_SKINNY) {
         if (a.in_dtype == GEMM_BF16) return launch_stream<BF16>(a);
         if (a.in_dtype == GEMM_F16) return launch_stream<F16>(a);
@@ -236,10 +285,10 @@ Geometry geometry_k4(int path, const Args& a)
         if (stream_deep(a)) return Geometry{16, D::COLS, D::TK, D::WAVES * 64, 2, D::LDS_BYTES, g};
         return Geometry{16, C::COLS, C::TK, C::WAVES * 64, 2, C::LDS_BYTES, g};
     }
-    if (kind == MFMA_VEC16 || kind == MFMA_PACKED) {
+    if (kind == MFMA_VEC16 || kind == MFMA_PACKED || kind == MFMA_SPLITK) {
         const bool small = k4_small_tiles(a);
         const int bt = small ? FastK4Small<BF16>::BM : FastK4<BF16>::BM;
-        const int64_t g = ((a.M + bt - 1) / bt) * ((a.N + bt - 1) / bt) * a.batch;
+        const int64_t g = ((a.M + bt - 1) / bt) * ((a.N + bt - 1) / bt) * a.batch * (kind == MFMA_SPLITK ? k4_splitk_factor(a) : 1);
         // stages: slabs in flight beyond the one in use
         return Geometry{bt, bt, ROW_BYTES / es, 256, 2, small ? FastK4Small<BF16>::LDS_BYTES : FastK4<BF16>::LDS_BYTES, g};
     }

@@ -115,6 +115,21 @@ def test_paper_shapes_pass_the_gate(name):
     torch.cuda.empty_cache()
 
 
+def test_split_k_on_a_decode_shape_passes_the_gate_and_is_faster():
+    """bf16 32 x 16384 x 16384 (more rows than the streaming kernel takes, 128 tiles): the expert state at
+    three seeds with the scratch its split-K form asks for, and once without; the split form must win."""
+    cfg = gen.CONFIGS["D32"]
+    reference, cache = OracleReference(cfg), {}
+    split = gate.run_gate(gemm.GEMM_K4_MFMA, cfg, reference, inputs_cache=cache, ledger_path=LEDGER, lend_workspace=True)
+    plain = gate.run_gate(gemm.GEMM_K4_MFMA, cfg, reference, seeds=(0,), inputs_cache=cache, ledger_path=LEDGER, lend_workspace=False)
+    split["variant_name"] += " [splitK]"
+    _entries.extend([split, plain])
+    assert split["verdict"] == plain["verdict"] == "passed", (split.get("correctness"), plain.get("correctness"))
+    assert "splitK(4)" in split["query"]["path"] and "splitK" not in plain["query"]["path"]
+    assert split["profile"]["median_us"] < 0.85 * plain["profile"]["median_us"], (split["profile"], plain["profile"])
+    torch.cuda.empty_cache()
+
+
 def test_simplifications_of_the_expert_state_pass_and_cost_time():
     """Guided deoptimisation on the expert kernel: with the LDS swizzle removed, or with loads no longer
     overlapping the MFMAs, the kernel still passes the gate on the headline workload and is slower;

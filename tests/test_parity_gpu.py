@@ -317,6 +317,33 @@ def test_vector_loads_removed_from_k2_and_k3(dtype, la, lb):
     assert rc == gemm.GEMM_ERR_BAD_ARG and torch.all(raw == util.POISON)
 
 
+@pytest.mark.parametrize("dtype", [gen.BF16, gen.F16, gen.E4M3])
+def test_split_k_with_lent_scratch(dtype):
+    """Few tiles and a long K: with scratch lent, K4 cuts K into ranges that run side by side and adds the
+    fp32 partial products in a second pass (scale, bias and the single rounding happen there)."""
+    out = gen.BF16 if dtype == gen.E4M3 else dtype
+    es = gen.ELEM_BYTES[dtype]
+    for (M, N, nslab, kw) in ((100, 300, 64, dict(biased=True)), (33, 130, 48, dict(scaled=True)), (200, 257, 32, {}), (64, 1024, 128, dict(ldc=1032))):
+        K = nslab * 128 // es
+        cfg = gen.Config("splitk", M, N, K, dtype, out, ROW, COL, "normal", rsqrt_k=True, **kw)
+        inp = gen.make_inputs(cfg, 23)
+        ref = oracle_for(inp)
+        d = gemm.make_desc(M, N, K, dtype, out, ROW, COL, ldc=inp.ldc)
+        q = gemm.gemm_query(4, d)
+        assert q.workspace_bytes > 0 and "splitK" not in q.path             # offered, not taken without scratch
+        check(4, inp, ref)                                                  # the unsplit kernel
+        d.workspace, d.workspace_bytes = 4096, q.workspace_bytes
+        assert "splitK" in gemm.gemm_query(4, d).path
+        check(4, inp, ref, lend_workspace=True)
+        check(4, inp, ref, out_dtype=gen.F32, lend_workspace=True)
+    # the scratch must be big enough
+    dA, dB = util.dev(inp.A), util.dev(inp.B)
+    dC = util.out_buffer(inp.stride_c, out)
+    ws = torch.empty(4096, dtype=torch.uint8, device="cuda")
+    d = gemm.make_desc(cfg.M, cfg.N, cfg.K, dtype, out, ROW, COL, ldc=inp.ldc, workspace=ws, workspace_bytes=4096)
+    assert gemm.gemm_run_ex(4, d, dA, dB, dC) == gemm.GEMM_ERR_WORKSPACE and torch.all(dC == util.POISON)
+
+
 def test_launches_are_capturable_and_replayable_in_a_hip_graph():
     """The library allocates nothing and only launches kernels on the given stream, so a sequence of
     calls can be captured into a HIP graph.  Three different states and shapes are captured once and

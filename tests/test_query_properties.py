@@ -66,7 +66,23 @@ def test_expert_state_paths_and_scratch(p):
     if fast_ok and p["M"] <= 16 and p["K"] % kvec == 0 and es == 2:
         assert q.path == "mfma16-stream(small-M)" and q.workspace_bytes == 0
     elif fast_ok and p["K"] % kslab == 0:
-        assert q.path.startswith("mfma32-direct-to-lds") and q.workspace_bytes == 0 and q.violated == 0
+        assert q.path.startswith("mfma32-direct-to-lds") and q.violated == 0
+        # split-K: offered (through workspace_bytes) when the product has few tiles and a long K, taken when scratch is lent
+        nslab, tiles = p["K"] // kslab, math.ceil(p["M"] / 128) * math.ceil(p["N"] / 128)
+        tail = es == 2 and p["M"] > 256 and 1 <= p["M"] % 256 <= 16
+        splits = 1
+        if p["batch"] == 1 and p["M"] > 16 and not tail and tiles < 256:
+            for s_ in range(2, 9):
+                if nslab % s_ == 0 and nslab // s_ >= 16 and tiles * s_ <= 640:
+                    splits = s_
+        assert q.workspace_bytes == (splits * p["M"] * p["N"] * 4 if splits > 1 else 0)
+        assert "splitK" not in q.path
+        if splits > 1:
+            lent = gemm.gemm_query(gemm.GEMM_K4_MFMA, make(p, workspace=4096, workspace_bytes=q.workspace_bytes))
+            assert lent.status == gemm.GEMM_OK and lent.path == "mfma32-direct-to-lds+splitK(%d)" % splits
+            assert lent.grid == q.grid * splits
+            small = gemm.gemm_query(gemm.GEMM_K4_MFMA, make(p, workspace=4096, workspace_bytes=q.workspace_bytes - 1))
+            assert small.status == gemm.GEMM_ERR_WORKSPACE
     else:
         kp = math.ceil(p["K"] / kslab) * kslab
         assert q.path.startswith("mfma32-") and "packed" not in q.path
