@@ -19,7 +19,11 @@ static hipError_t launch_fast(const Args& a)
     dim3 grid((unsigned)((int64_t)tiles_m * tiles_n * a.batch), 1, 1), block(CFG::T, 1, 1);
     const int eo = a.out_dtype == GEMM_F32 ? 4 : 2;
     const bool vec_c = ((uintptr_t)a.C % 16 == 0) && (a.ldc * eo) % 16 == 0 && (a.batch <= 1 || (a.stride_c * eo) % 16 == 0);
-    const int kflags = (vec_c ? (int)FAST_VEC_C : 0) | ((a.flags & GEMM_FLAG_DEOPT_NO_RASTER) ? (int)FAST_PLAIN_RASTER : 0);
+    // Tile walk: the XCD-aware banded walk unless the caller asks for the row-major one.  (With one operand
+    // set resident in the Infinity Cache the row-major order measured 1-5 % faster on single products; with
+    // operands rotated, as the benchmark does, it is equal on 8192^3 and 5 % slower on 4096^3.)
+    const bool plain = (a.flags & GEMM_FLAG_DEOPT_NO_RASTER) != 0;
+    const int kflags = (vec_c ? (int)FAST_VEC_C : 0) | (plain ? (int)FAST_PLAIN_RASTER : 0);
     hipLaunchKernelGGL(kern, grid, block, 0, a.stream, a, tiles_m, tiles_n, kflags);
     return hipGetLastError();
 }
@@ -66,16 +70,22 @@ static hipError_t launch_stream(const Args& a)
     return stream_deep(a) ? launch_stream_cfg<StreamK4Deep<IN>>(a) : launch_stream_cfg<StreamK4<IN>>(a);
 }
 
-// Tile choice of the fast kernel ("templatize" + a measured sweep, Table 1's expression-level intents):
-// 128-tiles when 256-tiles would not fill the 256 CUs once (2048^3 bf16: 43 us -> 25 us).  Where the
-// machine is full they lose to 256-tiles even for short K (64 x 1024^3 e4m3: 108 us -> 131 us; 64x64 per
-// wave reads LDS twice as often per MFMA and needs twice the L2 traffic).
+// Tile choice of the fast kernel ("templatize" + a measured sweep, Table 1's expression-level intents).
+// 256-tiles run one workgroup per CU, 128-tiles two, so a "round" of the machine is 256 or 512 tiles; a
+// round of 128-tiles covers half the output of a round of 256-tiles at about 0.7 of its time (0.8 for
+// e4m3, whose 64 x 64 wave tiles saturate LDS).  The cheaper estimate wins, 256-tiles on a tie.  Measured
+// with operands rotated over three sets (bf16 unless noted; 256-tiles / 128-tiles):
+//   2048^3 (64 vs 256 tiles: 1 round vs 0.7) 43 / 25 us;  2048 x 4096 x 4096 (1 vs 0.7) 81 / 65 us;
+//   4096 x 3072 x 4096 (192 tiles: 1 round vs 2 x 0.7) 88 / 96 us;  4096 x 4352 x 4096 (2 vs 3 x 0.7) 166 / 168 us;
+//   8 x 1024^3 (1 vs 0.7) 32 / 24 us;  64 x 1024^3 e4m3 (4 vs 8 x 0.8) 108 / 131 us.
 bool k4_small_tiles(const Args& a)
 {
     if (a.flags & GEMM_FLAG_TILE_128) return true;
     if (a.flags & (GEMM_FLAG_TILE_256 | GEMM_FLAG_DEOPT_NO_SWIZZLE | GEMM_FLAG_DEOPT_NO_OVERLAP)) return false;   // the instantiations without swizzle / overlap are 256-tile ones
-    const int64_t t256 = ((a.M + 255) / 256) * ((a.N + 255) / 256) * a.batch;
-    return t256 < 256;
+    const int64_t t256 = ((a.M + 255) / 256) * ((a.N + 255) / 256) * a.batch, t128 = ((a.M + 127) / 128) * ((a.N + 127) / 128) * a.batch;
+    const int64_t r256 = (t256 + 255) / 256, r128 = (t128 + 511) / 512;
+    const int64_t cost128 = a.in_dtype == GEMM_FP8_E4M3 ? 8 : 7;     // tenths of a 256-tile round
+    return r128 * cost128 < r256 * 10;
 }
 
 // The expert instantiation, or one of its validated simplifications when the caller asks for it.
