@@ -106,7 +106,7 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
     if (d->layout_b == GEMM_COL_MAJOR) holds |= GEMM_COND_K_CONTIG_B;
     holds |= GEMM_COND_DTYPE_HAS_MFMA;   // all four input types have one on gfx950 (fp32: v_mfma_f32_32x32x2_f32)
     if (variant >= GEMM_K1_LDS_TILED) holds |= GEMM_COND_LDS_STAGED;
-    if (d->M <= 16) holds |= GEMM_COND_SMALL_M;
+    if (d->M <= 64) holds |= GEMM_COND_SMALL_M;
 
     const uint32_t vecA = GEMM_COND_ALIGN16_A | GEMM_COND_LD16_A, vecB = GEMM_COND_ALIGN16_B | GEMM_COND_LD16_B;
     uint32_t required = 0;
@@ -143,7 +143,7 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
         // the streaming kernel addresses a strip of columns and the rows of A with 32-bit byte offsets
         const bool skinny = (holds & GEMM_COND_SMALL_M) && va && vb && d->K % kvec == 0 && d->K > 0 &&
                             (d->in_dtype == GEMM_BF16 || d->in_dtype == GEMM_F16) && d->ldb <= ((int64_t)1 << 24) &&
-                            d->lda <= ((int64_t)1 << 24);
+                            d->lda <= ((int64_t)1 << 24) && k4_streams_rows(a);
         // fp32 has its matrix instruction in the masked kernel only: no direct-to-LDS, packed or streaming form
         const bool f32 = d->in_dtype == GEMM_F32;
         if (f32) required = GEMM_COND_DTYPE_HAS_MFMA | GEMM_COND_LDS_STAGED;

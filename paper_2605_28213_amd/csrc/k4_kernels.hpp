@@ -870,9 +870,10 @@ __global__ __launch_bounds__(256) void k4_splitk_reduce(Args a, const float* __r
 }
 
 // ------------------------------------------------------------------------------------------------
-// Streaming kernel for M <= 16 (decode-like shapes): the product is bound by reading B once from
-// HBM.  A workgroup owns a strip of 16*NB columns of C; its WAVES waves split K, partial sums meet
-// in LDS at the end.  Needs: A row-major, B column-major, 16-byte aligned, K a multiple of 8.
+// Streaming kernel for M <= 64 (decode-like shapes): the product is bound by reading B once from
+// HBM.  A workgroup owns a strip of 16*NB columns of C and all MG groups of 16 rows of A; its WAVES
+// waves split K, partial sums meet in LDS at the end.  Needs: A row-major, B column-major, 16-byte
+// aligned, K a multiple of 8.
 //
 // The operands of v_mfma_f32_16x16x32 want, per instruction, 16 rows x 64 bytes of K; fetched that
 // way every wave instruction opens 16 separate 64-byte streams a leading dimension apart, and HBM
@@ -885,10 +886,11 @@ __global__ __launch_bounds__(256) void k4_splitk_reduce(Args a, const float* __r
 // serves a wave's requests in order, so the main loop has no barrier: waves only meet for the final
 // sum over the K split.
 //
-// Per wave and K tile: the A group and the NB column groups are parked and multiplied one after the
-// other (LDS holds A and one column group: 2 * 16 * TK * 2 bytes per wave); as soon as a group's
-// registers are parked its loads for the next K tile are issued, so (NB+1)*TK/32 loads stay in
-// flight per lane while the MFMAs of the current tile run.
+// Per wave and K tile: the MG groups of A and the NB column groups are parked and multiplied one after
+// the other (LDS holds A and one column group: (MG+1) * 16 * TK * 2 bytes per wave); as soon as a
+// group's registers are parked its loads for the next K tile are issued, so (MG+NB)*TK/32 loads stay
+// in flight per lane while the MFMAs of the current tile run.  A column group's fragment is read once
+// per k-step and multiplied with every group of A.
 // ------------------------------------------------------------------------------------------------
 template <typename IN>
 __device__ __forceinline__ void mfma16(const u32x4_t& a, const u32x4_t& b, f32x4_t& c)
@@ -899,26 +901,27 @@ __device__ __forceinline__ void mfma16(const u32x4_t& a, const u32x4_t& b, f32x4
         c = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
 }
 
-template <typename IN, int WAVES_, int NB_, int TK_, int ROT_ = 0>
+template <typename IN, int WAVES_, int NB_, int TK_, int ROT_ = 0, int MG_ = 1>
 struct StreamCfg {
     using In = IN;
-    static constexpr int WAVES = WAVES_, NB = NB_, TK = TK_, COLS = 16 * NB_, ROT = ROT_;
+    static constexpr int WAVES = WAVES_, NB = NB_, TK = TK_, COLS = 16 * NB_, ROT = ROT_, MG = MG_, ROWS = 16 * MG_;
     static constexpr int LPC = TK / 8;                     // lanes (16-byte chunks) per row per tile
     static constexpr int CPL = 64 / LPC;                   // rows covered by one load instruction
     static constexpr int GLD = 16 / CPL;                   // loads per group of 16 rows per lane
     static constexpr int KS = TK / 32;                     // MFMA k-steps per tile
     static constexpr int GROUP_BYTES = 16 * TK * 2;
-    static constexpr int TILE_BYTES = 2 * GROUP_BYTES;     // the A group and one group of B columns
+    static constexpr int TILE_BYTES = (MG + 1) * GROUP_BYTES;   // the groups of A and one group of B columns
     static constexpr int LDS_BYTES = WAVES * TILE_BYTES;
     static_assert(LPC >= 16 && LPC <= 64 && (LPC & (LPC - 1)) == 0, "a row's run is 16..64 lanes wide");
-    static_assert(WAVES * 16 * (COLS + 1) * 4 <= LDS_BYTES, "the K-split partial sums reuse the tiles");
+    static_assert(MG >= 1 && MG <= 4, "up to 64 rows of A");
+    static_assert(WAVES * ROWS * (COLS + 1) * 4 <= LDS_BYTES, "the K-split partial sums reuse the tiles");
 };
 
 template <typename CFG>
 __global__ __launch_bounds__(CFG::WAVES * 64) void k4_stream(Args a)
 {
     using IN = typename CFG::In;
-    constexpr int WAVES = CFG::WAVES, NB = CFG::NB, TK = CFG::TK, COLS = CFG::COLS;
+    constexpr int WAVES = CFG::WAVES, NB = CFG::NB, TK = CFG::TK, COLS = CFG::COLS, MG = CFG::MG, ROWS = CFG::ROWS;
     constexpr int LPC = CFG::LPC, CPL = CFG::CPL, GLD = CFG::GLD, KS = CFG::KS;
     constexpr int ROWB = TK * 2;                            // bytes per LDS row
     __shared__ __attribute__((aligned(16))) char lds[CFG::LDS_BYTES];
@@ -930,7 +933,7 @@ __global__ __launch_bounds__(CFG::WAVES * 64) void k4_stream(Args a)
     const uint16_t* A = (const uint16_t*)a.A + b * a.stride_a;
     const uint16_t* B = (const uint16_t*)a.B + b * a.stride_b;
     char* tile_a = lds + wave * CFG::TILE_BYTES;
-    char* tile_b = tile_a + CFG::GROUP_BYTES;
+    char* tile_b = tile_a + MG * CFG::GROUP_BYTES;
 
     // K tiles are dealt to the waves in turn (wave w takes tiles w, w+WAVES, ...): the waves of a
     // workgroup advance side by side, so that together they read WAVES*TK*2 contiguous bytes of every
@@ -944,13 +947,17 @@ __global__ __launch_bounds__(CFG::WAVES * 64) void k4_stream(Args a)
     const int lrow = lane / LPC, lc = lane % LPC;
     const char* Bs = (const char*)(B + j0 * a.b_sj);
     const char* As = (const char*)A;
-    uint32_t ao[GLD], bo[NB][GLD];
+    uint32_t ao[MG][GLD], bo[NB][GLD];
     int wr[GLD];
 #pragma unroll
     for (int n = 0; n < GLD; ++n) {
         const int c = n * CPL + lrow;                       // row inside a group, 0..15
         wr[n] = c * ROWB + ((lc ^ c) << 4);
-        ao[n] = (uint32_t)(((int64_t)(c < a.M ? c : a.M - 1) * a.a_si + lc * 8) * 2);
+#pragma unroll
+        for (int m = 0; m < MG; ++m) {
+            const int64_t rr = m * 16 + c < a.M ? m * 16 + c : a.M - 1;
+            ao[m][n] = (uint32_t)((rr * a.a_si + lc * 8) * 2);
+        }
 #pragma unroll
         for (int g = 0; g < NB; ++g) {
             const int64_t cc = j0 + g * 16 + c < a.N ? g * 16 + c : a.N - 1 - j0;
@@ -960,18 +967,22 @@ __global__ __launch_bounds__(CFG::WAVES * 64) void k4_stream(Args a)
     // operand side: lane (l16, lq) holds, for k-step s, chunk 4s+lq of row l16 of the group
     const int rd = l16 * ROWB;
 
-    f32x4_t acc[NB];
+    f32x4_t acc[MG][NB];
 #pragma unroll
-    for (int n = 0; n < NB; ++n) acc[n] = f32x4_t{0, 0, 0, 0};
+    for (int m = 0; m < MG; ++m)
+#pragma unroll
+        for (int n = 0; n < NB; ++n) acc[m][n] = f32x4_t{0, 0, 0, 0};
     const u32x4_t zero = {0, 0, 0, 0};
-    u32x4_t ra[GLD], rb[NB][GLD];
+    u32x4_t ra[MG][GLD], rb[NB][GLD];
 
     // `full`: the whole tile lies inside K, no lane needs a mask
     auto fetch_a = [&](auto full, int64_t k) __attribute__((always_inline)) {
         constexpr bool FULL = decltype(full)::value;
 #pragma unroll
-        for (int n = 0; n < GLD; ++n)
-            ra[n] = (FULL || k + lc * 8 < kend) ? *(const u32x4_t*)(As + k * 2 + ao[n]) : zero;
+        for (int m = 0; m < MG; ++m)
+#pragma unroll
+            for (int n = 0; n < GLD; ++n)
+                ra[m][n] = (FULL || k + lc * 8 < kend) ? *(const u32x4_t*)(As + k * 2 + ao[m][n]) : zero;
     };
     auto fetch_b = [&](auto full, int g, int64_t k) __attribute__((always_inline)) {
         constexpr bool FULL = decltype(full)::value;
@@ -981,7 +992,9 @@ __global__ __launch_bounds__(CFG::WAVES * 64) void k4_stream(Args a)
     };
     auto park_a = [&]() __attribute__((always_inline)) {
 #pragma unroll
-        for (int n = 0; n < GLD; ++n) *(u32x4_t*)(tile_a + wr[n]) = ra[n];
+        for (int m = 0; m < MG; ++m)
+#pragma unroll
+            for (int n = 0; n < GLD; ++n) *(u32x4_t*)(tile_a + m * CFG::GROUP_BYTES + wr[n]) = ra[m][n];
     };
     auto park_b = [&](int g) __attribute__((always_inline)) {
 #pragma unroll
@@ -991,9 +1004,12 @@ __global__ __launch_bounds__(CFG::WAVES * 64) void k4_stream(Args a)
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             const int pos = rd + (((4 * s + lq) ^ l16) << 4);
-            const u32x4_t fa = *(const u32x4_t*)(tile_a + pos);
             const u32x4_t fb = *(const u32x4_t*)(tile_b + pos);
-            mfma16<IN>(fa, fb, acc[g]);
+#pragma unroll
+            for (int m = 0; m < MG; ++m) {
+                const u32x4_t fa = *(const u32x4_t*)(tile_a + m * CFG::GROUP_BYTES + pos);
+                mfma16<IN>(fa, fb, acc[m][g]);
+            }
         }
     };
     using yes = std::integral_constant<bool, true>;
@@ -1055,16 +1071,18 @@ __global__ __launch_bounds__(CFG::WAVES * 64) void k4_stream(Args a)
     __syncthreads();
     float* part = (float*)lds;
 #pragma unroll
-    for (int n = 0; n < NB; ++n)
+    for (int m = 0; m < MG; ++m)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) part[(wave * 16 + 4 * lq + r) * (COLS + 1) + n * 16 + l16] = acc[n][r];
+        for (int n = 0; n < NB; ++n)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) part[(wave * ROWS + m * 16 + 4 * lq + r) * (COLS + 1) + n * 16 + l16] = acc[m][n][r];
     __syncthreads();
     const float sc = batch_scale(a, b);
-    for (int o = t; o < 16 * COLS; o += WAVES * 64) {
+    for (int o = t; o < ROWS * COLS; o += WAVES * 64) {
         const int i = o / COLS, j = o % COLS;
         float v = 0.0f;
 #pragma unroll
-        for (int w = 0; w < WAVES; ++w) v += part[(w * 16 + i) * (COLS + 1) + j];
+        for (int w = 0; w < WAVES; ++w) v += part[(w * ROWS + i) * (COLS + 1) + j];
         if (i < a.M && j0 + j < a.N)
             store_out(a.C, b * a.stride_c + (int64_t)i * a.ldc + j0 + j, v * sc + (a.bias ? a.bias[j0 + j] : 0.0f), a.out_dtype);
     }

@@ -201,9 +201,11 @@ CONFIGS: Dict[str, Config] = {
     "PBMM16": Config("PBMM16", 2048, 2048, 2048, BF16, BF16, ROW_MAJOR, COL_MAJOR, "normal", rsqrt_k=True, batch=16),
     "PBMM32": Config("PBMM32", 1024, 1024, 1024, BF16, BF16, ROW_MAJOR, COL_MAJOR, "normal", rsqrt_k=True, batch=32),
     "PADDMM": Config("PADDMM", 4096, 4096, 4096, BF16, BF16, ROW_MAJOR, COL_MAJOR, "normal", rsqrt_k=True, biased=True),
-    # decode-like shapes with more rows than the streaming kernel takes (C4's recipe): the split-K form's case
+    # decode-like shapes with more rows than C4 (its recipe): 32 and 64 rows still stream, 128 rows are
+    # the split-K form's case
     "D32": Config("D32", 32, 16384, 16384, BF16, BF16, ROW_MAJOR, COL_MAJOR, "normal", std=0.02),
     "D64": Config("D64", 64, 16384, 16384, BF16, BF16, ROW_MAJOR, COL_MAJOR, "normal", std=0.02),
+    "D128": Config("D128", 128, 16384, 16384, BF16, BF16, ROW_MAJOR, COL_MAJOR, "normal", std=0.02),
     # reduced-size counterparts: same dtype / layout / distribution / raggedness
     "C2_small": Config("C2_small", 512, 768, 640, BF16, BF16, ROW_MAJOR, COL_MAJOR, "normal", rsqrt_k=True),
     "C3_small": Config("C3_small", 387, 301, 259, F16, F16, ROW_MAJOR, ROW_MAJOR, "uniform"),

@@ -115,10 +115,23 @@ def test_paper_shapes_pass_the_gate(name):
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("name", ["D32", "D64"])
+def test_decode_shapes_with_32_and_64_rows_stream(name):
+    """bf16 32 and 64 x 16384 x 16384: the expert state reads B once, at more than half of the HBM roofline."""
+    cfg = gen.CONFIGS[name]
+    reference, cache = OracleReference(cfg), {}
+    e = gate.run_gate(gemm.GEMM_K4_MFMA, cfg, reference, inputs_cache=cache, ledger_path=LEDGER)
+    _entries.append(e)
+    assert e["verdict"] == "passed" and e["query"]["path"] == "mfma16-stream(small-M)", e
+    bytes_moved = 2 * (cfg.M * cfg.K + cfg.N * cfg.K + cfg.M * cfg.N)
+    assert bytes_moved / (e["profile"]["median_us"] * 1e-6) > 0.5 * 8e12, e["profile"]
+    torch.cuda.empty_cache()
+
+
 def test_split_k_on_a_decode_shape_passes_the_gate_and_is_faster():
-    """bf16 32 x 16384 x 16384 (more rows than the streaming kernel takes, 128 tiles): the expert state at
+    """bf16 128 x 16384 x 16384 (more rows than the streaming kernel takes, 128 tiles): the expert state at
     three seeds with the scratch its split-K form asks for, and once without; the split form must win."""
-    cfg = gen.CONFIGS["D32"]
+    cfg = gen.CONFIGS["D128"]
     reference, cache = OracleReference(cfg), {}
     split = gate.run_gate(gemm.GEMM_K4_MFMA, cfg, reference, inputs_cache=cache, ledger_path=LEDGER, lend_workspace=True)
     plain = gate.run_gate(gemm.GEMM_K4_MFMA, cfg, reference, seeds=(0,), inputs_cache=cache, ledger_path=LEDGER, lend_workspace=False)

@@ -124,6 +124,29 @@ def test_skinny_path_edges():
     check(4, inp)
 
 
+@pytest.mark.parametrize("dtype", [gen.BF16, gen.F16])
+def test_streaming_path_with_17_to_64_rows(dtype):
+    """Two to four groups of 16 rows of A per workgroup: every group boundary, a ragged last group, a
+    ragged last strip of columns, a ragged last K tile for every wave, batches, padded leading dimensions,
+    scales and bias; and the rule that hands such a product to the tiled kernel when its strips are few."""
+    cases = [(17, 4100, 520, {}), (32, 4096, 1024, {}), (33, 8200, 264, {}), (47, 520, 1160, dict(batch=16, scaled=True)),
+             (48, 8192, 128, dict(biased=True)), (49, 8256, 392, {}), (64, 8192, 2048, {}),
+             (20, 130, 1320, dict(batch=32, lda=1328, ldb=1336, ldc=136)), (64, 70, 776, dict(batch=70, scaled=True))]
+    for (M, N, K, kw) in cases:
+        cfg = gen.Config("rows", M, N, K, dtype, dtype, ROW, COL, "normal", std=0.02, **kw)
+        inp = gen.make_inputs(cfg, 6)
+        d = gemm.make_desc(M, N, K, dtype, dtype, ROW, COL, lda=inp.lda, ldb=inp.ldb, ldc=inp.ldc, batch=cfg.batch,
+                           stride_a=inp.stride_a, stride_b=inp.stride_b, stride_c=inp.stride_c)
+        q = gemm.gemm_query(4, d)
+        assert q.path == "mfma16-stream(small-M)" and q.bm == 16 * ((M + 15) // 16) and q.bn == (32 if M <= 32 else 64), (M, N, K, q)
+        ref = oracle_for(inp)
+        check(4, inp, ref)
+        check(4, inp, ref, out_dtype=gen.F32)
+    # too few strips for the chip: the tiled kernel keeps the product
+    for (M, N) in ((17, 4064), (64, 8128), (33, 4096)):
+        assert gemm.gemm_query(4, gemm.make_desc(M, N, 1024, dtype, dtype, ROW, COL)).path.startswith("mfma32-direct-to-lds")
+
+
 def test_batched_strides_scales_and_padding_untouched():
     """Batch strides larger than the matrices, ldc > N: the gaps keep their poison bytes."""
     M, N, K, nb = 70, 50, 96, 3

@@ -63,8 +63,11 @@ def test_expert_state_paths_and_scratch(p):
     fast_ok = (p["la"] == gemm.GEMM_ROW_MAJOR and p["lb"] == gemm.GEMM_COL_MAJOR and (p["lda"] * es) % 16 == 0
                and (p["ldb"] * es) % 16 == 0 and (p["batch"] == 1 or ((p["M"] * p["lda"] * es) % 16 == 0 and (p["N"] * p["ldb"] * es) % 16 == 0)))
     kvec, kslab = 16 // es, 128 // es
-    if fast_ok and p["M"] <= 16 and p["K"] % kvec == 0 and es == 2:
+    cols = 16 if p["M"] <= 16 else 32 if p["M"] <= 32 else 64
+    streams = p["M"] <= 16 or (p["M"] <= 64 and math.ceil(p["N"] / cols) * p["batch"] >= 128)
+    if fast_ok and streams and p["K"] % kvec == 0 and es == 2:
         assert q.path == "mfma16-stream(small-M)" and q.workspace_bytes == 0
+        assert q.bn == cols and q.bm == 16 * math.ceil(max(p["M"], 1) / 16) and q.grid == math.ceil(p["N"] / cols) * p["batch"]
     elif fast_ok and p["K"] % kslab == 0:
         assert q.path.startswith("mfma32-direct-to-lds") and q.violated == 0
         # split-K: offered (through workspace_bytes) when the product has few tiles and a long K, taken when scratch is lent
