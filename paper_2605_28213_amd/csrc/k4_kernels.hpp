@@ -128,7 +128,8 @@ __device__ __forceinline__ void store_tiles(const Args& a, int64_t b, const f32x
 // element at row (of C) l%32 and column 8*(r/4) + 4*(l/32) + r%4: four consecutive columns per
 // register quad.  Each wave rounds its accumulators to the output type, parks one 32-row block at a
 // time in a private LDS area (row pitch padded by 16 bytes) and writes it out again row by row, so
-// that global stores are 16 bytes per lane and whole 128-byte lines per row.
+// that global stores are 16 bytes per lane and whole 128-byte lines per row (also when C's rows are
+// aligned to an element only: then the stores are declared under-aligned).
 // ------------------------------------------------------------------------------------------------
 template <int OUT, bool INTERIOR, int TMI, int TNI>
 __device__ __forceinline__ void store_tiles_staged(const Args& a, int64_t b, const f32x16_t (&acc)[TMI][TNI],
@@ -190,25 +191,6 @@ __device__ __forceinline__ void store_tiles_staged(const Args& a, int64_t b, con
             }
             continue;
         }
-        if (!vec_ok) {
-            // C rows are aligned to an element only: consecutive lanes store consecutive elements of
-            // one row, so that a store instruction still covers whole lines
-            constexpr int RW = TNI * 32;                                   // columns of the block
-            for (int r = 0; r < 32; ++r) {
-                const int64_t gi = row0 + i * 32 + r;
-                if (gi >= a.M) break;
-#pragma unroll
-                for (int h = 0; h < (RW + 63) / 64; ++h) {
-                    const int c = h * 64 + lane;
-                    const int64_t gj = col0 + c;
-                    if (c < RW && gj < a.N) {
-                        if constexpr (OB == 4) ((uint32_t*)C)[gi * a.ldc + gj] = *(const uint32_t*)(stage + r * PITCH + c * 4);
-                        else ((uint16_t*)C)[gi * a.ldc + gj] = *(const uint16_t*)(stage + r * PITCH + c * 2);
-                    }
-                }
-            }
-            continue;
-        }
 #pragma unroll
         for (int p = 0; p < PASSES; ++p) {
             const int q = lane + 64 * p, r = q / CPR, c = q % CPR;
@@ -216,8 +198,14 @@ __device__ __forceinline__ void store_tiles_staged(const Args& a, int64_t b, con
             const int64_t gi = row0 + i * 32 + r, gj = col0 + c * EPC;
             if (gi < a.M) {
                 char* out = C + (gi * a.ldc + gj) * OB;
-                if (vec_ok && gj + EPC <= a.N) {
-                    *(u32x4_t*)out = w;
+                if (gj + EPC <= a.N) {
+                    // C rows aligned to an element only: the same 16 bytes per lane, declared under-aligned
+                    // (global memory takes vector stores at any element boundary; they cost more line splits)
+                    typedef u32x4_t __attribute__((aligned(2))) u32x4_a2_t;
+                    typedef u32x4_t __attribute__((aligned(4))) u32x4_a4_t;
+                    if (vec_ok) *(u32x4_t*)out = w;
+                    else if constexpr (OB == 4) *(u32x4_a4_t*)out = w;
+                    else *(u32x4_a2_t*)out = w;
                 } else {
 #pragma unroll
                     for (int e = 0; e < EPC; ++e)
@@ -741,11 +729,11 @@ __global__ __launch_bounds__(WM* WN * 64) void k4_mfma_masked(Args a, int vec_ma
 // lets the fast kernel run on operands that violate its conditions (odd leading dimensions, K
 // strided, ragged K): Table 1's "smem_transpose" applied ahead of the product.
 //
-// Source rows are aligned to their element size only, so nothing wider than an element can be
-// loaded at an element's own address.  Both kernels instead load the aligned dwords that contain the
-// elements they need (a dword that holds at least one valid byte lies inside the allocation) and
-// shift: by bytes within a register pair when K is contiguous (k4_pack_rows), by whole elements
-// into an LDS tile when the source is contiguous along the other axis (k4_pack_transpose).
+// Source rows are aligned to their element size only.  k4_pack_rows (K contiguous) loads a chunk
+// with one 16-byte load declared under-aligned, and a row's ragged end through the aligned dwords that
+// contain it (a dword that holds at least one valid byte lies inside the allocation), shifted by
+// bytes within a register pair.  k4_pack_transpose (source contiguous along the other axis) loads
+// aligned dwords and drops their elements into an LDS tile.
 // ------------------------------------------------------------------------------------------------
 
 // K contiguous in the source.  One thread makes one 16-byte chunk of the packed row.
@@ -761,19 +749,26 @@ __global__ __launch_bounds__(256) void k4_pack_rows(const char* __restrict__ src
     src += (int64_t)blockIdx.y * src_batch_bytes + r * row_bytes;
     const uintptr_t row = (uintptr_t)src, end = row + (uintptr_t)(K * BYTES);   // valid bytes of this row: [row, end)
     const uintptr_t p = row + (uintptr_t)(c * 16);
-    const uintptr_t base = p & ~(uintptr_t)3;
-    const uint32_t sh = (uint32_t)(p & 3);
-    uint32_t d[5];
-#pragma unroll
-    for (int i = 0; i < 5; ++i) d[i] = (base + 4 * i < end && (i < 4 || sh != 0)) ? *(const uint32_t*)(base + 4 * i) : 0u;
     u32x4_t out;
+    if (p + 16 <= end) {
+        // a whole chunk inside the row: one 16-byte load, declared aligned to a byte only
+        typedef u32x4_t __attribute__((aligned(1))) u32x4_a1_t;
+        out = *(const u32x4_a1_t*)p;
+    } else {
+        // the row's ragged end (or the zero padding past it): the aligned dwords that hold its last bytes
+        const uintptr_t base = p & ~(uintptr_t)3;
+        const uint32_t sh = (uint32_t)(p & 3);
+        uint32_t d[5];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        uint32_t w = __builtin_amdgcn_alignbyte(d[i + 1], d[i], sh);          // bytes p+4i .. p+4i+3
-        const int64_t left = (int64_t)(end - p) - 4 * i;                      // valid bytes from here on
-        if (left <= 0) w = 0;
-        else if (left < 4) w &= (1u << (8 * left)) - 1u;
-        out[i] = w;
+        for (int i = 0; i < 5; ++i) d[i] = (base + 4 * i < end && (i < 4 || sh != 0)) ? *(const uint32_t*)(base + 4 * i) : 0u;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            uint32_t w = __builtin_amdgcn_alignbyte(d[i + 1], d[i], sh);      // bytes p+4i .. p+4i+3
+            const int64_t left = (int64_t)(end - p) - 4 * i;                  // valid bytes from here on
+            if (left <= 0) w = 0;
+            else if (left < 4) w &= (1u << (8 * left)) - 1u;
+            out[i] = w;
+        }
     }
     *(u32x4_t*)(dst + (int64_t)blockIdx.y * dst_batch_bytes + (r * Kp + c * V) * BYTES) = out;
 }
