@@ -151,7 +151,9 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
         // that kernel addresses a 256-row tile with 32-bit byte offsets: rows are bounded to 4 MiB
         const bool rows_fit = d->lda * es <= ((int64_t)1 << 22) && d->ldb * es <= ((int64_t)1 << 22);
         // packing both operands into lent scratch turns any layout/alignment/K into the fast kernel's case
-        const bool can_pack = !f32 && d->K > 0 && k4_packed_k(a) * es <= ((int64_t)1 << 22);
+        // (and the pack kernels' one-dimensional grids, one workgroup per 2048..7936 packed elements, stay below 2^31)
+        const bool can_pack = !f32 && d->K > 0 && k4_packed_k(a) * es <= ((int64_t)1 << 22) &&
+                              (d->M + d->N) * k4_packed_k(a) < ((int64_t)1 << 40);
         if (skinny) {
             p.path = MFMA_SKINNY;
             path = "mfma16-stream(small-M)";

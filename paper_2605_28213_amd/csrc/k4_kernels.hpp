@@ -777,12 +777,16 @@ __global__ __launch_bounds__(256) void k4_pack_rows(const char* __restrict__ src
 // rows).  A workgroup transposes a tile of PackRows<IN> rows x 128 bytes of K through LDS.  A tile's
 // rows span 248 bytes of a source line: with the line's misalignment at most 63 aligned dwords, one per
 // lane of a wave (a 64-row tile left half of the lanes idle and fetched twice the bytes it used).
+// Neighbouring row tiles share the memory lines their spans end in: workgroup ids are laid out so that
+// all row tiles of one K tile run on the same XCD (ids are dealt to the eight XCDs in turn), one after
+// the other, and the shared lines are found in that XCD's L2 instead of being fetched once per L2
+// (fp16 4093 x 4097: 66.7 -> 33.7 MB fetched for a source of 33.5 MB; the time, 19 us, did not change).
 template <typename IN> constexpr int PackRows = 248 / IN::BYTES;
 
 template <typename IN>
 __global__ __launch_bounds__(256) void k4_pack_transpose(const char* __restrict__ src, int64_t k_bytes, int64_t rows, int64_t K,
                                                          int64_t Kp, char* __restrict__ dst, int64_t src_batch_bytes,
-                                                         int64_t dst_batch_bytes)
+                                                         int64_t dst_batch_bytes, int row_tiles)
 {
     using raw = typename IN::raw;
     constexpr int BYTES = IN::BYTES, KE = ROW_BYTES / BYTES, V = 16 / BYTES, TR = PackRows<IN>, EPD = 4 / BYTES;
@@ -790,9 +794,13 @@ __global__ __launch_bounds__(256) void k4_pack_transpose(const char* __restrict_
     constexpr int PITCH = KE + V;                       // elements; keeps rows 16-byte aligned, spreads banks
     __shared__ __attribute__((aligned(16))) raw tile[TR * PITCH];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    const int64_t k0 = (int64_t)blockIdx.x * KE, r0 = (int64_t)blockIdx.y * TR;
-    src += (int64_t)blockIdx.z * src_batch_bytes;
-    dst += (int64_t)blockIdx.z * dst_batch_bytes;
+    // id = 8 * j + xcd: K tile xcd + 8 * (j / row_tiles), row tile j % row_tiles (the grid is padded to
+    // eight K tiles per group; a workgroup past the last K tile leaves as a whole)
+    const int64_t j = blockIdx.x >> 3;
+    const int64_t k0 = ((int64_t)(blockIdx.x & 7) + 8 * (j / row_tiles)) * KE, r0 = (j % row_tiles) * TR;
+    if (k0 >= Kp) return;
+    src += (int64_t)blockIdx.y * src_batch_bytes;
+    dst += (int64_t)blockIdx.y * dst_batch_bytes;
     for (int i = t; i < TR * PITCH * BYTES / 16; i += 256) ((u32x4_t*)tile)[i] = u32x4_t{0, 0, 0, 0};
     __syncthreads();
     // source line of k: elements r0 .. r0+TR-1 are contiguous; lane l loads the l-th aligned dword of

@@ -235,9 +235,10 @@ static hipError_t launch_packed(const Args& a)
             hipLaunchKernelGGL(k4_pack_rows<IN>, g, dim3(256), 0, a.stream, (const char*)src, sr * IN::BYTES, rows, a.K, Kp,
                                (char*)dst, src_batch_bytes, dst_batch_bytes);
         } else {   // sr == 1: row- or column-major storage leaves no other case
-            dim3 g((unsigned)(Kp / KE), (unsigned)((rows + PackRows<IN> - 1) / PackRows<IN>), (unsigned)a.batch);
+            const int64_t row_tiles = (rows + PackRows<IN> - 1) / PackRows<IN>, k_groups = (Kp / KE + 7) / 8;
+            dim3 g((unsigned)(8 * k_groups * row_tiles), (unsigned)a.batch, 1);
             hipLaunchKernelGGL(k4_pack_transpose<IN>, g, dim3(256), 0, a.stream, (const char*)src, sk * IN::BYTES, rows, a.K, Kp,
-                               (char*)dst, src_batch_bytes, dst_batch_bytes);
+                               (char*)dst, src_batch_bytes, dst_batch_bytes, (int)row_tiles);
         }
     };
     pack(a.A, a.a_si, a.a_sk, a.M, a.stride_a, pa);
