@@ -63,3 +63,35 @@ def test_random_case(i):
             continue
         err = util.norm_err(C[:, :, : cfg.N], C_ref, D)
         assert err <= util.TOL[cfg.in_dtype], (cfg, gemm.gemm_variant_name(v), q.path, err)
+
+
+def draw_rows_case(rng, i):
+    """17..64 rows on the streaming kernel: few wide strips per problem, enough problems to pass its rule."""
+    dtype = int(rng.choice([gen.BF16, gen.F16]))
+    M = int(rng.integers(17, 65))
+    cols = 32 if M <= 32 else 64
+    strips = int(rng.integers(1, 7))
+    batch = -(-128 // strips) + int(rng.integers(0, 4))
+    N = cols * (strips - 1) + int(rng.integers(1, cols + 1))
+    K = 8 * int(rng.integers(1, 200))
+    pad = lambda n: n + 8 * int(rng.integers(0, 4))
+    out = int(rng.choice([dtype, gen.F32]))
+    return gen.Config(f"rows{i}", M, N, K, dtype, out, ROW, COL, str(rng.choice(["uniform", "normal"])), batch=batch,
+                      scaled=bool(rng.random() < 0.3), biased=bool(rng.random() < 0.3), lda=pad(K), ldb=pad(K), ldc=N + int(rng.integers(0, 5)))
+
+
+ROWS_CASES = [draw_rows_case(np.random.default_rng(2000 + i), i) for i in range(16)]
+
+
+@pytest.mark.parametrize("i", range(len(ROWS_CASES)))
+def test_random_case_with_17_to_64_rows(i):
+    cfg = ROWS_CASES[i]
+    inp = gen.make_inputs(cfg, 200 + i)
+    C_ref, D = oracle_for(inp)
+    q = gemm.gemm_query(4, gemm.make_desc(cfg.M, cfg.N, cfg.K, cfg.in_dtype, cfg.out_dtype, ROW, COL, lda=inp.lda, ldb=inp.ldb,
+                                          ldc=inp.ldc, batch=cfg.batch, stride_a=inp.stride_a, stride_b=inp.stride_b, stride_c=inp.stride_c))
+    assert q.path == "mfma16-stream(small-M)", (cfg, q)
+    rc, C, _ = util.run_config(4, inp)
+    assert rc == gemm.GEMM_OK, (cfg, gemm.gemm_status_string(rc), gemm.gemm_last_launch_error())
+    err = util.norm_err(C[:, :, : cfg.N], C_ref, D)
+    assert err <= util.TOL[cfg.in_dtype], (cfg, err)
