@@ -189,6 +189,15 @@ def main():
             flops_box.append(fl)
         tm = event_times(mfma_probe, 20, 10)
         mf = flops_box[-1] / (tm[len(tm) // 2] * 1e-3) / 1e12
+        # the same loop on all-zero operands: what the matrix pipe sustains when no operand bit toggles
+        Z0 = torch.zeros(need, dtype=torch.uint8, device="cuda")
+
+        def mfma_probe_zeros():
+            rc, fl = gemm.gemm_probe_mfma(gemm.GEMM_BF16, Z0, need, wgs, iters, sink, sink.numel() * 4, stream)
+            assert rc == gemm.GEMM_OK
+            flops_box.append(fl)
+        tz = event_times(mfma_probe_zeros, 20, 10)
+        mz = flops_box[-1] / (tz[len(tz) // 2] * 1e-3) / 1e12
         big = torch.empty(512 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
         dst = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
         s32 = torch.zeros(4, dtype=torch.int32, device="cuda")
@@ -200,11 +209,13 @@ def main():
         out["ceilings"] = {
             "mfma_bf16_on_headline_operands": {"TFLOP/s": mf, "frac_of_peak": mf / PEAK["mfma_bf16"],
                                                "what": f"{wgs} workgroups x 4 waves x {iters} x 32 v_mfma_f32_32x32x16_bf16, operands from A"},
+            "mfma_bf16_on_zeros": {"TFLOP/s": mz, "frac_of_peak": mz / PEAK["mfma_bf16"],
+                                   "what": "the same loop on all-zero operands: the gap to the line above is the clock the chip gives up to data-dependent power"},
             "hbm_stream_read": {"GB/s": rd, "frac_of_peak": rd / PEAK["hbm_GBs"], "what": "512 MiB, 16-byte loads"},
             "hbm_copy": {"GB/s": cp, "frac_of_peak": cp / PEAK["hbm_GBs"], "what": "256 MiB read + 256 MiB written"},
         }
         out["roofline"]["frac_of_measured_mfma_ceiling"] = out["roofline"]["achieved"] / mf
-        del big, dst, sink
+        del big, dst, sink, Z0
     del sets, keep
     torch.cuda.empty_cache()
 
