@@ -95,3 +95,38 @@ def test_largest_batch_count():
         assert util.norm_err(C[:, :, :8], C_ref, D) <= util.TOL[gen.BF16]
     d = gemm.make_desc(8, 8, 64, gen.BF16, gen.BF16, ROW, COL, batch=65536)
     assert gemm.gemm_query(4, d).status == gemm.GEMM_ERR_BAD_ARG
+
+
+def test_gather_with_activations_just_below_2_gib():
+    """The implicit-GEMM state addresses the activations with 32-bit byte offsets and needs them below
+    2^31 bytes: 255 images of 256 x 256 x 64 fp16 are 2 139 095 040 bytes.  Every image is the same seeded
+    one, so the oracle evaluates sampled outputs (all images, image corners included) on a single image."""
+    import oracle
+    from paper_2605_28213_amd import conv
+    N, H, C, F = 255, 256, 64, 64
+    one = gen.make_conv_inputs(gen.ConvConfig("below2GiB", 1, H, H, C, F, 3, 3, gen.F16, gen.F16), 41)
+    img = util.dev(one.x)
+    dx = img.repeat(N)
+    assert dx.numel() == N * H * H * C * 2 < 1 << 31
+    dw = util.dev(one.w)
+    dy = torch.full((N * H * H * F * 2,), util.POISON, dtype=torch.uint8, device="cuda")
+    d = conv.make_desc(N, H, H, C, F, 3, 3, gen.F16, gen.F16, stride=(1, 1), pad=(1, 1))
+    q = conv.conv2d_query(conv.CONV_C2_IMPLICIT_MFMA, d, dx, dw, dy)
+    assert q.status == gemm.GEMM_OK and q.violated == 0, q
+    rc = conv.conv2d_run(conv.CONV_C2_IMPLICIT_MFMA, d, dx, dw, dy)
+    torch.cuda.synchronize()
+    assert rc == gemm.GEMM_OK, conv.conv2d_last_launch_error()
+    rng = np.random.default_rng(7)
+    npts = 4000
+    pn = rng.integers(0, N, npts); pn[:200] = N - 1; pn[200:300] = 0
+    pp = rng.integers(0, H, npts); pq = rng.integers(0, H, npts); pf = rng.integers(0, F, npts)
+    pp[:50], pq[:50] = H - 1, H - 1                        # the last pixel of the last image: the largest offsets
+    pp[50:100], pq[50:100] = 0, 0
+    y_ref, D = oracle.conv2d_points(gen.F16, one.x, one.w, np.zeros(npts, dtype=np.int64), pp, pq, pf, stride=(1, 1), pad=(1, 1))
+    idx = torch.from_numpy((((pn * H + pp) * H + pq) * F + pf).astype(np.int64)).cuda()
+    got = dy.view(torch.int16)[idx].cpu().numpy().view(np.float16).astype(np.float64)
+    assert util.norm_err(got, y_ref, D) <= util.TOL[gen.F16]
+    # one image more and the state is refused
+    d = conv.make_desc(N + 1, H, H, C, F, 3, 3, gen.F16, gen.F16, stride=(1, 1), pad=(1, 1))
+    q = conv.conv2d_query(conv.CONV_C2_IMPLICIT_MFMA, d)
+    assert q.status == gemm.GEMM_ERR_PRECONDITION and conv.Query.names(q.violated) == ["X_BELOW_2GIB"]
