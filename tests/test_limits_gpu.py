@@ -130,3 +130,36 @@ def test_gather_with_activations_just_below_2_gib():
     d = conv.make_desc(N + 1, H, H, C, F, 3, 3, gen.F16, gen.F16, stride=(1, 1), pad=(1, 1))
     q = conv.conv2d_query(conv.CONV_C2_IMPLICIT_MFMA, d)
     assert q.status == gemm.GEMM_ERR_PRECONDITION and conv.Query.names(q.violated) == ["X_BELOW_2GIB"]
+
+
+def test_radix_select_on_rows_of_five_million():
+    """Rows far beyond what the oracle's rank count can walk: the selection is checked against its
+    definition (the k largest, ties at the threshold to the lower indices, indices increasing, values
+    bit for bit), which holds at any size.  Values are standard normal rounded to multiples of 1/1024, so
+    thousands of elements tie at the threshold; the second row sits ld - n elements after the first."""
+    from paper_2605_28213_amd import topk
+    n, k, ld = 5_000_003, 100_000, 5_000_008
+    x = np.zeros((2, ld), np.float32)
+    x[:, :n] = np.round(gen.normal(43, 0, 2 * n, 1.0).reshape(2, n) * 1024) / 1024
+    x[:, n:] = 99.0                                          # past the row: must never be selected
+    dx = torch.from_numpy(x.reshape(-1)).cuda()
+    didx = torch.full((2 * k,), -7, dtype=torch.int32, device="cuda")
+    dval = torch.full((2 * k,), -7.0, dtype=torch.float32, device="cuda")
+    d = topk.make_desc(2, n, k, ld=ld)
+    for refused in (topk.TOPK_T0_SELECTION, topk.TOPK_T2_RESIDENT):
+        assert topk.topk_query(refused, d, dx).status == gemm.GEMM_ERR_PRECONDITION
+    rc = topk.topk_run(topk.TOPK_T1_RADIX_SELECT, d, dx, didx, dval)
+    torch.cuda.synchronize()
+    assert rc == gemm.GEMM_OK, topk.topk_last_launch_error()
+    idx, val = didx.cpu().numpy().reshape(2, k), dval.cpu().numpy().reshape(2, k)
+    for b in range(2):
+        row = x[b, :n]
+        assert np.all(np.diff(idx[b]) > 0) and idx[b][0] >= 0 and idx[b][-1] < n
+        np.testing.assert_array_equal(val[b].view(np.uint32), row[idx[b]].view(np.uint32))
+        t = val[b].min()
+        chosen = np.zeros(n, bool)
+        chosen[idx[b]] = True
+        assert np.all(row[~chosen] <= t) and np.all(chosen[row > t])
+        at = np.flatnonzero(row == t)                        # the tie at the threshold goes to the lower indices
+        taken = chosen[at]
+        assert taken.sum() == k - int((row > t).sum()) and np.all(taken[: taken.sum()]) and not np.any(taken[taken.sum():])
