@@ -214,6 +214,50 @@ def test_launch_on_a_side_stream():
     assert util.norm_err(C, C_ref, D) <= util.TOL[c.in_dtype]
 
 
+def test_host_threads_and_streams_side_by_side():
+    """The library keeps no state between calls (the launch-error slot is per thread): four host threads,
+    each on a stream of its own, launch different paths of K4 and an earlier state at the same time, many
+    times over, into buffers of their own; every result must equal the one the same call gives alone."""
+    import threading
+    jobs = []
+    for name, variant, lend in (("C2_small", 4, False), ("C4_small", 4, False), ("C3_small", 4, True), ("C5_small", 2, False)):
+        inp = gen.make_inputs(gen.CONFIGS[name], 1)
+        c = inp.cfg
+        dA, dB = util.dev(inp.A), util.dev(inp.B)
+        sa = torch.from_numpy(inp.scale_a).cuda() if inp.scale_a is not None else None
+        sb = torch.from_numpy(inp.scale_b).cuda() if inp.scale_b is not None else None
+        stream = torch.cuda.Stream()
+        kw = dict(lda=inp.lda, ldb=inp.ldb, ldc=inp.ldc, batch=c.batch, stride_a=inp.stride_a, stride_b=inp.stride_b,
+                  stride_c=inp.stride_c, scale_a=sa, scale_b=sb)
+        d = gemm.make_desc(c.M, c.N, c.K, c.in_dtype, c.out_dtype, c.layout_a, c.layout_b, stream=stream, **kw)
+        ws = None
+        if lend:
+            need = gemm.gemm_query(variant, d, dA, dB).workspace_bytes
+            ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+            d.workspace, d.workspace_bytes = ws.data_ptr(), need
+        alone = util.out_buffer(c.batch * inp.stride_c, c.out_dtype)
+        assert gemm.gemm_run_ex(variant, d, dA, dB, alone) == gemm.GEMM_OK
+        stream.synchronize()
+        outs = [util.out_buffer(c.batch * inp.stride_c, c.out_dtype) for _ in range(3)]
+        jobs.append(dict(variant=variant, d=d, dA=dA, dB=dB, alone=alone, outs=outs, stream=stream, keep=(sa, sb, ws), rcs=[]))
+    torch.cuda.synchronize()
+
+    def work(j):
+        for i in range(60):
+            j["rcs"].append(gemm.gemm_run_ex(j["variant"], j["d"], j["dA"], j["dB"], j["outs"][i % 3]))
+
+    threads = [threading.Thread(target=work, args=(j,)) for j in jobs]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    for j in jobs:
+        assert all(rc == gemm.GEMM_OK for rc in j["rcs"]) and len(j["rcs"]) == 60
+        for o in j["outs"]:
+            assert torch.equal(o, j["alone"])
+
+
 @pytest.mark.parametrize("dtype", [gen.BF16, gen.F16, gen.E4M3])
 @pytest.mark.parametrize("la,lb", [(ROW, ROW), (ROW, COL), (COL, ROW), (COL, COL)])
 def test_packed_path_with_lent_workspace(dtype, la, lb):
