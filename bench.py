@@ -228,7 +228,7 @@ def main():
                     "PBMM32": ("TileLang +cfg, RTX PRO 6000, App. D", (0.226,)),
                     "PADDMM": ("TileLang +cfg, RTX PRO 6000, App. D", (0.375,))}
         for name, bound in (("C1", "mfma"), ("C3", "mfma"), ("C4", "hbm"), ("C5", "mfma"), ("P4096", "mfma"),
-                            ("P2048", "mfma"), ("PBMM16", "mfma"), ("PBMM32", "mfma"), ("PADDMM", "mfma"), ("D32", "hbm"), ("D64", "hbm"), ("D128", "hbm")):
+                            ("P2048", "mfma"), ("PBMM16", "mfma"), ("PBMM32", "mfma"), ("PADDMM", "mfma"), ("D32", "hbm"), ("D64", "hbm"), ("D128", "hbm"), ("D16_e4m3", "hbm")):
             c = gen.CONFIGS[name]
             v = gemm.GEMM_K4_MFMA
             _, s2, d2, keep2 = device_sets(c)

@@ -142,7 +142,7 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
         const int64_t kvec = 16 / es;
         // the streaming kernel addresses a strip of columns and the rows of A with 32-bit byte offsets
         const bool skinny = (holds & GEMM_COND_SMALL_M) && va && vb && d->K % kvec == 0 && d->K > 0 &&
-                            (d->in_dtype == GEMM_BF16 || d->in_dtype == GEMM_F16) && d->ldb <= ((int64_t)1 << 24) &&
+                            d->in_dtype != GEMM_F32 && d->ldb <= ((int64_t)1 << 24) &&
                             d->lda <= ((int64_t)1 << 24) && k4_streams_rows(a);
         // fp32 has its matrix instruction in the masked kernel only: no direct-to-LDS, packed or streaming form
         const bool f32 = d->in_dtype == GEMM_F32;

@@ -873,10 +873,11 @@ __global__ __launch_bounds__(256) void k4_splitk_reduce(Args a, const float* __r
 }
 
 // ------------------------------------------------------------------------------------------------
-// Streaming kernel for M <= 64 (decode-like shapes): the product is bound by reading B once from
-// HBM.  A workgroup owns a strip of 16*NB columns of C and all MG groups of 16 rows of A; its WAVES
+// Streaming kernel for M <= 64 (decode-like shapes; bf16, fp16 and e4m3): the product is bound by reading
+// B once from HBM.  A workgroup owns a strip of 16*NB columns of C and all MG groups of 16 rows of A; its WAVES
 // waves split K, partial sums meet in LDS at the end.  Needs: A row-major, B column-major, 16-byte
-// aligned, K a multiple of 8.
+// aligned, K a multiple of 16 bytes.  (Sizes below are those of the 2-byte types; for e4m3 a tile row holds
+// the same bytes and twice the elements, and a 64-byte k-step is two v_mfma_f32_16x16x32_fp8_fp8.)
 //
 // The operands of v_mfma_f32_16x16x32 want, per instruction, 16 rows x 64 bytes of K; fetched that
 // way every wave instruction opens 16 separate 64-byte streams a leading dimension apart, and HBM
@@ -898,20 +899,31 @@ __global__ __launch_bounds__(256) void k4_splitk_reduce(Args a, const float* __r
 template <typename IN>
 __device__ __forceinline__ void mfma16(const u32x4_t& a, const u32x4_t& b, f32x4_t& c)
 {
-    if constexpr (IN::ID == GEMM_BF16)
+    if constexpr (IN::ID == GEMM_BF16) {
         c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
-    else
+    } else if constexpr (IN::ID == GEMM_F16) {
         c = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+    } else {
+        // e4m3: the chunk's low and high 8 bytes are one K = 32 instruction each (which k a lane's bytes
+        // stand for is irrelevant as long as both operands agree)
+        const long alo = (long)(((uint64_t)a.y << 32) | a.x), ahi = (long)(((uint64_t)a.w << 32) | a.z);
+        const long blo = (long)(((uint64_t)b.y << 32) | b.x), bhi = (long)(((uint64_t)b.w << 32) | b.z);
+        c = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(alo, blo, c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(ahi, bhi, c, 0, 0, 0);
+    }
 }
 
 template <typename IN, int WAVES_, int NB_, int TK_, int ROT_ = 0, int MG_ = 1>
 struct StreamCfg {
     using In = IN;
     static constexpr int WAVES = WAVES_, NB = NB_, TK = TK_, COLS = 16 * NB_, ROT = ROT_, MG = MG_, ROWS = 16 * MG_;
+    // TK counts 2-byte units: a tile row is TK * 2 bytes of K for every input type (TK elements of a 2-byte
+    // type, 2 TK of e4m3)
+    static constexpr int TKE = TK * 2 / IN::BYTES;         // K elements per tile
     static constexpr int LPC = TK / 8;                     // lanes (16-byte chunks) per row per tile
     static constexpr int CPL = 64 / LPC;                   // rows covered by one load instruction
     static constexpr int GLD = 16 / CPL;                   // loads per group of 16 rows per lane
-    static constexpr int KS = TK / 32;                     // MFMA k-steps per tile
+    static constexpr int KS = TK / 32;                     // 64-byte k-steps per tile (one MFMA of a 2-byte type, two of e4m3)
     static constexpr int GROUP_BYTES = 16 * TK * 2;
     static constexpr int TILE_BYTES = (MG + 1) * GROUP_BYTES;   // the groups of A and one group of B columns
     static constexpr int LDS_BYTES = WAVES * TILE_BYTES;
@@ -927,14 +939,15 @@ __global__ __launch_bounds__(CFG::WAVES * 64) void k4_stream(Args a)
     constexpr int WAVES = CFG::WAVES, NB = CFG::NB, TK = CFG::TK, COLS = CFG::COLS, MG = CFG::MG, ROWS = CFG::ROWS;
     constexpr int LPC = CFG::LPC, CPL = CFG::CPL, GLD = CFG::GLD, KS = CFG::KS;
     constexpr int ROWB = TK * 2;                            // bytes per LDS row
+    constexpr int EB = IN::BYTES, V = 16 / EB, TKE = CFG::TKE;   // element size, elements per chunk and per tile
     __shared__ __attribute__((aligned(16))) char lds[CFG::LDS_BYTES];
     const int t = threadIdx.x, lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int l16 = lane & 15, lq = lane >> 4;
     const int64_t b = blockIdx.y;
     const int64_t j0 = (int64_t)blockIdx.x * COLS;
-    const uint16_t* A = (const uint16_t*)a.A + b * a.stride_a;
-    const uint16_t* B = (const uint16_t*)a.B + b * a.stride_b;
+    const char* A = (const char*)a.A + b * a.stride_a * EB;
+    const char* B = (const char*)a.B + b * a.stride_b * EB;
     char* tile_a = lds + wave * CFG::TILE_BYTES;
     char* tile_b = tile_a + MG * CFG::GROUP_BYTES;
 
@@ -942,14 +955,14 @@ __global__ __launch_bounds__(CFG::WAVES * 64) void k4_stream(Args a)
     // workgroup advance side by side, so that together they read WAVES*TK*2 contiguous bytes of every
     // column at a time, which keeps HBM pages open longer than WAVES far-apart runs would.
     const int64_t kend = a.K;
-    constexpr int64_t KSTRIDE = (int64_t)WAVES * TK;
+    constexpr int64_t KSTRIDE = (int64_t)WAVES * TKE;
 
     // load side: lane fetches chunk lc of row (n*CPL + lrow) of a group.  Rows of A past M and columns
     // past N are clamped (their sums are never stored).  Offsets are 32-bit from wave-uniform bases
     // (the host has checked that a strip's extent, COLS * ldb elements, fits).
     const int lrow = lane / LPC, lc = lane % LPC;
-    const char* Bs = (const char*)(B + j0 * a.b_sj);
-    const char* As = (const char*)A;
+    const char* Bs = B + j0 * a.b_sj * EB;
+    const char* As = A;
     uint32_t ao[MG][GLD], bo[NB][GLD];
     int wr[GLD];
 #pragma unroll
@@ -959,12 +972,12 @@ __global__ __launch_bounds__(CFG::WAVES * 64) void k4_stream(Args a)
 #pragma unroll
         for (int m = 0; m < MG; ++m) {
             const int64_t rr = m * 16 + c < a.M ? m * 16 + c : a.M - 1;
-            ao[m][n] = (uint32_t)((rr * a.a_si + lc * 8) * 2);
+            ao[m][n] = (uint32_t)((rr * a.a_si + lc * V) * EB);
         }
 #pragma unroll
         for (int g = 0; g < NB; ++g) {
             const int64_t cc = j0 + g * 16 + c < a.N ? g * 16 + c : a.N - 1 - j0;
-            bo[g][n] = (uint32_t)((cc * a.b_sj + lc * 8) * 2);
+            bo[g][n] = (uint32_t)((cc * a.b_sj + lc * V) * EB);
         }
     }
     // operand side: lane (l16, lq) holds, for k-step s, chunk 4s+lq of row l16 of the group
@@ -985,13 +998,13 @@ __global__ __launch_bounds__(CFG::WAVES * 64) void k4_stream(Args a)
         for (int m = 0; m < MG; ++m)
 #pragma unroll
             for (int n = 0; n < GLD; ++n)
-                ra[m][n] = (FULL || k + lc * 8 < kend) ? *(const u32x4_t*)(As + k * 2 + ao[m][n]) : zero;
+                ra[m][n] = (FULL || k + lc * V < kend) ? *(const u32x4_t*)(As + k * EB + ao[m][n]) : zero;
     };
     auto fetch_b = [&](auto full, int g, int64_t k) __attribute__((always_inline)) {
         constexpr bool FULL = decltype(full)::value;
 #pragma unroll
         for (int n = 0; n < GLD; ++n)
-            rb[g][n] = (FULL || k + lc * 8 < kend) ? __builtin_nontemporal_load((const u32x4_t*)(Bs + k * 2 + bo[g][n])) : zero;
+            rb[g][n] = (FULL || k + lc * V < kend) ? __builtin_nontemporal_load((const u32x4_t*)(Bs + k * EB + bo[g][n])) : zero;
     };
     auto park_a = [&]() __attribute__((always_inline)) {
 #pragma unroll
@@ -1020,16 +1033,16 @@ __global__ __launch_bounds__(CFG::WAVES * 64) void k4_stream(Args a)
 
     // The steady-state loop runs over whole tiles only and is free of branches; a ragged last tile
     // is fetched under masks after it.
-    const int64_t tiles = (a.K + TK - 1) / TK;                 // all K tiles, the last one possibly ragged
-    const int64_t whole = a.K / TK;                            // tiles without a mask
+    const int64_t tiles = (a.K + TKE - 1) / TKE;               // all K tiles, the last one possibly ragged
+    const int64_t whole = a.K / TKE;                           // tiles without a mask
     const int64_t mine = tiles > wave ? (tiles - wave + WAVES - 1) / WAVES : 0;
     const int64_t nfull = whole > wave ? (whole - wave + WAVES - 1) / WAVES : 0;
     const bool ragged = mine > nfull;                          // this wave owns the ragged tile
     // The whole tiles are walked from a start that differs from one workgroup to the next and wraps
     // round (sums commute): at any moment the workgroups then read different offsets inside their
     // columns instead of all the same one, a leading dimension apart.
-    const int64_t kwrap = ((int64_t)wave + WAVES * nfull) * TK; // this wave's first tile past the whole ones
-    int64_t k = (int64_t)wave * TK;
+    const int64_t kwrap = ((int64_t)wave + WAVES * nfull) * TKE; // this wave's first tile past the whole ones
+    int64_t k = (int64_t)wave * TKE;
     if (CFG::ROT && nfull > 0) k += ((int64_t)blockIdx.x * CFG::ROT % nfull) * KSTRIDE;
     if (nfull > 0) {
         fetch_a(yes{}, k);

@@ -275,6 +275,7 @@ hipError_t launch_k4(int path, const Args& a)
     if (kind == MFMA_SKINNY) {
         if (a.in_dtype == GEMM_BF16) return launch_stream<BF16>(a);
         if (a.in_dtype == GEMM_F16) return launch_stream<F16>(a);
+        if (a.in_dtype == GEMM_FP8_E4M3) return launch_stream<E4M3>(a);
         return hipErrorInvalidValue;
     }
     if (kind == MFMA_VEC16) {
@@ -323,7 +324,7 @@ Geometry geometry_k4(int path, const Args& a)
     if (kind == MFMA_SKINNY) {
         auto of = [&](auto cfg) {
             using C = decltype(cfg);
-            return Geometry{C::ROWS, C::COLS, C::TK, C::WAVES * 64, 2, C::LDS_BYTES, ((a.N + C::COLS - 1) / C::COLS) * a.batch};
+            return Geometry{C::ROWS, C::COLS, C::TK * 2 / es, C::WAVES * 64, 2, C::LDS_BYTES, ((a.N + C::COLS - 1) / C::COLS) * a.batch};
         };
         switch (stream_form(a)) {
         case STREAM_16: return of(StreamK4<BF16>{});

@@ -206,6 +206,8 @@ CONFIGS: Dict[str, Config] = {
     "D32": Config("D32", 32, 16384, 16384, BF16, BF16, ROW_MAJOR, COL_MAJOR, "normal", std=0.02),
     "D64": Config("D64", 64, 16384, 16384, BF16, BF16, ROW_MAJOR, COL_MAJOR, "normal", std=0.02),
     "D128": Config("D128", 128, 16384, 16384, BF16, BF16, ROW_MAJOR, COL_MAJOR, "normal", std=0.02),
+    # C4's shape with e4m3 operands and C5's value recipe and scales: the streaming kernel on one-byte elements
+    "D16_e4m3": Config("D16_e4m3", 16, 16384, 16384, E4M3, BF16, ROW_MAJOR, COL_MAJOR, "normal", scaled=True),
     # reduced-size counterparts: same dtype / layout / distribution / raggedness
     "C2_small": Config("C2_small", 512, 768, 640, BF16, BF16, ROW_MAJOR, COL_MAJOR, "normal", rsqrt_k=True),
     "C3_small": Config("C3_small", 387, 301, 259, F16, F16, ROW_MAJOR, ROW_MAJOR, "uniform"),

@@ -72,7 +72,7 @@ def test_fast_kernel_steady_state_loop(asm, dtype, mfma, per_slab):
 
 
 def test_stream_kernel_register_budget(asm):
-    for dtype in ("4BF16", "3F16"):
+    for dtype in ("4BF16", "3F16", "4E4M3"):
         for waves in (1, 4):
             meta = metadata(asm, "_ZN2gl9k4_streamINS_9StreamCfgINS_%sELi%dELi1ELi256ELi19ELi1EEE" % (dtype, waves))
             assert meta["vgpr_spill"] == 0 and meta["scratch"] == 0

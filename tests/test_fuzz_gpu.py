@@ -67,20 +67,20 @@ def test_random_case(i):
 
 def draw_rows_case(rng, i):
     """17..64 rows on the streaming kernel: few wide strips per problem, enough problems to pass its rule."""
-    dtype = int(rng.choice([gen.BF16, gen.F16]))
+    dtype = int(rng.choice([gen.BF16, gen.F16, gen.E4M3]))
     M = int(rng.integers(17, 65))
     cols = 32 if M <= 32 else 64
     strips = int(rng.integers(1, 7))
     batch = -(-128 // strips) + int(rng.integers(0, 4))
     N = cols * (strips - 1) + int(rng.integers(1, cols + 1))
-    K = 8 * int(rng.integers(1, 200))
-    pad = lambda n: n + 8 * int(rng.integers(0, 4))
-    out = int(rng.choice([dtype, gen.F32]))
+    K = 16 * int(rng.integers(1, 100))
+    pad = lambda n: n + 16 * int(rng.integers(0, 4))
+    out = int(rng.choice([gen.BF16 if dtype == gen.E4M3 else dtype, gen.F32]))
     return gen.Config(f"rows{i}", M, N, K, dtype, out, ROW, COL, str(rng.choice(["uniform", "normal"])), batch=batch,
                       scaled=bool(rng.random() < 0.3), biased=bool(rng.random() < 0.3), lda=pad(K), ldb=pad(K), ldc=N + int(rng.integers(0, 5)))
 
 
-ROWS_CASES = [draw_rows_case(np.random.default_rng(2000 + i), i) for i in range(16)]
+ROWS_CASES = [draw_rows_case(np.random.default_rng(2000 + i), i) for i in range(24)]
 
 
 @pytest.mark.parametrize("i", range(len(ROWS_CASES)))

@@ -108,12 +108,15 @@ def test_degenerate_shapes(M, N, K, dtype):
 
 def test_skinny_path_edges():
     """The small-M streaming path: M below 16, N not a multiple of its column block, K a multiple of
-    8 only, fp16 as well as bf16, fp32 output."""
-    for dtype in (gen.BF16, gen.F16):
-        for (M, N, K) in [(16, 512, 1024), (7, 100, 136), (1, 33, 8), (16, 2049, 4104)]:
-            cfg = gen.Config("skinny", M, N, K, dtype, dtype, ROW, COL, "normal", std=0.02)
+    16 bytes only, all three types, fp32 output."""
+    for dtype in (gen.BF16, gen.F16, gen.E4M3):
+        out = gen.BF16 if dtype == gen.E4M3 else dtype
+        cases = [(16, 512, 1024), (7, 100, 144), (1, 33, 16), (16, 2049, 4112)] if dtype == gen.E4M3 else \
+                [(16, 512, 1024), (7, 100, 136), (1, 33, 8), (16, 2049, 4104)]
+        for (M, N, K) in cases:
+            cfg = gen.Config("skinny", M, N, K, dtype, out, ROW, COL, "normal", std=0.02 if dtype != gen.E4M3 else 1.0)
             inp = gen.make_inputs(cfg, 4)
-            d = gemm.make_desc(M, N, K, dtype, dtype, ROW, COL)
+            d = gemm.make_desc(M, N, K, dtype, out, ROW, COL)
             assert gemm.gemm_query(4, d).path.startswith("mfma16-stream")
             check(4, inp)
             check(4, inp, out_dtype=gen.F32)
@@ -124,7 +127,7 @@ def test_skinny_path_edges():
     check(4, inp)
 
 
-@pytest.mark.parametrize("dtype", [gen.BF16, gen.F16])
+@pytest.mark.parametrize("dtype", [gen.BF16, gen.F16, gen.E4M3])
 def test_streaming_path_with_17_to_64_rows(dtype):
     """Two to four groups of 16 rows of A per workgroup: every group boundary, a ragged last group, a
     ragged last strip of columns, a ragged last K tile for every wave, batches, padded leading dimensions,
@@ -133,9 +136,13 @@ def test_streaming_path_with_17_to_64_rows(dtype):
              (48, 8192, 128, dict(biased=True)), (49, 8256, 392, {}), (64, 8192, 2048, {}),
              (20, 130, 1320, dict(batch=32, lda=1328, ldb=1336, ldc=136)), (64, 70, 776, dict(batch=70, scaled=True))]
     for (M, N, K, kw) in cases:
-        cfg = gen.Config("rows", M, N, K, dtype, dtype, ROW, COL, "normal", std=0.02, **kw)
+        out = gen.BF16 if dtype == gen.E4M3 else dtype
+        if dtype == gen.E4M3:
+            K = (K + 15) // 16 * 16
+            kw = {k_: (v_ + 15) // 16 * 16 if k_ in ("lda", "ldb") else v_ for k_, v_ in kw.items()}
+        cfg = gen.Config("rows", M, N, K, dtype, out, ROW, COL, "normal", std=0.02 if dtype != gen.E4M3 else 1.0, **kw)
         inp = gen.make_inputs(cfg, 6)
-        d = gemm.make_desc(M, N, K, dtype, dtype, ROW, COL, lda=inp.lda, ldb=inp.ldb, ldc=inp.ldc, batch=cfg.batch,
+        d = gemm.make_desc(M, N, K, dtype, out, ROW, COL, lda=inp.lda, ldb=inp.ldb, ldc=inp.ldc, batch=cfg.batch,
                            stride_a=inp.stride_a, stride_b=inp.stride_b, stride_c=inp.stride_c)
         q = gemm.gemm_query(4, d)
         assert q.path == "mfma16-stream(small-M)" and q.bm == 16 * ((M + 15) // 16) and q.bn == (32 if M <= 32 else 64), (M, N, K, q)
@@ -144,7 +151,7 @@ def test_streaming_path_with_17_to_64_rows(dtype):
         check(4, inp, ref, out_dtype=gen.F32)
     # too few strips for the chip: the tiled kernel keeps the product
     for (M, N) in ((17, 4064), (64, 8128), (33, 4096)):
-        assert gemm.gemm_query(4, gemm.make_desc(M, N, 1024, dtype, dtype, ROW, COL)).path.startswith("mfma32-direct-to-lds")
+        assert gemm.gemm_query(4, gemm.make_desc(M, N, 1024, dtype, out, ROW, COL)).path.startswith("mfma32-direct-to-lds")
 
 
 def test_batched_strides_scales_and_padding_untouched():

@@ -65,7 +65,7 @@ def test_expert_state_paths_and_scratch(p):
     kvec, kslab = 16 // es, 128 // es
     cols = 16 if p["M"] <= 16 else 32 if p["M"] <= 32 else 64
     streams = p["M"] <= 16 or (p["M"] <= 64 and math.ceil(p["N"] / cols) * p["batch"] >= 128)
-    if fast_ok and streams and p["K"] % kvec == 0 and es == 2:
+    if fast_ok and streams and p["K"] % kvec == 0:
         assert q.path == "mfma16-stream(small-M)" and q.workspace_bytes == 0
         assert q.bn == cols and q.bm == 16 * math.ceil(max(p["M"], 1) / 16) and q.grid == math.ceil(p["N"] / cols) * p["batch"]
     elif fast_ok and p["K"] % kslab == 0:
