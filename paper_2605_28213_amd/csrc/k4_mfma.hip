@@ -134,30 +134,28 @@ static hipError_t launch_fast_any(const Args& a)
 // A thin remainder of rows (1..16 past the last whole 256-row tile) would cost a whole extra row of
 // workgroup tiles, on a large square-ish problem a second round of the machine for a few rows.  It
 // is split off and handed to the streaming kernel, which reads B once more but finishes in the time
-// of that read.  Applies to 2-byte types (the streaming kernel's) on operands the fast kernel accepts.
+// of that read.  Applies to operands the fast kernel accepts (they satisfy the streaming kernel's conditions).
 bool k4_splits_m_tail(const Args& a)
 {
     const int64_t rem = a.M % 256;
-    return a.in_dtype != GEMM_FP8_E4M3 && a.M > 256 && rem >= 1 && rem <= 16;
+    return a.M > 256 && rem >= 1 && rem <= 16;
 }
 
 template <typename IN>
 static hipError_t launch_fast_split(const Args& a)
 {
-    if constexpr (IN::BYTES == 2) {
-        if (k4_splits_m_tail(a)) {
-            const int64_t rem = a.M % 256, top_rows = a.M - rem;
-            const int eo = a.out_dtype == GEMM_F32 ? 4 : 2;
-            Args top = a;
-            top.M = top_rows;
-            hipError_t e = launch_fast_any<IN>(top);
-            if (e != hipSuccess) return e;
-            Args bot = a;
-            bot.M = rem;
-            bot.A = (const char*)a.A + top_rows * a.a_si * IN::BYTES;
-            bot.C = (char*)a.C + top_rows * a.ldc * eo;
-            return launch_stream<IN>(bot);
-        }
+    if (k4_splits_m_tail(a)) {
+        const int64_t rem = a.M % 256, top_rows = a.M - rem;
+        const int eo = a.out_dtype == GEMM_F32 ? 4 : 2;
+        Args top = a;
+        top.M = top_rows;
+        hipError_t e = launch_fast_any<IN>(top);
+        if (e != hipSuccess) return e;
+        Args bot = a;
+        bot.M = rem;
+        bot.A = (const char*)a.A + top_rows * a.a_si * IN::BYTES;
+        bot.C = (char*)a.C + top_rows * a.ldc * eo;
+        return launch_stream<IN>(bot);
     }
     return launch_fast_any<IN>(a);
 }

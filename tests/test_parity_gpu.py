@@ -305,7 +305,7 @@ def test_lent_workspace_too_small_or_misaligned_is_refused():
 @pytest.mark.parametrize("dtype", [gen.BF16, gen.F16, gen.E4M3])
 @pytest.mark.parametrize("M", [256 + 3, 512 + 16, 256 + 17])
 def test_thin_row_remainder_goes_to_the_streaming_kernel(dtype, M):
-    """M a few rows past a whole number of 256-row tiles: the remainder (1..16 rows, 2-byte types) is
+    """M a few rows past a whole number of 256-row tiles: the remainder (1..16 rows) is
     multiplied by the streaming kernel instead of a whole extra row of tiles; both parts must agree
     with the oracle, in the aligned fast path and in the packed path."""
     N, K = 300, 256
@@ -314,7 +314,7 @@ def test_thin_row_remainder_goes_to_the_streaming_kernel(dtype, M):
     inp = gen.make_inputs(cfg, 6)
     ref = oracle_for(inp)
     d = gemm.make_desc(M, N, K, dtype, out, ROW, COL, batch=2)
-    split = dtype != gen.E4M3 and 1 <= M % 256 <= 16
+    split = 1 <= M % 256 <= 16
     assert gemm.gemm_query(4, d).path == ("mfma32-direct-to-lds+stream(M-tail)" if split else "mfma32-direct-to-lds")
     check(4, inp, ref)
     ragged = gen.Config("mtail_packed", M, N, K - 5, dtype, out, ROW, ROW, "normal", rsqrt_k=True)

@@ -72,7 +72,7 @@ def test_expert_state_paths_and_scratch(p):
         assert q.path.startswith("mfma32-direct-to-lds") and q.violated == 0
         # split-K: offered (through workspace_bytes) when the product has few tiles and a long K, taken when scratch is lent
         nslab, tiles = p["K"] // kslab, math.ceil(p["M"] / 128) * math.ceil(p["N"] / 128)
-        tail = es == 2 and p["M"] > 256 and 1 <= p["M"] % 256 <= 16
+        tail = p["M"] > 256 and 1 <= p["M"] % 256 <= 16
         splits = 1
         if p["batch"] == 1 and p["M"] > 16 and not tail and tiles < 256:
             for s_ in range(2, 9):
