@@ -131,14 +131,19 @@ static hipError_t launch_fast_any(const Args& a)
     return launch_fast<FastK4<IN>>(a);
 }
 
-// A thin remainder of rows (1..16 past the last whole 256-row tile) would cost a whole extra row of
-// workgroup tiles, on a large square-ish problem a second round of the machine for a few rows.  It
-// is split off and handed to the streaming kernel, which reads B once more but finishes in the time
-// of that read.  Applies to operands the fast kernel accepts (they satisfy the streaming kernel's conditions).
+// A thin remainder of rows (1..64 past the last whole 256-row tile) costs a whole extra row of workgroup
+// tiles.  When that row makes the product need one more round of the chip (fp16 4099 x 4093 x 4097: 17 x 16
+// tiles, a second round for 3 rows) the remainder is split off and handed to the streaming kernel, which
+// reads B once more but finishes in the time of that read; when the extra tiles fit into a round that
+// runs anyway, they cost nothing and stay.  Applies to products on 256-tiles whose operands the fast kernel
+// accepts (they satisfy the streaming kernel's conditions), up to 16384 columns (beyond, reading B again
+// costs about what the extra round does).
 bool k4_splits_m_tail(const Args& a)
 {
     const int64_t rem = a.M % 256;
-    return a.M > 256 && rem >= 1 && rem <= 16;
+    if (a.M <= 256 || rem < 1 || rem > 64 || a.N > 16384 || a.flags != 0 || k4_small_tiles(a)) return false;
+    const int64_t per_row = ((a.N + 255) / 256) * a.batch, rows = a.M / 256;
+    return (rows * per_row + 255) / 256 < ((rows + 1) * per_row + 255) / 256;
 }
 
 template <typename IN>

@@ -303,22 +303,32 @@ def test_lent_workspace_too_small_or_misaligned_is_refused():
 
 
 @pytest.mark.parametrize("dtype", [gen.BF16, gen.F16, gen.E4M3])
-@pytest.mark.parametrize("M", [256 + 3, 512 + 16, 256 + 17])
-def test_thin_row_remainder_goes_to_the_streaming_kernel(dtype, M):
-    """M a few rows past a whole number of 256-row tiles: the remainder (1..16 rows) is
-    multiplied by the streaming kernel instead of a whole extra row of tiles; both parts must agree
-    with the oracle, in the aligned fast path and in the packed path."""
-    N, K = 300, 256
+@pytest.mark.parametrize("rem", [3, 16, 17, 48, 64, 65])
+def test_thin_row_remainder_goes_to_the_streaming_kernel(dtype, rem):
+    """M a few rows past 16 whole rows of 256-tiles, 16 tile columns: the seventeenth row of tiles would be
+    a second round of the chip, so a remainder of up to 64 rows is multiplied by the streaming kernel
+    instead (all of its row-group forms); both parts must agree with the oracle, in the aligned fast path
+    and in the packed path.  A remainder whose tiles fit the round that runs anyway stays with the tiles."""
+    M, N, K = 4096 + rem, 4096, 256
     out = gen.BF16 if dtype == gen.E4M3 else dtype
-    cfg = gen.Config("mtail", M, N, K, dtype, out, ROW, COL, "normal", rsqrt_k=True, batch=2)
+    cfg = gen.Config("mtail", M, N, K, dtype, out, ROW, COL, "normal", rsqrt_k=True)
     inp = gen.make_inputs(cfg, 6)
     ref = oracle_for(inp)
-    d = gemm.make_desc(M, N, K, dtype, out, ROW, COL, batch=2)
-    split = 1 <= M % 256 <= 16
-    assert gemm.gemm_query(4, d).path == ("mfma32-direct-to-lds+stream(M-tail)" if split else "mfma32-direct-to-lds")
+    d = gemm.make_desc(M, N, K, dtype, out, ROW, COL)
+    assert gemm.gemm_query(4, d).path == ("mfma32-direct-to-lds+stream(M-tail)" if rem <= 64 else "mfma32-direct-to-lds")
     check(4, inp, ref)
-    ragged = gen.Config("mtail_packed", M, N, K - 5, dtype, out, ROW, ROW, "normal", rsqrt_k=True)
-    check(4, gen.make_inputs(ragged, 7), lend_workspace=True)
+    if rem in (3, 48):
+        ragged = gen.Config("mtail_packed", M, N, K - 5, dtype, out, ROW, ROW, "normal", rsqrt_k=True, biased=True)
+        rinp = gen.make_inputs(ragged, 7)
+        need = gemm.gemm_query(4, gemm.make_desc(M, N, K - 5, dtype, out, ROW, ROW)).workspace_bytes
+        lent = gemm.make_desc(M, N, K - 5, dtype, out, ROW, ROW, workspace=256, workspace_bytes=need)
+        assert gemm.gemm_query(4, lent).path == "mfma32-packed+direct-to-lds+stream(M-tail)"
+        check(4, rinp, lend_workspace=True)
+    # 2 x 2 tiles per problem: one round with or without the remainder
+    small = gemm.make_desc(256 + rem, 300, K, dtype, out, ROW, COL, batch=2)
+    assert "M-tail" not in gemm.gemm_query(4, small).path
+    scfg = gen.Config("mtail_small", 256 + rem, 300, K, dtype, out, ROW, COL, "normal", rsqrt_k=True, batch=2)
+    check(4, gen.make_inputs(scfg, 8))
 
 
 @pytest.mark.parametrize("flags", [gemm.GEMM_FLAG_DEOPT_NO_SWIZZLE, gemm.GEMM_FLAG_DEOPT_NO_OVERLAP,

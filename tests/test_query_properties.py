@@ -72,7 +72,14 @@ def test_expert_state_paths_and_scratch(p):
         assert q.path.startswith("mfma32-direct-to-lds") and q.violated == 0
         # split-K: offered (through workspace_bytes) when the product has few tiles and a long K, taken when scratch is lent
         nslab, tiles = p["K"] // kslab, math.ceil(p["M"] / 128) * math.ceil(p["N"] / 128)
-        tail = p["M"] > 256 and 1 <= p["M"] % 256 <= 16
+        # a thin row remainder goes to the streaming kernel when that saves a round of 256 tiles of 256 x 256
+        t256 = math.ceil(p["M"] / 256) * math.ceil(p["N"] / 256) * p["batch"]
+        t128 = math.ceil(p["M"] / 128) * math.ceil(p["N"] / 128) * p["batch"]
+        small = math.ceil(t128 / 512) * (8 if es == 1 else 7) < math.ceil(t256 / 256) * 10
+        per_row, rows = math.ceil(p["N"] / 256) * p["batch"], p["M"] // 256
+        tail = (p["M"] > 256 and 1 <= p["M"] % 256 <= 64 and p["N"] <= 16384 and not small
+                and math.ceil(rows * per_row / 256) < math.ceil((rows + 1) * per_row / 256))
+        assert ("M-tail" in q.path) == tail
         splits = 1
         if p["batch"] == 1 and p["M"] > 16 and not tail and tiles < 256:
             for s_ in range(2, 9):
