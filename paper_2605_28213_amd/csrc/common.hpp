@@ -118,7 +118,8 @@ size_t k4_packed_workspace_bytes(const Args& a);
 // is cut into (1: not applicable), and the fp32 scratch the partial products need.
 int k4_splitk_factor(const Args& a);
 size_t k4_splitk_workspace_bytes(const Args& a, int splits);
-// True when the fast kernel's launcher hands a thin remainder of rows (M % 256 in 1..16) to the streaming kernel.
+// True when the fast kernel's launcher hands a thin remainder of rows (M % 256 in 1..64, where that saves a
+// round of the chip) to the streaming kernel.
 bool k4_splits_m_tail(const Args& a);
 bool k4_streams_rows(const Args& a);      // a product of at most 64 rows goes to the streaming kernel
 // True when the fast kernel runs with 128 x 128 workgroup tiles instead of 256 x 256.

@@ -338,9 +338,12 @@ Geometry geometry_k4(int path, const Args& a)
         }
     }
     if (kind == MFMA_VEC16 || kind == MFMA_PACKED || kind == MFMA_SPLITK) {
-        const bool small = k4_small_tiles(a);
+        // (with a row remainder split off, the grid of the tiled part: the remainder is a second launch)
+        Args top = a;
+        if (kind != MFMA_SPLITK && k4_splits_m_tail(a)) top.M = a.M - a.M % 256;
+        const bool small = k4_small_tiles(top);
         const int bt = small ? FastK4Small<BF16>::BM : FastK4<BF16>::BM;
-        const int64_t g = ((a.M + bt - 1) / bt) * ((a.N + bt - 1) / bt) * a.batch * (kind == MFMA_SPLITK ? k4_splitk_factor(a) : 1);
+        const int64_t g = ((top.M + bt - 1) / bt) * ((a.N + bt - 1) / bt) * a.batch * (kind == MFMA_SPLITK ? k4_splitk_factor(a) : 1);
         // stages: slabs in flight beyond the one in use
         return Geometry{bt, bt, ROW_BYTES / es, 256, 2, small ? FastK4Small<BF16>::LDS_BYTES : FastK4<BF16>::LDS_BYTES, g};
     }
