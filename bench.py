@@ -271,9 +271,14 @@ def main():
                 if rc != gemm.GEMM_OK:
                     raise RuntimeError(f"conv2d_run: {gemm.gemm_status_string(rc)}")
             ss = stats(event_times(launch, 100, 25))
+            tf = cc.flops / (ss["mean_us"] * 1e-6) / 1e12
             layer[conv.conv2d_variant_name(v)] = {
                 "path": conv.conv2d_query(v, dd, xs[0], wd, yd).path, "launch_us": ss,
-                "TFLOP/s": cc.flops / (ss["mean_us"] * 1e-6) / 1e12, "GB/s": cc.algorithmic_bytes / (ss["mean_us"] * 1e-6) / 1e9}
+                "TFLOP/s": tf, "GB/s": cc.algorithmic_bytes / (ss["mean_us"] * 1e-6) / 1e9,
+                # 378 flop per algorithmic byte: above the ridge, so the matrix peak is the bound; one round of 196
+                # workgroups of 9 K slabs each is latency, not throughput
+                "roofline": {"bound": "mfma", "achieved": tf, "peak": PEAK["mfma_bf16"], "unit": "TFLOP/s",
+                             "frac": tf / PEAK["mfma_bf16"], "traffic": None}}
             del ws
         layer["workload"] = "fp16 N=8 H=W=56 C=64 F=128 3x3 stride 1 pad 1, NHWC, 3.70 GFLOP, 9.78 MB"
         layer["paper_context"] = {"source": "KLineage CUDA / cuDNN, H100 PCIe and RTX PRO 6000, App. A",
@@ -299,8 +304,11 @@ def main():
                 if rc != gemm.GEMM_OK:
                     raise RuntimeError(f"topk_run: {gemm.gemm_status_string(rc)}")
             ss = stats(event_times(launch_topk, 100, 25))
-            sel[topk.topk_variant_name(v)] = {"path": topk.topk_query(v, td, txs[0]).path, "launch_us": ss,
-                                              "GB/s": tc.algorithmic_bytes / (ss["mean_us"] * 1e-6) / 1e9}
+            gbs = tc.algorithmic_bytes / (ss["mean_us"] * 1e-6) / 1e9
+            # 1.3 MB in one round of 64 workgroups: far below any bandwidth bound, a chain of passes over a row
+            sel[topk.topk_variant_name(v)] = {"path": topk.topk_query(v, td, txs[0]).path, "launch_us": ss, "GB/s": gbs,
+                                              "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK["hbm_GBs"], "unit": "GB/s",
+                                                           "frac": gbs / PEAK["hbm_GBs"], "traffic": None}}
         sel["workload"] = "fp32 batch 64 x 4096, k = 512, indices + values out, 1.31 MB"
         sel["paper_context"] = {"source": "KLineage CUDA / FlashInfer, H100 PCIe and RTX PRO 6000, App. A",
                                 "latency_ms": {"H100 KLineage": 0.0143, "H100 FlashInfer": 0.0160, "RTX PRO 6000 KLineage": 0.0131,
