@@ -95,3 +95,80 @@ def test_random_case_with_17_to_64_rows(i):
     assert rc == gemm.GEMM_OK, (cfg, gemm.gemm_status_string(rc), gemm.gemm_last_launch_error())
     err = util.norm_err(C[:, :, : cfg.N], C_ref, D)
     assert err <= util.TOL[cfg.in_dtype], (cfg, err)
+
+
+def draw_conv_case(rng, i):
+    """A random layer inside the documented limits: image and filter sizes, strides and paddings drawn
+    independently per axis, channel counts that are whole 128-byte slabs (every state) or not (C0, C1)."""
+    dtype = int(rng.choice([gen.F16, gen.BF16, gen.E4M3]))
+    es = gen.ELEM_BYTES[dtype]
+    slab = 128 // es
+    C = int(rng.choice([slab, 2 * slab, slab, int(rng.integers(1, 40))]))
+    R, S = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+    pad = (int(rng.integers(0, R)), int(rng.integers(0, S)))
+    stride = (int(rng.integers(1, 4)), int(rng.integers(1, 4)))
+    H = int(rng.integers(max(1, R - 2 * pad[0]), 24)) + 1
+    W = int(rng.integers(max(1, S - 2 * pad[1]), 24)) + 1
+    out = int(rng.choice([gen.BF16 if dtype == gen.E4M3 else dtype, gen.F32]))
+    return gen.ConvConfig(f"convfuzz{i}", int(rng.integers(1, 4)), H, W, C, int(rng.integers(1, 200)), R, S, dtype, out,
+                          stride=stride, pad=pad, biased=bool(rng.random() < 0.4))
+
+
+CONV_CASES = [draw_conv_case(np.random.default_rng(3000 + i), i) for i in range(24)]
+
+
+@pytest.mark.parametrize("i", range(len(CONV_CASES)))
+def test_random_convolution_layer(i):
+    from paper_2605_28213_amd import conv
+    from tests.test_conv_gpu import reference, run_state
+    cfg = CONV_CASES[i]
+    inp = gen.make_conv_inputs(cfg, 300 + i)
+    y_ref, D = reference(inp)
+    whole = (cfg.C * gen.ELEM_BYTES[cfg.in_dtype]) % 128 == 0
+    for variant in range(3):
+        rc, y, q, _ = run_state(variant, inp)
+        if variant == 2 and not whole:
+            assert rc == gemm.GEMM_ERR_PRECONDITION, (cfg, q)
+            continue
+        assert rc == gemm.GEMM_OK, (cfg, variant, gemm.gemm_status_string(rc), conv.conv2d_last_launch_error(), q)
+        err = util.norm_err(y, y_ref, D)
+        assert err <= util.TOL[cfg.in_dtype], (cfg, variant, q.path, err)
+
+
+def draw_topk_case(rng, i):
+    """Row length, k, leading dimension and value distribution at random: normal, heavily tied (multiples of
+    1/4), or a handful of distinct values; k from 0 to n."""
+    n = int(rng.choice([int(rng.integers(1, 300)), int(rng.integers(300, 5000)), int(rng.integers(5000, 17000))]))
+    k = int(rng.choice([0, 1, n, int(rng.integers(0, n + 1)), max(1, n // 8)]))
+    batch = int(rng.integers(1, 6))
+    # mostly a multiple of 4 (the resident state loads 16 bytes per lane and refuses other rows), sometimes not
+    ld = (n + 3) // 4 * 4 + 4 * int(rng.choice([0, 0, 1])) if rng.random() < 0.7 else n + int(rng.choice([0, 7]))
+    kind = str(rng.choice(["normal", "quarters", "few"]))
+    return batch, n, k, ld, kind
+
+
+TOPK_CASES = [draw_topk_case(np.random.default_rng(4000 + i), i) for i in range(24)]
+
+
+@pytest.mark.parametrize("i", range(len(TOPK_CASES)))
+def test_random_selection(i):
+    import oracle
+    from paper_2605_28213_amd import topk
+    from tests.test_topk_gpu import run_state
+    batch, n, k, ld, kind = TOPK_CASES[i]
+    v = gen.normal(400 + i, 0, batch * ld, 1.0).reshape(batch, ld)
+    if kind == "quarters":
+        v = np.round(v * 4) / 4
+    elif kind == "few":
+        v = np.round(v)                                      # about seven distinct values, both zeros among them
+    x = v.astype(np.float32)
+    ridx, rval = oracle.topk(x[:, :n], k)
+    for variant in range(3):
+        q = topk.topk_query(variant, topk.make_desc(batch, n, k, ld=ld))
+        rc, idx, val, _ = run_state(variant, x, n, k)
+        if q.status != gemm.GEMM_OK:
+            assert rc == q.status == gemm.GEMM_ERR_PRECONDITION, (TOPK_CASES[i], variant, q)
+            continue
+        assert rc == gemm.GEMM_OK, (TOPK_CASES[i], variant, topk.topk_last_launch_error())
+        np.testing.assert_array_equal(idx, ridx)
+        np.testing.assert_array_equal(val.view(np.uint32), rval.view(np.uint32))
