@@ -122,9 +122,11 @@ typedef struct {
                                         fused into every state's epilogue; shared by all batch items. */
     void *workspace;                 /* optional device scratch lent by the caller (16-byte aligned), or NULL.
                                         Only K4 uses it, in two cases.  (1) Its fast path's conditions fail:
-                                        with scratch of at least gemm_query's workspace_bytes it packs both
-                                        operands (K contiguous, aligned, zero-padded K) and runs the fast
-                                        kernel on the copies; without scratch its masked kernel runs.  (2) The
+                                        with scratch of at least gemm_query's workspace_bytes it packs the
+                                        operands (K contiguous, aligned, zero-padded K; an operand that meets
+                                        the conditions by itself is used in place when K is whole slabs) and
+                                        runs the fast kernel on the copies; without scratch its masked kernel
+                                        runs.  (2) The
                                         fast path applies but the product has too few tiles to fill the chip
                                         and a long K (batch 1, 17 or more rows): with scratch it splits K into
                                         ranges that run side by side and adds their fp32 partial products in a

@@ -113,7 +113,7 @@ enum MfmaPath { MFMA_ELEMENTWISE = 0, MFMA_VEC16 = 1, MFMA_SKINNY = 2, MFMA_PACK
 
 // Workspace of the packed K4 path: both operands rewritten as [rows][Kp], Kp = K rounded up to a slab.
 int64_t k4_packed_k(const Args& a);
-size_t k4_packed_workspace_bytes(const Args& a);
+size_t k4_packed_workspace_bytes(const Args& a, int keep_mask);   // keep_mask: bit 0 / 1 = A / B is used in place
 // Split-K form of the fast kernel: how many K ranges a product with too few tiles to fill the chip
 // is cut into (1: not applicable), and the fp32 scratch the partial products need.
 int k4_splitk_factor(const Args& a);

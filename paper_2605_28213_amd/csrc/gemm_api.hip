@@ -152,6 +152,8 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
         const bool rows_fit = d->lda * es <= ((int64_t)1 << 22) && d->ldb * es <= ((int64_t)1 << 22);
         // packing both operands into lent scratch turns any layout/alignment/K into the fast kernel's case
         // (and the pack kernels' one-dimensional grids, one workgroup per 2048..7936 packed elements, stay below 2^31)
+        // an operand that meets the fast kernel's conditions by itself is used in place (K whole slabs: no padding needed)
+        const int keep = (va && kdiv && d->lda * es <= ((int64_t)1 << 22) ? 1 : 0) | (vb && kdiv && d->ldb * es <= ((int64_t)1 << 22) ? 2 : 0);
         const bool can_pack = !f32 && d->K > 0 && k4_packed_k(a) * es <= ((int64_t)1 << 22) &&
                               (d->M + d->N) * k4_packed_k(a) < ((int64_t)1 << 40);
         if (skinny) {
@@ -173,11 +175,13 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
             }
         } else if (can_pack && d->workspace != nullptr) {
             // the caller lent scratch: repair the violated conditions by packing, then run the fast kernel
-            p.path = MFMA_PACKED;
-            path = k4_splits_m_tail(a) ? "mfma32-packed+direct-to-lds+stream(M-tail)" : "mfma32-packed+direct-to-lds";
-            pack_bytes = k4_packed_workspace_bytes(a);
+            p.path = MFMA_PACKED | (keep << 8);
+            snprintf(splitk_path, sizeof(splitk_path), "mfma32-packed%s+direct-to-lds%s", keep == 1 ? "(B)" : keep == 2 ? "(A)" : "",
+                     k4_splits_m_tail(a) ? "+stream(M-tail)" : "");
+            path = splitk_path;
+            pack_bytes = k4_packed_workspace_bytes(a, keep);
         } else {
-            if (can_pack) pack_bytes = k4_packed_workspace_bytes(a);   // what lending scratch would buy
+            if (can_pack) pack_bytes = k4_packed_workspace_bytes(a, keep);   // what lending scratch would buy
             p.path = MFMA_ELEMENTWISE | (((va ? 1 : 0) | (vb ? 2 : 0)) << 8);
             path = va && vb ? "mfma32-vec16-masked" : va ? "mfma32-vec16(A)+elementwise-masked(B)"
                             : vb ? "mfma32-elementwise-masked(A)+vec16(B)" : "mfma32-elementwise-masked";

@@ -213,21 +213,24 @@ int64_t k4_packed_k(const Args& a)
     return (a.K + ke - 1) / ke * ke;
 }
 
-size_t k4_packed_workspace_bytes(const Args& a)
+size_t k4_packed_workspace_bytes(const Args& a, int keep_mask)
 {
-    return (size_t)(a.batch * (a.M + a.N) * k4_packed_k(a)) * elem_size(a.in_dtype);
+    const int64_t rows = ((keep_mask & 1) ? 0 : a.M) + ((keep_mask & 2) ? 0 : a.N);
+    return (size_t)(a.batch * rows * k4_packed_k(a)) * elem_size(a.in_dtype);
 }
 
-// Packed path: both operands are rewritten K-contiguous, aligned and zero-padded along K in the
-// workspace ([batch][M][Kp] then [batch][N][Kp]), then the fast kernel runs on the copies.
+// Packed path: the operands are rewritten K-contiguous, aligned and zero-padded along K in the workspace
+// ([batch][M][Kp] then [batch][N][Kp]), then the fast kernel runs on the copies.  An operand that already
+// meets the fast kernel's conditions (and K is whole slabs, so nothing needs padding) is used in place.
 template <typename IN>
-static hipError_t launch_packed(const Args& a)
+static hipError_t launch_packed(const Args& a, int keep_mask)
 {
     using raw = typename IN::raw;
     constexpr int KE = ROW_BYTES / IN::BYTES;
     const int64_t Kp = k4_packed_k(a);
+    const bool keep_a = (keep_mask & 1) != 0, keep_b = (keep_mask & 2) != 0;
     raw* pa = (raw*)a.workspace;
-    raw* pb = pa + a.batch * a.M * Kp;
+    raw* pb = keep_a ? pa : pa + a.batch * a.M * Kp;
     // one operand: `rows` logical rows (M or N), element strides sr along rows and sk along K
     auto pack = [&](const void* src, int64_t sr, int64_t sk, int64_t rows, int64_t src_batch, raw* dst) {
         if (rows <= 0 || Kp <= 0) return;
@@ -244,26 +247,26 @@ static hipError_t launch_packed(const Args& a)
                                (char*)dst, src_batch_bytes, dst_batch_bytes, (int)row_tiles);
         }
     };
-    pack(a.A, a.a_si, a.a_sk, a.M, a.stride_a, pa);
-    pack(a.B, a.b_sj, a.b_sk, a.N, a.stride_b, pb);
+    if (!keep_a) pack(a.A, a.a_si, a.a_sk, a.M, a.stride_a, pa);
+    if (!keep_b) pack(a.B, a.b_sj, a.b_sk, a.N, a.stride_b, pb);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     Args p = a;
-    p.A = pa; p.B = pb; p.K = Kp;
-    p.a_si = Kp; p.a_sk = 1; p.b_sj = Kp; p.b_sk = 1;
-    p.stride_a = a.M * Kp; p.stride_b = a.N * Kp;
+    p.K = Kp;
+    if (!keep_a) { p.A = pa; p.a_si = Kp; p.a_sk = 1; p.stride_a = a.M * Kp; }
+    if (!keep_b) { p.B = pb; p.b_sj = Kp; p.b_sk = 1; p.stride_b = a.N * Kp; }
     return launch_fast_split<IN>(p);
 }
 
 // `path`: low byte = MfmaPath, next byte = bitmask of operands whose 16-byte loads are legal.
 hipError_t launch_k4(int path, const Args& a)
 {
-    const int kind = path & 0xFF, vec_mask = (path >> 8) & 3;
+    const int kind = path & 0xFF, vec_mask = (path >> 8) & 3;   // (packed path: the mask of operands used in place)
     if (kind == MFMA_PACKED) {
         switch (a.in_dtype) {
-        case GEMM_BF16: return launch_packed<BF16>(a);
-        case GEMM_F16: return launch_packed<F16>(a);
-        case GEMM_FP8_E4M3: return launch_packed<E4M3>(a);
+        case GEMM_BF16: return launch_packed<BF16>(a, vec_mask);
+        case GEMM_F16: return launch_packed<F16>(a, vec_mask);
+        case GEMM_FP8_E4M3: return launch_packed<E4M3>(a, vec_mask);
         default: return hipErrorInvalidValue;
         }
     }

@@ -221,6 +221,26 @@ def test_launch_on_a_side_stream():
     assert util.norm_err(C, C_ref, D) <= util.TOL[c.in_dtype]
 
 
+@pytest.mark.parametrize("dtype", [gen.BF16, gen.F16, gen.E4M3])
+@pytest.mark.parametrize("la,lb,tag", [(ROW, ROW, "(B)"), (COL, COL, "(A)"), (COL, ROW, "")])
+def test_packed_path_leaves_a_conforming_operand_in_place(dtype, la, lb, tag):
+    """Aligned operands and K in whole slabs, but K strided in one or both operands: only the operand that
+    breaks the fast kernel's conditions is packed; the scratch asked for covers that operand alone."""
+    M, N, K, nb = 392, 264, 384, 2
+    out = gen.BF16 if dtype == gen.E4M3 else dtype
+    es = gen.ELEM_BYTES[dtype]
+    cfg = gen.Config("halfpacked", M, N, K, dtype, out, la, lb, "normal", rsqrt_k=True, batch=nb, biased=True)
+    inp = gen.make_inputs(cfg, 12)
+    d = gemm.make_desc(M, N, K, dtype, out, la, lb, batch=nb)
+    q = gemm.gemm_query(4, d)
+    rows = {"(B)": N, "(A)": M, "": M + N}[tag]
+    assert q.workspace_bytes == nb * rows * K * es and "packed" not in q.path
+    d.workspace, d.workspace_bytes = 256, q.workspace_bytes
+    assert gemm.gemm_query(4, d).path == "mfma32-packed%s+direct-to-lds" % tag
+    check(4, inp, lend_workspace=True)
+    check(4, inp, out_dtype=gen.F32, lend_workspace=True)
+
+
 def test_host_threads_and_streams_side_by_side():
     """The library keeps no state between calls (the launch-error slot is per thread): four host threads,
     each on a stream of its own, launch different paths of K4 and an earlier state at the same time, many

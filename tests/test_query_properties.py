@@ -96,9 +96,17 @@ def test_expert_state_paths_and_scratch(p):
     else:
         kp = math.ceil(p["K"] / kslab) * kslab
         assert q.path.startswith("mfma32-") and "packed" not in q.path
-        assert q.workspace_bytes == p["batch"] * (p["M"] + p["N"]) * kp * es
+        # an operand that meets the fast kernel's conditions by itself is used in place, the other one is packed
+        whole = p["K"] % kslab == 0
+        a_ok = (whole and p["la"] == gemm.GEMM_ROW_MAJOR and (p["lda"] * es) % 16 == 0 and p["lda"] * es <= 1 << 22
+                and (p["batch"] == 1 or (p["M"] * p["lda"] * es) % 16 == 0))
+        b_ok = (whole and p["lb"] == gemm.GEMM_COL_MAJOR and (p["ldb"] * es) % 16 == 0 and p["ldb"] * es <= 1 << 22
+                and (p["batch"] == 1 or (p["N"] * p["ldb"] * es) % 16 == 0))
+        assert not (a_ok and b_ok)
+        assert q.workspace_bytes == p["batch"] * ((0 if a_ok else p["M"]) + (0 if b_ok else p["N"])) * kp * es
         lent = gemm.gemm_query(gemm.GEMM_K4_MFMA, make(p, workspace=4096, workspace_bytes=q.workspace_bytes))
-        assert lent.status == gemm.GEMM_OK and lent.path.startswith("mfma32-packed+direct-to-lds")
+        tag = "(B)" if a_ok else "(A)" if b_ok else ""
+        assert lent.status == gemm.GEMM_OK and lent.path.startswith("mfma32-packed%s+direct-to-lds" % tag)
         small = gemm.gemm_query(gemm.GEMM_K4_MFMA, make(p, workspace=4096, workspace_bytes=q.workspace_bytes - 1))
         assert small.status == gemm.GEMM_ERR_WORKSPACE
         odd = gemm.gemm_query(gemm.GEMM_K4_MFMA, make(p, workspace=4100, workspace_bytes=q.workspace_bytes))
