@@ -39,10 +39,14 @@ struct Args {
     int64_t ldc;
     int64_t stride_a, stride_b, stride_c;
     int32_t in_dtype, out_dtype;
-    uint32_t flags;      // GEMM_FLAG_DEOPT_* bits (host side only: they select an instantiation)
+    uint32_t flags;      // GEMM_FLAG_DEOPT_* bits (host side only: they select an instantiation); ARGS_C_TRANSPOSED
     hipStream_t stream;
     ConvGeom conv;       // all zero for a plain matrix product
 };
+
+// Set by the launcher of the streaming kernel when it multiplies the transposed product (few columns instead
+// of few rows): the kernel's (row, column) is C's (column, row), and the bias belongs to the kernel's rows.
+constexpr uint32_t ARGS_C_TRANSPOSED = 1u << 31;
 
 // ---- storage formats ------------------------------------------------------------------------
 struct F32 { using raw = float;    static constexpr int BYTES = 4; static constexpr int ID = GEMM_F32; };
@@ -109,7 +113,7 @@ inline bool dtype_pair_supported(int in, int out)
 // Each returns hipSuccess or the launch error.  `path` selects a code path that the caller
 // (gemm_api.hip) has already proven legal for these arguments.
 enum ValuPath { VALU_SCALAR = 0, VALU_VEC16 = 1 };
-enum MfmaPath { MFMA_ELEMENTWISE = 0, MFMA_VEC16 = 1, MFMA_SKINNY = 2, MFMA_PACKED = 3, MFMA_SPLITK = 4 };
+enum MfmaPath { MFMA_ELEMENTWISE = 0, MFMA_VEC16 = 1, MFMA_SKINNY = 2, MFMA_PACKED = 3, MFMA_SPLITK = 4, MFMA_SKINNY_N = 5 };
 
 // Workspace of the packed K4 path: both operands rewritten as [rows][Kp], Kp = K rounded up to a slab.
 int64_t k4_packed_k(const Args& a);
@@ -122,6 +126,7 @@ size_t k4_splitk_workspace_bytes(const Args& a, int splits);
 // round of the chip) to the streaming kernel.
 bool k4_splits_m_tail(const Args& a);
 bool k4_streams_rows(const Args& a);      // a product of at most 64 rows goes to the streaming kernel
+Args k4_transposed(const Args& a);        // the same product as C^T = B^T A^T (operands swapped, ARGS_C_TRANSPOSED set)
 // True when the fast kernel runs with 128 x 128 workgroup tiles instead of 256 x 256.
 bool k4_small_tiles(const Args& a);
 

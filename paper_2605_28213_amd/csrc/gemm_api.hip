@@ -144,6 +144,10 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
         const bool skinny = (holds & GEMM_COND_SMALL_M) && va && vb && d->K % kvec == 0 && d->K > 0 &&
                             d->in_dtype != GEMM_F32 && d->ldb <= ((int64_t)1 << 24) &&
                             d->lda <= ((int64_t)1 << 24) && k4_streams_rows(a);
+        // few columns instead of few rows: the same kernel on the transposed product (C^T = B^T A^T)
+        const bool skinny_n = !skinny && d->M > 64 && d->N <= 64 && va && vb && d->K % kvec == 0 && d->K > 0 &&
+                              d->in_dtype != GEMM_F32 && d->ldb <= ((int64_t)1 << 24) && d->lda <= ((int64_t)1 << 24) &&
+                              k4_streams_rows(k4_transposed(a));
         // fp32 has its matrix instruction in the masked kernel only: no direct-to-LDS, packed or streaming form
         const bool f32 = d->in_dtype == GEMM_F32;
         if (f32) required = GEMM_COND_DTYPE_HAS_MFMA | GEMM_COND_LDS_STAGED;
@@ -159,6 +163,10 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
         if (skinny) {
             p.path = MFMA_SKINNY;
             path = "mfma16-stream(small-M)";
+            required &= ~(uint32_t)GEMM_COND_TILE_DIV_K;
+        } else if (skinny_n) {
+            p.path = MFMA_SKINNY_N;
+            path = "mfma16-stream(small-N)";
             required &= ~(uint32_t)GEMM_COND_TILE_DIV_K;
         } else if (!f32 && va && vb && kdiv && rows_fit) {
             p.path = MFMA_VEC16 | (3 << 8);

@@ -1094,13 +1094,17 @@ __global__ __launch_bounds__(CFG::WAVES * 64) void k4_stream(Args a)
             for (int r = 0; r < 4; ++r) part[(wave * ROWS + m * 16 + 4 * lq + r) * (COLS + 1) + n * 16 + l16] = acc[m][n][r];
     __syncthreads();
     const float sc = batch_scale(a, b);
+    // (transposed product: the kernel's row i is C's column, so consecutive threads take consecutive i)
+    const bool tr = (a.flags & ARGS_C_TRANSPOSED) != 0;
     for (int o = t; o < ROWS * COLS; o += WAVES * 64) {
-        const int i = o / COLS, j = o % COLS;
+        const int i = tr ? o % ROWS : o / COLS, j = tr ? o / ROWS : o % COLS;
         float v = 0.0f;
 #pragma unroll
         for (int w = 0; w < WAVES; ++w) v += part[(w * ROWS + i) * (COLS + 1) + j];
-        if (i < a.M && j0 + j < a.N)
-            store_out(a.C, b * a.stride_c + (int64_t)i * a.ldc + j0 + j, v * sc + (a.bias ? a.bias[j0 + j] : 0.0f), a.out_dtype);
+        if (i < a.M && j0 + j < a.N) {
+            const int64_t at = tr ? (j0 + j) * a.ldc + i : (int64_t)i * a.ldc + j0 + j;
+            store_out(a.C, b * a.stride_c + at, v * sc + (a.bias ? a.bias[tr ? i : j0 + j] : 0.0f), a.out_dtype);
+        }
     }
 }
 

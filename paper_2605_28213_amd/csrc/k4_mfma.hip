@@ -89,6 +89,18 @@ bool k4_streams_rows(const Args& a)
     return ((a.N + cols - 1) / cols) * a.batch >= 128;
 }
 
+// C = A B with few columns is C^T = B^T A^T with few rows: B's columns (K contiguous) become the rows of the
+// first operand, A's rows the columns of the second, and the kernel writes its output transposed.
+Args k4_transposed(const Args& a)
+{
+    Args s = a;
+    s.A = a.B; s.a_si = a.b_sj; s.a_sk = a.b_sk; s.stride_a = a.stride_b;
+    s.B = a.A; s.b_sj = a.a_si; s.b_sk = a.a_sk; s.stride_b = a.stride_a;
+    s.M = a.N; s.N = a.M;
+    s.flags = a.flags | ARGS_C_TRANSPOSED;
+    return s;
+}
+
 template <typename IN>
 static hipError_t launch_stream(const Args& a)
 {
@@ -278,10 +290,11 @@ hipError_t launch_k4(int path, const Args& a)
         default: return hipErrorInvalidValue;
         }
     }
-    if (kind == MFMA_SKINNY) {
-        if (a.in_dtype == GEMM_BF16) return launch_stream<BF16>(a);
-        if (a.in_dtype == GEMM_F16) return launch_stream<F16>(a);
-        if (a.in_dtype == GEMM_FP8_E4M3) return launch_stream<E4M3>(a);
+    if (kind == MFMA_SKINNY || kind == MFMA_SKINNY_N) {
+        const Args s = kind == MFMA_SKINNY_N ? k4_transposed(a) : a;
+        if (a.in_dtype == GEMM_BF16) return launch_stream<BF16>(s);
+        if (a.in_dtype == GEMM_F16) return launch_stream<F16>(s);
+        if (a.in_dtype == GEMM_FP8_E4M3) return launch_stream<E4M3>(s);
         return hipErrorInvalidValue;
     }
     if (kind == MFMA_VEC16) {
@@ -327,12 +340,15 @@ Geometry geometry_k4(int path, const Args& a)
 {
     const int kind = path & 0xFF;
     const int es = elem_size(a.in_dtype);
-    if (kind == MFMA_SKINNY) {
+    if (kind == MFMA_SKINNY || kind == MFMA_SKINNY_N) {
+        const bool tr = kind == MFMA_SKINNY_N;          // transposed product: the strip runs along M
+        const Args s = tr ? k4_transposed(a) : a;
         auto of = [&](auto cfg) {
             using C = decltype(cfg);
-            return Geometry{C::ROWS, C::COLS, C::TK * 2 / es, C::WAVES * 64, 2, C::LDS_BYTES, ((a.N + C::COLS - 1) / C::COLS) * a.batch};
+            return Geometry{tr ? C::COLS : C::ROWS, tr ? C::ROWS : C::COLS, C::TK * 2 / es, C::WAVES * 64, 2, C::LDS_BYTES,
+                            ((s.N + C::COLS - 1) / C::COLS) * a.batch};
         };
-        switch (stream_form(a)) {
+        switch (stream_form(s)) {
         case STREAM_16: return of(StreamK4<BF16>{});
         case STREAM_16_DEEP: return of(StreamK4Deep<BF16>{});
         case STREAM_32: return of(StreamK4Rows32<BF16>{});

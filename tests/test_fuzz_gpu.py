@@ -83,6 +83,35 @@ def draw_rows_case(rng, i):
 ROWS_CASES = [draw_rows_case(np.random.default_rng(2000 + i), i) for i in range(24)]
 
 
+def draw_cols_case(rng, i):
+    """Few columns on the streaming kernel's transposed form: the rows case with M and N exchanged."""
+    c = draw_rows_case(rng, i)
+    n = int(rng.integers(1, 65))
+    cols = 16 if n <= 16 else 32 if n <= 32 else 64
+    strips = int(rng.integers(1, 7))
+    batch = 1 if n <= 16 and rng.random() < 0.5 else -(-128 // strips) + int(rng.integers(0, 3))
+    M = max(65, cols * (strips - 1) + int(rng.integers(1, cols + 1)))
+    return gen.Config(f"cols{i}", M, n, c.K, c.in_dtype, c.out_dtype, ROW, COL, c.dist, batch=batch, scaled=c.scaled, biased=c.biased,
+                      lda=c.ld[0], ldb=c.ld[1], ldc=n + int(rng.integers(0, 5)))
+
+
+COLS_CASES = [draw_cols_case(np.random.default_rng(2500 + i), i) for i in range(24)]
+
+
+@pytest.mark.parametrize("i", range(len(COLS_CASES)))
+def test_random_case_with_few_columns(i):
+    cfg = COLS_CASES[i]
+    inp = gen.make_inputs(cfg, 250 + i)
+    C_ref, D = oracle_for(inp)
+    q = gemm.gemm_query(4, gemm.make_desc(cfg.M, cfg.N, cfg.K, cfg.in_dtype, cfg.out_dtype, ROW, COL, lda=inp.lda, ldb=inp.ldb,
+                                          ldc=inp.ldc, batch=cfg.batch, stride_a=inp.stride_a, stride_b=inp.stride_b, stride_c=inp.stride_c))
+    assert q.path == "mfma16-stream(small-N)", (cfg, q)
+    rc, C, _ = util.run_config(4, inp)
+    assert rc == gemm.GEMM_OK, (cfg, gemm.gemm_status_string(rc), gemm.gemm_last_launch_error())
+    err = util.norm_err(C[:, :, : cfg.N], C_ref, D)
+    assert err <= util.TOL[cfg.in_dtype], (cfg, err)
+
+
 @pytest.mark.parametrize("i", range(len(ROWS_CASES)))
 def test_random_case_with_17_to_64_rows(i):
     cfg = ROWS_CASES[i]

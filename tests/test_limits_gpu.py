@@ -83,16 +83,17 @@ def test_output_and_operand_beyond_4_gib(variant):
 
 def test_largest_batch_count():
     """65 535 problems: one workgroup tile each on the direct-to-LDS kernel (K = 64) and on the masked one
-    (K = 40) with 72 rows, one strip each on the streaming kernel with 8 rows."""
-    for M, K, path in ((72, 64, "mfma32-direct-to-lds"), (72, 40, "mfma32-"), (8, 40, "mfma16-stream")):
-        cfg = gen.Config("batch65535", M, 8, K, gen.BF16, gen.BF16, ROW, COL, "normal", rsqrt_k=True, batch=65535)
+    (K = 40) with 72 rows and columns, one strip each on the streaming kernel with 8 rows or 8 columns."""
+    for M, N, K, path in ((72, 72, 64, "mfma32-direct-to-lds"), (72, 72, 40, "mfma32-"), (8, 8, 40, "mfma16-stream(small-M)"),
+                          (72, 8, 40, "mfma16-stream(small-N)")):
+        cfg = gen.Config("batch65535", M, N, K, gen.BF16, gen.BF16, ROW, COL, "normal", rsqrt_k=True, batch=65535)
         inp = gen.make_inputs(cfg, 36)
-        d = gemm.make_desc(M, 8, K, gen.BF16, gen.BF16, ROW, COL, batch=65535)
+        d = gemm.make_desc(M, N, K, gen.BF16, gen.BF16, ROW, COL, batch=65535)
         assert gemm.gemm_query(4, d).path.startswith(path)
         C_ref, D = oracle_for(inp)
         rc, C, _ = util.run_config(4, inp)
         assert rc == gemm.GEMM_OK
-        assert util.norm_err(C[:, :, :8], C_ref, D) <= util.TOL[gen.BF16]
+        assert util.norm_err(C[:, :, :N], C_ref, D) <= util.TOL[gen.BF16]
     d = gemm.make_desc(8, 8, 64, gen.BF16, gen.BF16, ROW, COL, batch=65536)
     assert gemm.gemm_query(4, d).status == gemm.GEMM_ERR_BAD_ARG
 

@@ -154,6 +154,34 @@ def test_streaming_path_with_17_to_64_rows(dtype):
         assert gemm.gemm_query(4, gemm.make_desc(M, N, 1024, dtype, out, ROW, COL)).path.startswith("mfma32-direct-to-lds")
 
 
+@pytest.mark.parametrize("dtype", [gen.BF16, gen.F16, gen.E4M3])
+def test_streaming_path_with_few_columns(dtype):
+    """Up to 64 columns and many rows: the streaming kernel multiplies the transposed product (B's columns as
+    its rows, strips along M) and writes C transposed back; bias per column of C, scales, ragged strips,
+    ragged K tiles, padded leading dimensions, batches, fp32 output."""
+    cases = [(200, 16, 1024, {}), (4100, 7, 136, dict(biased=True)), (300, 1, 8, {}), (4100, 17, 520, dict(biased=True)),
+             (8200, 33, 264, {}), (8192, 64, 2048, dict(biased=True, ldc=72)), (530, 48, 1160, dict(batch=16, scaled=True, biased=True)),
+             (70, 16, 1320, dict(batch=3, lda=1328, ldb=1336, ldc=24))]
+    for (M, N, K, kw) in cases:
+        out = gen.BF16 if dtype == gen.E4M3 else dtype
+        if dtype == gen.E4M3:
+            K = (K + 15) // 16 * 16
+            kw = {k_: (v_ + 15) // 16 * 16 if k_ in ("lda", "ldb") else v_ for k_, v_ in kw.items()}
+        cfg = gen.Config("cols", M, N, K, dtype, out, ROW, COL, "normal", std=0.02 if dtype != gen.E4M3 else 1.0, **kw)
+        inp = gen.make_inputs(cfg, 13)
+        d = gemm.make_desc(M, N, K, dtype, out, ROW, COL, lda=inp.lda, ldb=inp.ldb, ldc=inp.ldc, batch=cfg.batch,
+                           stride_a=inp.stride_a, stride_b=inp.stride_b, stride_c=inp.stride_c)
+        q = gemm.gemm_query(4, d)
+        assert q.path == "mfma16-stream(small-N)" and q.bn == 16 * ((N + 15) // 16), (M, N, K, q)
+        ref = oracle_for(inp)
+        check(4, inp, ref)
+        check(4, inp, ref, out_dtype=gen.F32)
+    # 17..64 columns and too few strips along M for the chip: the tiled kernel keeps the product
+    out = gen.BF16 if dtype == gen.E4M3 else dtype
+    for (M, N) in ((4064, 17), (8128, 64)):
+        assert gemm.gemm_query(4, gemm.make_desc(M, N, 1024, dtype, out, ROW, COL)).path.startswith("mfma32-direct-to-lds")
+
+
 def test_batched_strides_scales_and_padding_untouched():
     """Batch strides larger than the matrices, ldc > N: the gaps keep their poison bytes."""
     M, N, K, nb = 70, 50, 96, 3

@@ -68,6 +68,12 @@ def test_expert_state_paths_and_scratch(p):
     if fast_ok and streams and p["K"] % kvec == 0:
         assert q.path == "mfma16-stream(small-M)" and q.workspace_bytes == 0
         assert q.bn == cols and q.bm == 16 * math.ceil(max(p["M"], 1) / 16) and q.grid == math.ceil(p["N"] / cols) * p["batch"]
+    elif (fast_ok and p["K"] % kvec == 0 and p["M"] > 64 and p["N"] <= 64
+          and (p["N"] <= 16 or math.ceil(p["M"] / (32 if p["N"] <= 32 else 64)) * p["batch"] >= 128)):
+        # few columns: the streaming kernel on the transposed product, strips along M
+        strip = 16 if p["N"] <= 16 else 32 if p["N"] <= 32 else 64
+        assert q.path == "mfma16-stream(small-N)" and q.workspace_bytes == 0
+        assert q.bm == strip and q.bn == 16 * math.ceil(max(p["N"], 1) / 16) and q.grid == math.ceil(p["M"] / strip) * p["batch"]
     elif fast_ok and p["K"] % kslab == 0:
         assert q.path.startswith("mfma32-direct-to-lds") and q.violated == 0
         # split-K: offered (through workspace_bytes) when the product has few tiles and a long K, taken when scratch is lent
