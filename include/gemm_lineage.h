@@ -82,7 +82,7 @@ enum {
     GEMM_COND_K_CONTIG_B     = 1u << 10, /* B stored with K contiguous (column-major) */
     GEMM_COND_DTYPE_HAS_MFMA = 1u << 11, /* the input dtype has a matrix instruction on gfx950 (all four do) */
     GEMM_COND_LDS_STAGED     = 1u << 12, /* operands pass through LDS (holds from K1 on) */
-    GEMM_COND_SMALL_M        = 1u << 13  /* M <= 64: few enough rows for the streaming (bandwidth-bound) path (bf16, fp16, e4m3); with 17..64 rows K4 takes it when the strips of 32 (up to 32 rows) or 64 columns number at least 128.  A product of more than 64 rows and at most 64 columns takes the same path transposed (path "...(small-N)"), under the same rule with rows and columns exchanged */
+    GEMM_COND_SMALL_M        = 1u << 13  /* M <= 96: few enough rows for the streaming (bandwidth-bound) path (bf16, fp16, e4m3); with 17..96 rows K4 takes it when the strips of 32 (up to 32 rows) or 64 columns number at least 128.  A product of at most 96 columns, fewer than its rows, that does not stream by its rows takes the same path transposed (path "...(small-N)"), under the same rule with rows and columns exchanged */
 };
 
 enum {

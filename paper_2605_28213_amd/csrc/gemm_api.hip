@@ -106,7 +106,7 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
     if (d->layout_b == GEMM_COL_MAJOR) holds |= GEMM_COND_K_CONTIG_B;
     holds |= GEMM_COND_DTYPE_HAS_MFMA;   // all four input types have one on gfx950 (fp32: v_mfma_f32_32x32x2_f32)
     if (variant >= GEMM_K1_LDS_TILED) holds |= GEMM_COND_LDS_STAGED;
-    if (d->M <= 64) holds |= GEMM_COND_SMALL_M;
+    if (d->M <= 96) holds |= GEMM_COND_SMALL_M;
 
     const uint32_t vecA = GEMM_COND_ALIGN16_A | GEMM_COND_LD16_A, vecB = GEMM_COND_ALIGN16_B | GEMM_COND_LD16_B;
     uint32_t required = 0;
@@ -145,7 +145,7 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
                             d->in_dtype != GEMM_F32 && d->ldb <= ((int64_t)1 << 24) &&
                             d->lda <= ((int64_t)1 << 24) && k4_streams_rows(a);
         // few columns instead of few rows: the same kernel on the transposed product (C^T = B^T A^T)
-        const bool skinny_n = !skinny && d->M > 64 && d->N <= 64 && va && vb && d->K % kvec == 0 && d->K > 0 &&
+        const bool skinny_n = !skinny && d->M > d->N && d->N <= 96 && va && vb && d->K % kvec == 0 && d->K > 0 &&
                               d->in_dtype != GEMM_F32 && d->ldb <= ((int64_t)1 << 24) && d->lda <= ((int64_t)1 << 24) &&
                               k4_streams_rows(k4_transposed(a));
         // fp32 has its matrix instruction in the masked kernel only: no direct-to-LDS, packed or streaming form

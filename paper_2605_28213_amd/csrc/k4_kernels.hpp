@@ -873,7 +873,7 @@ __global__ __launch_bounds__(256) void k4_splitk_reduce(Args a, const float* __r
 }
 
 // ------------------------------------------------------------------------------------------------
-// Streaming kernel for M <= 64 (decode-like shapes; bf16, fp16 and e4m3): the product is bound by reading
+// Streaming kernel for M <= 96 (decode-like shapes; bf16, fp16 and e4m3): the product is bound by reading
 // B once from HBM.  A workgroup owns a strip of 16*NB columns of C and all MG groups of 16 rows of A; its WAVES
 // waves split K, partial sums meet in LDS at the end.  Needs: A row-major, B column-major, 16-byte
 // aligned, K a multiple of 16 bytes.  (Sizes below are those of the 2-byte types; for e4m3 a tile row holds
@@ -928,7 +928,7 @@ struct StreamCfg {
     static constexpr int TILE_BYTES = (MG + 1) * GROUP_BYTES;   // the groups of A and one group of B columns
     static constexpr int LDS_BYTES = WAVES * TILE_BYTES;
     static_assert(LPC >= 16 && LPC <= 64 && (LPC & (LPC - 1)) == 0, "a row's run is 16..64 lanes wide");
-    static_assert(MG >= 1 && MG <= 4, "up to 64 rows of A");
+    static_assert(MG >= 1 && MG <= 6, "up to 96 rows of A (eight groups spill registers)");
     static_assert(WAVES * ROWS * (COLS + 1) * 4 <= LDS_BYTES, "the K-split partial sums reuse the tiles");
 };
 

@@ -12,6 +12,7 @@ template <typename IN> using StreamK4Deep = StreamCfg<IN, 4, 1, 256, 19>;  // th
 template <typename IN> using StreamK4Rows32 = StreamCfg<IN, 2, 2, 256, 19, 2>;   // 17..32 rows: 32 columns, two groups of A
 template <typename IN> using StreamK4Rows48 = StreamCfg<IN, 4, 4, 128, 19, 3>;   // 33..48 rows: 64 columns, 256-byte runs
 template <typename IN> using StreamK4Rows64 = StreamCfg<IN, 4, 4, 128, 19, 4>;   // 49..64 rows
+template <typename IN> using StreamK4Rows96 = StreamCfg<IN, 4, 4, 128, 19, 6>;   // 65..96 rows
 constexpr int MASKED_BM = 128, MASKED_BN = 128, MASKED_WM = 2, MASKED_WN = 2;   // (64 x 64 for small problems, see masked_tile)
 
 template <typename CFG>
@@ -67,24 +68,25 @@ static hipError_t launch_stream_cfg(const Args& a)
 // spread over the memory channels); with fewer strips than CUs, 4 waves split each strip's K.
 static bool stream_deep(const Args& a) { return ((a.N + 15) / 16) * a.batch < 512; }
 
-// 17..64 rows: every workgroup reads all of A (from L2) beside its strip of B, so the strip widens with the
+// 17..96 rows: every workgroup reads all of A (from L2) beside its strip of B, so the strip widens with the
 // rows to keep A's share of the load traffic at one half.  Measured on N = K = 16384 bf16, B read once from
 // HBM (537 MB): 32 rows 87 us (2 waves x 32 columns; 100 us with 16 columns, 93 us with 4 waves x 64
 // columns), 48 rows 90 us, 64 rows 97 us (4 waves x 64 columns x 256-byte runs; 104 us with 2 waves x 32
-// columns); the split-K form of the tiled kernel took 139-142 us on the same products.
-enum StreamForm { STREAM_16 = 0, STREAM_16_DEEP, STREAM_32, STREAM_48, STREAM_64 };
+// columns); the split-K form of the tiled kernel took 139-142 us on the same products.  96 rows (six groups of
+// A, 484 registers): 113 us against about 150 us for the split-K form; eight groups spill and lose to it.
+enum StreamForm { STREAM_16 = 0, STREAM_16_DEEP, STREAM_32, STREAM_48, STREAM_64, STREAM_96 };
 static StreamForm stream_form(const Args& a)
 {
     if (a.M <= 16) return stream_deep(a) ? STREAM_16_DEEP : STREAM_16;
-    return a.M <= 32 ? STREAM_32 : a.M <= 48 ? STREAM_48 : STREAM_64;
+    return a.M <= 32 ? STREAM_32 : a.M <= 48 ? STREAM_48 : a.M <= 64 ? STREAM_64 : STREAM_96;
 }
 
-// Whether a product of 17..64 rows is given to the streaming kernel: when its strips fill at least half of
+// Whether a product of 17..96 rows is given to the streaming kernel: when its strips fill at least half of
 // the CUs (below that the tiled kernel, split along K, has more workgroups to offer).
 bool k4_streams_rows(const Args& a)
 {
     if (a.M <= 16) return true;
-    if (a.M > 64) return false;
+    if (a.M > 96) return false;
     const int cols = a.M <= 32 ? 32 : 64;
     return ((a.N + cols - 1) / cols) * a.batch >= 128;
 }
@@ -109,7 +111,8 @@ static hipError_t launch_stream(const Args& a)
     case STREAM_16_DEEP: return launch_stream_cfg<StreamK4Deep<IN>>(a);
     case STREAM_32: return launch_stream_cfg<StreamK4Rows32<IN>>(a);
     case STREAM_48: return launch_stream_cfg<StreamK4Rows48<IN>>(a);
-    default: return launch_stream_cfg<StreamK4Rows64<IN>>(a);
+    case STREAM_64: return launch_stream_cfg<StreamK4Rows64<IN>>(a);
+    default: return launch_stream_cfg<StreamK4Rows96<IN>>(a);
     }
 }
 
@@ -353,7 +356,8 @@ Geometry geometry_k4(int path, const Args& a)
         case STREAM_16_DEEP: return of(StreamK4Deep<BF16>{});
         case STREAM_32: return of(StreamK4Rows32<BF16>{});
         case STREAM_48: return of(StreamK4Rows48<BF16>{});
-        default: return of(StreamK4Rows64<BF16>{});
+        case STREAM_64: return of(StreamK4Rows64<BF16>{});
+        default: return of(StreamK4Rows96<BF16>{});
         }
     }
     if (kind == MFMA_VEC16 || kind == MFMA_PACKED || kind == MFMA_SPLITK) {

@@ -78,7 +78,7 @@ def test_stream_kernel_register_budget(asm):
             assert meta["vgpr_spill"] == 0 and meta["scratch"] == 0
             assert meta["lds"] == waves * 16 * 1024, "per wave the A group and one column group of 16 x 512 B"
         # 17..64 rows: (waves, column groups, K tile, groups of A); per wave MG + 1 groups of 16 x 2 TK bytes
-        for waves, nb, tk, mg in ((2, 2, 256, 2), (4, 4, 128, 3), (4, 4, 128, 4)):
+        for waves, nb, tk, mg in ((2, 2, 256, 2), (4, 4, 128, 3), (4, 4, 128, 4), (4, 4, 128, 6)):
             meta = metadata(asm, "_ZN2gl9k4_streamINS_9StreamCfgINS_%sELi%dELi%dELi%dELi19ELi%dEEE" % (dtype, waves, nb, tk, mg))
             assert meta["vgpr_spill"] == 0 and meta["scratch"] == 0
             assert meta["lds"] == waves * (mg + 1) * 16 * 2 * tk

@@ -66,9 +66,9 @@ def test_random_case(i):
 
 
 def draw_rows_case(rng, i):
-    """17..64 rows on the streaming kernel: few wide strips per problem, enough problems to pass its rule."""
+    """17..96 rows on the streaming kernel: few wide strips per problem, enough problems to pass its rule."""
     dtype = int(rng.choice([gen.BF16, gen.F16, gen.E4M3]))
-    M = int(rng.integers(17, 65))
+    M = int(rng.integers(17, 97))
     cols = 32 if M <= 32 else 64
     strips = int(rng.integers(1, 7))
     batch = -(-128 // strips) + int(rng.integers(0, 4))
@@ -86,11 +86,11 @@ ROWS_CASES = [draw_rows_case(np.random.default_rng(2000 + i), i) for i in range(
 def draw_cols_case(rng, i):
     """Few columns on the streaming kernel's transposed form: the rows case with M and N exchanged."""
     c = draw_rows_case(rng, i)
-    n = int(rng.integers(1, 65))
+    n = int(rng.integers(1, 97))
     cols = 16 if n <= 16 else 32 if n <= 32 else 64
     strips = int(rng.integers(1, 7))
     batch = 1 if n <= 16 and rng.random() < 0.5 else -(-128 // strips) + int(rng.integers(0, 3))
-    M = max(65, cols * (strips - 1) + int(rng.integers(1, cols + 1)))
+    M = max(97, cols * (strips - 1) + int(rng.integers(1, cols + 1)))       # more rows than the row forms take
     return gen.Config(f"cols{i}", M, n, c.K, c.in_dtype, c.out_dtype, ROW, COL, c.dist, batch=batch, scaled=c.scaled, biased=c.biased,
                       lda=c.ld[0], ldb=c.ld[1], ldc=n + int(rng.integers(0, 5)))
 
@@ -113,7 +113,7 @@ def test_random_case_with_few_columns(i):
 
 
 @pytest.mark.parametrize("i", range(len(ROWS_CASES)))
-def test_random_case_with_17_to_64_rows(i):
+def test_random_case_with_17_to_96_rows(i):
     cfg = ROWS_CASES[i]
     inp = gen.make_inputs(cfg, 200 + i)
     C_ref, D = oracle_for(inp)

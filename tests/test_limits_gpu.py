@@ -82,10 +82,11 @@ def test_output_and_operand_beyond_4_gib(variant):
 
 
 def test_largest_batch_count():
-    """65 535 problems: one workgroup tile each on the direct-to-LDS kernel (K = 64) and on the masked one
-    (K = 40) with 72 rows and columns, one strip each on the streaming kernel with 8 rows or 8 columns."""
-    for M, N, K, path in ((72, 72, 64, "mfma32-direct-to-lds"), (72, 72, 40, "mfma32-"), (8, 8, 40, "mfma16-stream(small-M)"),
-                          (72, 8, 40, "mfma16-stream(small-N)")):
+    """65 535 problems.  On the streaming kernel (8 rows, or 8 columns and 104 rows) one strip each, every
+    problem with operands of its own.  On the direct-to-LDS kernel (K = 64) and on the masked one (K = 40)
+    one 104 x 104 tile each; there all problems share one pair of operands (batch strides of zero), so the
+    65 535 outputs must equal the first one bit for bit and the first one the oracle."""
+    for M, N, K, path in ((8, 8, 40, "mfma16-stream(small-M)"), (104, 8, 40, "mfma16-stream(small-N)")):
         cfg = gen.Config("batch65535", M, N, K, gen.BF16, gen.BF16, ROW, COL, "normal", rsqrt_k=True, batch=65535)
         inp = gen.make_inputs(cfg, 36)
         d = gemm.make_desc(M, N, K, gen.BF16, gen.BF16, ROW, COL, batch=65535)
@@ -94,6 +95,23 @@ def test_largest_batch_count():
         rc, C, _ = util.run_config(4, inp)
         assert rc == gemm.GEMM_OK
         assert util.norm_err(C[:, :, :N], C_ref, D) <= util.TOL[gen.BF16]
+    M = N = 104
+    for K, path in ((64, "mfma32-direct-to-lds"), (40, "mfma32-vec16-masked")):
+        cfg = gen.Config("batch65535_shared", M, N, K, gen.BF16, gen.BF16, ROW, COL, "normal", rsqrt_k=True)
+        inp = gen.make_inputs(cfg, 37)
+        C_ref, D = oracle_for(inp)
+        dA, dB = util.dev(inp.A), util.dev(inp.B)
+        dC = torch.full((65535 * M * N * 2,), util.POISON, dtype=torch.uint8, device="cuda")
+        d = gemm.make_desc(M, N, K, gen.BF16, gen.BF16, ROW, COL, batch=65535, stride_a=0, stride_b=0)
+        assert gemm.gemm_query(4, d, dA, dB, dC).path == path
+        assert gemm.gemm_run_ex(4, d, dA, dB, dC) == gemm.GEMM_OK
+        torch.cuda.synchronize()
+        items = dC.view(65535, M * N * 2)
+        assert bool((items == items[0]).all())
+        first = util.decode_out(items[0].contiguous(), gen.BF16).reshape(1, M, N)
+        assert util.norm_err(first, C_ref, D) <= util.TOL[gen.BF16]
+        del dC
+        torch.cuda.empty_cache()
     d = gemm.make_desc(8, 8, 64, gen.BF16, gen.BF16, ROW, COL, batch=65536)
     assert gemm.gemm_query(4, d).status == gemm.GEMM_ERR_BAD_ARG
 

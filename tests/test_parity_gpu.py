@@ -128,12 +128,13 @@ def test_skinny_path_edges():
 
 
 @pytest.mark.parametrize("dtype", [gen.BF16, gen.F16, gen.E4M3])
-def test_streaming_path_with_17_to_64_rows(dtype):
-    """Two to four groups of 16 rows of A per workgroup: every group boundary, a ragged last group, a
+def test_streaming_path_with_17_to_96_rows(dtype):
+    """Two to six groups of 16 rows of A per workgroup: every group boundary, a ragged last group, a
     ragged last strip of columns, a ragged last K tile for every wave, batches, padded leading dimensions,
     scales and bias; and the rule that hands such a product to the tiled kernel when its strips are few."""
     cases = [(17, 4100, 520, {}), (32, 4096, 1024, {}), (33, 8200, 264, {}), (47, 520, 1160, dict(batch=16, scaled=True)),
-             (48, 8192, 128, dict(biased=True)), (49, 8256, 392, {}), (64, 8192, 2048, {}),
+             (48, 8192, 128, dict(biased=True)), (49, 8256, 392, {}), (64, 8192, 2048, {}), (65, 8200, 392, {}),
+             (81, 530, 1160, dict(batch=16, scaled=True, biased=True)), (96, 8192, 1024, {}),
              (20, 130, 1320, dict(batch=32, lda=1328, ldb=1336, ldc=136)), (64, 70, 776, dict(batch=70, scaled=True))]
     for (M, N, K, kw) in cases:
         out = gen.BF16 if dtype == gen.E4M3 else dtype
@@ -145,12 +146,12 @@ def test_streaming_path_with_17_to_64_rows(dtype):
         d = gemm.make_desc(M, N, K, dtype, out, ROW, COL, lda=inp.lda, ldb=inp.ldb, ldc=inp.ldc, batch=cfg.batch,
                            stride_a=inp.stride_a, stride_b=inp.stride_b, stride_c=inp.stride_c)
         q = gemm.gemm_query(4, d)
-        assert q.path == "mfma16-stream(small-M)" and q.bm == 16 * ((M + 15) // 16) and q.bn == (32 if M <= 32 else 64), (M, N, K, q)
+        assert q.path == "mfma16-stream(small-M)" and q.bm == (16 * ((M + 15) // 16) if M <= 64 else 96) and q.bn == (32 if M <= 32 else 64), (M, N, K, q)
         ref = oracle_for(inp)
         check(4, inp, ref)
         check(4, inp, ref, out_dtype=gen.F32)
     # too few strips for the chip: the tiled kernel keeps the product
-    for (M, N) in ((17, 4064), (64, 8128), (33, 4096)):
+    for (M, N) in ((17, 4064), (64, 8128), (33, 4096), (96, 8128), (97, 16384)):
         assert gemm.gemm_query(4, gemm.make_desc(M, N, 1024, dtype, out, ROW, COL)).path.startswith("mfma32-direct-to-lds")
 
 
@@ -161,6 +162,7 @@ def test_streaming_path_with_few_columns(dtype):
     ragged K tiles, padded leading dimensions, batches, fp32 output."""
     cases = [(200, 16, 1024, {}), (4100, 7, 136, dict(biased=True)), (300, 1, 8, {}), (4100, 17, 520, dict(biased=True)),
              (8200, 33, 264, {}), (8192, 64, 2048, dict(biased=True, ldc=72)), (530, 48, 1160, dict(batch=16, scaled=True, biased=True)),
+             (8200, 80, 392, dict(biased=True)),
              (70, 16, 1320, dict(batch=3, lda=1328, ldb=1336, ldc=24))]
     for (M, N, K, kw) in cases:
         out = gen.BF16 if dtype == gen.E4M3 else dtype
@@ -172,7 +174,7 @@ def test_streaming_path_with_few_columns(dtype):
         d = gemm.make_desc(M, N, K, dtype, out, ROW, COL, lda=inp.lda, ldb=inp.ldb, ldc=inp.ldc, batch=cfg.batch,
                            stride_a=inp.stride_a, stride_b=inp.stride_b, stride_c=inp.stride_c)
         q = gemm.gemm_query(4, d)
-        assert q.path == "mfma16-stream(small-N)" and q.bn == 16 * ((N + 15) // 16), (M, N, K, q)
+        assert q.path == "mfma16-stream(small-N)" and q.bn == (16 * ((N + 15) // 16) if N <= 64 else 96), (M, N, K, q)
         ref = oracle_for(inp)
         check(4, inp, ref)
         check(4, inp, ref, out_dtype=gen.F32)

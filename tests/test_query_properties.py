@@ -64,16 +64,17 @@ def test_expert_state_paths_and_scratch(p):
                and (p["ldb"] * es) % 16 == 0 and (p["batch"] == 1 or ((p["M"] * p["lda"] * es) % 16 == 0 and (p["N"] * p["ldb"] * es) % 16 == 0)))
     kvec, kslab = 16 // es, 128 // es
     cols = 16 if p["M"] <= 16 else 32 if p["M"] <= 32 else 64
-    streams = p["M"] <= 16 or (p["M"] <= 64 and math.ceil(p["N"] / cols) * p["batch"] >= 128)
+    streams = p["M"] <= 16 or (p["M"] <= 96 and math.ceil(p["N"] / cols) * p["batch"] >= 128)
+    group_rows = lambda r: 16 if r <= 16 else 32 if r <= 32 else 48 if r <= 48 else 64 if r <= 64 else 96   # rows a form holds
     if fast_ok and streams and p["K"] % kvec == 0:
         assert q.path == "mfma16-stream(small-M)" and q.workspace_bytes == 0
-        assert q.bn == cols and q.bm == 16 * math.ceil(max(p["M"], 1) / 16) and q.grid == math.ceil(p["N"] / cols) * p["batch"]
-    elif (fast_ok and p["K"] % kvec == 0 and p["M"] > 64 and p["N"] <= 64
+        assert q.bn == cols and q.bm == group_rows(p["M"]) and q.grid == math.ceil(p["N"] / cols) * p["batch"]
+    elif (fast_ok and p["K"] % kvec == 0 and p["M"] > p["N"] and p["N"] <= 96
           and (p["N"] <= 16 or math.ceil(p["M"] / (32 if p["N"] <= 32 else 64)) * p["batch"] >= 128)):
         # few columns: the streaming kernel on the transposed product, strips along M
         strip = 16 if p["N"] <= 16 else 32 if p["N"] <= 32 else 64
         assert q.path == "mfma16-stream(small-N)" and q.workspace_bytes == 0
-        assert q.bm == strip and q.bn == 16 * math.ceil(max(p["N"], 1) / 16) and q.grid == math.ceil(p["M"] / strip) * p["batch"]
+        assert q.bm == strip and q.bn == group_rows(p["N"]) and q.grid == math.ceil(p["M"] / strip) * p["batch"]
     elif fast_ok and p["K"] % kslab == 0:
         assert q.path.startswith("mfma32-direct-to-lds") and q.violated == 0
         # split-K: offered (through workspace_bytes) when the product has few tiles and a long K, taken when scratch is lent
