@@ -3,7 +3,7 @@
  * (AMD Instinct MI355X, gfx950).
  *
  * The paper's second workload (Sec. 4.1, workload table: Conv2d, N=8, C=64, H=W=56, F=128, 3x3,
- * stride 1, padding 1, FP16) reaches its expert state along "im2col + tensor core" (Sec. 4.3); a
+ * stride 1, padding 1, FP16) reaches its expert state along "im2col + tensor core" (Sec. 4.2); a
  * matrix intrinsic without staging, swizzle and pipelining stays 5-14x behind (Sec. 4.4, generated-only
  * ablation).  Here the layer is a short lineage of three states, the last two on the GEMM lineage's
  * K4 kernel:

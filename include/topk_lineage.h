@@ -3,7 +3,7 @@
  *
  * The paper's selection workload (Sec. 4.1, workload table: Top-K, batch 64, sequence 4096, k = 512,
  * FP32) reaches its expert state by one algorithmic step, from selection sort to radix select
- * (Sec. 4.3; Table 1 lists `radix_select` with the carrier "coarse + refine pass").  Three states:
+ * (Sec. 4.2; Table 1 lists `radix_select` with the carrier "coarse + refine pass").  Three states:
  *
  *     T0 selection        k rounds of a workgroup-wide arg-max over the not yet taken elements
  *     T1 radix select     the k-th largest key by four 8-bit histogram passes over the row (most

@@ -1,4 +1,4 @@
-// Convolution layer (paper Sec. 4.1 workload table: Conv2d; Sec. 4.3: "im2col + tensor core"): the two
+// Convolution layer (paper Sec. 4.1 workload table: Conv2d; Sec. 4.2: "im2col + tensor core"): the two
 // kernels of its own that the layer's lineage needs (direct, im2col), and the C ABI that dispatches a
 // state either to them or to the GEMM lineage's K4 kernel (plain for C1, gathering for C2).
 #include <stdio.h>

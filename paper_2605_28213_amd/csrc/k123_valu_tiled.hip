@@ -4,7 +4,7 @@
 //                                    BK slabs staged through LDS; each thread owns TM x TN outputs.
 //   K2 = K1 + "vectorize_global"     slabs are fetched with 16-byte global loads along the
 //                                    contiguous dimension.  Precondition (Table 1: 128-bit aligned
-//                                    access; Sec. 1: alignment and valid tail handling): base pointer
+//                                    access; Sec. 1): base pointer
 //                                    and leading dimension multiples of 16 bytes.  A vector that
 //                                    crosses the M/N/K edge, or an operand that breaks the
 //                                    precondition, is fetched element by element under a mask.

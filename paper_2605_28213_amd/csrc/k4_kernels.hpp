@@ -2,8 +2,7 @@
 // CDNA4 as wave64 MFMA with fp32 accumulators and an LDS operand layout in which the 16-byte
 // fragment reads of a wave are bank-conflict free.
 //
-// Preconditions recorded for this state (Table 1: "tile fits mma", "mma fragment layout";
-// Sec. 1: matrix intrinsics need compatible tile shapes, layouts and hardware support):
+// Preconditions recorded for this state (Table 1: "tile fits mma", "mma fragment layout"; Sec. 1):
 //   - the input dtype has a matrix instruction (bf16, fp16, OCP e4m3);
 //   - the fast kernel needs K contiguous in both operands, 16-byte aligned bases and leading
 //     dimensions, and K a whole number of 128-byte slabs; otherwise the masked kernel gathers
@@ -299,9 +298,9 @@ __device__ __forceinline__ void for_each_step(std::integer_sequence<int, KS...>,
     (f(std::integral_constant<int, KS>{}), ...);
 }
 
-// SWIZZLE and OVERLAP are on in the expert state.  Switching one off gives a validated simplification
-// of it (paper Sec. 3.2: a backward step removes or weakens one optimisation and must still pass the
-// gate); the latency it costs is the evidence for what that optimisation buys on this hardware.
+// SWIZZLE and OVERLAP are on in the expert state.  Switching one off is one edge of the backward walk
+// from it (paper Sec. 3.2); the result goes through the gate like any state, and the latency it costs
+// is the evidence for what that optimisation buys on this hardware.
 //   SWIZZLE = false: LDS rows keep their chunks in order; a wave's operand read then hits the same
 //                    banks from all 32 rows
 //   OVERLAP = false: every group of direct loads is waited for right after it is issued, so no load is

@@ -1,4 +1,4 @@
-// Row-wise top-k selection (paper Sec. 4.1 workload table: Top-K; Sec. 4.3: selection sort -> radix
+// Row-wise top-k selection (paper Sec. 4.1 workload table: Top-K; Sec. 4.2: selection sort -> radix
 // select; Table 1: `radix_select`, "coarse + refine pass"): the kernels of its three states and the C ABI.
 // One workgroup per row.  A value's key is its bit pattern made monotone (sign bit flipped for
 // non-negative values, all bits for negative ones; -0.0 takes +0.0's key), so "k-th largest value" is

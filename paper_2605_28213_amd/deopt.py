@@ -1,5 +1,5 @@
 """Guided deoptimisation trace of the expert GEMM state (paper Sec. 3.2 and the deoptimisation-trace
-figure of Sec. 4.6: the expert kernel is walked backwards, one optimisation removed per edge, every
+figure of Sec. 4.5: the expert kernel is walked backwards, one optimisation removed per edge, every
 intermediate state re-validated, the latency of each recorded; the inverse edges are the lineage's
 forward skills).
 

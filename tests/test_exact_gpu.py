@@ -1,0 +1,194 @@
+"""Bit-exact parity of every code path of the expert state (K4) with the CPU oracle, through the C ABI.
+
+Operand entries are integers in {-2..2} (exact in bf16, fp16 and e4m3) and the output is fp32: every
+partial sum of every summation order is an integer below 2^24, so a correct fp32-accumulating kernel
+must reproduce the oracle's product bit for bit.  A dropped, doubled or misplaced K slab, a wrong
+fragment, a stale LDS region or a mis-stored element cannot hide under a tolerance here.
+
+Each case names the code path it is meant for and asserts, through gemm_query, that the planner takes
+it: the direct-to-LDS kernel with 256- and 128-tiles (K long enough that the steady-state ring loop
+runs several trips and leaves through the tail loop), its split-K form, the packed path in every
+layout pair, the row-remainder split, every form of the streaming kernel (16 rows, 16 rows with K
+split over waves, 32, 48, 64, 96 rows, few columns), the simplified expert states, and the headline
+workload's shape at full size.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2605_28213_amd import gemm
+from paper_2605_28213_amd import inputs as gen
+from tests import util
+
+pytestmark = pytest.mark.gpu
+
+ROW, COL = gen.ROW_MAJOR, gen.COL_MAJOR
+K4 = gemm.GEMM_K4_MFMA
+DTYPES = [gen.BF16, gen.F16, gen.E4M3]
+
+
+def int_inputs(dtype, M, N, K, la=ROW, lb=COL, *, batch=1, lda=0, ldb=0, ldc=0, seed=0, biased=False):
+    """Operands with integer entries in {-2..2}, laid out as the descriptor says; gaps between rows
+    (leading dimension beyond the extent) hold 3, which a kernel reading them would add in."""
+    cfg = gen.Config("ints", M, N, K, dtype, gen.F32, la, lb, "uniform", batch=batch, lda=lda, ldb=ldb, ldc=ldc, biased=biased)
+    lda, ldb, ldc = cfg.ld
+    rows_a, ext_a = (M, K) if la == ROW else (K, M)
+    rows_b, ext_b = (K, N) if lb == ROW else (N, K)
+    rng = np.random.default_rng(1000 + seed)
+
+    def draw(rows, ext, ld):
+        x = np.full((batch, rows, ld), 3.0, dtype=np.float32)
+        x[:, :, :ext] = rng.integers(-2, 3, (batch, rows, ext)).astype(np.float32)
+        return gen.quantise(dtype, x.reshape(-1))
+    A, B = draw(rows_a, ext_a, lda), draw(rows_b, ext_b, ldb)
+    bias = rng.integers(-5, 6, N).astype(np.float32) if biased else None
+    return gen.Inputs(cfg, seed, A, B, lda, ldb, ldc, rows_a * lda, rows_b * ldb, M * ldc, None, None, bias)
+
+
+def oracle_for(inp):
+    c = inp.cfg
+    return oracle.gemm(c.in_dtype, c.layout_a, c.layout_b, c.M, c.N, c.K, inp.A, inp.lda, inp.B, inp.ldb, batch=c.batch,
+                       stride_a=inp.stride_a, stride_b=inp.stride_b, bias=inp.bias)
+
+
+def run_exact(inp, path, *, flags=0, lend=False, exact_path=True):
+    """Runs K4 on `inp`, asserts the planner's path, and compares every output with the oracle bit for bit."""
+    c = inp.cfg
+    d = gemm.make_desc(c.M, c.N, c.K, c.in_dtype, gen.F32, c.layout_a, c.layout_b, lda=inp.lda, ldb=inp.ldb, ldc=inp.ldc,
+                       batch=c.batch, stride_a=inp.stride_a, stride_b=inp.stride_b, stride_c=inp.stride_c, flags=flags)
+    q = gemm.gemm_query(K4, d)
+    if lend:
+        assert q.workspace_bytes > 0, (q.path, "asks for no scratch")
+        d.workspace, d.workspace_bytes = 4096, q.workspace_bytes        # any aligned non-null address: query only
+        q = gemm.gemm_query(K4, d)
+    assert (q.path == path) if exact_path else (path in q.path), (q.path, path, (c.M, c.N, c.K, c.batch))
+    C_ref, _ = oracle_for(inp)
+    rc, C, _ = util.run_config(K4, inp, flags=flags, lend_workspace=lend)
+    assert rc == gemm.GEMM_OK, gemm.gemm_status_string(rc)
+    np.testing.assert_array_equal(C[:, :, : c.N], C_ref, err_msg=f"{q.path} {(c.M, c.N, c.K, c.batch)}")
+    return q
+
+
+def slabs(dtype, n):
+    """K of n whole 128-byte slabs."""
+    return n * 128 // gen.ELEM_BYTES[dtype]
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("tile_flag,bm", [(gemm.GEMM_FLAG_TILE_256, 256), (gemm.GEMM_FLAG_TILE_128, 128), (0, 0)])
+def test_direct_to_lds_kernel_is_exact(dtype, tile_flag, bm):
+    """M and N cross tile edges and end inside a tile; 24 slabs: first slab, four trips of the five-slab
+    ring loop, three slabs of tail.  Also 7 and 11 slabs (one trip; tail of every length class), a batch,
+    and a leading dimension beyond K."""
+    for (M, N, ns, nb, pad) in [(520, 300, 24, 2, 0), (257, 513, 7, 1, 0), (300, 260, 11, 3, 1), (256, 256, 12, 1, 0)]:
+        K = slabs(dtype, ns)
+        ld = K + pad * 128 // gen.ELEM_BYTES[dtype]      # rows 128 bytes apart from tight
+        inp = int_inputs(dtype, M, N, K, batch=nb, lda=ld, ldb=ld, seed=ns)
+        q = run_exact(inp, "mfma32-direct-to-lds", flags=tile_flag)
+        if bm:
+            assert q.bm == bm
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("flags,tag", [(gemm.GEMM_FLAG_DEOPT_NO_SWIZZLE, "-noswz"), (gemm.GEMM_FLAG_DEOPT_NO_OVERLAP, "-noovl"),
+                                       (gemm.GEMM_FLAG_DEOPT_NO_RASTER, "-noraster"),
+                                       (gemm.GEMM_FLAG_DEOPT_NO_RASTER | gemm.GEMM_FLAG_TILE_128, "-noraster")])
+def test_simplified_expert_states_are_exact(dtype, flags, tag):
+    inp = int_inputs(dtype, 520, 300, slabs(dtype, 17), batch=2, seed=3)
+    run_exact(inp, "mfma32-direct-to-lds" + tag, flags=flags)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_split_k_form_is_exact(dtype):
+    """Few tiles, long K, scratch lent: K ranges as batch items of the fast kernel, then the adding pass."""
+    for (M, N, ns, kw) in [(100, 300, 64, dict(biased=True)), (200, 257, 32, {}), (64, 1024, 128, dict(ldc=1032))]:
+        inp = int_inputs(dtype, M, N, slabs(dtype, ns), seed=ns, **kw)
+        run_exact(inp, "+splitK(", lend=True, exact_path=False)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("la,lb,path", [(ROW, ROW, "mfma32-packed+direct-to-lds"), (COL, ROW, "mfma32-packed+direct-to-lds"),
+                                        (COL, COL, "mfma32-packed+direct-to-lds"), (ROW, COL, "mfma32-packed+direct-to-lds")])
+def test_packed_path_is_exact(dtype, la, lb, path):
+    """Odd leading dimensions and a ragged K in every layout pair, scratch lent: both pack kernels (rows
+    and transposing), zero padding of K, then the fast kernel on the copies."""
+    M, N, K = 300, 270, 1203
+    inp = int_inputs(dtype, M, N, K, la, lb, batch=2, lda=(K if la == ROW else M) + 3, ldb=(N if lb == ROW else K) + 5,
+                     ldc=N + 1, seed=7)
+    run_exact(inp, path, lend=True)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("la,lb,tag", [(ROW, ROW, "(B)"), (COL, COL, "(A)")])
+def test_packed_path_with_one_operand_in_place_is_exact(dtype, la, lb, tag):
+    inp = int_inputs(dtype, 392, 264, slabs(dtype, 9), la, lb, batch=2, seed=8)
+    run_exact(inp, "mfma32-packed%s+direct-to-lds" % tag, lend=True)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("rem", [3, 17, 48, 64])
+def test_row_remainder_split_is_exact(dtype, rem):
+    """16 rows of 256-tiles by 16 columns plus a thin remainder: the tiled kernel and the streaming kernel
+    (one, two, three, four groups of rows) each write their part of one C."""
+    inp = int_inputs(dtype, 4096 + rem, 4096, slabs(dtype, 8), seed=rem)
+    run_exact(inp, "mfma32-direct-to-lds+stream(M-tail)")
+
+
+STREAM_CASES = [  # (M, N, K in 2-byte units, batch, what)
+    (16, 8200, 1032, 1, "16 rows, one wave per strip of 16 columns"),
+    (9, 1000, 2056, 1, "16 rows, K tiles dealt to 4 waves"),
+    (32, 4100, 1032, 1, "two groups of rows"),
+    (47, 8200, 520, 1, "three groups"),
+    (64, 8200, 520, 1, "four groups"),
+    (96, 8200, 520, 1, "six groups"),
+    (81, 530, 1160, 16, "six groups, batched"),
+]
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("case", STREAM_CASES, ids=[c[4] for c in STREAM_CASES])
+def test_streaming_kernel_is_exact(dtype, case):
+    """Every form of the streaming kernel, with ragged row groups, a ragged last strip and a ragged last K
+    tile (K a multiple of 16 bytes only)."""
+    M, N, K2, nb, _ = case
+    K = K2 * 2 // gen.ELEM_BYTES[dtype]
+    q = run_exact(int_inputs(dtype, M, N, K, batch=nb, seed=M), "mfma16-stream(small-M)")
+    assert q.bm == (16 * ((M + 15) // 16) if M <= 64 else 96)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_streaming_kernel_on_few_columns_is_exact(dtype):
+    for (M, N, K2) in [(4100, 7, 136), (8200, 33, 264), (8200, 80, 392)]:
+        K = K2 * 2 // gen.ELEM_BYTES[dtype]
+        run_exact(int_inputs(dtype, M, N, K, seed=N, biased=True), "mfma16-stream(small-N)")
+
+
+@pytest.mark.parametrize("dtype", DTYPES + [gen.F32])
+def test_masked_kernel_is_exact(dtype):
+    """No scratch, ragged K, odd leading dimensions: the masked kernel in both of its tile sizes."""
+    for (M, N, K) in [(259, 130, 1000), (1100, 2100, 203)]:
+        inp = int_inputs(dtype, M, N, K, ROW, ROW, lda=K + 1, ldb=N + 3, seed=K)
+        run_exact(inp, "mfma32-elementwise-masked" if dtype != gen.E4M3 else "mfma32-", exact_path=False)
+
+
+def test_headline_shape_full_size_is_exact():
+    """bf16 8192^3, A row-major, B column-major, fp32 out, integer-valued operands: all 67 million outputs
+    of the launch configuration the benchmark times (256-tiles, 1024 workgroups, 128 slabs each) against
+    the oracle's full product.  Partial sums stay below 4 * 8192 < 2^24."""
+    M = N = K = 8192
+    rng = np.random.default_rng(8192)
+    A = gen.quantise(gen.BF16, rng.integers(-2, 3, M * K).astype(np.float32))
+    B = gen.quantise(gen.BF16, rng.integers(-2, 3, N * K).astype(np.float32))
+    cfg = gen.Config("C2_ints", M, N, K, gen.BF16, gen.F32, ROW, COL, "uniform")
+    inp = gen.Inputs(cfg, 0, A, B, K, K, N, M * K, N * K, M * N)
+    d = gemm.make_desc(M, N, K, gen.BF16, gen.F32, ROW, COL)
+    q = gemm.gemm_query(K4, d)
+    assert q.path == "mfma32-direct-to-lds" and q.bm == 256 and q.grid == 1024
+    C_ref, _ = oracle_for(inp)
+    rc, C, _ = util.run_config(K4, inp)
+    assert rc == gemm.GEMM_OK
+    C = C.reshape(M, N)
+    bad = np.flatnonzero(C != C_ref[0])
+    assert bad.size == 0, f"{bad.size} outputs differ, first at {np.unravel_index(bad[0], (M, N))}"
+    torch.cuda.empty_cache()
