@@ -21,9 +21,13 @@
  *   - The library allocates and frees nothing and keeps no state between calls.
  *   - Launches are asynchronous on the given stream; nothing synchronises.
  *   - Errors are returned as gemm_status_t values; no exception crosses the ABI.
- *     On any status other than GEMM_OK no kernel was launched and C is untouched.
- *   - A variant never substitutes another variant (Sec. B "wrapper" audit: a
- *     submission that falls back to a reference is not a kernel).  When the
+ *     Argument, variant, dtype, precondition and workspace errors are found before
+ *     anything is launched: C and the workspace are untouched.  GEMM_ERR_LAUNCH comes
+ *     from the HIP runtime in the middle of a call that may consist of several
+ *     launches (pack + product, product + row remainder, K ranges + their sum):
+ *     after it, C and the workspace are unspecified.
+ *   - A variant never substitutes another variant (App. B audits submissions for
+ *     wrappers around a reference; a state of this lineage is always its own kernel).  When the
  *     fast path of a variant does not apply, either its own documented slow
  *     path runs (and gemm_query names it) or, with GEMM_FLAG_STRICT, the call
  *     is refused with GEMM_ERR_PRECONDITION.
@@ -65,9 +69,9 @@ typedef enum {
     GEMM_VARIANT_COUNT = 5
 } gemm_variant_t;
 
-/* Conditions a variant may rely on (Table 1's precondition column; Sec. 1: vectorised
- * loads need alignment and tail handling, pipelining needs staged data movement, matrix
- * intrinsics need compatible tile shapes, layouts and hardware support). */
+/* Conditions a variant may rely on: one bit per entry of Table 1's precondition column as it
+ * applies to this product on gfx950 (Sec. 1 names the same three families: access width,
+ * staging, matrix-instruction shape). */
 enum {
     GEMM_COND_ALIGN16_A      = 1u << 0,  /* base pointer of A (incl. batch stride) is 16-byte aligned */
     GEMM_COND_ALIGN16_B      = 1u << 1,
@@ -82,15 +86,15 @@ enum {
     GEMM_COND_K_CONTIG_B     = 1u << 10, /* B stored with K contiguous (column-major) */
     GEMM_COND_DTYPE_HAS_MFMA = 1u << 11, /* the input dtype has a matrix instruction on gfx950 (all four do) */
     GEMM_COND_LDS_STAGED     = 1u << 12, /* operands pass through LDS (holds from K1 on) */
-    GEMM_COND_SMALL_M        = 1u << 13  /* M <= 96: few enough rows for the streaming (bandwidth-bound) path (bf16, fp16, e4m3); with 17..96 rows K4 takes it when the strips of 32 (up to 32 rows) or 64 columns number at least 128.  A product of at most 96 columns, fewer than its rows, that does not stream by its rows takes the same path transposed (path "...(small-N)"), under the same rule with rows and columns exchanged */
+    GEMM_COND_SMALL_M        = 1u << 13  /* M <= 96: few enough rows for K4's streaming (bandwidth-bound) kernel */
 };
 
 enum {
     GEMM_FLAG_STRICT = 1u << 0, /* refuse (GEMM_ERR_PRECONDITION) instead of taking a variant's slow path */
-    /* Validated simplifications of the expert state (Sec. 3.2, guided deoptimisation: a backward step
-     * removes or weakens one optimisation and must still pass the gate).  Only K4's fast kernel has them;
-     * on any other variant or path they are refused with GEMM_ERR_BAD_ARG.  Same result, slower: the
-     * latency difference is the evidence for what the optimisation buys. */
+    /* Edges of the backward walk from the expert state (Sec. 3.2): each switches one optimisation of
+     * K4's fast kernel off, and the result goes through the gate like any state.  On any other variant
+     * or path they are refused with GEMM_ERR_BAD_ARG.  Same result, slower: the latency difference is
+     * the evidence for what the optimisation buys. */
     GEMM_FLAG_DEOPT_NO_SWIZZLE = 1u << 1, /* LDS operand rows unswizzled: fragment reads conflict on banks */
     GEMM_FLAG_DEOPT_NO_OVERLAP = 1u << 2, /* loads waited for at once: nothing in flight under the MFMAs */
     /* Tile override for K4's fast kernel (Table 1 "autotune": the sweep that froze the default choice
@@ -153,7 +157,8 @@ typedef struct {
 } gemm_query_t;
 
 /*
- * gemm_run: the short form named in the lineage's problem statement.  Batch 1, tight
+ * gemm_run: one validated state of the lineage L = (K0, ..., K*) of Sec. 3.1 applied to one product,
+ * short form.  Batch 1, tight
  * leading dimensions, output dtype = input dtype (bf16 for fp8 input), no scales, default
  * stream, layouts A row-major and B row-major for GEMM_F32/GEMM_F16, A row-major and B
  * column-major (K contiguous) for GEMM_BF16/GEMM_FP8_E4M3.
@@ -161,10 +166,12 @@ typedef struct {
 int gemm_run(int variant, int64_t M, int64_t N, int64_t K, int dtype,
              const void *A, const void *B, void *C);
 
-/* gemm_run_ex: full form.  Validates, checks the variant's conditions, launches on d->stream. */
+/* gemm_run_ex: full form of the same (Sec. 3.1: the state the gate compiles, checks and profiles; Table 1:
+ * the conditions it checks).  Validates, checks the variant's conditions, launches on d->stream. */
 int gemm_run_ex(int variant, const gemm_desc_t *d, const void *A, const void *B, void *C);
 
-/* gemm_query: host only, launches nothing.  Reports which conditions the variant relies on,
+/* gemm_query: host only, launches nothing.  The deterministic part of a skill record's `pre` field
+ * (Sec. 3.1) for this call.  Reports which conditions the variant relies on,
  * which of them this call violates, the path that would run and its launch geometry.  A, B, C
  * may be NULL (then the ALIGN16 conditions are reported as holding).  Returns the status
  * gemm_run_ex would return before launching. */
