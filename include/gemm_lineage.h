@@ -170,6 +170,24 @@ int gemm_run(int variant, int64_t M, int64_t N, int64_t K, int dtype,
  * the conditions it checks).  Validates, checks the variant's conditions, launches on d->stream. */
 int gemm_run_ex(int variant, const gemm_desc_t *d, const void *A, const void *B, void *C);
 
+/*
+ * gemm_run_static: gemm_run_ex for callers that cannot allocate device memory and have none to lend:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * checks, paths, kernels and results as gemm_run_ex, except that d->workspace must be NULL and
+ * d->workspace_bytes 0 (else GEMM_ERR_BAD_ARG): where K4's packed or split-K path wants scratch, it
+ * uses a fixed array of GEMM_STATIC_SCRATCH_BYTES that is part of the loaded library (each GPU the
+ * library runs on holds its own copy until the process ends).  A call whose path wants more than
+ * that is refused with GEMM_ERR_WORKSPACE before anything is launched (gemm_query with a non-NULL
+ * workspace reports the size a call wants).  The call allocates and frees nothing.  Its very first
+ * call on a device looks the array's address up (once; outside graph capture).  All calls on one GPU
+ * share the array, whose contents are unspecified between calls (every path writes what it reads, so
+ * nothing needs clearing): calls that use it and overlap on one GPU -- different streams, or threads
+ * -- race; order them on one stream.
+ */
+#define GEMM_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+int gemm_run_static(int variant, const gemm_desc_t *d, const void *A, const void *B, void *C);
+size_t gemm_static_scratch_bytes(void);
+
 /* gemm_query: host only, launches nothing.  The deterministic part of a skill record's `pre` field
  * (Sec. 3.1) for this call.  Reports which conditions the variant relies on,
  * which of them this call violates, the path that would run and its launch geometry.  A, B, C

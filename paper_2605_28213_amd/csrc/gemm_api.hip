@@ -8,14 +8,43 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "common.hpp"
 
 using namespace gl;
 
+// Scratch of gemm_run_static: device memory that belongs to the loaded code object, one copy per GPU,
+// held until the process ends.  In host code the array's name only stands for the symbol; the address a
+// kernel can use is looked up once per device (static_scratch_of) and passed on like a lent workspace.
+static __device__ __align__(256) unsigned char scratch[GEMM_STATIC_SCRATCH_BYTES];
+
 namespace {
 
-constexpr int ABI_VERSION = 2;
+constexpr int ABI_VERSION = 3;
 thread_local hipError_t last_launch_error = hipSuccess;   // of the calling thread's most recent GEMM_ERR_LAUNCH
+
+constexpr int MAX_DEVICES = 64;
+void* scratch_ptr[MAX_DEVICES];       // per device, filled on the first call with that device current
+std::mutex scratch_lock;
+
+hipError_t static_scratch_of(void** out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> hold(scratch_lock);
+    if (!scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        scratch_ptr[dev] = p;
+    }
+    *out = scratch_ptr[dev];
+    return hipSuccess;
+}
 
 bool aligned16(const void* p, int64_t batch, int64_t stride, int es)
 {
@@ -234,6 +263,22 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
     return p;
 }
 
+// Launches the kernel(s) of a plan that make_plan accepted.
+int run_plan(int variant, const Plan& p)
+{
+    (void)hipGetLastError();   // the thread's last-error slot may hold someone else's stale error: GEMM_ERR_LAUNCH must mean this launch
+    hipError_t e;
+    switch (variant) {
+    case GEMM_K0_NAIVE: e = launch_k0(p.args); break;
+    case GEMM_K1_LDS_TILED:
+    case GEMM_K2_VECTORIZED:
+    case GEMM_K3_PIPELINED: e = launch_valu_tiled(variant, p.path, p.args); break;
+    default: e = launch_k4(p.path, p.args); break;
+    }
+    if (e != hipSuccess) last_launch_error = e;
+    return e == hipSuccess ? GEMM_OK : GEMM_ERR_LAUNCH;
+}
+
 }  // namespace
 
 extern "C" {
@@ -272,17 +317,26 @@ int gemm_run_ex(int variant, const gemm_desc_t* d, const void* A, const void* B,
     Plan p = make_plan(variant, d, A, B, C, /*need_ptrs=*/true);
     if (p.status != GEMM_OK) return p.status;
     if (p.empty) return GEMM_OK;
-    (void)hipGetLastError();   // the thread's last-error slot may hold someone else's stale error: GEMM_ERR_LAUNCH must mean this launch
-    hipError_t e;
-    switch (variant) {
-    case GEMM_K0_NAIVE: e = launch_k0(p.args); break;
-    case GEMM_K1_LDS_TILED:
-    case GEMM_K2_VECTORIZED:
-    case GEMM_K3_PIPELINED: e = launch_valu_tiled(variant, p.path, p.args); break;
-    default: e = launch_k4(p.path, p.args); break;
-    }
-    if (e != hipSuccess) last_launch_error = e;
-    return e == hipSuccess ? GEMM_OK : GEMM_ERR_LAUNCH;
+    return run_plan(variant, p);
+}
+
+size_t gemm_static_scratch_bytes(void) { return GEMM_STATIC_SCRATCH_BYTES; }
+
+int gemm_run_static(int variant, const gemm_desc_t* d, const void* A, const void* B, void* C)
+{
+    if (!d) return GEMM_ERR_BAD_ARG;
+    if (d->workspace != nullptr || d->workspace_bytes != 0) return GEMM_ERR_BAD_ARG;   // this form brings its own scratch
+    void* ws = nullptr;
+    const hipError_t e = static_scratch_of(&ws);
+    if (e != hipSuccess) { last_launch_error = e; return GEMM_ERR_LAUNCH; }
+    gemm_desc_t own = *d;
+    own.workspace = ws;
+    own.workspace_bytes = GEMM_STATIC_SCRATCH_BYTES;
+    // a path that wants more scratch than the array holds comes back as GEMM_ERR_WORKSPACE from the plan
+    Plan p = make_plan(variant, &own, A, B, C, /*need_ptrs=*/true);
+    if (p.status != GEMM_OK) return p.status;
+    if (p.empty) return GEMM_OK;
+    return run_plan(variant, p);
 }
 
 const char* gemm_last_launch_error(void) { return hipGetErrorString(last_launch_error); }

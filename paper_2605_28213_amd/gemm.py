@@ -78,6 +78,10 @@ def lib() -> ctypes.CDLL:
         L.gemm_run.argtypes = [ci, i64, i64, i64, ci, vp, vp, vp]
         L.gemm_run_ex.restype = ci
         L.gemm_run_ex.argtypes = [ci, ctypes.POINTER(gemm_desc_t), vp, vp, vp]
+        L.gemm_run_static.restype = ci
+        L.gemm_run_static.argtypes = [ci, ctypes.POINTER(gemm_desc_t), vp, vp, vp]
+        L.gemm_static_scratch_bytes.restype = ctypes.c_size_t
+        L.gemm_static_scratch_bytes.argtypes = []
         L.gemm_query.restype = ci
         L.gemm_query.argtypes = [ci, ctypes.POINTER(gemm_desc_t), vp, vp, vp, ctypes.POINTER(gemm_query_t)]
         L.gemm_default_desc.restype = ci
@@ -149,6 +153,14 @@ def gemm_run(variant: int, M: int, N: int, K: int, dtype: int, A: Any, B: Any, C
 
 def gemm_run_ex(variant: int, d: gemm_desc_t, A: Any, B: Any, C: Any) -> int:
     return int(lib().gemm_run_ex(variant, ctypes.byref(d), _addr(A), _addr(B), _addr(C)))
+
+
+def gemm_run_static(variant: int, d: gemm_desc_t, A: Any, B: Any, C: Any) -> int:
+    return int(lib().gemm_run_static(variant, ctypes.byref(d), _addr(A), _addr(B), _addr(C)))
+
+
+def gemm_static_scratch_bytes() -> int:
+    return int(lib().gemm_static_scratch_bytes())
 
 
 @dataclass

@@ -25,7 +25,7 @@ def test_every_declared_symbol_is_exported():
     for n in sorted(names):
         assert hasattr(L, n), f"{n} declared in the header but not exported"
     assert gemm.gemm_variant_count() == gemm.GEMM_VARIANT_COUNT == 5
-    assert gemm.gemm_abi_version() == 2
+    assert gemm.gemm_abi_version() == 3
 
 
 def test_struct_layout_matches_the_header_as_plain_c(tmp_path):

@@ -98,3 +98,21 @@ def test_gathering_instantiation_keeps_two_workgroups_per_cu(asm):
         assert meta["lds"] == 80 * 1024 and meta["vgpr"] <= 256 and meta["vgpr_spill"] == 0 and meta["scratch"] == 0
         body = kernel_body(asm, "_ZN2gl12k4_mfma_fastINS_7FastCfgINS_" + dtype + "ELi128ELi8ELb1ELb1ELi0ELb1E")
         assert "v_readfirstlane_b32" not in first_inner_loop(body), "the activations' buffer resource must stay scalar"
+
+
+def test_static_scratch_array_is_a_visible_device_symbol(tmp_path):
+    """gemm_run_static finds its scratch array through hipGetSymbolAddress, which looks the name up in the
+    loaded code object: the array must be emitted as a global symbol of the declared size, 256-byte
+    aligned (a symbol kept local is not found and the runtime aborts the process)."""
+    src = os.path.join(ROOT, "paper_2605_28213_amd", "csrc", "gemm_api.hip")
+    out = tmp_path / "api.s"
+    flags = [f for f in gl_build.FLAGS if f != "-fPIC"]
+    r = subprocess.run(["hipcc", *flags, "-S", "--cuda-device-only", src, "-o", str(out)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr[-2000:]
+    text = out.read_text()
+    header = open(os.path.join(ROOT, "include", "gemm_lineage.h")).read()
+    mib = int(re.search(r"#define GEMM_STATIC_SCRATCH_BYTES \(\(size_t\)(\d+) << 20\)", header).group(1))
+    m = re.search(r"\.globl\s+(\w*scratch\w*)\n\s*\.p2align\s+(\d+)", text)
+    assert m, "the scratch array is not a global symbol of the device code"
+    assert int(m.group(2)) >= 8
+    assert re.search(r"\.size\s+%s, %d\b" % (re.escape(m.group(1)), mib << 20), text)
