@@ -48,6 +48,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=25)
+    ap.add_argument("--ramp-seconds", type=float, default=1.0,
+                    help="untimed launches of the headline kernel for this long before the warm-up (clock ramp from idle)")
     ap.add_argument("--no-extras", action="store_true", help="headline workload only (used for profiling)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     return ap.parse_args()
@@ -93,23 +95,37 @@ def main():
             d.workspace, d.workspace_bytes = ws.data_ptr(), need
         return inp, sets, d, (sa, sb, bias, ws)
 
-    def timed(variant, sets, d, steps, warmup):
-        """Returns (wall seconds for `steps` launches, list of per-launch ms from HIP events)."""
+    def timed(variant, sets, d, steps, warmup, ramp_s=0.0):
+        """Returns (wall seconds for `steps` launches, list of per-launch ms from HIP events, launches of the
+        clock-ramp phase).  The ramp phase (headline only) keeps the GPU busy with the same launches for
+        `ramp_s` seconds before the warm-up: an idle MI355X sits at a few hundred MHz and takes some tenths
+        of a second to reach the clock its power limit allows, far longer than a handful of warm-up launches."""
+        ramp_n = 0
+        t_ramp = time.perf_counter()
+        while time.perf_counter() - t_ramp < ramp_s:
+            for i in range(20):
+                A, B, C = sets[i % NSETS]
+                rc = gemm.gemm_run_ex(variant, d, A, B, C)
+                assert rc == gemm.GEMM_OK, gemm.gemm_status_string(rc)
+            stream.synchronize()
+            ramp_n += 20
         for i in range(warmup):
             A, B, C = sets[i % NSETS]
             rc = gemm.gemm_run_ex(variant, d, A, B, C)
             assert rc == gemm.GEMM_OK, gemm.gemm_status_string(rc)
         ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        rcs = [gemm.GEMM_OK] * steps
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(steps):
             A, B, C = sets[i % NSETS]
             ev[i][0].record(stream)
-            gemm.gemm_run_ex(variant, d, A, B, C)
+            rcs[i] = gemm.gemm_run_ex(variant, d, A, B, C)
             ev[i][1].record(stream)
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
-        return wall, [a.elapsed_time(b) for a, b in ev]
+        assert all(rc == gemm.GEMM_OK for rc in rcs), "a timed launch failed"
+        return wall, [a.elapsed_time(b) for a, b in ev], ramp_n
 
     def stats(ms):
         s = sorted(ms)
@@ -130,7 +146,12 @@ def main():
     cfg = gen.CONFIGS["C2"]
     inp, sets, d, keep = device_sets(cfg)
     q = gemm.gemm_query(gemm.GEMM_K4_MFMA, d, *sets[0])
-    wall, ms = timed(gemm.GEMM_K4_MFMA, sets, d, args.steps, args.warmup)
+    from paper_2605_28213_amd import telemetry
+    sampler = telemetry.Sampler(interval=0.01).start()
+    t_phase = time.perf_counter()
+    wall, ms, ramp_n = timed(gemm.GEMM_K4_MFMA, sets, d, args.steps, args.warmup, ramp_s=args.ramp_seconds)
+    t_end = time.perf_counter() - t_phase
+    samples = sampler.stop()
     st = stats(ms)
     value = cfg.flops * args.steps / wall / 1e12
     out = {
@@ -147,7 +168,18 @@ def main():
                    "cache_state": f"operands rotated over {NSETS} buffer sets"},
         "launch_us": st,
         "roofline": roofline_for(cfg, st["mean_us"], "mfma"),
+        "clock_ramp": {"seconds": args.ramp_seconds, "launches": ramp_n,
+                       "what": "untimed launches of the same kernel before the warm-up, so that the timed steps do not run on a clock still rising from idle"},
     }
+    # launch statistics of the timed steps (the first five apart: a clock still ramping would show there)
+    out["roofline"]["launch_stats_us"] = {"min": st["min_us"], "median": st["median_us"], "p90": st["p90_us"], "mean": st["mean_us"],
+                                          "first_five": [1e3 * x for x in ms[:5]]}
+    # socket power and shader clock sampled over the timed steps and the last half second before them
+    win = [x for x in samples if x[0] >= t_end - wall - 0.5]
+    ps = telemetry.Sampler.summary(win)
+    out["roofline"]["power"] = {"cap_w": sampler.power_cap_w(), "socket_w_mean": ps["power_w_mean"], "socket_w_max": ps["power_w_max"],
+                                "sclk_mhz_mean": ps["sclk_mhz_mean"], "sclk_mhz_min": ps["sclk_mhz_min"], "samples": ps["samples"],
+                                "source": "hwmon power1_input and pp_dpm_sclk, sampled every 10 ms"}
     if kernel_sources_digest() == TRAFFIC_C2["sources_sha256"]:
         out["roofline"]["traffic"] = TRAFFIC_C2["bytes"]
 
@@ -156,7 +188,7 @@ def main():
         lineage = {}
         for v in range(gemm.gemm_variant_count()):
             n = 2 if v == 0 else 10
-            _, vms = timed(v, sets, d, n, 1)
+            _, vms, _ = timed(v, sets, d, n, 1)
             m = sorted(vms)[len(vms) // 2]
             lineage[gemm.gemm_variant_name(v)] = {"median_us": 1e3 * m, "TFLOP/s": cfg.flops / (m * 1e-3) / 1e12,
                                                   "path": gemm.gemm_query(v, d, *sets[0]).path, "launches": n}
@@ -232,7 +264,7 @@ def main():
             c = gen.CONFIGS[name]
             v = gemm.GEMM_K4_MFMA
             _, s2, d2, keep2 = device_sets(c)
-            _, sms = timed(v, s2, d2, 100, 25)
+            _, sms, _ = timed(v, s2, d2, 100, 25)
             ss = stats(sms)
             rl = roofline_for(c, ss["mean_us"], bound)
             entry = {"variant": gemm.gemm_variant_name(v), "path": gemm.gemm_query(v, d2, *s2[0]).path,
@@ -328,6 +360,41 @@ def main():
                                "cores": oracle.num_threads(), "kind": "oracle",
                                "sample": f"first {rows} rows of C of the same product ({rows}x8192x8192), {dt:.1f} s, "
                                          "fp64 triple loop incl. operand decode"}
+        # ---- gate pass rate (the other half of the metric): correctness legs against the oracle -------
+        # every state on the five reduced workloads at seeds 0..2 (whole product), and the expert state on
+        # the five full-size workloads at seed 0 (sampled outputs: random points, first and last row and column)
+        from paper_2605_28213_amd import gate
+        entries = []
+
+        def whole(c):
+            return lambda i: gate.Reference(*oracle.gemm(c.in_dtype, c.layout_a, c.layout_b, c.M, c.N, c.K, i.A, i.lda, i.B, i.ldb,
+                                                         batch=c.batch, stride_a=i.stride_a, stride_b=i.stride_b,
+                                                         scale_a=i.scale_a, scale_b=i.scale_b, bias=i.bias))
+
+        def sampled(c):
+            def ref(i):
+                rng = np.random.default_rng(7)
+                n = 4000
+                pb, pi, pj = rng.integers(0, c.batch, n), rng.integers(0, c.M, n), rng.integers(0, c.N, n)
+                pi[:500], pi[500:1000], pj[1000:1500], pj[1500:2000] = 0, c.M - 1, 0, c.N - 1
+                pts = (pb.astype(np.int64), pi.astype(np.int64), pj.astype(np.int64))
+                C_ref, D = oracle.gemm_points(c.in_dtype, c.layout_a, c.layout_b, c.M, c.N, c.K, i.A, i.lda, i.B, i.ldb, *pts,
+                                              batch=c.batch, stride_a=i.stride_a, stride_b=i.stride_b,
+                                              scale_a=i.scale_a, scale_b=i.scale_b, bias=i.bias)
+                return gate.Reference(C_ref, D, pts)
+            return ref
+        for name in ("C1", "C2_small", "C3_small", "C4_small", "C5_small"):
+            c, cache = gen.CONFIGS[name], {}
+            for v in range(gemm.gemm_variant_count()):
+                entries.append(gate.run_gate(v, c, whole(c), inputs_cache=cache, reps=5, warmup=1))
+        for name in ("C2", "C3", "C4", "C5"):
+            c = gen.CONFIGS[name]
+            entries.append(gate.run_gate(gemm.GEMM_K4_MFMA, c, sampled(c), seeds=(0,), reps=5, warmup=1))
+        pr = gate.pass_rate(entries)
+        out["gate"] = {"attempted": pr["attempted"], "passed": pr["passed"], "rate": pr["rate"], "refused": pr["refused"],
+                       "what": "(state, workload, seed) correctness legs against the CPU oracle: K0..K4 on C1 and the reduced "
+                               "C2..C5 at seeds 0..2 (all outputs), K4 on the full-size C2..C5 at seed 0 (4000 sampled outputs)",
+                       "failed": [(e.get("variant_name"), e["workload"], e["verdict"]) for e in entries if e["verdict"] != "passed"]}
     print(json.dumps(out))
 
 

@@ -25,6 +25,14 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 OUT_DIR = os.environ.get("GEMM_GATE_OUT") or os.path.join(ROOT, "gate_out")
 LEDGER = os.path.join(OUT_DIR, "gate_ledger.jsonl")
 TABLE = os.path.join(OUT_DIR, "gate_table.txt")
+# optional: a directory of rocprofv3 counter files, one sub-directory "<variant>_<workload>" per pair, written by
+# running `python3 -m paper_2605_28213_amd.profile_run` under rocprofv3 (the commands are in that module)
+COUNTERS = os.environ.get("GEMM_GATE_COUNTERS")
+
+
+def counters_dir(variant, name):
+    d = os.path.join(COUNTERS, f"{variant}_{name}") if COUNTERS else None
+    return d if d and os.path.isdir(d) else None
 _entries = []
 # the oracle's whole product at seed 0 up to the headline workload's size (about 20 s of host time there)
 FULL_PRODUCT_FLOPS = 1.2e12
@@ -97,20 +105,32 @@ def ledger_file():
     yield
     with open(TABLE, "w") as f:
         f.write(gate.format_table(_entries) + "\n\n" + json.dumps(gate.pass_rate(_entries)) + "\n")
+    with open(os.path.join(OUT_DIR, "gate_resources.txt"), "w") as f:
+        f.write(gate.format_resources(_entries) + "\n")
 
 
 @pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5"])
 def test_every_state_passes_the_gate(name):
     cfg = gen.CONFIGS[name]
     reference, cache = reference_for(cfg), {}
+    prev = None
     for v in range(gemm.GEMM_VARIANT_COUNT):
         print(f"[gate] {name} {gemm.gemm_variant_name(v)}", flush=True)
-        e = gate.run_gate(v, cfg, reference, inputs_cache=cache, ledger_path=LEDGER, time_budget_s=1.0)
+        e = gate.run_gate(v, cfg, reference, inputs_cache=cache, ledger_path=LEDGER, time_budget_s=1.0, predecessor=prev,
+                          counters_dir=counters_dir(v, name))
         _entries.append(e)
-        assert e["compile"]["ok"]
+        assert e["compile"]["ok"] and not e["compile"]["was_stale"] and len(e["compile"]["sources_sha256"]) == 64
         assert e["verdict"] == "passed", (name, e["variant_name"], e["verdict"], e.get("correctness"))
         assert len(e["correctness"]) == 3 and all(s["all_outputs_finite"] for s in e["correctness"])
-        assert e["profile"]["launches"] >= 3
+        assert e["profile"]["launches"] >= 3 and "rotated over 3" in e["profile"]["cache_state"]
+        # compile leg: the compiler's figures for the kernels this state launches; none may spill to scratch
+        assert e["compile"]["kernels"], (name, e["variant_name"], e["query"]["path"])
+        assert all(k["scratch_bytes_per_lane"] == 0 and k["vgpr_spill"] == 0 for k in e["compile"]["kernels"].values())
+        # skill-record fields: what the transition changed against the state before it, and where it applies
+        assert (e["effect"] is None) == (v == 0) and e["scope"]["prior_actions"] == [gemm.gemm_variant_intent(u) for u in range(1, v)]
+        if prev is not None:
+            assert e["effect"]["against"] == prev["variant_name"] and e["effect"]["speedup"] > 0
+        prev = e
     torch.cuda.empty_cache()
 
 
@@ -221,6 +241,34 @@ def test_strict_mode_refuses_and_names_the_violated_conditions():
         _entries.append(e)
         assert e["verdict"].startswith("refused(precondition")
         assert "LD16_A" in e["query"]["violated"] and "correctness" not in e
+
+
+def test_risk_field_of_the_conditioned_states():
+    """What K2, K3 and K4 do where their conditions fail (the ragged fp16 workload, full size and reduced):
+    refusal with the violated conditions under STRICT, their own slow path (still correct) otherwise, and
+    the measured slowdown against a conforming workload of the same size; the complete record (intent,
+    pre, effect, evidence, risk, scope, ver) goes to the ledger."""
+    for vname, cname in (("C3", "C3_aligned"), ("C3_small", "C3_small_aligned")):
+        viol = gen.CONFIGS[vname]
+        up = lambda n, m: (n + m - 1) // m * m
+        conf = gen.Config(cname, up(viol.M, 8), up(viol.N, 8), up(viol.K, 64), viol.in_dtype, viol.out_dtype, gen.ROW_MAJOR,
+                          gen.COL_MAJOR, viol.dist)
+        ref_v, ref_c = reference_for(viol), reference_for(conf)
+        prev = None
+        for v in (gemm.GEMM_K2_VECTORIZED, gemm.GEMM_K3_PIPELINED, gemm.GEMM_K4_MFMA):
+            print(f"[risk] {vname} {gemm.gemm_variant_name(v)}", flush=True)
+            risk = gate.risk_probe(v, viol, conf, ref_v, ref_c, ledger_path=LEDGER, time_budget_s=0.5)
+            assert risk["strict"].startswith("refused(precondition") and "LD16_A" in risk["violated"], risk
+            assert risk["slow_path_verdict"] == "passed" and risk["fast_path_verdict"] == "passed", risk
+            assert "masked" in risk["slow_path"] and "masked" not in risk["fast_path"], risk
+            assert risk["slowdown"] > 1.0, risk
+            e = gate.run_gate(v, conf, ref_c, seeds=(0,), ledger_path=LEDGER, time_budget_s=0.5, predecessor=prev, risk=risk)
+            e["workload"] = conf.name
+            _entries.append(e)
+            for field in ("intent", "query", "effect", "profile", "risk", "scope", "correctness"):
+                assert field in e, field
+            prev = e
+    torch.cuda.empty_cache()
 
 
 def test_pass_rate_of_the_ledger():
