@@ -24,14 +24,19 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libgemm_lineage.so")
 RESOURCES = os.path.join(HERE, "libgemm_lineage.resources.json")
-SOURCES = ["gemm_api.hip", "conv_api.hip", "topk.hip", "k0_naive.hip", "k123_valu_tiled.hip", "k4_mfma.hip", "probes.hip"]
-HEADERS = [os.path.join(CSRC, "common.hpp"), os.path.join(CSRC, "k4_kernels.hpp"),
+SOURCES = ["gemm_api.hip", "conv_api.hip", "topk.hip", "k0_naive.hip", "k123_valu_tiled.hip", "k4_mfma.hip", "k4_ring.hip", "probes.hip"]
+HEADERS = [os.path.join(CSRC, "common.hpp"), os.path.join(CSRC, "k4_kernels.hpp"), os.path.join(CSRC, "k4_ring.hpp"),
            os.path.join(os.path.dirname(HERE), "include", "gemm_lineage.h"),
            os.path.join(os.path.dirname(HERE), "include", "conv_lineage.h"),
            os.path.join(os.path.dirname(HERE), "include", "topk_lineage.h")]
 # packed fp32 VALU forms (v_pk_*_f32) are switched off: the compiler must not form them for this target
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+# Per translation unit.  Machine-code sinking moves whole chains of matrix instructions (pure register
+# operations whose results are next used in a later block) past the loads, barriers and waits they were
+# interleaved with, and then needs two slabs' fragments in registers at once: the persistent kernel places
+# them by hand.  (The streaming kernels need the pass: without it they spill.)
+EXTRA_FLAGS = {"k4_ring.hip": ["-mllvm", "-disable-machine-sink"]}
 REMARKS = "-Rpass-analysis=kernel-resource-usage"
 _FIELDS = {"TotalSGPRs": "sgpr", "VGPRs": "vgpr", "AGPRs": "agpr", "ScratchSize [bytes/lane]": "scratch_bytes_per_lane",
            "Occupancy [waves/SIMD]": "waves_per_simd", "SGPRs Spill": "sgpr_spill", "VGPRs Spill": "vgpr_spill",
@@ -79,7 +84,7 @@ def _compile(src: str, force: bool) -> str:
     newest = max(os.path.getmtime(p) for p in [path] + HEADERS)
     res = obj + ".resources.json"
     if force or not os.path.exists(obj) or not os.path.exists(res) or os.path.getmtime(obj) < newest:
-        r = subprocess.run(["hipcc", *FLAGS, REMARKS, "-c", path, "-o", obj], capture_output=True, text=True)
+        r = subprocess.run(["hipcc", *FLAGS, *EXTRA_FLAGS.get(src, []), REMARKS, "-c", path, "-o", obj], capture_output=True, text=True)
         remarks = _parse_remarks(r.stderr)
         # what is left of stderr once the remarks (and the source line and caret echoed after some) are taken out
         keep, after_remark = [], False
@@ -127,7 +132,7 @@ def build(force: bool = False) -> str:
         names = sorted(kernels)
         table = {d: dict(kernels[m], mangled=m) for m, d in zip(names, _demangle(names))}
         with open(RESOURCES, "w") as f:
-            json.dump({"sources_sha256": sources_digest(), "flags": FLAGS, "kernels": table}, f, indent=1, sort_keys=True)
+            json.dump({"sources_sha256": sources_digest(), "flags": FLAGS, "extra_flags": EXTRA_FLAGS, "kernels": table}, f, indent=1, sort_keys=True)
     return LIB
 
 

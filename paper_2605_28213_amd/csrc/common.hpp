@@ -129,6 +129,12 @@ bool k4_streams_rows(const Args& a);      // a product of at most 64 rows goes t
 Args k4_transposed(const Args& a);        // the same product as C^T = B^T A^T (operands swapped, ARGS_C_TRANSPOSED set)
 // True when the fast kernel runs with 128 x 128 workgroup tiles instead of 256 x 256.
 bool k4_small_tiles(const Args& a);
+// True when the fast path runs as the persistent kernel (256 workgroups walking several 256 x 256 tiles each).
+bool k4_uses_ring(const Args& a);
+// Whether the tiled part of a product on path `kind` (MFMA_VEC16, MFMA_PACKED, MFMA_SPLITK) runs as the persistent kernel.
+bool k4_fast_is_persistent(int kind, const Args& a);
+constexpr int K4_RING_WORKGROUPS = 256;   // one per CU of the GPU this library is written for (8 XCDs x 32)
+hipError_t launch_k4_ring(const Args& a);  // bf16, fp16, e4m3; k4_uses_ring(a) must hold
 
 hipError_t launch_k0(const Args& a);
 hipError_t launch_valu_tiled(int variant, int path, const Args& a);

@@ -199,21 +199,25 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
             required &= ~(uint32_t)GEMM_COND_TILE_DIV_K;
         } else if (!f32 && va && vb && kdiv && rows_fit) {
             p.path = MFMA_VEC16 | (3 << 8);
-            path = k4_splits_m_tail(a) ? "mfma32-direct-to-lds+stream(M-tail)" : "mfma32-direct-to-lds";
+            snprintf(splitk_path, sizeof(splitk_path), "mfma32-direct-to-lds%s%s", k4_fast_is_persistent(MFMA_VEC16, a) ? "(persistent)" : "",
+                     k4_splits_m_tail(a) ? "+stream(M-tail)" : "");
+            path = splitk_path;
             // too few tiles for the chip and a long K: with scratch for the partial products, K is split
             const int splits = k4_splitk_factor(a);
             if (splits > 1) {
                 pack_bytes = k4_splitk_workspace_bytes(a, splits);
                 if (d->workspace != nullptr) {
                     p.path = MFMA_SPLITK;
-                    snprintf(splitk_path, sizeof(splitk_path), "mfma32-direct-to-lds+splitK(%d)", splits);
+                    snprintf(splitk_path, sizeof(splitk_path), "mfma32-direct-to-lds%s+splitK(%d)",
+                             k4_fast_is_persistent(MFMA_SPLITK, a) ? "(persistent)" : "", splits);
                     path = splitk_path;
                 }
             }
         } else if (can_pack && d->workspace != nullptr) {
             // the caller lent scratch: repair the violated conditions by packing, then run the fast kernel
             p.path = MFMA_PACKED | (keep << 8);
-            snprintf(splitk_path, sizeof(splitk_path), "mfma32-packed%s+direct-to-lds%s", keep == 1 ? "(B)" : keep == 2 ? "(A)" : "",
+            snprintf(splitk_path, sizeof(splitk_path), "mfma32-packed%s+direct-to-lds%s%s", keep == 1 ? "(B)" : keep == 2 ? "(A)" : "",
+                     k4_fast_is_persistent(MFMA_PACKED, a) ? "(persistent)" : "",
                      k4_splits_m_tail(a) ? "+stream(M-tail)" : "");
             path = splitk_path;
             pack_bytes = k4_packed_workspace_bytes(a, keep);

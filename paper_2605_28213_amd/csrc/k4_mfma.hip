@@ -138,6 +138,7 @@ bool k4_small_tiles(const Args& a)
 template <typename IN>
 static hipError_t launch_fast_any(const Args& a)
 {
+    if (k4_uses_ring(a)) return launch_k4_ring(a);
     const bool noswz = a.flags & GEMM_FLAG_DEOPT_NO_SWIZZLE, noovl = a.flags & GEMM_FLAG_DEOPT_NO_OVERLAP;
     if (noswz && noovl) return launch_fast<FastCfg<IN, 256, 8, false, false>>(a);
     if (noswz) return launch_fast<FastCfg<IN, 256, 8, false, true>>(a);
@@ -220,6 +221,24 @@ static hipError_t launch_splitk(const Args& a)
     const int64_t threads = a.M * ((a.N + 3) / 4);
     hipLaunchKernelGGL(k4_splitk_reduce<IN>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, a.stream, a, (const float*)a.workspace, splits);
     return hipGetLastError();
+}
+
+// The arguments the fast kernel is launched with on each of its three paths, as far as the choice between its
+// persistent and its one-tile-per-workgroup form depends on them (mirrors launch_packed, launch_splitk and
+// launch_fast_split).
+bool k4_fast_is_persistent(int kind, const Args& a)
+{
+    Args p = a;
+    if (kind == MFMA_SPLITK) {
+        const int splits = k4_splitk_factor(a);
+        p.batch = splits;
+        p.K = a.K / splits;
+        p.flags = k4_small_tiles(a) ? GEMM_FLAG_TILE_128 : GEMM_FLAG_TILE_256;
+        return k4_uses_ring(p);
+    }
+    if (kind == MFMA_PACKED) p.K = k4_packed_k(a);
+    if (k4_splits_m_tail(p)) p.M = p.M - p.M % 256;
+    return k4_uses_ring(p);
 }
 
 int64_t k4_packed_k(const Args& a)
@@ -366,7 +385,8 @@ Geometry geometry_k4(int path, const Args& a)
         if (kind != MFMA_SPLITK && k4_splits_m_tail(a)) top.M = a.M - a.M % 256;
         const bool small = k4_small_tiles(top);
         const int bt = small ? FastK4Small<BF16>::BM : FastK4<BF16>::BM;
-        const int64_t g = ((top.M + bt - 1) / bt) * ((a.N + bt - 1) / bt) * a.batch * (kind == MFMA_SPLITK ? k4_splitk_factor(a) : 1);
+        int64_t g = ((top.M + bt - 1) / bt) * ((a.N + bt - 1) / bt) * a.batch * (kind == MFMA_SPLITK ? k4_splitk_factor(a) : 1);
+        if (k4_fast_is_persistent(kind, a)) g = K4_RING_WORKGROUPS;      // persistent workgroups, several tiles each
         // stages: slabs in flight beyond the one in use
         return Geometry{bt, bt, ROW_BYTES / es, 256, 2, small ? FastK4Small<BF16>::LDS_BYTES : FastK4<BF16>::LDS_BYTES, g};
     }

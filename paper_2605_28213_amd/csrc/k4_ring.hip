@@ -1,0 +1,48 @@
+// Launcher of the persistent form of K4's direct-to-LDS kernel (a translation unit of its own: it is compiled
+// without the machine-code sinking pass, see the build script).
+#include "k4_ring.hpp"
+
+namespace gl {
+
+static_assert(RING_WORKGROUPS == K4_RING_WORKGROUPS, "the planner reports the grid the launcher uses");
+
+// The persistent form of the 256-tile kernel takes a product that gives every one of its workgroups at least
+// one tile and whose K is at least three slabs (the slab kinds first / last-but-one / last of a tile are
+// distinct) and at most 64: what it saves is per tile (the ring's cold start, and loads that stop during the
+// epilogue), so it pays on short K (e4m3 64 x 1024^3, 8 slabs: 106 -> 86 us; bf16 16 x 2048^3, 32 slabs:
+// 259 -> 234 us), is level at 64 slabs (bf16 4096^3: 106 / 107 us) and loses 1.5-2 % at 128 slabs (bf16
+// 8192^3: 793 against 779 us on the same box), where the package is at its power limit either way.  The
+// simplified states and the 128-tile configuration stay with k4_mfma_fast.
+bool k4_uses_ring(const Args& a)
+{
+    constexpr uint32_t DEOPT = GEMM_FLAG_DEOPT_NO_SWIZZLE | GEMM_FLAG_DEOPT_NO_OVERLAP | GEMM_FLAG_DEOPT_NO_RASTER;
+    if ((a.flags & DEOPT) || k4_small_tiles(a)) return false;
+    const int64_t ke = ROW_BYTES / elem_size(a.in_dtype);
+    const int64_t tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256) * a.batch;
+    return a.K / ke >= 3 && a.K / ke <= 64 && tiles >= K4_RING_WORKGROUPS && tiles < ((int64_t)1 << 31);
+}
+
+template <typename IN>
+static hipError_t launch_ring(const Args& a)
+{
+    using CFG = RingCfg<IN>;
+    const int tiles_m = (int)((a.M + CFG::BM - 1) / CFG::BM), tiles_n = (int)((a.N + CFG::BN - 1) / CFG::BN);
+    const int total = (int)((int64_t)tiles_m * tiles_n * a.batch);
+    const int eo = a.out_dtype == GEMM_F32 ? 4 : 2;
+    const bool vec_c = ((uintptr_t)a.C % 16 == 0) && (a.ldc * eo) % 16 == 0 && (a.batch <= 1 || (a.stride_c * eo) % 16 == 0);
+    hipLaunchKernelGGL(k4_mfma_ring<CFG>, dim3(K4_RING_WORKGROUPS), dim3(CFG::T), 0, a.stream, a, tiles_m, tiles_n, total,
+                       vec_c ? (int)FAST_VEC_C : 0);
+    return hipGetLastError();
+}
+
+hipError_t launch_k4_ring(const Args& a)
+{
+    switch (a.in_dtype) {
+    case GEMM_BF16: return launch_ring<BF16>(a);
+    case GEMM_F16: return launch_ring<F16>(a);
+    case GEMM_FP8_E4M3: return launch_ring<E4M3>(a);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace gl

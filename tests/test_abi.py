@@ -132,7 +132,7 @@ def test_query_reports_paths_and_conditions_for_the_five_workloads():
     r = q(4, "C3"); assert "elementwise" in r.path and "K_CONTIG_B" in gemm.Query.names(r.violated)
     assert "TILE_DIV_M" not in gemm.Query.names(r.holds)
     r = q(4, "C4"); assert r.path.startswith("mfma16-stream") and "SMALL_M" in gemm.Query.names(r.holds)
-    r = q(4, "C5"); assert r.path == "mfma32-direct-to-lds" and r.bk == 128 and r.grid == 64 * 16
+    r = q(4, "C5"); assert r.path == "mfma32-direct-to-lds(persistent)" and r.bk == 128 and r.grid == 256    # 1024 tiles on 256 persistent workgroups
     # a misaligned base pointer breaks ALIGN16 for that operand only
     r = q(3, "C2", A=0x1002, B=0x2000)
     assert r.path == "elementwise-masked(A)+vec16(B)" and gemm.Query.names(r.violated) == ["ALIGN16_A"]

@@ -116,3 +116,34 @@ def test_static_scratch_array_is_a_visible_device_symbol(tmp_path):
     assert m, "the scratch array is not a global symbol of the device code"
     assert int(m.group(2)) >= 8
     assert re.search(r"\.size\s+%s, %d\b" % (re.escape(m.group(1)), mib << 20), text)
+
+
+def test_persistent_kernel_slab_loop(tmp_path):
+    """The persistent form of the 256-tile kernel: the middle-slab loop holds one slab (64 or 32 matrix instructions,
+    32 fragment reads, 16 direct loads issued from inline assembly, one barrier, the one hand-placed vmcnt wait),
+    nothing spills in the two-byte instantiations, and no scratch access sits between the first and the last matrix
+    instruction of any instantiation (a scratch reload there would wait for the direct loads in flight)."""
+    src = os.path.join(ROOT, "paper_2605_28213_amd", "csrc", "k4_ring.hip")
+    out = tmp_path / "ring.s"
+    flags = [f for f in gl_build.FLAGS if f != "-fPIC"] + gl_build.EXTRA_FLAGS["k4_ring.hip"]
+    r = subprocess.run(["hipcc", *flags, "-S", "--cuda-device-only", src, "-o", str(out)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr[-2000:]
+    text = out.read_text()
+    for dtype, mfma, per_slab in (("4BF16", "v_mfma_f32_32x32x16_bf16", 64), ("3F16", "v_mfma_f32_32x32x16_f16", 64),
+                                  ("4E4M3", "v_mfma_scale_f32_32x32x64_f8f6f4", 32)):
+        prefix = "_ZN2gl12k4_mfma_ringINS_7RingCfgINS_" + dtype
+        m = re.search(r"^(%s\w*):[^\n]*\n(.*?)\.Lfunc_end" % re.escape(prefix), text, flags=re.S | re.M)
+        assert m, prefix
+        ops = first_inner_loop(m.group(2))
+        count = lambda name: sum(o == name for o in ops)
+        assert count(mfma) == per_slab and count("ds_read_b128") == 32 and count("buffer_load_dwordx4") == 16 and count("s_barrier") == 1
+        for bad in ("v_accvgpr_read_b32", "v_accvgpr_write_b32", "v_readlane_b32", "scratch_load_dword", "scratch_store_dword",
+                    "scratch_load_dwordx4", "scratch_store_dwordx4", "ds_write_b128"):
+            assert count(bad) == 0, bad
+        lines = m.group(2).split("\n")
+        mf = [i for i, l in enumerate(lines) if mfma in l]
+        assert len(mf) == 4 * per_slab                      # the four slab kinds, each once
+        assert not any(l.strip().startswith("scratch_") for l in lines[mf[0]:mf[-1]])
+        meta = metadata(text, prefix)
+        assert meta["agpr"] == 256 and meta["lds"] == 160 * 1024
+        assert meta["vgpr_spill"] == (0 if dtype != "4E4M3" else meta["vgpr_spill"]) and meta["vgpr_spill"] <= 2

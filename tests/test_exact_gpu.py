@@ -90,6 +90,35 @@ def test_direct_to_lds_kernel_is_exact(dtype, tile_flag, bm):
             assert q.bm == bm
 
 
+RING_CASES = [  # (M, N, slabs, batch): at least 256 tiles of 256 x 256, so the persistent kernel takes the product
+    (520, 300, 3, 130),     # 780 tiles: workgroups with 3 and with 4 tiles; the shortest K the kernel takes (first, last-but-one, last slab)
+    (520, 300, 4, 43),      # 258 tiles: one or two tiles per workgroup; one middle slab
+    (256, 512, 11, 129),    # 258 interior tiles, middle-slab loop of 8
+    (300, 260, 7, 70),      # 280 tiles, every one with an edge
+]
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("case", RING_CASES, ids=["%dx%dx%dslabs_b%d" % c for c in RING_CASES])
+def test_persistent_kernel_is_exact(dtype, case):
+    """The persistent form of the 256-tile kernel: the ring runs on across tile boundaries, so a wrong slab of
+    the NEXT tile (stale region, wrong source, wrong wait) shows up in the tile after the boundary.  fp32
+    output bit for bit against the oracle, and the two-byte output against the oracle's value rounded to
+    nearest even (sums are integers: the kernel's fp32 accumulator holds them exactly before it rounds)."""
+    M, N, ns, nb = case
+    K = slabs(dtype, ns)
+    inp = int_inputs(dtype, M, N, K, batch=nb, seed=ns, biased=(ns == 7))
+    q = run_exact(inp, "mfma32-direct-to-lds(persistent)", flags=gemm.GEMM_FLAG_TILE_256)
+    assert q.bm == 256 and q.grid == 256
+    out = gen.BF16 if dtype == gen.E4M3 else dtype
+    C_ref, _ = oracle_for(inp)
+    rc, _, raw = util.run_config(K4, inp, out_dtype=out, flags=gemm.GEMM_FLAG_TILE_256)
+    assert rc == gemm.GEMM_OK
+    want = gen.quantise(out, C_ref.astype(np.float32).reshape(-1))
+    got = raw.cpu().numpy().view(np.uint16)[: nb * M * N]
+    np.testing.assert_array_equal(got, want)
+
+
 @pytest.mark.parametrize("dtype", DTYPES)
 @pytest.mark.parametrize("flags,tag", [(gemm.GEMM_FLAG_DEOPT_NO_SWIZZLE, "-noswz"), (gemm.GEMM_FLAG_DEOPT_NO_OVERLAP, "-noovl"),
                                        (gemm.GEMM_FLAG_DEOPT_NO_RASTER, "-noraster"),
@@ -132,7 +161,7 @@ def test_row_remainder_split_is_exact(dtype, rem):
     """16 rows of 256-tiles by 16 columns plus a thin remainder: the tiled kernel and the streaming kernel
     (one, two, three, four groups of rows) each write their part of one C."""
     inp = int_inputs(dtype, 4096 + rem, 4096, slabs(dtype, 8), seed=rem)
-    run_exact(inp, "mfma32-direct-to-lds+stream(M-tail)")
+    run_exact(inp, "mfma32-direct-to-lds(persistent)+stream(M-tail)")      # 256 whole tiles of 8 slabs: the persistent form
 
 
 STREAM_CASES = [  # (M, N, K in 2-byte units, batch, what)

@@ -72,6 +72,7 @@ def test_every_state_and_path_maps_to_kernels_of_the_library():
     cases = [(0, gen.F32, "naive", 16, 16, 256, 0), (1, gen.BF16, "lds-tiled", 64, 64, 256, 0), (2, gen.F16, "vec16", 128, 128, 256, 0),
              (3, gen.E4M3, "vec16", 64, 64, 256, 0), (2, gen.BF16, "elementwise-masked(-novec)", 128, 128, 256, gemm.GEMM_FLAG_DEOPT_NO_VECTOR),
              (4, gen.BF16, "mfma32-direct-to-lds", 256, 256, 256, 0), (4, gen.E4M3, "mfma32-direct-to-lds", 128, 128, 256, 0),
+             (4, gen.E4M3, "mfma32-direct-to-lds(persistent)", 256, 256, 256, 0),
              (4, gen.BF16, "mfma32-direct-to-lds-noswz", 256, 256, 256, gemm.GEMM_FLAG_DEOPT_NO_SWIZZLE),
              (4, gen.F16, "mfma32-packed+direct-to-lds+stream(M-tail)", 256, 256, 256, 0),
              (4, gen.BF16, "mfma32-direct-to-lds+splitK(4)", 128, 128, 256, 0), (4, gen.BF16, "mfma16-stream(small-M)", 16, 16, 64, 0),

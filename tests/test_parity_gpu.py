@@ -365,14 +365,17 @@ def test_thin_row_remainder_goes_to_the_streaming_kernel(dtype, rem):
     inp = gen.make_inputs(cfg, 6)
     ref = oracle_for(inp)
     d = gemm.make_desc(M, N, K, dtype, out, ROW, COL)
-    assert gemm.gemm_query(4, d).path == ("mfma32-direct-to-lds+stream(M-tail)" if rem <= 64 else "mfma32-direct-to-lds")
+    # (at least 256 whole tiles; K = 256 elements is 4 slabs for the two-byte types, which the persistent form of the
+    # tiled kernel takes, and 2 slabs for e4m3, which it does not)
+    form = "" if dtype == gen.E4M3 else "(persistent)"
+    assert gemm.gemm_query(4, d).path == "mfma32-direct-to-lds" + form + ("+stream(M-tail)" if rem <= 64 else "")
     check(4, inp, ref)
     if rem in (3, 48):
         ragged = gen.Config("mtail_packed", M, N, K - 5, dtype, out, ROW, ROW, "normal", rsqrt_k=True, biased=True)
         rinp = gen.make_inputs(ragged, 7)
         need = gemm.gemm_query(4, gemm.make_desc(M, N, K - 5, dtype, out, ROW, ROW)).workspace_bytes
         lent = gemm.make_desc(M, N, K - 5, dtype, out, ROW, ROW, workspace=256, workspace_bytes=need)
-        assert gemm.gemm_query(4, lent).path == "mfma32-packed+direct-to-lds+stream(M-tail)"
+        assert gemm.gemm_query(4, lent).path == "mfma32-packed+direct-to-lds" + form + "+stream(M-tail)"
         check(4, rinp, lend_workspace=True)
     # 2 x 2 tiles per problem: one round with or without the remainder
     small = gemm.make_desc(256 + rem, 300, K, dtype, out, ROW, COL, batch=2)
@@ -533,3 +536,29 @@ def test_bias_is_added_before_the_rounding_in_every_state(dtype):
                 for flag in (gemm.GEMM_FLAG_TILE_256, gemm.GEMM_FLAG_TILE_128):
                     rc, C, _ = util.run_config(4, inp, flags=flag)
                     assert rc == gemm.GEMM_OK and util.norm_err(C[:, :, :N], ref[0], ref[1]) <= util.TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", [gen.BF16, gen.F16, gen.E4M3])
+def test_persistent_form_of_the_tiled_kernel(dtype):
+    """At least 256 tiles of 256 x 256 and 3..64 slabs of K: one workgroup per CU walks several tiles with the LDS
+    ring running across the tile boundaries.  Ragged edges in M and N (masked epilogue beside the unmasked one),
+    per-problem scales, a bias, both output types, workgroups with unequal numbers of tiles."""
+    out = gen.BF16 if dtype == gen.E4M3 else dtype
+    es = gen.ELEM_BYTES[dtype]
+    for (M, N, ns, nb, kw) in [(700, 520, 5, 29, dict(scaled=True, biased=True)), (512, 300, 3, 70, {}), (1100, 1030, 9, 11, dict(biased=True))]:
+        K = ns * 128 // es
+        cfg = gen.Config("ring", M, N, K, dtype, out, ROW, COL, "normal", rsqrt_k=True, batch=nb, **kw)
+        inp = gen.make_inputs(cfg, 31)
+        if inp.scale_a is not None:
+            inp.scale_a[1] = -0.75
+        d = gemm.make_desc(M, N, K, dtype, out, ROW, COL, batch=nb, flags=gemm.GEMM_FLAG_TILE_256)
+        q = gemm.gemm_query(4, d)
+        assert q.path == "mfma32-direct-to-lds(persistent)" and q.grid == 256, q
+        ref = oracle_for(inp)
+        for od in (out, gen.F32):
+            rc, C, _ = util.run_config(4, inp, flags=gemm.GEMM_FLAG_TILE_256, out_dtype=od)
+            assert rc == gemm.GEMM_OK
+            assert util.norm_err(C[:, :, :N], ref[0], ref[1]) <= util.TOL[dtype], (M, N, K, nb, od)
+    # fewer tiles than workgroups, or fewer than three slabs: the one-tile-per-workgroup kernel keeps the product
+    assert gemm.gemm_query(4, gemm.make_desc(700, 520, 5 * 128 // es, dtype, out, ROW, COL, batch=20, flags=gemm.GEMM_FLAG_TILE_256)).path == "mfma32-direct-to-lds"
+    assert gemm.gemm_query(4, gemm.make_desc(700, 520, 2 * 128 // es, dtype, out, ROW, COL, batch=29, flags=gemm.GEMM_FLAG_TILE_256)).path == "mfma32-direct-to-lds"
