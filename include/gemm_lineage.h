@@ -107,9 +107,21 @@ enum {
      * edge for each of them. */
     GEMM_FLAG_DEOPT_NO_RASTER = 1u << 5, /* K4's fast kernel only: workgroup i takes tile i in row-major order
                                             instead of the XCD-aware banded walk */
-    GEMM_FLAG_DEOPT_NO_VECTOR = 1u << 6  /* K2 and K3 only: slabs fetched element by element (K3 with it is
+    GEMM_FLAG_DEOPT_NO_VECTOR = 1u << 6, /* K2 and K3 only: slabs fetched element by element (K3 with it is
                                             "pipeline without vectorised loads", an order the lineage skips) */
+    GEMM_FLAG_DEOPT_NO_PERSISTENT = 1u << 7, /* K4's fast kernel only: one workgroup per tile (ring filled from a cold
+                                            start and drained per tile) where the default would keep one workgroup per
+                                            CU walking several tiles with the ring running across their boundaries */
+    /* Configuration override for K4's streaming kernel (Table 1 "autotune" over the "templatize"d configuration:
+     * waves per workgroup x columns per strip x K tile x row groups).  Bits 8..10 hold 1 + the form:
+     *   0: 1 wave x 16 columns x 512-byte runs, 16 rows     1: 4 waves x 16 x 512 B, 16 rows (K tiles dealt to the waves)
+     *   2: 2 waves x 32 x 512 B, 32 rows    3 / 4 / 5: 4 waves x 64 columns x 256-byte runs, 48 / 64 / 96 rows
+     * Only on the streaming path and only a form with at least the product's rows (of the transposed product on the
+     * small-N path); otherwise GEMM_ERR_BAD_ARG.  0 in these bits: the frozen rule chooses. */
+    GEMM_FLAG_STREAM_FORM_SHIFT = 8,
+    GEMM_FLAG_STREAM_FORM_MASK = 7u << 8
 };
+#define GEMM_FLAG_STREAM_FORM(form) ((uint32_t)((form) + 1) << GEMM_FLAG_STREAM_FORM_SHIFT)
 
 typedef struct {
     int64_t M, N, K;                 /* logical sizes: A is M x K, B is K x N, C is M x N; >= 0 */

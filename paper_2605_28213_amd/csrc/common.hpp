@@ -126,6 +126,8 @@ size_t k4_splitk_workspace_bytes(const Args& a, int splits);
 // round of the chip) to the streaming kernel.
 bool k4_splits_m_tail(const Args& a);
 bool k4_streams_rows(const Args& a);      // a product of at most 64 rows goes to the streaming kernel
+// With a streaming-form override in the flags: whether that form holds the product's rows.
+bool k4_stream_form_fits(const Args& a);
 Args k4_transposed(const Args& a);        // the same product as C^T = B^T A^T (operands swapped, ARGS_C_TRANSPOSED set)
 // True when the fast kernel runs with 128 x 128 workgroup tiles instead of 256 x 256.
 bool k4_small_tiles(const Args& a);

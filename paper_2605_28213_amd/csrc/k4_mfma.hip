@@ -75,10 +75,19 @@ static bool stream_deep(const Args& a) { return ((a.N + 15) / 16) * a.batch < 51
 // columns); the split-K form of the tiled kernel took 139-142 us on the same products.  96 rows (six groups of
 // A, 484 registers): 113 us against about 150 us for the split-K form; eight groups spill and lose to it.
 enum StreamForm { STREAM_16 = 0, STREAM_16_DEEP, STREAM_32, STREAM_48, STREAM_64, STREAM_96 };
+static const int STREAM_FORM_ROWS[6] = {16, 16, 32, 48, 64, 96};
 static StreamForm stream_form(const Args& a)
 {
+    const uint32_t forced = (a.flags & GEMM_FLAG_STREAM_FORM_MASK) >> GEMM_FLAG_STREAM_FORM_SHIFT;
+    if (forced) return (StreamForm)(forced - 1);
     if (a.M <= 16) return stream_deep(a) ? STREAM_16_DEEP : STREAM_16;
     return a.M <= 32 ? STREAM_32 : a.M <= 48 ? STREAM_48 : a.M <= 64 ? STREAM_64 : STREAM_96;
+}
+
+bool k4_stream_form_fits(const Args& a)
+{
+    const uint32_t forced = (a.flags & GEMM_FLAG_STREAM_FORM_MASK) >> GEMM_FLAG_STREAM_FORM_SHIFT;
+    return forced >= 1 && forced <= 6 && a.M <= STREAM_FORM_ROWS[forced - 1];
 }
 
 // Whether a product of 17..96 rows is given to the streaming kernel: when its strips fill at least half of
@@ -157,7 +166,7 @@ static hipError_t launch_fast_any(const Args& a)
 bool k4_splits_m_tail(const Args& a)
 {
     const int64_t rem = a.M % 256;
-    if (a.M <= 256 || rem < 1 || rem > 64 || a.N > 16384 || a.flags != 0 || k4_small_tiles(a)) return false;
+    if (a.M <= 256 || rem < 1 || rem > 64 || a.N > 16384 || (a.flags & ~(uint32_t)GEMM_FLAG_DEOPT_NO_PERSISTENT) != 0 || k4_small_tiles(a)) return false;
     const int64_t per_row = ((a.N + 255) / 256) * a.batch, rows = a.M / 256;
     return (rows * per_row + 255) / 256 < ((rows + 1) * per_row + 255) / 256;
 }
@@ -190,7 +199,7 @@ static hipError_t launch_fast_split(const Args& a)
 // range and at most about 512 workgroups, at most 8.
 int k4_splitk_factor(const Args& a)
 {
-    if (a.batch != 1 || a.flags != 0 || a.M <= 16 || k4_splits_m_tail(a)) return 1;
+    if (a.batch != 1 || (a.flags & ~(uint32_t)GEMM_FLAG_DEOPT_NO_PERSISTENT) != 0 || a.M <= 16 || k4_splits_m_tail(a)) return 1;
     const int64_t ke = ROW_BYTES / elem_size(a.in_dtype);
     if (a.K <= 0 || a.K % ke != 0) return 1;
     const int64_t nslab = a.K / ke, tiles = ((a.M + 127) / 128) * ((a.N + 127) / 128);
@@ -215,7 +224,7 @@ static hipError_t launch_splitk(const Args& a)
     p.C = a.workspace; p.ldc = a.N; p.stride_c = a.M * a.N;
     p.out_dtype = GEMM_F32;
     p.scale_a = p.scale_b = nullptr; p.bias = nullptr;
-    p.flags = k4_small_tiles(a) ? GEMM_FLAG_TILE_128 : GEMM_FLAG_TILE_256;   // the tile the product itself would get
+    p.flags = (k4_small_tiles(a) ? GEMM_FLAG_TILE_128 : GEMM_FLAG_TILE_256) | (a.flags & GEMM_FLAG_DEOPT_NO_PERSISTENT);   // the tile the product itself would get
     hipError_t e = launch_fast_any<IN>(p);
     if (e != hipSuccess) return e;
     const int64_t threads = a.M * ((a.N + 3) / 4);
@@ -233,7 +242,7 @@ bool k4_fast_is_persistent(int kind, const Args& a)
         const int splits = k4_splitk_factor(a);
         p.batch = splits;
         p.K = a.K / splits;
-        p.flags = k4_small_tiles(a) ? GEMM_FLAG_TILE_128 : GEMM_FLAG_TILE_256;
+        p.flags = (k4_small_tiles(a) ? GEMM_FLAG_TILE_128 : GEMM_FLAG_TILE_256) | (a.flags & GEMM_FLAG_DEOPT_NO_PERSISTENT);
         return k4_uses_ring(p);
     }
     if (kind == MFMA_PACKED) p.K = k4_packed_k(a);

@@ -15,7 +15,7 @@ static_assert(RING_WORKGROUPS == K4_RING_WORKGROUPS, "the planner reports the gr
 // simplified states and the 128-tile configuration stay with k4_mfma_fast.
 bool k4_uses_ring(const Args& a)
 {
-    constexpr uint32_t DEOPT = GEMM_FLAG_DEOPT_NO_SWIZZLE | GEMM_FLAG_DEOPT_NO_OVERLAP | GEMM_FLAG_DEOPT_NO_RASTER;
+    constexpr uint32_t DEOPT = GEMM_FLAG_DEOPT_NO_SWIZZLE | GEMM_FLAG_DEOPT_NO_OVERLAP | GEMM_FLAG_DEOPT_NO_RASTER | GEMM_FLAG_DEOPT_NO_PERSISTENT;
     if ((a.flags & DEOPT) || k4_small_tiles(a)) return false;
     const int64_t ke = ROW_BYTES / elem_size(a.in_dtype);
     const int64_t tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256) * a.batch;

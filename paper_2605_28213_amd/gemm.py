@@ -26,6 +26,12 @@ GEMM_FLAG_STRICT = 1
 GEMM_FLAG_DEOPT_NO_SWIZZLE, GEMM_FLAG_DEOPT_NO_OVERLAP = 2, 4
 GEMM_FLAG_TILE_256, GEMM_FLAG_TILE_128 = 8, 16
 GEMM_FLAG_DEOPT_NO_RASTER, GEMM_FLAG_DEOPT_NO_VECTOR = 32, 64
+GEMM_FLAG_DEOPT_NO_PERSISTENT = 128
+GEMM_FLAG_STREAM_FORM_SHIFT, GEMM_FLAG_STREAM_FORM_MASK = 8, 7 << 8
+
+
+def GEMM_FLAG_STREAM_FORM(form: int) -> int:
+    return (form + 1) << GEMM_FLAG_STREAM_FORM_SHIFT
 COND_BITS = {name: 1 << i for i, name in enumerate(
     ["ALIGN16_A", "ALIGN16_B", "ALIGN16_C", "LD16_A", "LD16_B", "LD16_C", "TILE_DIV_M", "TILE_DIV_N",
      "TILE_DIV_K", "K_CONTIG_A", "K_CONTIG_B", "DTYPE_HAS_MFMA", "LDS_STAGED", "SMALL_M"])}

@@ -187,6 +187,29 @@ def test_streaming_kernel_is_exact(dtype, case):
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
+def test_streaming_kernel_forms_forced_by_the_sweep_flags_are_exact(dtype):
+    """GEMM_FLAG_STREAM_FORM: every compiled form that holds the product's rows, on 9 rows (all six) and on 40 rows
+    (the three forms of 48, 64 and 96 rows), and on the transposed (few columns) product."""
+    eb = gen.ELEM_BYTES[dtype]
+    for (M, N, K2, forms) in [(9, 1000, 1032, range(6)), (40, 8200, 520, (3, 4, 5)), (4100, 7, 136, range(6))]:
+        inp = int_inputs(dtype, M, N, K2 * 2 // eb, seed=M)
+        for f in forms:
+            run_exact(inp, "-form%d" % f, flags=gemm.GEMM_FLAG_STREAM_FORM(f), exact_path=False)
+    # a form with fewer rows than the product, or the override on a product that does not stream, is refused
+    d = gemm.make_desc(40, 8200, 1024, dtype, gen.F32, ROW, COL, flags=gemm.GEMM_FLAG_STREAM_FORM(2))
+    assert gemm.gemm_query(K4, d).status == gemm.GEMM_ERR_BAD_ARG
+    d = gemm.make_desc(512, 512, 1024, dtype, gen.F32, ROW, COL, flags=gemm.GEMM_FLAG_STREAM_FORM(0))
+    assert gemm.gemm_query(K4, d).status == gemm.GEMM_ERR_BAD_ARG
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_one_tile_per_workgroup_form_forced_on_a_product_the_persistent_kernel_would_take(dtype):
+    inp = int_inputs(dtype, 520, 300, slabs(dtype, 5), batch=43, seed=5)
+    q = run_exact(inp, "mfma32-direct-to-lds-nopersist", flags=gemm.GEMM_FLAG_TILE_256 | gemm.GEMM_FLAG_DEOPT_NO_PERSISTENT)
+    assert q.grid == 6 * 43
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
 def test_streaming_kernel_on_few_columns_is_exact(dtype):
     for (M, N, K2) in [(4100, 7, 136), (8200, 33, 264), (8200, 80, 392)]:
         K = K2 * 2 // gen.ELEM_BYTES[dtype]
