@@ -16,8 +16,9 @@
 // buffer_load_dwordx4 ... offen lds) and waited for by the explicit s_waitcnt vmcnt before each slab's
 // barrier, exactly the waits k4_mfma_fast already places by hand.  Fragment reads stay ordinary loads
 // (their lgkmcnt waits are the compiler's).  No compiler-issued vector memory load is in flight while
-// these loads are issued (scales come through the scalar cache, the bias is loaded in the epilogue),
-// so the compiler's own vmcnt counting is not disturbed.
+// these loads are issued (scales come through the scalar cache, the bias is loaded and consumed inside
+// the epilogue); and a compiler-computed vmcnt wait that does not know of them can only wait longer than
+// needed, never shorter (the counter is in order and it undercounts the younger operations).
 //
 // Epilogue staging.  After the barrier of a tile's last slab its B region is free until the A loads of
 // the slab after next are issued.  Wave w stages in exactly the 1 KB blocks w, w+4, ... of that region
@@ -53,8 +54,6 @@ __device__ __forceinline__ char* ring_stage_row(char* stage, int wave, int r)
     return stage + ((wave + 4 * (r >> 2)) << 10) + ((r & 3) << 8);
 }
 
-// BIAS is a template parameter: with the test at run time the compiler waits, where the two paths join, for the
-// bias loads of the path not taken, and that wait (the counter is shared) drains the next tile's direct loads.
 // One fp32 through the scalar cache (read-only inputs: the per-problem scales).  The compiler loads them with a
 // vector load, and the wait for that load would drain the next tile's direct loads (one counter for both).
 __device__ __forceinline__ float scalar_load_f32(const float* p)
@@ -64,6 +63,8 @@ __device__ __forceinline__ float scalar_load_f32(const float* p)
     return v;
 }
 
+// BIAS is a template parameter: with the test at run time the compiler waits, where the two paths join, for the
+// bias loads of the path not taken, and that wait (the counter is shared) drains the next tile's direct loads.
 template <int OUT, bool INTERIOR, bool BIAS, int TMI, int TNI>
 __device__ __forceinline__ void store_tiles_ring(const Args& a, int64_t b, const f32x16_t (&acc)[TMI][TNI], int64_t row0,
                                                  int64_t col0, int wave, char* stage, bool vec_ok)
