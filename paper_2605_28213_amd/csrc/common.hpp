@@ -113,7 +113,7 @@ inline bool dtype_pair_supported(int in, int out)
 // Each returns hipSuccess or the launch error.  `path` selects a code path that the caller
 // (gemm_api.hip) has already proven legal for these arguments.
 enum ValuPath { VALU_SCALAR = 0, VALU_VEC16 = 1 };
-enum MfmaPath { MFMA_ELEMENTWISE = 0, MFMA_VEC16 = 1, MFMA_SKINNY = 2, MFMA_PACKED = 3, MFMA_SPLITK = 4, MFMA_SKINNY_N = 5 };
+enum MfmaPath { MFMA_ELEMENTWISE = 0, MFMA_VEC16 = 1, MFMA_SKINNY = 2, MFMA_PACKED = 3, MFMA_SPLITK = 4, MFMA_SKINNY_N = 5, MFMA_VEC16_BROW = 6 };
 
 // Workspace of the packed K4 path: both operands rewritten as [rows][Kp], Kp = K rounded up to a slab.
 int64_t k4_packed_k(const Args& a);
@@ -137,6 +137,9 @@ bool k4_uses_ring(const Args& a);
 bool k4_fast_is_persistent(int kind, const Args& a);
 constexpr int K4_RING_WORKGROUPS = 256;   // one per CU of the GPU this library is written for (8 XCDs x 32)
 hipError_t launch_k4_ring(const Args& a);  // bf16, fp16, e4m3; k4_uses_ring(a) must hold
+// The persistent kernel on a row-major B read in place (bf16, fp16), and whether a product qualifies for it.
+bool k4_ring_takes_row_major_b(const Args& a);
+hipError_t launch_k4_ring_row_major_b(const Args& a);
 
 hipError_t launch_k0(const Args& a);
 hipError_t launch_valu_tiled(int variant, int path, const Args& a);

@@ -214,6 +214,13 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
                     path = splitk_path;
                 }
             }
+        } else if (!f32 && va && kdiv && d->layout_b == GEMM_ROW_MAJOR && (holds & vecB) == vecB && d->lda * es <= ((int64_t)1 << 22) &&
+                   k4_ring_takes_row_major_b(a)) {
+            // B row-major and aligned, enough tiles for the persistent kernel: it reads B in place (transposing LDS
+            // reads), so no scratch and no packing pass; K contiguous in B is then not among the conditions relied on
+            p.path = MFMA_VEC16_BROW | (3 << 8);
+            path = "mfma32-direct-to-lds(persistent,B-row-major)";
+            required &= ~(uint32_t)GEMM_COND_K_CONTIG_B;
         } else if (can_pack && d->workspace != nullptr) {
             // the caller lent scratch: repair the violated conditions by packing, then run the fast kernel
             p.path = MFMA_PACKED | (keep << 8);

@@ -328,6 +328,7 @@ hipError_t launch_k4(int path, const Args& a)
         if (a.in_dtype == GEMM_FP8_E4M3) return launch_stream<E4M3>(s);
         return hipErrorInvalidValue;
     }
+    if (kind == MFMA_VEC16_BROW) return launch_k4_ring_row_major_b(a);
     if (kind == MFMA_VEC16) {
         switch (a.in_dtype) {
         case GEMM_BF16: return launch_fast_split<BF16>(a);
@@ -388,6 +389,7 @@ Geometry geometry_k4(int path, const Args& a)
         default: return of(StreamK4Rows96<BF16>{});
         }
     }
+    if (kind == MFMA_VEC16_BROW) return Geometry{256, 256, ROW_BYTES / es, 256, 2, FastK4<BF16>::LDS_BYTES, K4_RING_WORKGROUPS};
     if (kind == MFMA_VEC16 || kind == MFMA_PACKED || kind == MFMA_SPLITK) {
         // (with a row remainder split off, the grid of the tiled part: the remainder is a second launch)
         Args top = a;

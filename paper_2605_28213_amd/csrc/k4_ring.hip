@@ -22,10 +22,24 @@ bool k4_uses_ring(const Args& a)
     return a.K / ke >= 3 && a.K / ke <= 64 && tiles >= K4_RING_WORKGROUPS && tiles < ((int64_t)1 << 31);
 }
 
-template <typename IN>
+// Row-major B read in place (transposing LDS reads): two-byte types, A row-major, both operands 16-byte aligned,
+// K whole slabs, at least three of them, at least 256 tiles of 256 x 256, B below 2 GiB (its k rows are addressed
+// with 32-bit byte offsets from the tile's first column).  No upper limit on K: this is the only kernel that reads
+// such a B without a packing pass.
+bool k4_ring_takes_row_major_b(const Args& a)
+{
+    if (a.flags != 0 || a.in_dtype == GEMM_FP8_E4M3 || a.in_dtype == GEMM_F32) return false;
+    if (a.a_sk != 1 || a.b_sj != 1) return false;
+    const int64_t ke = ROW_BYTES / elem_size(a.in_dtype);
+    const int64_t tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256) * a.batch;
+    return a.K % ke == 0 && a.K / ke >= 3 && tiles >= K4_RING_WORKGROUPS && tiles < ((int64_t)1 << 31) &&
+           a.K * a.b_sk * elem_size(a.in_dtype) < ((int64_t)1 << 31);
+}
+
+template <typename IN, bool BROW = false>
 static hipError_t launch_ring(const Args& a)
 {
-    using CFG = RingCfg<IN>;
+    using CFG = RingCfg<IN, 8, BROW>;
     const int tiles_m = (int)((a.M + CFG::BM - 1) / CFG::BM), tiles_n = (int)((a.N + CFG::BN - 1) / CFG::BN);
     const int total = (int)((int64_t)tiles_m * tiles_n * a.batch);
     const int eo = a.out_dtype == GEMM_F32 ? 4 : 2;
@@ -33,6 +47,15 @@ static hipError_t launch_ring(const Args& a)
     hipLaunchKernelGGL(k4_mfma_ring<CFG>, dim3(K4_RING_WORKGROUPS), dim3(CFG::T), 0, a.stream, a, tiles_m, tiles_n, total,
                        vec_c ? (int)FAST_VEC_C : 0);
     return hipGetLastError();
+}
+
+hipError_t launch_k4_ring_row_major_b(const Args& a)
+{
+    switch (a.in_dtype) {
+    case GEMM_BF16: return launch_ring<BF16, true>(a);
+    case GEMM_F16: return launch_ring<F16, true>(a);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 hipError_t launch_k4_ring(const Args& a)

@@ -36,9 +36,19 @@ namespace gl {
 
 constexpr int RING_WORKGROUPS = 256;      // one per CU of the GPU this library is written for (8 XCDs x 32)
 
-template <typename IN, int GROUP_M_ = 8>
+// BROW: B is stored row-major (N contiguous; two-byte types).  Its slab is then kept in LDS as it lies in
+// memory, 64 rows of k x 512 bytes of n, and the MFMA fragment (8 consecutive k per lane for one n) is read with the
+// transposing LDS read ds_read_b64_tr_b16.  That instruction works on blocks of 16 lanes: lane 4 kk + q of a block
+// points at 4 consecutive 16-bit elements (here: k row kk, columns 4q..4q+3 of a 4 x 16 patch), and lane 4 q + e
+// receives element e of the lanes q, q+4, q+8, q+12 (here: the four k of column 4q+e).  Two such reads give a
+// lane its 8 k.  Chunk c (16 bytes = 8 columns) of k row r is kept at c ^ 4 (r % 4): the four rows a block reads
+// then lie in four different quarters of the banks.  (Table 1 "smem_transpose" / "ldmatrix.swizzle" with the
+// transpose done by the read instead of by a pass over the operand.)
+template <typename IN, int GROUP_M_ = 8, bool BROW_ = false>
 struct RingCfg {
     using In = IN;
+    static constexpr bool BROW = BROW_;
+    static_assert(!BROW_ || IN::BYTES == 2, "the transposing read used here is the 16-bit one");
     static constexpr int BM = 256, BN = 256, WM = 2, WN = 2, GROUP_M = GROUP_M_;
     static constexpr int T = WM * WN * 64;
     static constexpr int TMI = BM / WM / 32, TNI = BN / WN / 32;
@@ -218,7 +228,9 @@ void k4_mfma_ring(Args a, int tiles_m, int tiles_n, int total, int flags)
         const char* A = (const char*)a.A + (T.b * a.stride_a + T.m0 * a.a_si) * IN::BYTES;
         const char* B = (const char*)a.B + (T.b * a.stride_b + T.n0 * a.b_sj) * IN::BYTES;
         const int64_t bytes_a = valid ? ((a.M - 1 - T.m0) * a.a_si + a.K) * IN::BYTES : 0;
-        const int64_t bytes_b = valid ? ((a.N - 1 - T.n0) * a.b_sj + a.K) * IN::BYTES : 0;
+        // (row-major B: the tile's columns start at n0 of every k row; the resource ends with the last row's last column)
+        const int64_t bytes_b = !valid ? 0 : CFG::BROW ? ((a.K - 1) * a.b_sk + (a.N - T.n0)) * IN::BYTES
+                                                        : ((a.N - 1 - T.n0) * a.b_sj + a.K) * IN::BYTES;
         auto desc = [&](const char* p, int64_t bytes) __attribute__((always_inline)) -> rsrc_t {
             const uint64_t u = (uint64_t)(uintptr_t)p;
             return rsrc_t{__builtin_amdgcn_readfirstlane((int)(uint32_t)u), __builtin_amdgcn_readfirstlane((int)(uint32_t)((u >> 32) & 0xFFFFu)),
@@ -234,13 +246,20 @@ void k4_mfma_ring(Args a, int tiles_m, int tiles_n, int total, int flags)
     const int orow = lane >> 3;
     const int gchunk = (lane & 7) ^ swz(orow + 8 * (wave & 1));
     const int voff_a = (int)((orow * a.a_si + gchunk * V) * IN::BYTES);
-    const int voff_b = (int)((orow * a.b_sj + gchunk * V) * IN::BYTES);
-    const int oct_a = (int)(8 * a.a_si * IN::BYTES), oct_b = (int)(8 * a.b_sj * IN::BYTES);
+    // row-major B: a wave-wide load covers two k rows x 512 bytes; lane L fetches, for k row L/32 of the pair, the
+    // chunk whose swizzled position is L%32 (instruction number idx = wave + 4n holds rows 2 idx, 2 idx + 1 of the
+    // slab, so a row's number modulo 4 is 2 (wave % 2) + L/32 for every n)
+    const int brow_g = 4 * ((2 * (wave & 1) + (lane >> 5)) & 3);
+    const int voff_b = CFG::BROW ? (int)(((lane >> 5) * a.b_sk + ((lane & 31) ^ brow_g) * V) * IN::BYTES)
+                                 : (int)((orow * a.b_sj + gchunk * V) * IN::BYTES);
+    const int oct_a = (int)(8 * a.a_si * IN::BYTES), oct_b = CFG::BROW ? (int)(2 * a.b_sk * IN::BYTES) : (int)(8 * a.b_sj * IN::BYTES);
+    // bytes from one K slab of an operand to the next
+    const int slab_a = ROW_BYTES, slab_b = CFG::BROW ? (int)(KE * a.b_sk * IN::BYTES) : ROW_BYTES;
     using lptr = __attribute__((address_space(3))) char*;
     const int lds0 = (int)(uint32_t)(uintptr_t)(lptr)lds;      // LDS address of region 0
     // loads [lo, hi) of this wave's share of slab `sidx` of an operand into the region at byte offset `reg`
-    auto issue = [&](rsrc_t rsrc, int voff, int oct, int sidx, int reg, int lo, int hi) __attribute__((always_inline)) {
-        const int k0 = sidx * ROW_BYTES;
+    auto issue = [&](rsrc_t rsrc, int voff, int oct, int slab_bytes, int sidx, int reg, int lo, int hi) __attribute__((always_inline)) {
+        const int k0 = sidx * slab_bytes;
 #pragma unroll
         for (int n = lo; n < hi; ++n) {
             const int dst = lds0 + reg + (wave + n * NW) * 1024, soff = k0 + (wave + n * NW) * oct;
@@ -255,20 +274,44 @@ void k4_mfma_ring(Args a, int tiles_m, int tiles_n, int total, int flags)
     const int rd_b = (wn * (BN / WN) + lrow) * ROW_BYTES;
 
     constexpr int NMF = TMI * TNI;                   // MFMA instructions per k-step
-    constexpr int NRD = (TMI + TNI) * CPS;           // fragment reads per k-step
+    constexpr int NRD = CFG::BROW ? TMI + 2 * TNI : (TMI + TNI) * CPS;   // fragment reads per k-step
+    // row-major B: the lane's place in its block of 16 (see RingCfg): k row 8 (lane/32) + (lane%16)/4 of a k-step,
+    // columns 16 ((lane/16)%2) + 4 (lane%4) .. +3 of a 32-column tile; per column tile j the swizzled chunk differs
+    // in the tile number only (j ^ (lane%16)/4)
+    typedef short v4s_t __attribute__((ext_vector_type(4)));
+    typedef __attribute__((address_space(3))) v4s_t* tr_ptr;
+    const int tr_jx = (lane & 15) >> 2, tr_n = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+    const int tr_base = (8 * lhalf + tr_jx) * 512 + ((wn * 16 + (tr_n >> 3)) << 4) + ((tr_n >> 2) & 1) * 8;
     f32x16_t acc[TMI][TNI];
     Frag<IN> fa[2][TMI], fb[2][TNI];
     // fragment reads of k-step ks into `slot`, part `part` of PARTS (B fragments first, as the MFMA walk needs them)
     auto read_part = [&](int ra, int rb, int ks, int slot, auto part_, auto parts_) __attribute__((always_inline)) {
         constexpr int part = decltype(part_)::value, PARTS = decltype(parts_)::value;
-        constexpr int TOTAL = (TMI + TNI) * CPS, PER = TOTAL / PARTS;
+        constexpr int TOTAL = NRD, PER = TOTAL / PARTS;
         static_assert(TOTAL % PARTS == 0, "fragment reads split evenly");
 #pragma unroll
         for (int n = part * PER; n < (part + 1) * PER; ++n) {
-            const int q = n / (TMI + TNI), m = n % (TMI + TNI);
-            const int pos = ((2 * CPS * ks + q) ^ rd_mask) << 4;
-            if (m < TNI) fb[slot][m].c[q] = *(const u32x4_t*)(lds + rb + rd_b + m * 32 * ROW_BYTES + pos);
-            else fa[slot][m - TNI].c[q] = *(const u32x4_t*)(lds + ra + rd_a + (m - TNI) * 32 * ROW_BYTES + pos);
+            if constexpr (CFG::BROW) {
+                if (n < 2 * TNI) {
+                    // B tile j = n/2, k 4 (n%2) .. +3 of the lane's eight: the low or the high half of the fragment
+                    const int j = n >> 1, half = n & 1;
+                    const int off = rb + tr_base + (((j ^ tr_jx) << 2) << 4) + (16 * ks + 4 * half) * 512;
+                    const v4s_t v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((tr_ptr)(lds + off));
+                    const uint32_t lo = (uint32_t)(uint16_t)v[0] | ((uint32_t)(uint16_t)v[1] << 16);
+                    const uint32_t hi = (uint32_t)(uint16_t)v[2] | ((uint32_t)(uint16_t)v[3] << 16);
+                    if (half == 0) { fb[slot][j].c[0].x = lo; fb[slot][j].c[0].y = hi; }
+                    else { fb[slot][j].c[0].z = lo; fb[slot][j].c[0].w = hi; }
+                } else {
+                    const int i = n - 2 * TNI;
+                    const int pos = ((2 * ks) ^ rd_mask) << 4;
+                    fa[slot][i].c[0] = *(const u32x4_t*)(lds + ra + rd_a + i * 32 * ROW_BYTES + pos);
+                }
+            } else {
+                const int q = n / (TMI + TNI), m = n % (TMI + TNI);
+                const int pos = ((2 * CPS * ks + q) ^ rd_mask) << 4;
+                if (m < TNI) fb[slot][m].c[q] = *(const u32x4_t*)(lds + rb + rd_b + m * 32 * ROW_BYTES + pos);
+                else fa[slot][m - TNI].c[q] = *(const u32x4_t*)(lds + ra + rd_a + (m - TNI) * 32 * ROW_BYTES + pos);
+            }
         }
     };
     auto read = [&](int ra, int rb, int ks, int slot) __attribute__((always_inline)) {
@@ -339,11 +382,11 @@ void k4_mfma_ring(Args a, int tiles_m, int tiles_n, int total, int flags)
             constexpr int NL = LASTSTEP ? ((KIND == RING_LAST || BWHOLE) ? LD : HALF) : N0 + N1 + N2;
             auto load_n = [&](int n) __attribute__((always_inline)) {
                 if constexpr (LASTSTEP) {
-                    issue(b2, voff_b, oct_b, i2, ra, n, n + 1);
+                    issue(b2, voff_b, oct_b, slab_b, i2, ra, n, n + 1);
                 } else {
-                    if (n < N0) issue(b1, voff_b, oct_b, i1, nb, HALF + n, HALF + n + 1);
-                    else if (n < N0 + N1) issue(a2, voff_a, oct_a, i2, fifth, n - N0, n - N0 + 1);
-                    else issue(a2, voff_a, oct_a, i2, fifth, HALF + n - N0 - N1, HALF + n - N0 - N1 + 1);
+                    if (n < N0) issue(b1, voff_b, oct_b, slab_b, i1, nb, HALF + n, HALF + n + 1);
+                    else if (n < N0 + N1) issue(a2, voff_a, oct_a, slab_a, i2, fifth, n - N0, n - N0 + 1);
+                    else issue(a2, voff_a, oct_a, slab_a, i2, fifth, HALF + n - N0 - N1, HALF + n - N0 - N1 + 1);
                 }
             };
             if constexpr (LASTSTEP) {
@@ -378,10 +421,10 @@ void k4_mfma_ring(Args a, int tiles_m, int tiles_n, int total, int flags)
 
     // ---- prologue, once per workgroup: slabs 0 and 1 of the first tile into regions 0..3, wait for slab 0 ----
     int o0 = 0, o1 = REGION, o2 = 2 * REGION, o3 = 3 * REGION, o4 = 4 * REGION;   // ra, rb, na, nb, fifth of the next slab
-    issue(cur.ra, voff_a, oct_a, 0, o0, 0, LD);
-    issue(cur.rb, voff_b, oct_b, 0, o1, 0, LD);
-    issue(cur.ra, voff_a, oct_a, 1, o2, 0, LD);
-    issue(cur.rb, voff_b, oct_b, 1, o3, 0, LD);
+    issue(cur.ra, voff_a, oct_a, slab_a, 0, o0, 0, LD);
+    issue(cur.rb, voff_b, oct_b, slab_b, 0, o1, 0, LD);
+    issue(cur.ra, voff_a, oct_a, slab_a, 1, o2, 0, LD);
+    issue(cur.rb, voff_b, oct_b, slab_b, 1, o3, 0, LD);
     asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");

@@ -105,8 +105,10 @@ def kernel_patterns(variant: int, in_dtype: int, path: str, bm: int, bn: int, th
     if "direct-to-lds" in path:
         swz = "false" if flags & gemm.GEMM_FLAG_DEOPT_NO_SWIZZLE else "true"
         ovl = "false" if flags & gemm.GEMM_FLAG_DEOPT_NO_OVERLAP else "true"
-        if "(persistent)" in path:
-            pats.append(r"k4_mfma_ring<gl::RingCfg<%s, " % dt)
+        if "(persistent,B-row-major)" in path:
+            pats.append(r"k4_mfma_ring<gl::RingCfg<%s, \d+, true>" % dt)
+        elif "(persistent)" in path:
+            pats.append(r"k4_mfma_ring<gl::RingCfg<%s, \d+, false>" % dt)
         else:
             pats.append(r"k4_mfma_fast<gl::FastCfg<%s, %d, \d+, %s, %s, \d+, false>" % (dt, bm, swz, ovl))
         if "packed" in path:

@@ -119,6 +119,20 @@ def test_persistent_kernel_is_exact(dtype, case):
     np.testing.assert_array_equal(got, want)
 
 
+@pytest.mark.parametrize("dtype", [gen.BF16, gen.F16])
+@pytest.mark.parametrize("case", RING_CASES + [(1024, 768, 70, 22)], ids=["%dx%dx%dslabs_b%d" % c for c in RING_CASES + [(1024, 768, 70, 22)]])
+def test_persistent_kernel_reads_a_row_major_b_in_place(dtype, case):
+    """B stored row-major (N contiguous), aligned: the persistent kernel keeps B's slab in LDS as it lies in memory
+    and reads the fragments with transposing LDS reads.  Integer operands, fp32 output: bit for bit.  The cases
+    cover edge tiles (columns past N are whatever follows in memory and must only reach masked outputs), unequal
+    tile counts per workgroup, a leading dimension beyond N, and a K of more than 64 slabs."""
+    M, N, ns, nb = case
+    K = slabs(dtype, ns)
+    inp = int_inputs(dtype, M, N, K, ROW, ROW, batch=nb, ldb=N + (8 if ns == 7 else 0) + (-N) % 8, seed=ns + 100)
+    q = run_exact(inp, "mfma32-direct-to-lds(persistent,B-row-major)")
+    assert q.grid == 256 and q.workspace_bytes == 0 and q.violated == 0
+
+
 @pytest.mark.parametrize("dtype", DTYPES)
 @pytest.mark.parametrize("flags,tag", [(gemm.GEMM_FLAG_DEOPT_NO_SWIZZLE, "-noswz"), (gemm.GEMM_FLAG_DEOPT_NO_OVERLAP, "-noovl"),
                                        (gemm.GEMM_FLAG_DEOPT_NO_RASTER, "-noraster"),
