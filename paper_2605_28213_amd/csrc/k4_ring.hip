@@ -22,18 +22,32 @@ bool k4_uses_ring(const Args& a)
     return a.K / ke >= 3 && a.K / ke <= 64 && tiles >= K4_RING_WORKGROUPS && tiles < ((int64_t)1 << 31);
 }
 
-// Row-major B read in place (transposing LDS reads): two-byte types, A row-major, both operands 16-byte aligned,
-// K whole slabs, at least three of them, at least 256 tiles of 256 x 256, B below 2 GiB (its k rows are addressed
-// with 32-bit byte offsets from the tile's first column).  No upper limit on K: this is the only kernel that reads
-// such a B without a packing pass.
+// Row-major B read in place (transposing LDS reads): two-byte types, A row-major; any leading dimensions and any K
+// (rows aligned to an element only are loaded with under-aligned 16-byte loads, a ragged last slab is cleared in
+// LDS), at least three slabs, at least 256 tiles of 256 x 256, rows of A up to 4 MiB, B below 2 GiB (its k rows are
+// addressed with 32-bit byte offsets from the tile's first column).  No upper limit on K: this is the only kernel
+// that reads such a B without a packing pass.  When the last row of an operand has an odd number of elements
+// (K odd for A, N odd for B) the kernel's loads reach the one element after the operand (RING_BROW_SLACK): with the
+// pointers known, such a product is only taken when that element lies in the same 4 KiB page as the operand's last
+// byte, so that it is mapped whatever follows the operand.
+static bool tail_element_in_last_page(const void* base, int64_t elems, int64_t last_row_len, int es)
+{
+    if (!base || last_row_len % 2 == 0) return true;          // (a query without pointers; no dword straddles the end)
+    const uintptr_t end = (uintptr_t)base + (uintptr_t)(elems * es);     // first byte past the operand
+    return (end & 4095u) != 0;
+}
+
 bool k4_ring_takes_row_major_b(const Args& a)
 {
     if (a.flags != 0 || a.in_dtype == GEMM_FP8_E4M3 || a.in_dtype == GEMM_F32) return false;
-    if (a.a_sk != 1 || a.b_sj != 1) return false;
-    const int64_t ke = ROW_BYTES / elem_size(a.in_dtype);
+    if (a.a_sk != 1 || a.b_sj != 1 || a.M <= 0 || a.N <= 0 || a.K <= 0) return false;
+    const int es = elem_size(a.in_dtype);
+    const int64_t ke = ROW_BYTES / es;
     const int64_t tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256) * a.batch;
-    return a.K % ke == 0 && a.K / ke >= 3 && tiles >= K4_RING_WORKGROUPS && tiles < ((int64_t)1 << 31) &&
-           a.K * a.b_sk * elem_size(a.in_dtype) < ((int64_t)1 << 31);
+    if ((a.K + ke - 1) / ke < 3 || tiles < K4_RING_WORKGROUPS || tiles >= ((int64_t)1 << 31)) return false;
+    if (a.a_si * es > ((int64_t)1 << 22) || a.K * a.b_sk * es >= ((int64_t)1 << 31)) return false;
+    return tail_element_in_last_page(a.A, (a.batch - 1) * a.stride_a + (a.M - 1) * a.a_si + a.K, a.K, es) &&
+           tail_element_in_last_page(a.B, (a.batch - 1) * a.stride_b + (a.K - 1) * a.b_sk + a.N, a.N, es);
 }
 
 template <typename IN, bool BROW = false>

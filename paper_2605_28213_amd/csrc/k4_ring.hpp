@@ -34,6 +34,10 @@
 
 namespace gl {
 
+// Bytes past an operand's end that the row-major-B form may read.  Buffer loads are range-checked dword by dword,
+// and a row with an odd number of two-byte elements ends in the middle of a dword (rows are loaded as dwords from
+// their first element): that dword is wanted, and its other half is the one element after the operand.
+constexpr int RING_BROW_SLACK = 2;
 constexpr int RING_WORKGROUPS = 256;      // one per CU of the GPU this library is written for (8 XCDs x 32)
 
 // BROW: B is stored row-major (N contiguous; two-byte types).  Its slab is then kept in LDS as it lies in
@@ -188,7 +192,7 @@ void k4_mfma_ring(Args a, int tiles_m, int tiles_n, int total, int flags)
     static_assert(BM == 256 && BN == 256 && NW == 4 && LD == 8 && NK >= 2, "written for 256 x 256 tiles and four waves");
     __shared__ __attribute__((aligned(1024))) char lds[CFG::LDS_BYTES];
 
-    const int t = threadIdx.x, lane = t & 63;
+    const int t = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int wm = wave / WN, wn = wave % WN;
 
@@ -236,22 +240,49 @@ void k4_mfma_ring(Args a, int tiles_m, int tiles_n, int total, int flags)
             return rsrc_t{__builtin_amdgcn_readfirstlane((int)(uint32_t)u), __builtin_amdgcn_readfirstlane((int)(uint32_t)((u >> 32) & 0xFFFFu)),
                           __builtin_amdgcn_readfirstlane((int)(uint32_t)(bytes < CAP ? bytes : CAP)), RSRC_FLAGS};
         };
-        T.ra = desc(A, bytes_a);
-        T.rb = desc(B, bytes_b);
+        // (row-major B form: the dword that holds the last element of an odd-length last row reaches one element past
+        // the operand; the resources end SLACK bytes later, which the host has checked to lie in the page of the
+        // operand's last byte; that element lands beyond K in A, where clear_tail removes it, and in a column past N
+        // in B, which only feeds outputs that are never stored)
+        constexpr int64_t SLACK = CFG::BROW ? RING_BROW_SLACK : 0;
+        T.ra = desc(A, valid ? bytes_a + SLACK : 0);
+        T.rb = desc(B, valid ? bytes_b + SLACK : 0);
         return T;
     };
 
     // ---- global -> LDS (as in k4_mfma_fast: lane L of a wave-wide 16-byte load lands at byte 16 L of a 1 KB
     // block = 8 LDS rows; the lane -> chunk assignment applies the swizzle; octet and slab are scalar) ----
-    const int orow = lane >> 3;
-    const int gchunk = (lane & 7) ^ swz(orow + 8 * (wave & 1));
-    const int voff_a = (int)((orow * a.a_si + gchunk * V) * IN::BYTES);
-    // row-major B: a wave-wide load covers two k rows x 512 bytes; lane L fetches, for k row L/32 of the pair, the
-    // chunk whose swizzled position is L%32 (instruction number idx = wave + 4n holds rows 2 idx, 2 idx + 1 of the
-    // slab, so a row's number modulo 4 is 2 (wave % 2) + L/32 for every n)
-    const int brow_g = 4 * ((2 * (wave & 1) + (lane >> 5)) & 3);
-    const int voff_b = CFG::BROW ? (int)(((lane >> 5) * a.b_sk + ((lane & 31) ^ brow_g) * V) * IN::BYTES)
-                                 : (int)((orow * a.b_sj + gchunk * V) * IN::BYTES);
+    // Everything derived from the lane id is (re)computed by lane_setup() at the top of every tile, from a lane id
+    // taken behind an opaque statement: kept across the epilogue (which needs most of the registers) such values get
+    // spilled, and a scratch reload waits on the same counter as the direct loads in flight.
+    int lane, orow, gchunk, voff_a, voff_b, lrow, lhalf, rd_mask, rd_a, rd_b, tr_jx, tr_base;
+    auto lane_setup = [&]() __attribute__((always_inline)) {
+        unsigned all = ~0u;
+        asm volatile("" : "+s"(all));
+        lane = (int)__builtin_amdgcn_mbcnt_hi(all, __builtin_amdgcn_mbcnt_lo(all, 0u));
+        orow = lane >> 3;
+        gchunk = (lane & 7) ^ swz(orow + 8 * (wave & 1));
+        voff_a = (int)((orow * a.a_si + gchunk * V) * IN::BYTES);
+        // row-major B: a wave-wide load covers two k rows x 512 bytes; lane L fetches, for k row L/32 of the pair, the
+        // chunk whose swizzled position is L%32 (instruction number idx = wave + 4n holds rows 2 idx, 2 idx + 1 of the
+        // slab, so a row's number modulo 4 is 2 (wave % 2) + L/32 for every n)
+        const int brow_g = 4 * ((2 * (wave & 1) + (lane >> 5)) & 3);
+        voff_b = CFG::BROW ? (int)(((lane >> 5) * a.b_sk + ((lane & 31) ^ brow_g) * V) * IN::BYTES)
+                           : (int)((orow * a.b_sj + gchunk * V) * IN::BYTES);
+        // LDS -> registers
+        lrow = lane & 31;
+        lhalf = lane >> 5;
+        rd_mask = (lhalf * CPS) ^ swz(lrow);
+        rd_a = (wm * (BM / CFG::WM) + lrow) * ROW_BYTES;
+        rd_b = (wn * (BN / WN) + lrow) * ROW_BYTES;
+        // row-major B: the lane's place in its block of 16 (see RingCfg): k row 8 (lane/32) + (lane%16)/4 of a k-step,
+        // columns 16 ((lane/16)%2) + 4 (lane%4) .. +3 of a 32-column tile; per column tile j the swizzled chunk
+        // differs in the tile number only (j ^ (lane%16)/4)
+        tr_jx = (lane & 15) >> 2;
+        const int tr_n = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+        tr_base = (8 * lhalf + tr_jx) * 512 + ((wn * 16 + (tr_n >> 3)) << 4) + ((tr_n >> 2) & 1) * 8;
+    };
+    lane_setup();
     const int oct_a = (int)(8 * a.a_si * IN::BYTES), oct_b = CFG::BROW ? (int)(2 * a.b_sk * IN::BYTES) : (int)(8 * a.b_sj * IN::BYTES);
     // bytes from one K slab of an operand to the next
     const int slab_a = ROW_BYTES, slab_b = CFG::BROW ? (int)(KE * a.b_sk * IN::BYTES) : ROW_BYTES;
@@ -267,21 +298,10 @@ void k4_mfma_ring(Args a, int tiles_m, int tiles_n, int total, int flags)
         }
     };
 
-    // ---- LDS -> registers ----------------------------------------------------------------------------
-    const int lrow = lane & 31, lhalf = lane >> 5;
-    const int rd_mask = (lhalf * CPS) ^ swz(lrow);
-    const int rd_a = (wm * (BM / CFG::WM) + lrow) * ROW_BYTES;
-    const int rd_b = (wn * (BN / WN) + lrow) * ROW_BYTES;
-
     constexpr int NMF = TMI * TNI;                   // MFMA instructions per k-step
     constexpr int NRD = CFG::BROW ? TMI + 2 * TNI : (TMI + TNI) * CPS;   // fragment reads per k-step
-    // row-major B: the lane's place in its block of 16 (see RingCfg): k row 8 (lane/32) + (lane%16)/4 of a k-step,
-    // columns 16 ((lane/16)%2) + 4 (lane%4) .. +3 of a 32-column tile; per column tile j the swizzled chunk differs
-    // in the tile number only (j ^ (lane%16)/4)
     typedef short v4s_t __attribute__((ext_vector_type(4)));
     typedef __attribute__((address_space(3))) v4s_t* tr_ptr;
-    const int tr_jx = (lane & 15) >> 2, tr_n = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-    const int tr_base = (8 * lhalf + tr_jx) * 512 + ((wn * 16 + (tr_n >> 3)) << 4) + ((tr_n >> 2) & 1) * 8;
     f32x16_t acc[TMI][TNI];
     Frag<IN> fa[2][TMI], fb[2][TNI];
     // fragment reads of k-step ks into `slot`, part `part` of PARTS (B fragments first, as the MFMA walk needs them)
@@ -342,7 +362,37 @@ void k4_mfma_ring(Args a, int tiles_m, int tiles_n, int total, int flags)
 
     Tile cur = tile_at(0), nxt = tile_at(1);
     int stores_behind = 0;                           // 16-byte stores this wave issued in the epilogue before the current tile (unmasked path only)
-    const int nslab = (int)(a.K / KE);               // whole slabs, at least 3 (checked by the launcher)
+    // Slabs per tile, at least 3 (checked by the launcher).  Only the row-major-B form takes a K that is not whole
+    // slabs: `ktail` is the number of valid k in its last slab (0: the slab is whole).
+    const int nslab = CFG::BROW ? (int)((a.K + KE - 1) / KE) : (int)(a.K / KE);
+    const int ktail = CFG::BROW ? (int)(a.K % KE) : 0;
+    // Ragged K: the last slab of A holds, beyond k = K, the next row's first elements (or the element after the
+    // operand), and B's rows beyond K are zeros from the range check; anything but zeros on either side could turn
+    // into NaN (0 x NaN), so both are cleared.  Once the slab has landed (the wait of the slab before it) and before the barrier that releases it
+    // to the readers, every lane clears what lies beyond K in the chunks its own loads wrote.
+    auto clear_tail = [&](int reg_a, int reg_b) __attribute__((always_inline)) {
+        unsigned zero = 0;                        // (opaque: a zero vector kept in registers across the main loop would be spilled)
+        asm volatile("" : "+v"(zero));
+#pragma unroll
+        for (int n = 0; n < LD; ++n) {
+            const int blk = (wave + n * NW) * 1024 + lane * 16;
+            {   // A: row 8 (wave + 4n) + orow, logical chunk gchunk = elements gchunk*V .. +V-1 of the slab
+                const int valid = ktail - gchunk * V;
+                if (valid < V) {
+                    u32x4_t w = *(const u32x4_t*)(lds + reg_a + blk);
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) {
+                        const int left = valid - 2 * d;           // valid 16-bit elements of this dword
+                        w[d] = left <= 0 ? 0u : left == 1 ? (w[d] & 0xFFFFu) : w[d];
+                    }
+                    *(u32x4_t*)(lds + reg_a + blk) = w;
+                }
+            }
+            // B: k row 2 (wave + 4n) + lane/32 of the slab
+            if (2 * (wave + n * NW) + (lane >> 5) >= ktail) *(u32x4_t*)(lds + reg_b + blk) = u32x4_t{zero, zero, zero, zero};
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    };
 
     // One slab of the stream; ra, rb: byte offsets of the regions holding its A and B, na, nb: those of the
     // next slab, fifth: the free one.  Prefetches, in issue order: second half of B of the next slab, both
@@ -398,6 +448,9 @@ void k4_mfma_ring(Args a, int tiles_m, int tiles_n, int total, int flags)
                 if (KIND == RING_FIRST && stores_behind == 32) asm volatile("s_waitcnt vmcnt(40) lgkmcnt(0)" ::: "memory");
                 else if (KIND == RING_FIRST && stores_behind == 64) asm volatile("s_waitcnt vmcnt(63) lgkmcnt(0)" ::: "memory");
                 else asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
+                if constexpr (CFG::BROW && KIND == RING_PEN) {
+                    if (ktail != 0) clear_tail(na, nb);       // the tile's last slab has just landed in the next regions
+                }
                 __builtin_amdgcn_s_barrier();
                 asm volatile("" ::: "memory");
             }
@@ -436,6 +489,7 @@ void k4_mfma_ring(Args a, int tiles_m, int tiles_n, int total, int flags)
     };
     const bool vec_ok = (flags & FAST_VEC_C) != 0;
     for (int i = 0; i < n_mine; ++i) {
+        lane_setup();
         slab(std::integral_constant<int, RING_FIRST>{}, 0, o0, o1, o2, o3, o4);
         rotate();
         for (int s = 1; s + 2 < nslab; ++s) {

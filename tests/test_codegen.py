@@ -131,7 +131,7 @@ def test_persistent_kernel_slab_loop(tmp_path):
     text = out.read_text()
     for dtype, mfma, per_slab in (("4BF16", "v_mfma_f32_32x32x16_bf16", 64), ("3F16", "v_mfma_f32_32x32x16_f16", 64),
                                   ("4E4M3", "v_mfma_scale_f32_32x32x64_f8f6f4", 32)):
-        prefix = "_ZN2gl12k4_mfma_ringINS_7RingCfgINS_" + dtype
+        prefix = "_ZN2gl12k4_mfma_ringINS_7RingCfgINS_" + dtype + "ELi8ELb0E"
         m = re.search(r"^(%s\w*):[^\n]*\n(.*?)\.Lfunc_end" % re.escape(prefix), text, flags=re.S | re.M)
         assert m, prefix
         ops = first_inner_loop(m.group(2))
@@ -147,3 +147,14 @@ def test_persistent_kernel_slab_loop(tmp_path):
         meta = metadata(text, prefix)
         assert meta["agpr"] == 256 and meta["lds"] == 160 * 1024
         assert meta["vgpr_spill"] == (0 if dtype != "4E4M3" else meta["vgpr_spill"]) and meta["vgpr_spill"] <= 2
+    # the form that reads a row-major B in place: per slab 16 fragment reads of A and 32 transposing reads of B
+    for dtype, mfma in (("4BF16", "v_mfma_f32_32x32x16_bf16"), ("3F16", "v_mfma_f32_32x32x16_f16")):
+        prefix = "_ZN2gl12k4_mfma_ringINS_7RingCfgINS_" + dtype + "ELi8ELb1E"
+        m = re.search(r"^(%s\w*):[^\n]*\n(.*?)\.Lfunc_end" % re.escape(prefix), text, flags=re.S | re.M)
+        assert m, prefix
+        ops = first_inner_loop(m.group(2))
+        count = lambda name: sum(o == name for o in ops)
+        assert count(mfma) == 64 and count("ds_read_b128") == 16 and count("ds_read_b64_tr_b16") == 32
+        assert count("buffer_load_dwordx4") == 16 and count("s_barrier") == 1
+        meta = metadata(text, prefix)
+        assert meta["vgpr_spill"] == 0 and meta["scratch"] == 0 and meta["lds"] == 160 * 1024

@@ -133,6 +133,28 @@ def test_persistent_kernel_reads_a_row_major_b_in_place(dtype, case):
     assert q.grid == 256 and q.workspace_bytes == 0 and q.violated == 0
 
 
+BROW_RAGGED = [  # (M, N, K, batch, lda - K, ldb - N, path suffix)
+    (520, 300, 256, 43, 1, 1, ""),             # odd leading dimensions: every row aligned to an element only
+    (512, 509, 320, 70, 3, 0, ""),             # N odd: the last row of B ends in the middle of a dword
+    (512, 509, 321, 70, 0, 0, ""),             # K odd as well: a last slab of one element, A's last row ends mid-dword
+    (700, 515, 203, 29, 0, 0, ""),             # three whole slabs and a ragged fourth, edge tiles in both directions
+    (4099, 4093, 449, 1, 0, 0, ""),            # the ragged fp16 workload's shape with a shorter K: 17 x 16 tiles, 3 rows in the last
+    (4096 + 40, 4096, 200, 1, 0, 5, ""),
+]
+
+
+@pytest.mark.parametrize("dtype", [gen.BF16, gen.F16])
+@pytest.mark.parametrize("case", BROW_RAGGED, ids=["%dx%dx%d_b%d_%d_%d%s" % c for c in BROW_RAGGED])
+def test_row_major_operands_with_odd_leading_dimensions_and_ragged_k_in_place(dtype, case):
+    """A and B row-major, nothing aligned, K not whole slabs, no scratch lent: the persistent kernel loads the rows
+    with under-aligned 16-byte loads, clears what lies beyond K in the last slab (the gaps between rows hold 3, the
+    operands' neighbours whatever the allocator left); a thin remainder of rows is a last, mostly empty row of tiles."""
+    M, N, K, nb, pa, pb, suffix = case
+    inp = int_inputs(dtype, M, N, K, ROW, ROW, batch=nb, lda=K + pa, ldb=N + pb, seed=K)
+    q = run_exact(inp, "mfma32-direct-to-lds(persistent,B-row-major)" + suffix)
+    assert q.violated == 0
+
+
 @pytest.mark.parametrize("dtype", DTYPES)
 @pytest.mark.parametrize("flags,tag", [(gemm.GEMM_FLAG_DEOPT_NO_SWIZZLE, "-noswz"), (gemm.GEMM_FLAG_DEOPT_NO_OVERLAP, "-noovl"),
                                        (gemm.GEMM_FLAG_DEOPT_NO_RASTER, "-noraster"),

@@ -266,7 +266,10 @@ def test_risk_field_of_the_conditioned_states():
             risk = gate.risk_probe(v, viol, conf, ref_v, ref_c, ledger_path=LEDGER, time_budget_s=0.5)
             assert risk["strict"].startswith("refused(precondition") and "LD16_A" in risk["violated"], risk
             assert risk["slow_path_verdict"] == "passed" and risk["fast_path_verdict"] == "passed", risk
-            assert "masked" in risk["slow_path"] and "masked" not in risk["fast_path"], risk
+            # (K4 on the full-size ragged workload without scratch: the persistent kernel reads B row-major in place,
+            # with under-aligned loads and a seventeenth, mostly empty row of tiles; everywhere else the masked paths)
+            in_place = v == gemm.GEMM_K4_MFMA and vname == "C3"
+            assert ("B-row-major" if in_place else "masked") in risk["slow_path"] and "masked" not in risk["fast_path"], risk
             assert risk["slowdown"] > 1.0, risk
             e = gate.run_gate(v, conf, ref_c, seeds=(0,), ledger_path=LEDGER, time_budget_s=0.5, predecessor=prev, risk=risk)
             e["workload"] = conf.name
