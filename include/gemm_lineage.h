@@ -141,8 +141,10 @@ typedef struct {
                                         with scratch of at least gemm_query's workspace_bytes it packs the
                                         operands (K contiguous, aligned, zero-padded K; an operand that meets
                                         the conditions by itself is used in place when K is whole slabs) and
-                                        runs the fast kernel on the copies; without scratch its masked kernel
-                                        runs.  (2) The
+                                        runs the fast kernel on the copies; without scratch a product with A and
+                                        B row-major and at least 256 tiles of 256 x 256 (bf16, fp16) is multiplied
+                                        in place by the persistent kernel (gemm_query names the path), any other
+                                        by the masked kernel.  (2) The
                                         fast path applies but the product has too few tiles to fill the chip
                                         and a long K (batch 1, 17 or more rows): with scratch it splits K into
                                         ranges that run side by side and adds their fp32 partial products in a
