@@ -222,6 +222,16 @@ def effect_of(entry: dict, predecessor: Optional[dict]) -> Optional[dict]:
     delta = {c: {"before": ca[c], "after": cb[c]} for c in sorted(set(ca) & set(cb))}
     if delta:
         eff["counters"] = delta
+        # what the counters say about the step, in words (kept with the numbers: Sec. 3.3 feeds profile deltas into the record)
+        ratio = lambda c: (cb[c] / ca[c]) if c in delta and ca[c] else None
+        parts = []
+        for c, what in (("SQ_INSTS_LDS", "LDS instructions"), ("SQ_INSTS_VMEM_RD", "vector memory reads"), ("SQ_INSTS_VALU", "VALU instructions"),
+                        ("SQ_WAIT_INST_ANY", "wave cycles spent waiting"), ("FETCH_SIZE_bytes", "bytes fetched past L2")):
+            r = ratio(c)
+            if r is not None:
+                parts.append("%s x%.2f" % (what, r))
+        if parts:
+            eff["reading"] = ("slower" if eff["regression"] else "faster" if eff["speedup"] > 1.02 else "level") + ": " + ", ".join(parts)
     return eff
 
 

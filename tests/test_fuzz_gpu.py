@@ -98,6 +98,48 @@ def draw_cols_case(rng, i):
 COLS_CASES = [draw_cols_case(np.random.default_rng(2500 + i), i) for i in range(24)]
 
 
+def draw_many_tiles_case(rng, i):
+    """At least 256 tiles of 256 x 256 with a short K: the persistent forms of the tiled kernel.  B column-major with
+    aligned operands and whole slabs (all three types), or A and B row-major with anything (bf16, fp16: read in place)."""
+    row_major_b = bool(rng.random() < 0.5)
+    dtype = int(rng.choice([gen.BF16, gen.F16] if row_major_b else [gen.BF16, gen.F16, gen.E4M3]))
+    es = gen.ELEM_BYTES[dtype]
+    tm, tn = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+    batch = -(-256 // (tm * tn)) + int(rng.integers(0, 3))
+    M = 256 * (tm - 1) + int(rng.integers(97, 257))        # (more than 96 rows and columns: not the streaming kernel's)
+    N = 256 * (tn - 1) + int(rng.integers(97, 257))
+    if row_major_b:
+        K = int(rng.integers(2 * 128 // es + 1, 6 * 128 // es))
+        lda, ldb = K + int(rng.integers(0, 4)), N + int(rng.integers(0, 4))
+    else:
+        K = 128 // es * int(rng.integers(3, 8))
+        lda = ldb = K + 16 // es * int(rng.integers(0, 3))
+    out = int(rng.choice([gen.BF16 if dtype == gen.E4M3 else dtype, gen.F32]))
+    return gen.Config(f"tiles{i}", M, N, K, dtype, out, ROW, ROW if row_major_b else COL, str(rng.choice(["uniform", "normal"])),
+                      batch=batch, scaled=bool(rng.random() < 0.3), biased=bool(rng.random() < 0.3), lda=lda, ldb=ldb,
+                      ldc=N + int(rng.integers(0, 3)))
+
+
+TILES_CASES = [draw_many_tiles_case(np.random.default_rng(3000 + i), i) for i in range(24)]
+
+
+@pytest.mark.parametrize("i", range(len(TILES_CASES)))
+def test_random_case_with_many_tiles(i):
+    cfg = TILES_CASES[i]
+    inp = gen.make_inputs(cfg, 300 + i)
+    C_ref, D = oracle_for(inp)
+    q = gemm.gemm_query(4, gemm.make_desc(cfg.M, cfg.N, cfg.K, cfg.in_dtype, cfg.out_dtype, ROW, cfg.layout_b, lda=inp.lda, ldb=inp.ldb,
+                                          ldc=inp.ldc, batch=cfg.batch, stride_a=inp.stride_a, stride_b=inp.stride_b, stride_c=inp.stride_c))
+    if cfg.layout_b == ROW:
+        assert q.path == "mfma32-direct-to-lds(persistent,B-row-major)" and q.grid == 256, (cfg, q)
+    else:   # (the tile rule may prefer 128-tiles, which have no persistent form)
+        assert q.path in ("mfma32-direct-to-lds(persistent)", "mfma32-direct-to-lds"), (cfg, q)
+    rc, C, _ = util.run_config(4, inp)
+    assert rc == gemm.GEMM_OK, (cfg, gemm.gemm_status_string(rc), gemm.gemm_last_launch_error())
+    err = util.norm_err(C[:, :, : cfg.N], C_ref, D)
+    assert err <= util.TOL[cfg.in_dtype], (cfg, err)
+
+
 @pytest.mark.parametrize("i", range(len(COLS_CASES)))
 def test_random_case_with_few_columns(i):
     cfg = COLS_CASES[i]
