@@ -25,7 +25,7 @@ if ROOT not in sys.path:
 # HBM-side bytes per launch of the headline kernel from the FETCH_SIZE / WRITE_SIZE counter runs
 # summarised in profiles/gate_counters_all_states.md and profiles/k4_mfma_fast_bf16_C2.md (scaled by the copy probe's factor).  The figure
 # belongs to one version of the kernel sources: when their digest differs it is reported as null.
-TRAFFIC_C2 = {"bytes": 1.754e9, "sources_sha256": "b2cc213a76c76811e2df49c574344f0c31df0dc5a3dc3a326b8509c610edd814"}
+TRAFFIC_C2 = {"bytes": 1.746e9, "sources_sha256": "528565ff516ad75536711f1dff3ec35a427133f2b268779b17ee4dbd42f93ae5"}
 KERNEL_SOURCES = ["csrc/common.hpp", "csrc/k4_kernels.hpp", "csrc/k4_mfma.hip"]
 
 
@@ -48,7 +48,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=25)
-    ap.add_argument("--ramp-seconds", type=float, default=1.0,
+    ap.add_argument("--ramp-seconds", type=float, default=3.0,
                     help="untimed launches of the headline kernel for this long before the warm-up (clock ramp from idle)")
     ap.add_argument("--no-extras", action="store_true", help="headline workload only (used for profiling)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
@@ -264,7 +264,7 @@ def main():
             c = gen.CONFIGS[name]
             v = gemm.GEMM_K4_MFMA
             _, s2, d2, keep2 = device_sets(c)
-            _, sms, _ = timed(v, s2, d2, 100, 25)
+            _, sms, _ = timed(v, s2, d2, 100, 25, ramp_s=0.3)     # (each shape gets a short clock ramp of its own)
             ss = stats(sms)
             rl = roofline_for(c, ss["mean_us"], bound)
             entry = {"variant": gemm.gemm_variant_name(v), "path": gemm.gemm_query(v, d2, *s2[0]).path,
