@@ -29,6 +29,9 @@
 // Conditions on top of k4_mfma_fast's: at least 3 slabs per tile (the kinds first / last-but-one / last are
 // distinct slabs), at least as many tiles as workgroups launched.  Paper Table 1: "cp.async + pipeline"
 // carried across tile boundaries; the persistent tile loop is the "stream-K" family's scheduling.
+//
+// A second form of the same kernel (RingCfg<..., BROW = true>) reads a ROW-MAJOR B in place, with transposing LDS
+// reads, from rows that need not be aligned and a K that need not be whole slabs: see RingCfg below.
 #pragma once
 #include "k4_kernels.hpp"
 
