@@ -297,7 +297,10 @@ void k4_mfma_ring(Args a, int tiles_m, int tiles_n, int total, int flags)
 #pragma unroll
         for (int n = lo; n < hi; ++n) {
             const int dst = lds0 + reg + (wave + n * NW) * 1024, soff = k0 + (wave + n * NW) * oct;
-            asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds" ::"s"(dst), "v"(voff), "s"(rsrc), "s"(soff) : "memory");   // (M0 is reserved: the compiler keeps nothing in it and this kernel has no other user)
+            // (one wait state between a scalar write of M0 and a load to LDS that reads it: gfx9 does not interlock the
+            // pair, and the compiler's hazard pass does not look inside inline assembly.  M0 is reserved: the compiler
+            // keeps nothing in it and this kernel has no other user.)
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds" ::"s"(dst), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
         }
     };
 

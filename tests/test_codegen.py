@@ -147,6 +147,13 @@ def test_persistent_kernel_slab_loop(tmp_path):
         meta = metadata(text, prefix)
         assert meta["agpr"] == 256 and meta["lds"] == 160 * 1024
         assert meta["vgpr_spill"] == (0 if dtype != "4E4M3" else meta["vgpr_spill"]) and meta["vgpr_spill"] <= 2
+    # every direct load issued from inline assembly keeps a wait state between its write of M0 and the load (gfx9 does
+    # not interlock the pair and the compiler's hazard pass does not look inside inline assembly)
+    lines = [l.strip() for l in text.split("\n")]
+    loads = [i for i, l in enumerate(lines) if l.startswith("buffer_load_dwordx4") and l.endswith("lds")]
+    assert len(loads) > 100
+    for i in loads:
+        assert lines[i - 1].startswith("s_nop") and lines[i - 2].startswith("s_mov_b32 m0"), lines[i - 3:i + 1]
     # the form that reads a row-major B in place: per slab 16 fragment reads of A and 32 transposing reads of B
     for dtype, mfma in (("4BF16", "v_mfma_f32_32x32x16_bf16"), ("3F16", "v_mfma_f32_32x32x16_f16")):
         prefix = "_ZN2gl12k4_mfma_ringINS_7RingCfgINS_" + dtype + "ELi8ELb1E"
