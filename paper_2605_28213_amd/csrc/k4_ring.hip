@@ -8,18 +8,19 @@ static_assert(RING_WORKGROUPS == K4_RING_WORKGROUPS, "the planner reports the gr
 
 // The persistent form of the 256-tile kernel takes a product that gives every one of its workgroups at least
 // one tile and whose K is at least three slabs (the slab kinds first / last-but-one / last of a tile are
-// distinct) and at most 64: what it saves is per tile (the ring's cold start, and loads that stop during the
-// epilogue), so it pays on short K (e4m3 64 x 1024^3, 8 slabs: 106 -> 86 us; bf16 16 x 2048^3, 32 slabs:
-// 259 -> 234 us), is level at 64 slabs (bf16 4096^3: 106 / 107 us) and loses 1.5-2 % at 128 slabs (bf16
-// 8192^3: 793 against 779 us on the same box), where the package is at its power limit either way.  The
-// simplified states and the 128-tile configuration stay with k4_mfma_fast.
+// distinct) and at most 48: what it saves is per tile (the ring's cold start, and loads that stop during the
+// epilogue), so it pays on short K (same box, one-tile form against this one: e4m3 64 x 1024^3, 8 slabs, 95 -> 84 us;
+// bf16 32 x 1024^3, 16 slabs, 85 -> 70 us; bf16 16 x 2048^3, 32 slabs, 243 -> 230 us), and loses 2 % at 64 slabs
+// (bf16 4096^3: 106 -> 108 us) and at 128 (bf16 8192^3: 779 -> 793 us), where the package is at its power limit either
+// way and the loads issued outside the steady-state loop carry their wait states.  The simplified states and the
+// 128-tile configuration stay with k4_mfma_fast.
 bool k4_uses_ring(const Args& a)
 {
     constexpr uint32_t DEOPT = GEMM_FLAG_DEOPT_NO_SWIZZLE | GEMM_FLAG_DEOPT_NO_OVERLAP | GEMM_FLAG_DEOPT_NO_RASTER | GEMM_FLAG_DEOPT_NO_PERSISTENT;
     if ((a.flags & DEOPT) || k4_small_tiles(a)) return false;
     const int64_t ke = ROW_BYTES / elem_size(a.in_dtype);
     const int64_t tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256) * a.batch;
-    return a.K / ke >= 3 && a.K / ke <= 64 && tiles >= K4_RING_WORKGROUPS && tiles < ((int64_t)1 << 31);
+    return a.K / ke >= 3 && a.K / ke <= 48 && tiles >= K4_RING_WORKGROUPS && tiles < ((int64_t)1 << 31);
 }
 
 // Row-major B read in place (transposing LDS reads): two-byte types, A row-major; any leading dimensions and any K

@@ -292,15 +292,25 @@ void k4_mfma_ring(Args a, int tiles_m, int tiles_n, int total, int flags)
     using lptr = __attribute__((address_space(3))) char*;
     const int lds0 = (int)(uint32_t)(uintptr_t)(lptr)lds;      // LDS address of region 0
     // loads [lo, hi) of this wave's share of slab `sidx` of an operand into the region at byte offset `reg`
-    auto issue = [&](rsrc_t rsrc, int voff, int oct, int slab_bytes, int sidx, int reg, int lo, int hi) __attribute__((always_inline)) {
+    //
+    // Wait states the hardware does not interlock and the compiler's hazard pass cannot place inside inline assembly:
+    // one between a scalar write of M0 and a load to LDS that reads it, and five between a vector instruction that
+    // writes a scalar register -- the reload of a spilled scalar is one -- and a memory instruction that reads that
+    // register as descriptor or offset.  `guarded` loads carry s_nop 4 (six wait states with the s_mov); they are
+    // the ones issued outside the steady-state loop, where such reloads occur.  The loads of the middle slabs carry
+    // the one wait state for M0 only (the five cost 4 % there): the steady-state loop has no vector instruction that
+    // writes a scalar register at all, which tests/test_codegen.py checks on the compiled code for every
+    // instantiation, as it checks the distance to such a write for every other load.  M0 is reserved: the compiler
+    // keeps nothing in it and this kernel has no other user.
+    auto issue = [&](auto guarded, rsrc_t rsrc, int voff, int oct, int slab_bytes, int sidx, int reg, int lo, int hi) __attribute__((always_inline)) {
         const int k0 = sidx * slab_bytes;
 #pragma unroll
         for (int n = lo; n < hi; ++n) {
             const int dst = lds0 + reg + (wave + n * NW) * 1024, soff = k0 + (wave + n * NW) * oct;
-            // (one wait state between a scalar write of M0 and a load to LDS that reads it: gfx9 does not interlock the
-            // pair, and the compiler's hazard pass does not look inside inline assembly.  M0 is reserved: the compiler
-            // keeps nothing in it and this kernel has no other user.)
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds" ::"s"(dst), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
+            if constexpr (decltype(guarded)::value)
+                asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds" ::"s"(dst), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
+            else
+                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds" ::"s"(dst), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
         }
     };
 
@@ -419,6 +429,7 @@ void k4_mfma_ring(Args a, int tiles_m, int tiles_n, int total, int flags)
     static_assert(NMF % QUARTERS == 0 && NRD % 2 == 0, "quarters of a k-step");
     auto slab = [&](auto kind_, int s, int ra, int rb, int na, int nb, int fifth) __attribute__((always_inline)) {
         constexpr int KIND = decltype(kind_)::value;
+        constexpr std::integral_constant<bool, KIND != RING_MID> guard{};     // (see `issue`)
         // sources of the prefetches
         const rsrc_t b1 = KIND == RING_LAST ? nxt.rb : cur.rb;                       // B of slab s+1
         const rsrc_t a2 = (KIND == RING_PEN || KIND == RING_LAST) ? nxt.ra : cur.ra; // A, B of slab s+2
@@ -438,11 +449,11 @@ void k4_mfma_ring(Args a, int tiles_m, int tiles_n, int total, int flags)
             constexpr int NL = LASTSTEP ? ((KIND == RING_LAST || BWHOLE) ? LD : HALF) : N0 + N1 + N2;
             auto load_n = [&](int n) __attribute__((always_inline)) {
                 if constexpr (LASTSTEP) {
-                    issue(b2, voff_b, oct_b, slab_b, i2, ra, n, n + 1);
+                    issue(guard, b2, voff_b, oct_b, slab_b, i2, ra, n, n + 1);
                 } else {
-                    if (n < N0) issue(b1, voff_b, oct_b, slab_b, i1, nb, HALF + n, HALF + n + 1);
-                    else if (n < N0 + N1) issue(a2, voff_a, oct_a, slab_a, i2, fifth, n - N0, n - N0 + 1);
-                    else issue(a2, voff_a, oct_a, slab_a, i2, fifth, HALF + n - N0 - N1, HALF + n - N0 - N1 + 1);
+                    if (n < N0) issue(guard, b1, voff_b, oct_b, slab_b, i1, nb, HALF + n, HALF + n + 1);
+                    else if (n < N0 + N1) issue(guard, a2, voff_a, oct_a, slab_a, i2, fifth, n - N0, n - N0 + 1);
+                    else issue(guard, a2, voff_a, oct_a, slab_a, i2, fifth, HALF + n - N0 - N1, HALF + n - N0 - N1 + 1);
                 }
             };
             if constexpr (LASTSTEP) {
@@ -480,10 +491,10 @@ void k4_mfma_ring(Args a, int tiles_m, int tiles_n, int total, int flags)
 
     // ---- prologue, once per workgroup: slabs 0 and 1 of the first tile into regions 0..3, wait for slab 0 ----
     int o0 = 0, o1 = REGION, o2 = 2 * REGION, o3 = 3 * REGION, o4 = 4 * REGION;   // ra, rb, na, nb, fifth of the next slab
-    issue(cur.ra, voff_a, oct_a, slab_a, 0, o0, 0, LD);
-    issue(cur.rb, voff_b, oct_b, slab_b, 0, o1, 0, LD);
-    issue(cur.ra, voff_a, oct_a, slab_a, 1, o2, 0, LD);
-    issue(cur.rb, voff_b, oct_b, slab_b, 1, o3, 0, LD);
+    issue(std::true_type{}, cur.ra, voff_a, oct_a, slab_a, 0, o0, 0, LD);
+    issue(std::true_type{}, cur.rb, voff_b, oct_b, slab_b, 0, o1, 0, LD);
+    issue(std::true_type{}, cur.ra, voff_a, oct_a, slab_a, 1, o2, 0, LD);
+    issue(std::true_type{}, cur.rb, voff_b, oct_b, slab_b, 1, o3, 0, LD);
     asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");

@@ -137,9 +137,10 @@ def test_persistent_kernel_slab_loop(tmp_path):
         ops = first_inner_loop(m.group(2))
         count = lambda name: sum(o == name for o in ops)
         assert count(mfma) == per_slab and count("ds_read_b128") == 32 and count("buffer_load_dwordx4") == 16 and count("s_barrier") == 1
-        for bad in ("v_accvgpr_read_b32", "v_accvgpr_write_b32", "v_readlane_b32", "scratch_load_dword", "scratch_store_dword",
-                    "scratch_load_dwordx4", "scratch_store_dwordx4", "ds_write_b128"):
+        for bad in ("v_accvgpr_read_b32", "v_accvgpr_write_b32", "v_readlane_b32", "v_readfirstlane_b32", "scratch_load_dword",
+                    "scratch_store_dword", "scratch_load_dwordx4", "scratch_store_dwordx4", "ds_write_b128"):
             assert count(bad) == 0, bad
+        assert not any(o.startswith("v_cmp") for o in ops), "no vector instruction of the middle-slab loop writes a scalar register"
         lines = m.group(2).split("\n")
         mf = [i for i, l in enumerate(lines) if mfma in l]
         assert len(mf) == 4 * per_slab                      # the four slab kinds, each once
@@ -147,13 +148,34 @@ def test_persistent_kernel_slab_loop(tmp_path):
         meta = metadata(text, prefix)
         assert meta["agpr"] == 256 and meta["lds"] == 160 * 1024
         assert meta["vgpr_spill"] == (0 if dtype != "4E4M3" else meta["vgpr_spill"]) and meta["vgpr_spill"] <= 2
-    # every direct load issued from inline assembly keeps a wait state between its write of M0 and the load (gfx9 does
-    # not interlock the pair and the compiler's hazard pass does not look inside inline assembly)
-    lines = [l.strip() for l in text.split("\n")]
-    loads = [i for i, l in enumerate(lines) if l.startswith("buffer_load_dwordx4") and l.endswith("lds")]
+    # Every direct load issued from inline assembly keeps the wait states gfx9 does not interlock (and the compiler's
+    # hazard pass does not place inside inline assembly): one after the scalar write of M0, and five after a vector
+    # instruction that wrote a scalar register the load reads as descriptor or offset (a scalar spill reload is one).
+    code = [l.strip() for l in text.split("\n")]
+    code = [l for l in code if l and not l.startswith((";", ".", "//")) and not l.endswith(":")]
+    loads = [i for i, l in enumerate(code) if l.startswith("buffer_load_dwordx4") and l.endswith("lds")]
     assert len(loads) > 100
+    checked = 0
     for i in loads:
-        assert lines[i - 1].startswith("s_nop") and lines[i - 2].startswith("s_mov_b32 m0"), lines[i - 3:i + 1]
+        assert code[i - 1].startswith("s_nop") and code[i - 2].startswith("s_mov_b32 m0"), code[i - 3:i + 1]
+        m = re.match(r"buffer_load_dwordx4 v\d+, s\[(\d+):(\d+)\], (s\d+|vcc_lo|vcc_hi) offen lds", code[i])
+        assert m, code[i]
+        used = {"s%d" % r for r in range(int(m.group(1)), int(m.group(2)) + 1)} | {m.group(3)}
+        waited, j = 0, i - 1
+        while waited < 5 and j >= 0:
+            ins = code[j]
+            w = re.match(r"(v_readlane_b32|v_readfirstlane_b32) (s\d+|vcc_lo|vcc_hi),", ins)
+            assert not (w and w.group(2) in used), (code[j:i + 1], "a scalar register written by a vector instruction is read %d wait states later" % waited)
+            if used & {"vcc_lo", "vcc_hi"}:     # (the implicit destination of the short compare and carry forms)
+                assert not re.match(r"v_(cmp|cmpx|add_co|sub_co|subrev_co|addc_co|subb_co|div_scale)", ins), code[j:i + 1]
+            w = re.match(r"v_\S+ (s\[(\d+):(\d+)\]|s\d+),", ins)       # any other vector instruction with a scalar destination
+            if w:
+                regs = {w.group(1)} if w.group(2) is None else {"s%d" % r for r in range(int(w.group(2)), int(w.group(3)) + 1)}
+                assert not (regs & used), code[j:i + 1]
+            waited += (int(ins.split()[1]) + 1) if ins.startswith("s_nop") else 1
+            j -= 1
+        checked += 1
+    assert checked == len(loads)
     # the form that reads a row-major B in place: per slab 16 fragment reads of A and 32 transposing reads of B
     for dtype, mfma in (("4BF16", "v_mfma_f32_32x32x16_bf16"), ("3F16", "v_mfma_f32_32x32x16_f16")):
         prefix = "_ZN2gl12k4_mfma_ringINS_7RingCfgINS_" + dtype + "ELi8ELb1E"
