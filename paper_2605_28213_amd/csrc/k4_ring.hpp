@@ -76,7 +76,8 @@ __device__ __forceinline__ char* ring_stage_row(char* stage, int wave, int r)
 __device__ __forceinline__ float scalar_load_f32(const float* p)
 {
     float v;
-    asm volatile("s_load_dword %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(p) : "memory");
+    // (s_nop first: the address may have been reloaded from a spill by a vector instruction just before)
+    asm volatile("s_nop 4\n\ts_load_dword %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(p) : "memory");
     return v;
 }
 
