@@ -101,6 +101,27 @@ def test_expert_state_paths_and_scratch(p):
             assert lent.grid == q.grid * splits
             small = gemm.gemm_query(gemm.GEMM_K4_MFMA, make(p, workspace=4096, workspace_bytes=q.workspace_bytes - 1))
             assert small.status == gemm.GEMM_ERR_WORKSPACE
+    elif (p["dt"] in (gemm.GEMM_BF16, gemm.GEMM_F16) and p["la"] == gemm.GEMM_ROW_MAJOR and p["lb"] == gemm.GEMM_ROW_MAJOR
+          and math.ceil(p["M"] / 256) * math.ceil(p["N"] / 256) * p["batch"] >= 256 and math.ceil(p["K"] / kslab) >= 3
+          and p["lda"] * es <= 1 << 22 and p["K"] * p["ldb"] * es < 1 << 31):
+        # both operands row-major and at least 256 tiles: the persistent kernel reads them in place, whatever their
+        # alignment and K; nothing violated, no scratch -- unless a thin row remainder makes the packed path (with its
+        # streaming remainder) worth lending scratch for, which the query then advertises and takes when it is lent
+        assert q.path == "mfma32-direct-to-lds(persistent,B-row-major)" and q.violated == 0 and q.grid == 256
+        kp = math.ceil(p["K"] / kslab) * kslab
+        t256 = math.ceil(p["M"] / 256) * math.ceil(p["N"] / 256) * p["batch"]
+        t128 = math.ceil(p["M"] / 128) * math.ceil(p["N"] / 128) * p["batch"]
+        small = math.ceil(t128 / 512) * 7 < math.ceil(t256 / 256) * 10
+        per_row, rows = math.ceil(p["N"] / 256) * p["batch"], p["M"] // 256
+        tail = (p["M"] > 256 and 1 <= p["M"] % 256 <= 64 and p["N"] <= 16384 and not small
+                and math.ceil(rows * per_row / 256) < math.ceil((rows + 1) * per_row / 256))
+        whole = p["K"] % kslab == 0
+        a_ok = (whole and (p["lda"] * es) % 16 == 0 and (p["batch"] == 1 or (p["M"] * p["lda"] * es) % 16 == 0))
+        want = p["batch"] * ((0 if a_ok else p["M"]) + p["N"]) * kp * es if tail else 0
+        assert q.workspace_bytes == want
+        if tail:
+            lent = gemm.gemm_query(gemm.GEMM_K4_MFMA, make(p, workspace=4096, workspace_bytes=want))
+            assert lent.status == gemm.GEMM_OK and lent.path.startswith("mfma32-packed") and "M-tail" in lent.path
     else:
         kp = math.ceil(p["K"] / kslab) * kslab
         assert q.path.startswith("mfma32-") and "packed" not in q.path
@@ -128,7 +149,8 @@ def test_expert_state_paths_and_scratch(p):
 def test_expert_only_switches_are_refused_elsewhere(p, variant, flag):
     plain = gemm.gemm_query(variant, make(p))
     q = gemm.gemm_query(variant, make(p, flags=flag))
-    on_fast_kernel = variant == gemm.GEMM_K4_MFMA and plain.status == gemm.GEMM_OK and plain.path.startswith("mfma32-direct-to-lds")
+    on_fast_kernel = (variant == gemm.GEMM_K4_MFMA and plain.status == gemm.GEMM_OK and plain.path.startswith("mfma32-direct-to-lds")
+                      and "B-row-major" not in plain.path)      # (the in-place form has no simplified states: with a switch the masked kernel keeps the product)
     if on_fast_kernel:
         assert q.status == gemm.GEMM_OK
         if flag == gemm.GEMM_FLAG_TILE_128:
