@@ -113,7 +113,7 @@ inline bool dtype_pair_supported(int in, int out)
 // Each returns hipSuccess or the launch error.  `path` selects a code path that the caller
 // (gemm_api.hip) has already proven legal for these arguments.
 enum ValuPath { VALU_SCALAR = 0, VALU_VEC16 = 1 };
-enum MfmaPath { MFMA_ELEMENTWISE = 0, MFMA_VEC16 = 1, MFMA_SKINNY = 2, MFMA_PACKED = 3, MFMA_SPLITK = 4, MFMA_SKINNY_N = 5, MFMA_VEC16_BROW = 6 };
+enum MfmaPath { MFMA_ELEMENTWISE = 0, MFMA_VEC16 = 1, MFMA_SKINNY = 2, MFMA_PACKED = 3, MFMA_SPLITK = 4, MFMA_SKINNY_N = 5, MFMA_VEC16_BROW = 6, MFMA_THIN_BROW = 7 };
 
 // Workspace of the packed K4 path: both operands rewritten as [rows][Kp], Kp = K rounded up to a slab.
 int64_t k4_packed_k(const Args& a);
@@ -140,6 +140,20 @@ hipError_t launch_k4_ring(const Args& a);  // bf16, fp16, e4m3; k4_uses_ring(a) 
 // The persistent kernel on a row-major B read in place (bf16, fp16), and whether a product qualifies for it.
 bool k4_ring_takes_row_major_b(const Args& a);
 hipError_t launch_k4_ring_row_major_b(const Args& a);
+// Thin products (at most 64 rows) with A and B row-major, two-byte types: B is read once, in place.  The row-major-B
+// form above hands this kernel a remainder of rows that would cost it a round of tiles (the rule says when).
+bool k4_brow_splits_m_tail(const Args& a);
+bool k4_thin_takes_row_major_b(const Args& a);      // a whole product for the thin kernel
+// Both row-major-B kernels load rows as dwords from their first element, so the dword that holds the last element
+// of an odd-length last row reaches one element past the operand.  With the pointer known, such a product is only
+// taken when that element lies in the same 4 KiB page as the operand's last byte (mapped whatever follows).
+inline bool tail_element_in_last_page(const void* base, int64_t elems, int64_t last_row_len, int es)
+{
+    if (!base || last_row_len % 2 == 0) return true;          // (a query without pointers; no dword straddles the end)
+    const uintptr_t end = (uintptr_t)base + (uintptr_t)(elems * es);     // first byte past the operand
+    return (end & 4095u) != 0;
+}
+hipError_t launch_k4_thin_row_major_b(const Args& a);
 
 hipError_t launch_k0(const Args& a);
 hipError_t launch_valu_tiled(int variant, int path, const Args& a);

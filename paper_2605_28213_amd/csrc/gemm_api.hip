@@ -214,19 +214,20 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
                     path = splitk_path;
                 }
             }
-        } else if (!f32 && d->layout_a == GEMM_ROW_MAJOR && d->layout_b == GEMM_ROW_MAJOR && k4_ring_takes_row_major_b(a) &&
-                   !(can_pack && d->workspace != nullptr && k4_splits_m_tail(a))) {
+        } else if (!f32 && d->layout_a == GEMM_ROW_MAJOR && d->layout_b == GEMM_ROW_MAJOR && k4_ring_takes_row_major_b(a)) {
             // A and B row-major, enough tiles for the persistent kernel: it reads B in place (transposing LDS reads),
             // rows aligned to an element only with under-aligned loads, a ragged K cleared in LDS: no scratch, no
-            // packing pass, and none of the alignment, K-layout and K-divisibility conditions is relied on.
-            // (Exception: scratch is lent and the product has a thin remainder of rows that costs a whole round of
-            // tiles.  The packed path hands such a remainder to the streaming kernel, which wants B packed; this path
-            // has nothing cheap to give it to -- the masked kernel takes as long on the strip as the round it saves --
-            // and multiplies it as a seventeenth row of tiles.  Ragged fp16 workload: 157 us packed, 215 us in place.)
+            // packing pass, and none of the alignment, K-layout and K-divisibility conditions is relied on.  A thin
+            // remainder of rows that would cost a whole round of tiles goes to the thin kernel, which reads B in place
+            // as well; lent scratch is not used (ragged fp16 workload: 150 us in place, 157 us packed).
             p.path = MFMA_VEC16_BROW | (3 << 8);
-            path = "mfma32-direct-to-lds(persistent,B-row-major)";
+            path = k4_brow_splits_m_tail(a) ? "mfma32-direct-to-lds(persistent,B-row-major)+thin(M-tail)" : "mfma32-direct-to-lds(persistent,B-row-major)";
             required = GEMM_COND_DTYPE_HAS_MFMA | GEMM_COND_LDS_STAGED | GEMM_COND_K_CONTIG_A;
-            if (can_pack && k4_splits_m_tail(a)) pack_bytes = k4_packed_workspace_bytes(a, keep);   // what lending scratch would buy
+        } else if (!f32 && d->layout_a == GEMM_ROW_MAJOR && d->layout_b == GEMM_ROW_MAJOR && k4_thin_takes_row_major_b(a)) {
+            // at most 64 rows, A and B row-major: B is read once, in place, by the thin kernel (no scratch)
+            p.path = MFMA_THIN_BROW | (3 << 8);
+            path = "mfma16-thin(B-row-major)";
+            required = GEMM_COND_DTYPE_HAS_MFMA | GEMM_COND_LDS_STAGED | GEMM_COND_K_CONTIG_A | GEMM_COND_SMALL_M;
         } else if (can_pack && d->workspace != nullptr) {
             // the caller lent scratch: repair the violated conditions by packing, then run the fast kernel
             p.path = MFMA_PACKED | (keep << 8);

@@ -329,6 +329,7 @@ hipError_t launch_k4(int path, const Args& a)
         return hipErrorInvalidValue;
     }
     if (kind == MFMA_VEC16_BROW) return launch_k4_ring_row_major_b(a);
+    if (kind == MFMA_THIN_BROW) return launch_k4_thin_row_major_b(a);
     if (kind == MFMA_VEC16) {
         switch (a.in_dtype) {
         case GEMM_BF16: return launch_fast_split<BF16>(a);
@@ -389,6 +390,7 @@ Geometry geometry_k4(int path, const Args& a)
         default: return of(StreamK4Rows96<BF16>{});
         }
     }
+    if (kind == MFMA_THIN_BROW) return Geometry{a.M <= 16 ? 16 : a.M <= 32 ? 32 : 64, 64, 32, 512, 2, 33280, ((a.N + 63) / 64) * a.batch};
     if (kind == MFMA_VEC16_BROW) return Geometry{256, 256, ROW_BYTES / es, 256, 2, FastK4<BF16>::LDS_BYTES, K4_RING_WORKGROUPS};
     if (kind == MFMA_VEC16 || kind == MFMA_PACKED || kind == MFMA_SPLITK) {
         // (with a row remainder split off, the grid of the tiled part: the remainder is a second launch)

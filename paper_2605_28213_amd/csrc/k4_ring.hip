@@ -31,13 +31,6 @@ bool k4_uses_ring(const Args& a)
 // (K odd for A, N odd for B) the kernel's loads reach the one element after the operand (RING_BROW_SLACK): with the
 // pointers known, such a product is only taken when that element lies in the same 4 KiB page as the operand's last
 // byte, so that it is mapped whatever follows the operand.
-static bool tail_element_in_last_page(const void* base, int64_t elems, int64_t last_row_len, int es)
-{
-    if (!base || last_row_len % 2 == 0) return true;          // (a query without pointers; no dword straddles the end)
-    const uintptr_t end = (uintptr_t)base + (uintptr_t)(elems * es);     // first byte past the operand
-    return (end & 4095u) != 0;
-}
-
 bool k4_ring_takes_row_major_b(const Args& a)
 {
     if (a.flags != 0 || a.in_dtype == GEMM_FP8_E4M3 || a.in_dtype == GEMM_F32) return false;
@@ -66,6 +59,18 @@ static hipError_t launch_ring(const Args& a)
 
 hipError_t launch_k4_ring_row_major_b(const Args& a)
 {
+    if (k4_brow_splits_m_tail(a)) {          // a thin remainder of rows that would cost a round of tiles: see the rule
+        const int64_t rem = a.M % 256, top_rows = a.M - rem;
+        Args top = a;
+        top.M = top_rows;
+        hipError_t e = launch_k4_ring_row_major_b(top);
+        if (e != hipSuccess) return e;
+        Args bot = a;
+        bot.M = rem;
+        bot.A = (const char*)a.A + top_rows * a.a_si * elem_size(a.in_dtype);
+        bot.C = (char*)a.C + top_rows * a.ldc * (a.out_dtype == GEMM_F32 ? 4 : 2);
+        return launch_k4_thin_row_major_b(bot);
+    }
     switch (a.in_dtype) {
     case GEMM_BF16: return launch_ring<BF16, true>(a);
     case GEMM_F16: return launch_ring<F16, true>(a);

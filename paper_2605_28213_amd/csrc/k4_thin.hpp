@@ -1,0 +1,182 @@
+// K4, thin products with a ROW-MAJOR B: C (R x N, R <= 64) = A (R x K, row-major) . B (K x N, row-major), two-byte
+// types, nothing aligned, any K.  Bound by reading B once (the counterpart of k4_stream, which wants B column-major).
+//
+// A workgroup owns a strip of 64 columns of C; its 8 waves split K (wave w takes the 32-row k tiles w, w + 8, ...)
+// and add their partial sums in LDS at the end.  Per k tile a wave loads the strip's 32 rows x 128 bytes of B as it
+// lies in memory (four 16-byte loads per lane, under-aligned, through a buffer resource that ends with the matrix:
+// rows past K come back as zeros, columns past N are whatever follows and only feed outputs that are never stored),
+// parks it in a wave-private LDS tile and reads the fragments of v_mfma_f32_16x16x32 back with the transposing read
+// ds_read_b64_tr_b16 (see RingCfg in k4_ring.hpp for its lane layout: a block of 16 lanes turns a 4 k x 16 n patch
+// into 4 consecutive k per lane); chunk c of k row r is kept at c ^ (r & 7), so that the four rows a block reads lie
+// in different banks.  A's fragments (16 rows x 8 consecutive k per lane) come straight from memory: A is small and
+// stays in L2.  K ragged: A's elements past K are masked to zero in registers (B's are zeros already).  The loads of
+// the next one or two k tiles are in flight while a tile is multiplied (register sets taken in turn).
+//
+// Used for the thin remainder of rows that the persistent kernel's row-major-B form would otherwise multiply as
+// one more, mostly empty, row of tiles (fp16 4099 x 4093 x 4097: 215 -> 150 us), and for whole products of at most
+// 64 rows with both operands row-major (3 / 33 / 64 rows x 4093 x 4097: 18 / 43 / 65 us; 64 workgroups).
+// Paper Table 1: "smem_transpose" on the small side of the lineage's expert state.
+#pragma once
+#include "k4_kernels.hpp"
+
+namespace gl {
+
+template <typename IN, int MG_>
+struct ThinCfg {
+    using In = IN;
+    static constexpr int MG = MG_, ROWS = 16 * MG_;      // groups of 16 rows of A (and C)
+    static constexpr int WAVES = 8, COLS = 64, TK = 32;  // waves per workgroup; columns per strip; k rows per tile
+    static constexpr int TILE_BYTES = TK * COLS * 2;     // 4 KB per wave
+    static constexpr int LDS_BYTES = WAVES * TILE_BYTES > WAVES * 16 * (COLS + 1) * 4 ? WAVES * TILE_BYTES : WAVES * 16 * (COLS + 1) * 4;
+    static constexpr int SETS = MG_ <= 2 ? 3 : 2;         // k tiles held in registers per wave (one in hand, the rest landing)
+    static_assert(IN::BYTES == 2, "two-byte types (the transposing read used here is the 16-bit one)");
+    static_assert(MG_ == 1 || MG_ == 2 || MG_ == 4, "16, 32 or 64 rows");
+};
+
+template <typename CFG>
+__global__ __launch_bounds__(CFG::WAVES * 64) void k4_thin_brow(Args a)
+{
+    using IN = typename CFG::In;
+    constexpr int MG = CFG::MG, WAVES = CFG::WAVES, COLS = CFG::COLS, TK = CFG::TK;
+    __shared__ __attribute__((aligned(16))) char lds[CFG::LDS_BYTES];
+    const int t = threadIdx.x, lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int64_t b = blockIdx.y;
+    const int64_t j0 = (int64_t)blockIdx.x * COLS;
+    char* tile = lds + wave * CFG::TILE_BYTES;
+
+    // buffer resources over this batch item's A and this strip's part of B (both below 2 GiB: checked by the host)
+    const char* A = (const char*)a.A + b * a.stride_a * 2;
+    const char* B = (const char*)a.B + (b * a.stride_b + j0) * 2;
+    const int64_t bytes_a = ((a.M - 1) * a.a_si + a.K) * 2 + 2;          // (+ one element: the dword that holds an odd row's last one)
+    const int64_t bytes_b = ((a.K - 1) * a.b_sk + (a.N - j0)) * 2 + 2;
+    constexpr int RSRC_FLAGS = 0x00020000;
+    const __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc((void*)A, 0, (int)bytes_a, RSRC_FLAGS);
+    const __amdgpu_buffer_rsrc_t rsrc_b = __builtin_amdgcn_make_buffer_rsrc((void*)B, 0, (int)bytes_b, RSRC_FLAGS);
+
+    // B loads: load n (0..3) of a lane covers k row 8 n + lane/8 of the tile, chunk lane%8 (8 columns)
+    const int brow = lane >> 3, bchunk = lane & 7;
+    const int voff_b = (int)((brow * a.b_sk + bchunk * 8) * 2);
+    const int step_b = (int)(8 * a.b_sk * 2);                              // bytes from load n to load n + 1
+    // parked at: row * 128 + ((chunk ^ (row & 7)) << 4); rows 8 n + lane/8: (row & 7) = lane/8 for every n
+    const int park = brow * 128 + ((bchunk ^ brow) << 4);
+    // fragment reads (per 16-column block jb and half h of the lane's 8 k): lane l of a block of 16 points at k row
+    // 8 (l/16) + 4 h + (l%16)/4 and columns 16 jb + 4 (l%4) .. +3
+    const int l16 = lane & 15, kq = lane >> 4;
+    const int fr_row = 8 * kq + (l16 >> 2), fr_col = 4 * (l16 & 3);
+    // A fragments: lane holds row l16 of a group, k 8 kq .. 8 kq + 7 of the tile
+    int voff_a[MG];
+#pragma unroll
+    for (int m = 0; m < MG; ++m) {
+        const int64_t r = m * 16 + l16 < a.M ? m * 16 + l16 : a.M - 1;      // (rows past M: clamped, never stored)
+        voff_a[m] = (int)((r * a.a_si + 8 * kq) * 2);
+    }
+
+    typedef short v4s_t __attribute__((ext_vector_type(4)));
+    typedef __attribute__((address_space(3))) v4s_t* tr_ptr;
+    f32x4_t acc[MG][4];
+#pragma unroll
+    for (int m = 0; m < MG; ++m)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[m][j] = f32x4_t{0, 0, 0, 0};
+
+    const int64_t tiles = (a.K + TK - 1) / TK;
+    // One k tile in registers: 4 loads of B (k rows 8 n + lane/8), one load of A per row group.
+    struct Held { u32x4_t b[4]; u32x4_t a[MG]; };
+    auto fetch = [&](Held& h, int64_t kt) __attribute__((always_inline)) {
+        const int k0 = (int)(kt * TK);
+#pragma unroll
+        for (int n = 0; n < 4; ++n)
+            h.b[n] = __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc_b, voff_b + n * step_b, (int)(k0 * a.b_sk * 2), 0));
+#pragma unroll
+        for (int m = 0; m < MG; ++m) h.a[m] = __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc_a, voff_a[m], k0 * 2, 0));
+    };
+    auto multiply = [&](Held& h, int64_t kt) __attribute__((always_inline)) {
+        // A's elements beyond K are the next row's first ones (or the slack element): zero them
+        const int valid = (int)(a.K - kt * TK) - 8 * kq;                   // this lane's k that lie inside K
+        if (valid < 8) {
+#pragma unroll
+            for (int m = 0; m < MG; ++m)
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    const int left = valid - 2 * d;
+                    h.a[m][d] = left <= 0 ? 0u : left == 1 ? (h.a[m][d] & 0xFFFFu) : h.a[m][d];
+                }
+        }
+#pragma unroll
+        for (int n = 0; n < 4; ++n) *(u32x4_t*)(tile + n * 8 * 128 + park) = h.b[n];
+#pragma unroll
+        for (int jb = 0; jb < 4; ++jb) {
+            u32x4_t fb;
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh) {
+                const int row = fr_row + 4 * hh, chunk = (16 * jb + fr_col) >> 3;
+                const int off = row * 128 + ((chunk ^ (row & 7)) << 4) + ((fr_col >> 2) & 1) * 8;
+                const v4s_t v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((tr_ptr)(tile + off));
+                const uint32_t lo = (uint32_t)(uint16_t)v[0] | ((uint32_t)(uint16_t)v[1] << 16);
+                const uint32_t hi = (uint32_t)(uint16_t)v[2] | ((uint32_t)(uint16_t)v[3] << 16);
+                if (hh == 0) { fb.x = lo; fb.y = hi; } else { fb.z = lo; fb.w = hi; }
+            }
+#pragma unroll
+            for (int m = 0; m < MG; ++m) mfma16<IN>(h.a[m], fb, acc[m][jb]);
+        }
+    };
+    // Wave w takes k tiles w, w + WAVES, ...  Up to 32 rows, two tiles' loads are in flight while a third is
+    // multiplied (three register sets taken in turn: 8 KB of B per wave on its way beside the tile in hand); with
+    // 64 rows the accumulators leave room for two sets.
+    int64_t kt = wave;
+    if constexpr (CFG::SETS == 3) {
+        Held h0, h1, h2;
+        if (kt < tiles) fetch(h0, kt);
+        if (kt + WAVES < tiles) fetch(h1, kt + WAVES);
+        while (kt < tiles) {
+            if (kt + 2 * WAVES < tiles) fetch(h2, kt + 2 * WAVES);
+            multiply(h0, kt);
+            kt += WAVES;
+            if (kt >= tiles) break;
+            if (kt + 2 * WAVES < tiles) fetch(h0, kt + 2 * WAVES);
+            multiply(h1, kt);
+            kt += WAVES;
+            if (kt >= tiles) break;
+            if (kt + 2 * WAVES < tiles) fetch(h1, kt + 2 * WAVES);
+            multiply(h2, kt);
+            kt += WAVES;
+        }
+    } else {
+        Held h0, h1;
+        if (kt < tiles) fetch(h0, kt);
+        while (kt < tiles) {
+            if (kt + WAVES < tiles) fetch(h1, kt + WAVES);
+            multiply(h0, kt);
+            kt += WAVES;
+            if (kt >= tiles) break;
+            if (kt + WAVES < tiles) fetch(h0, kt + WAVES);
+            multiply(h1, kt);
+            kt += WAVES;
+        }
+    }
+
+    // partial sums of the waves meet in LDS, one group of 16 rows at a time.  16 x 16 accumulator: register r of lane
+    // l holds row 4 (l/16) + r, column l%16.
+    const float sc = batch_scale(a, b);
+    float* part = (float*)lds;
+#pragma unroll
+    for (int m = 0; m < MG; ++m) {
+        __syncthreads();
+#pragma unroll
+        for (int jb = 0; jb < 4; ++jb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) part[(wave * 16 + 4 * kq + r) * (COLS + 1) + jb * 16 + l16] = acc[m][jb][r];
+        __syncthreads();
+        for (int o = t; o < 16 * COLS; o += WAVES * 64) {
+            const int i = o / COLS, j = o % COLS;
+            float v = 0.0f;
+#pragma unroll
+            for (int w = 0; w < WAVES; ++w) v += part[(w * 16 + i) * (COLS + 1) + j];
+            const int64_t gi = m * 16 + i, gj = j0 + j;
+            if (gi < a.M && gj < a.N) store_out(a.C, b * a.stride_c + gi * a.ldc + gj, v * sc + (a.bias ? a.bias[gj] : 0.0f), a.out_dtype);
+        }
+    }
+}
+
+}  // namespace gl

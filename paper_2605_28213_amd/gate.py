@@ -102,6 +102,8 @@ def kernel_patterns(variant: int, in_dtype: int, path: str, bm: int, bn: int, th
     pats = []
     if "stream(small" in path:
         return [r"k4_stream<gl::StreamCfg<%s, %d, " % (dt, threads // 64)]
+    if path.startswith("mfma16-thin"):
+        return [r"k4_thin_brow<gl::ThinCfg<%s, %d>" % (dt, bm // 16)]
     if "direct-to-lds" in path:
         swz = "false" if flags & gemm.GEMM_FLAG_DEOPT_NO_SWIZZLE else "true"
         ovl = "false" if flags & gemm.GEMM_FLAG_DEOPT_NO_OVERLAP else "true"
@@ -115,8 +117,10 @@ def kernel_patterns(variant: int, in_dtype: int, path: str, bm: int, bn: int, th
             pats.append(r"k4_pack_(rows|transpose)<%s>" % dt)
         if "splitK" in path:
             pats.append(r"k4_splitk_reduce<%s>" % dt)
-        if "M-tail" in path:
+        if "stream(M-tail)" in path:
             pats.append(r"k4_stream<gl::StreamCfg<%s, " % dt)
+        if "thin(M-tail)" in path:
+            pats.append(r"k4_thin_brow<gl::ThinCfg<%s, " % dt)
         return pats
     return [r"k4_mfma_masked<%s, %d, %d, " % (dt, bm, bn)]
 

@@ -129,14 +129,17 @@ def test_query_reports_paths_and_conditions_for_the_five_workloads():
     r = q(4, "C2"); assert r.path == "mfma32-direct-to-lds" and r.violated == 0 and (r.bm, r.bn, r.bk) == (256, 256, 64)
     assert {"TILE_DIV_M", "TILE_DIV_N", "TILE_DIV_K"} <= set(gemm.Query.names(r.holds)) and r.grid == 1024
     r = q(2, "C3"); assert r.path == "elementwise-masked" and set(gemm.Query.names(r.violated)) == {"LD16_A", "LD16_B"}
-    # the ragged fp16 workload without scratch: B row-major read in place by the persistent kernel, nothing violated;
-    # the query still says what lending scratch would buy (the packed path, whose streaming kernel takes the three rows
-    # past the last whole tile)
-    r = q(4, "C3"); assert r.path == "mfma32-direct-to-lds(persistent,B-row-major)" and r.violated == 0 and r.workspace_bytes > 0
+    # the ragged fp16 workload: B row-major read in place by the persistent kernel, the three rows past the last whole
+    # tile by the thin kernel; nothing violated, no scratch asked for, and lent scratch changes nothing
+    r = q(4, "C3"); assert r.path == "mfma32-direct-to-lds(persistent,B-row-major)+thin(M-tail)" and r.violated == 0 and r.workspace_bytes == 0
     assert "TILE_DIV_M" not in gemm.Query.names(r.holds)
     c = gen.CONFIGS["C3"]
-    lent = gemm.make_desc(c.M, c.N, c.K, c.in_dtype, c.out_dtype, 0, 0, workspace=4096, workspace_bytes=r.workspace_bytes)
-    r = gemm.gemm_query(4, lent); assert r.path == "mfma32-packed+direct-to-lds+stream(M-tail)" and "K_CONTIG_B" in gemm.Query.names(r.violated)
+    lent = gemm.make_desc(c.M, c.N, c.K, c.in_dtype, c.out_dtype, 0, 0, workspace=4096, workspace_bytes=1 << 30)
+    assert gemm.gemm_query(4, lent).path == r.path
+    # the same sizes with A column-major: no kernel reads that in place, the packed path takes it when scratch is lent
+    need = gemm.gemm_query(4, gemm.make_desc(c.M, c.N, c.K, c.in_dtype, c.out_dtype, 1, 0)).workspace_bytes
+    lent = gemm.make_desc(c.M, c.N, c.K, c.in_dtype, c.out_dtype, 1, 0, workspace=4096, workspace_bytes=need)
+    r = gemm.gemm_query(4, lent); assert r.path == "mfma32-packed+direct-to-lds+stream(M-tail)" and "K_CONTIG_A" in gemm.Query.names(r.violated)
     # fewer than 256 tiles: the masked kernel, with the conditions it misses
     r = gemm.gemm_query(4, gemm.make_desc(1027, 1021, 1025, c.in_dtype, c.out_dtype, 0, 0))
     assert "elementwise" in r.path and "K_CONTIG_B" in gemm.Query.names(r.violated)

@@ -129,7 +129,7 @@ def test_persistent_kernel_reads_a_row_major_b_in_place(dtype, case):
     M, N, ns, nb = case
     K = slabs(dtype, ns)
     inp = int_inputs(dtype, M, N, K, ROW, ROW, batch=nb, ldb=N + (8 if ns == 7 else 0) + (-N) % 8, seed=ns + 100)
-    q = run_exact(inp, "mfma32-direct-to-lds(persistent,B-row-major)")
+    q = run_exact(inp, "mfma32-direct-to-lds(persistent,B-row-major)", exact_path=False)    # (a thin remainder of rows may go to the thin kernel)
     assert q.grid == 256 and q.workspace_bytes == 0 and q.violated == 0
 
 
@@ -138,8 +138,11 @@ BROW_RAGGED = [  # (M, N, K, batch, lda - K, ldb - N, path suffix)
     (512, 509, 320, 70, 3, 0, ""),             # N odd: the last row of B ends in the middle of a dword
     (512, 509, 321, 70, 0, 0, ""),             # K odd as well: a last slab of one element, A's last row ends mid-dword
     (700, 515, 203, 29, 0, 0, ""),             # three whole slabs and a ragged fourth, edge tiles in both directions
-    (4099, 4093, 449, 1, 0, 0, ""),            # the ragged fp16 workload's shape with a shorter K: 17 x 16 tiles, 3 rows in the last
-    (4096 + 40, 4096, 200, 1, 0, 5, ""),
+    (4099, 4093, 449, 1, 0, 0, "+thin(M-tail)"),   # the ragged fp16 workload's shape with a shorter K: 16 x 16 tiles, 3 rows to the thin kernel
+    (4096 + 40, 4096, 200, 1, 0, 5, "+thin(M-tail)"),  # 40 rows: four row groups in the thin kernel
+    (4096 + 17, 4093, 203, 1, 1, 1, "+thin(M-tail)"),  # 17 rows: two row groups, odd leading dimensions
+    (1024 + 64, 1000, 333, 64, 0, 3, "+thin(M-tail)"), # batched: 4 x 4 tiles x 64 = 4 rounds, the fifth row of tiles would be a fifth
+    (4096 + 65, 4096, 200, 1, 0, 0, ""),               # 65 rows stay a row of tiles
 ]
 
 
@@ -148,11 +151,42 @@ BROW_RAGGED = [  # (M, N, K, batch, lda - K, ldb - N, path suffix)
 def test_row_major_operands_with_odd_leading_dimensions_and_ragged_k_in_place(dtype, case):
     """A and B row-major, nothing aligned, K not whole slabs, no scratch lent: the persistent kernel loads the rows
     with under-aligned 16-byte loads, clears what lies beyond K in the last slab (the gaps between rows hold 3, the
-    operands' neighbours whatever the allocator left); a thin remainder of rows is a last, mostly empty row of tiles."""
+    operands' neighbours whatever the allocator left); a thin remainder of rows that would cost a round of tiles is
+    multiplied by the thin kernel, which reads B in place as well."""
     M, N, K, nb, pa, pb, suffix = case
     inp = int_inputs(dtype, M, N, K, ROW, ROW, batch=nb, lda=K + pa, ldb=N + pb, seed=K)
     q = run_exact(inp, "mfma32-direct-to-lds(persistent,B-row-major)" + suffix)
     assert q.violated == 0
+
+
+THIN_CASES = [  # (M, N, K, batch, lda - K, ldb - N, biased)
+    (1, 64, 32, 1, 0, 0, False),               # one row, one strip, one k tile: seven of the eight waves have nothing
+    (3, 4093, 4097, 1, 0, 0, False),           # the ragged workload's remainder as a product of its own
+    (16, 1000, 777, 1, 1, 1, True),            # one full row group, odd leading dimensions, bias
+    (17, 130, 2050, 3, 3, 0, False),           # two row groups, batched, a strip of two columns
+    (32, 515, 256, 2, 0, 5, False),
+    (33, 257, 1031, 1, 0, 0, True),            # four row groups (two sets of registers), one-column last strip
+    (64, 2048, 1024, 1, 0, 0, False),          # everything whole and aligned
+    (64, 777, 95, 2, 5, 1, False),             # fewer k tiles than waves x sets
+]
+
+
+@pytest.mark.parametrize("dtype", [gen.BF16, gen.F16])
+@pytest.mark.parametrize("case", THIN_CASES, ids=["%dx%dx%d_b%d_%d_%d_%s" % c for c in THIN_CASES])
+def test_thin_kernel_reads_a_row_major_b_in_place(dtype, case):
+    """At most 64 rows, A and B row-major, nothing aligned, any K, no scratch: a strip of 64 columns per workgroup,
+    K dealt to its eight waves, B parked as it lies in memory and read back with transposing LDS reads.  fp32 output
+    bit for bit, and the two-byte output against the oracle's value rounded to nearest even."""
+    M, N, K, nb, pa, pb, biased = case
+    inp = int_inputs(dtype, M, N, K, ROW, ROW, batch=nb, lda=K + pa, ldb=N + pb, seed=K + M, biased=biased)
+    q = run_exact(inp, "mfma16-thin(B-row-major)")
+    assert q.violated == 0 and q.workspace_bytes == 0 and q.grid == -(-N // 64) * nb
+    C_ref, _ = oracle_for(inp)
+    rc, _, raw = util.run_config(K4, inp, out_dtype=dtype)
+    assert rc == gemm.GEMM_OK
+    want = gen.quantise(dtype, C_ref.astype(np.float32).reshape(-1))
+    got = raw.cpu().numpy().view(np.uint16)[: nb * M * N]
+    np.testing.assert_array_equal(got, want)
 
 
 @pytest.mark.parametrize("dtype", DTYPES)

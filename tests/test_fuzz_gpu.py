@@ -131,7 +131,7 @@ def test_random_case_with_many_tiles(i):
     q = gemm.gemm_query(4, gemm.make_desc(cfg.M, cfg.N, cfg.K, cfg.in_dtype, cfg.out_dtype, ROW, cfg.layout_b, lda=inp.lda, ldb=inp.ldb,
                                           ldc=inp.ldc, batch=cfg.batch, stride_a=inp.stride_a, stride_b=inp.stride_b, stride_c=inp.stride_c))
     if cfg.layout_b == ROW:
-        assert q.path == "mfma32-direct-to-lds(persistent,B-row-major)" and q.grid == 256, (cfg, q)
+        assert q.path in ("mfma32-direct-to-lds(persistent,B-row-major)", "mfma32-direct-to-lds(persistent,B-row-major)+thin(M-tail)") and q.grid == 256, (cfg, q)
     else:   # (the tile rule may prefer 128-tiles, which have no persistent form)
         assert q.path in ("mfma32-direct-to-lds(persistent)", "mfma32-direct-to-lds"), (cfg, q)
     rc, C, _ = util.run_config(4, inp)

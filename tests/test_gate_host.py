@@ -75,6 +75,8 @@ def test_every_state_and_path_maps_to_kernels_of_the_library():
              (4, gen.E4M3, "mfma32-direct-to-lds(persistent)", 256, 256, 256, 0),
              (4, gen.BF16, "mfma32-direct-to-lds-noswz", 256, 256, 256, gemm.GEMM_FLAG_DEOPT_NO_SWIZZLE),
              (4, gen.F16, "mfma32-packed+direct-to-lds+stream(M-tail)", 256, 256, 256, 0),
+             (4, gen.F16, "mfma32-direct-to-lds(persistent,B-row-major)+thin(M-tail)", 256, 256, 256, 0),
+             (4, gen.BF16, "mfma16-thin(B-row-major)", 32, 64, 512, 0),
              (4, gen.BF16, "mfma32-direct-to-lds+splitK(4)", 128, 128, 256, 0), (4, gen.BF16, "mfma16-stream(small-M)", 16, 16, 64, 0),
              (4, gen.F32, "mfma32-elementwise-masked", 64, 64, 256, 0), (4, gen.F16, "mfma32-vec16-masked", 128, 128, 256, 0)]
     for (v, dt, path, bm, bn, threads, flags) in cases:

@@ -44,8 +44,8 @@ def test_masks_status_and_geometry_are_consistent(p, variant):
     assert (strict.status == gemm.GEMM_ERR_PRECONDITION) == (q.violated != 0)
     assert strict.path == q.path and strict.violated == q.violated
     if q.status == gemm.GEMM_OK:
-        assert q.path and q.threads in (64, 128, 256) and q.grid >= 1
-        if q.bm and q.bn and "stream" not in q.path:
+        assert q.path and q.threads in (64, 128, 256, 512) and q.grid >= 1
+        if q.bm and q.bn and "stream" not in q.path and "thin" not in q.path:
             assert q.grid >= math.ceil(p["M"] / q.bm) * math.ceil(p["N"] / q.bn) * p["batch"] or "M-tail" in q.path or \
                     ("persistent" in q.path and q.grid == 256)      # (256 workgroups walking several tiles each)
         assert q.lds_bytes <= 160 * 1024
@@ -105,23 +105,24 @@ def test_expert_state_paths_and_scratch(p):
           and math.ceil(p["M"] / 256) * math.ceil(p["N"] / 256) * p["batch"] >= 256 and math.ceil(p["K"] / kslab) >= 3
           and p["lda"] * es <= 1 << 22 and p["K"] * p["ldb"] * es < 1 << 31):
         # both operands row-major and at least 256 tiles: the persistent kernel reads them in place, whatever their
-        # alignment and K; nothing violated, no scratch -- unless a thin row remainder makes the packed path (with its
-        # streaming remainder) worth lending scratch for, which the query then advertises and takes when it is lent
-        assert q.path == "mfma32-direct-to-lds(persistent,B-row-major)" and q.violated == 0 and q.grid == 256
-        kp = math.ceil(p["K"] / kslab) * kslab
-        t256 = math.ceil(p["M"] / 256) * math.ceil(p["N"] / 256) * p["batch"]
-        t128 = math.ceil(p["M"] / 128) * math.ceil(p["N"] / 128) * p["batch"]
-        small = math.ceil(t128 / 512) * 7 < math.ceil(t256 / 256) * 10
+        # alignment and K; nothing violated, no scratch asked for or used
+        # a thin remainder of rows that would cost a round of tiles goes to the thin kernel (which also reads B in place)
         per_row, rows = math.ceil(p["N"] / 256) * p["batch"], p["M"] // 256
-        tail = (p["M"] > 256 and 1 <= p["M"] % 256 <= 64 and p["N"] <= 16384 and not small
-                and math.ceil(rows * per_row / 256) < math.ceil((rows + 1) * per_row / 256))
-        whole = p["K"] % kslab == 0
-        a_ok = (whole and (p["lda"] * es) % 16 == 0 and (p["batch"] == 1 or (p["M"] * p["lda"] * es) % 16 == 0))
-        want = p["batch"] * ((0 if a_ok else p["M"]) + p["N"]) * kp * es if tail else 0
-        assert q.workspace_bytes == want
-        if tail:
-            lent = gemm.gemm_query(gemm.GEMM_K4_MFMA, make(p, workspace=4096, workspace_bytes=want))
-            assert lent.status == gemm.GEMM_OK and lent.path.startswith("mfma32-packed") and "M-tail" in lent.path
+        thin_tail = (p["M"] > 256 and 1 <= p["M"] % 256 <= 64 and p["N"] <= 16384 and rows * per_row >= 256
+                     and (p["K"] + 32) * p["ldb"] * 2 < 1 << 31
+                     and math.ceil(rows * per_row / 256) < math.ceil((rows + 1) * per_row / 256))
+        assert q.path == "mfma32-direct-to-lds(persistent,B-row-major)" + ("+thin(M-tail)" if thin_tail else "")
+        assert q.violated == 0 and q.grid == 256
+        assert q.workspace_bytes == 0
+        lent = gemm.gemm_query(gemm.GEMM_K4_MFMA, make(p, workspace=4096, workspace_bytes=1 << 30))
+        assert lent.status == gemm.GEMM_OK and lent.path == q.path
+    elif (p["dt"] in (gemm.GEMM_BF16, gemm.GEMM_F16) and p["la"] == gemm.GEMM_ROW_MAJOR and p["lb"] == gemm.GEMM_ROW_MAJOR
+          and p["M"] <= 64 and (p["K"] + 32) * p["ldb"] * 2 < 1 << 31 and p["M"] * p["lda"] * 2 < 1 << 31):
+        # at most 64 rows, both operands row-major: the thin kernel reads B once, in place; no scratch, lent or not
+        assert q.path == "mfma16-thin(B-row-major)" and q.violated == 0 and q.workspace_bytes == 0
+        assert q.grid == math.ceil(p["N"] / 64) * p["batch"] and q.bn == 64 and q.bm >= min(p["M"], 64) and q.threads == 512
+        lent = gemm.gemm_query(gemm.GEMM_K4_MFMA, make(p, workspace=4096, workspace_bytes=1 << 30))
+        assert lent.path == q.path
     else:
         kp = math.ceil(p["K"] / kslab) * kslab
         assert q.path.startswith("mfma32-") and "packed" not in q.path

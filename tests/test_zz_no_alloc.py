@@ -82,9 +82,10 @@ def test_paths_without_scratch_run_as_in_gemm_run_ex_and_every_state_is_accepted
 
 
 def test_requests_beyond_the_array_and_lent_workspaces_are_refused():
-    # the ragged fp16 workload's packed copies take 68 MB: more than the array
+    # the ragged fp16 workload's sizes with A column-major (no kernel reads that in place): the packed copies take
+    # 68 MB, more than the array
     cfg = gen.CONFIGS["C3"]
-    d = gemm.make_desc(cfg.M, cfg.N, cfg.K, cfg.in_dtype, cfg.out_dtype, cfg.layout_a, cfg.layout_b)
+    d = gemm.make_desc(cfg.M, cfg.N, cfg.K, cfg.in_dtype, cfg.out_dtype, COL, cfg.layout_b)
     assert gemm.gemm_query(K4, d).workspace_bytes > gemm.gemm_static_scratch_bytes()
     es = gen.ELEM_BYTES[cfg.in_dtype]
     dA = torch.zeros(cfg.M * cfg.K * es, dtype=torch.uint8, device="cuda")
