@@ -247,6 +247,26 @@ def main():
             "hbm_copy": {"GB/s": cp, "frac_of_peak": cp / PEAK["hbm_GBs"], "what": "256 MiB read + 256 MiB written"},
         }
         out["roofline"]["frac_of_measured_mfma_ceiling"] = out["roofline"]["achieved"] / mf
+        # The vendor's GEMM on the same operands in the same session, as the paper sets its kernels beside cuBLAS
+        # (App. A): torch.mm reaches hipBLASLt / rocBLAS.  Context for the headline number, not part of the path.
+        try:
+            vs = [(A.view(torch.bfloat16).view(cfg.M, cfg.K), B.view(torch.bfloat16).view(cfg.N, cfg.K).t(),
+                   torch.empty(cfg.M, cfg.N, dtype=torch.bfloat16, device="cuda")) for (A, B, _) in sets]
+            box = [0]
+
+            def vendor_mm():
+                a_, b_, c_ = vs[box[0] % NSETS]
+                box[0] += 1
+                torch.mm(a_, b_, out=c_)
+            with torch.cuda.stream(stream):
+                tv = event_times(vendor_mm, 30, 60)
+            vm = tv[len(tv) // 2]
+            out["ceilings"]["vendor_library_bf16_8192"] = {
+                "TFLOP/s": cfg.flops / (vm * 1e-3) / 1e12, "median_us": 1e3 * vm, "frac_of_peak": cfg.flops / (vm * 1e-3) / 1e12 / PEAK["mfma_bf16"],
+                "what": "torch.mm (hipBLASLt / rocBLAS) on the headline workload's operands, A row-major, B column-major, rotated over the same 3 sets"}
+            del vs
+        except Exception as e:      # context only: a vendor library that refuses the call does not fail the bench
+            out["ceilings"]["vendor_library_bf16_8192"] = {"error": str(e)[:200]}
         del big, dst, sink, Z0
     del sets, keep
     torch.cuda.empty_cache()

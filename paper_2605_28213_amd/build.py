@@ -24,7 +24,7 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libgemm_lineage.so")
 RESOURCES = os.path.join(HERE, "libgemm_lineage.resources.json")
-SOURCES = ["gemm_api.hip", "conv_api.hip", "topk.hip", "k0_naive.hip", "k123_valu_tiled.hip", "k4_mfma.hip", "k4_ring.hip", "k4_thin.hip", "probes.hip"]
+SOURCES = ["gemm_api.hip", "conv_api.hip", "topk.hip", "k0_naive.hip", "k123_valu_tiled.hip", "k3_async.hip", "k4_mfma.hip", "k4_ring.hip", "k4_thin.hip", "probes.hip"]
 HEADERS = [os.path.join(CSRC, "common.hpp"), os.path.join(CSRC, "k4_kernels.hpp"), os.path.join(CSRC, "k4_ring.hpp"), os.path.join(CSRC, "k4_thin.hpp"),
            os.path.join(os.path.dirname(HERE), "include", "gemm_lineage.h"),
            os.path.join(os.path.dirname(HERE), "include", "conv_lineage.h"),

@@ -112,7 +112,7 @@ inline bool dtype_pair_supported(int in, int out)
 // ---- host-side launchers, one per translation unit ---------------------------------------------
 // Each returns hipSuccess or the launch error.  `path` selects a code path that the caller
 // (gemm_api.hip) has already proven legal for these arguments.
-enum ValuPath { VALU_SCALAR = 0, VALU_VEC16 = 1 };
+enum ValuPath { VALU_SCALAR = 0, VALU_VEC16 = 1, VALU_ASYNC = 4 };    // (K2/K3 paths 0..3: bitmask of operands loaded 16 bytes at a time)
 enum MfmaPath { MFMA_ELEMENTWISE = 0, MFMA_VEC16 = 1, MFMA_SKINNY = 2, MFMA_PACKED = 3, MFMA_SPLITK = 4, MFMA_SKINNY_N = 5, MFMA_VEC16_BROW = 6, MFMA_THIN_BROW = 7 };
 
 // Workspace of the packed K4 path: both operands rewritten as [rows][Kp], Kp = K rounded up to a slab.
@@ -157,6 +157,10 @@ hipError_t launch_k4_thin_row_major_b(const Args& a);
 
 hipError_t launch_k0(const Args& a);
 hipError_t launch_valu_tiled(int variant, int path, const Args& a);
+// K3's asynchronous form (direct-to-LDS loads, three stages, operands kept in storage format in LDS): whether a
+// product whose operands both take 16-byte loads qualifies, its launcher and geometry.
+bool k3_async_applies(const Args& a);
+hipError_t launch_k3_async(const Args& a);
 hipError_t launch_k4(int path, const Args& a);
 // K4's fast kernel with A gathered from the activations of a convolution layer (a.conv); a.A = x,
 // a.B = filters (F rows of K contiguous elements), 2-byte or 1-byte types, whole slabs per tap.
@@ -166,6 +170,7 @@ hipError_t launch_k4_conv(const Args& a);
 struct Geometry { int bm, bn, bk, threads, stages, lds_bytes; int64_t grid; };
 Geometry geometry_k0(const Args& a);
 Geometry geometry_valu_tiled(int variant, int path, const Args& a);
+Geometry geometry_k3_async(const Args& a);
 Geometry geometry_k4(int path, const Args& a);
 Geometry geometry_k4_conv(const Args& a);
 

@@ -161,6 +161,18 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
         p.path = (va ? 1 : 0) | (vb ? 2 : 0);
         path = va && vb ? "vec16" : va ? "vec16(A)+elementwise-masked(B)" : vb ? "elementwise-masked(A)+vec16(B)"
                                                                               : "elementwise-masked";
+        if (variant == GEMM_K3_PIPELINED) {
+            // the pipelined state's asynchronous form (slabs travel global -> LDS without registers, three stages)
+            // also wants K contiguous in both operands and K whole 64-byte slabs; where that fails, or on small
+            // problems, the state runs its register-staged form
+            required |= GEMM_COND_K_CONTIG_A | GEMM_COND_K_CONTIG_B | GEMM_COND_TILE_DIV_K;
+            if (va && vb && k3_async_applies(a)) {
+                p.path = VALU_ASYNC;
+                path = "vec16-direct-to-lds(3 stages)";
+                g = geometry_k3_async(a);
+                break;
+            }
+        }
         g = geometry_valu_tiled(variant, p.path, a);
         break;
     }
@@ -248,7 +260,9 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
     }
     if (g.bm > 0 && d->M % g.bm == 0) holds |= GEMM_COND_TILE_DIV_M;
     if (g.bn > 0 && d->N % g.bn == 0) holds |= GEMM_COND_TILE_DIV_N;
-    if (g.bk > 0 && d->K % g.bk == 0) holds |= GEMM_COND_TILE_DIV_K;
+    // (K3 relies on whole 64-byte slabs, the K tile of its asynchronous form, whichever of its forms runs)
+    const int64_t ktile = variant == GEMM_K3_PIPELINED ? 64 / es : g.bk;
+    if (ktile > 0 && d->K % ktile == 0) holds |= GEMM_COND_TILE_DIV_K;
 
     gemm_query_t& q = p.q;
     q.required = required;
@@ -302,7 +316,7 @@ int run_plan(int variant, const Plan& p)
     case GEMM_K0_NAIVE: e = launch_k0(p.args); break;
     case GEMM_K1_LDS_TILED:
     case GEMM_K2_VECTORIZED:
-    case GEMM_K3_PIPELINED: e = launch_valu_tiled(variant, p.path, p.args); break;
+    case GEMM_K3_PIPELINED: e = (variant == GEMM_K3_PIPELINED && p.path == VALU_ASYNC) ? launch_k3_async(p.args) : launch_valu_tiled(variant, p.path, p.args); break;
     default: e = launch_k4(p.path, p.args); break;
     }
     if (e != hipSuccess) last_launch_error = e;

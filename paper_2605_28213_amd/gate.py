@@ -98,6 +98,8 @@ def kernel_patterns(variant: int, in_dtype: int, path: str, bm: int, bn: int, th
     if variant in (gemm.GEMM_K1_LDS_TILED, gemm.GEMM_K2_VECTORIZED, gemm.GEMM_K3_PIPELINED):
         vec = "false" if variant == gemm.GEMM_K1_LDS_TILED or (flags & gemm.GEMM_FLAG_DEOPT_NO_VECTOR) else "true"
         dbuf = "true" if variant == gemm.GEMM_K3_PIPELINED else "false"
+        if variant == gemm.GEMM_K3_PIPELINED and path.startswith("vec16-direct-to-lds"):
+            return [r"valu_async<%s, %d>" % (dt, bm // 16)]
         return [r"valu_tiled<%s, gl::ValuCfg<%d, %d, \d+, \d+, \d+, %s, %s>" % (dt, bm, bn, vec, dbuf)]
     pats = []
     if "stream(small" in path:

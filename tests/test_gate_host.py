@@ -64,13 +64,21 @@ def test_compile_leg_rebuilds_a_stale_unit_and_records_kernel_resources():
     fast = [v for k, v in kernels.items() if "k4_mfma_fast<gl::FastCfg<gl::BF16, 256, 8, true, true, 0, false>" in k]
     assert len(fast) == 1 and fast[0]["agpr"] == 256 and fast[0]["vgpr_spill"] == 0 and fast[0]["scratch_bytes_per_lane"] == 0
     assert fast[0]["lds_bytes"] == 5 * 32768 and fast[0]["waves_per_simd"] == 1
+    # the pipelined state's asynchronous form: three workgroups per CU by LDS (3 stages x 16 KB) and by registers, no spill
+    pipe = {k: v for k, v in kernels.items() if "valu_async<" in k}
+    assert len(pipe) == 8 and all(v["vgpr_spill"] == 0 and v["scratch_bytes_per_lane"] == 0 for v in pipe.values())
+    assert all(v["waves_per_simd"] >= 3 and v["lds_bytes"] == 3 * 16384 for k, v in pipe.items() if ", 8>" in k)
+    # the thin kernel for a row-major B: at most 256 registers (two waves per SIMD in a workgroup of eight), no spill
+    thin = {k: v for k, v in kernels.items() if "k4_thin_brow<" in k}
+    assert len(thin) == 6 and all(v["vgpr_spill"] == 0 and v["scratch_bytes_per_lane"] == 0 and v["waves_per_simd"] >= 2 for v in thin.values())
 
 
 def test_every_state_and_path_maps_to_kernels_of_the_library():
     from paper_2605_28213_amd import gemm
     from paper_2605_28213_amd import inputs as gen
     cases = [(0, gen.F32, "naive", 16, 16, 256, 0), (1, gen.BF16, "lds-tiled", 64, 64, 256, 0), (2, gen.F16, "vec16", 128, 128, 256, 0),
-             (3, gen.E4M3, "vec16", 64, 64, 256, 0), (2, gen.BF16, "elementwise-masked(-novec)", 128, 128, 256, gemm.GEMM_FLAG_DEOPT_NO_VECTOR),
+             (3, gen.E4M3, "vec16", 64, 64, 256, 0),
+             (3, gen.BF16, "vec16-direct-to-lds(3 stages)", 128, 128, 256, 0), (3, gen.F32, "vec16-direct-to-lds(3 stages)", 64, 64, 256, 0), (2, gen.BF16, "elementwise-masked(-novec)", 128, 128, 256, gemm.GEMM_FLAG_DEOPT_NO_VECTOR),
              (4, gen.BF16, "mfma32-direct-to-lds", 256, 256, 256, 0), (4, gen.E4M3, "mfma32-direct-to-lds", 128, 128, 256, 0),
              (4, gen.E4M3, "mfma32-direct-to-lds(persistent)", 256, 256, 256, 0),
              (4, gen.BF16, "mfma32-direct-to-lds-noswz", 256, 256, 256, gemm.GEMM_FLAG_DEOPT_NO_SWIZZLE),
