@@ -119,7 +119,13 @@ enum {
      * Only on the streaming path and only a form with at least the product's rows (of the transposed product on the
      * small-N path); otherwise GEMM_ERR_BAD_ARG.  0 in these bits: the frozen rule chooses. */
     GEMM_FLAG_STREAM_FORM_SHIFT = 8,
-    GEMM_FLAG_STREAM_FORM_MASK = 7u << 8
+    GEMM_FLAG_STREAM_FORM_MASK = 7u << 8,
+    /* Instruction override for K4's fast kernel (a sweep point of Table 1 "autotune", and an edge of the backward
+     * walk): bf16 / fp16 products on 256 x 256 tiles with one tile per workgroup multiply with v_mfma_f32_16x16x32
+     * (8 x 8 accumulator tiles per wave: less accumulator traffic per flop, a higher clock under the power limit);
+     * with this bit they use v_mfma_f32_32x32x16 (4 x 4 tiles), as every other form of the kernel does.  Accepted
+     * where the other fast-kernel switches are; no effect on forms that use 32x32 already. */
+    GEMM_FLAG_MFMA_32X32 = 1u << 11
 };
 #define GEMM_FLAG_STREAM_FORM(form) ((uint32_t)((form) + 1) << GEMM_FLAG_STREAM_FORM_SHIFT)
 

@@ -135,6 +135,8 @@ bool k4_small_tiles(const Args& a);
 bool k4_uses_ring(const Args& a);
 // Whether the tiled part of a product on path `kind` (MFMA_VEC16, MFMA_PACKED, MFMA_SPLITK) runs as the persistent kernel.
 bool k4_fast_is_persistent(int kind, const Args& a);
+// Switches that change which kernel form multiplies the tiles but not how the product is cut up (row remainder, K ranges).
+constexpr uint32_t K4_NEUTRAL_FLAGS = GEMM_FLAG_DEOPT_NO_PERSISTENT | GEMM_FLAG_MFMA_32X32;
 constexpr int K4_RING_WORKGROUPS = 256;   // one per CU of the GPU this library is written for (8 XCDs x 32)
 hipError_t launch_k4_ring(const Args& a);  // bf16, fp16, e4m3; k4_uses_ring(a) must hold
 // The persistent kernel on a row-major B read in place (bf16, fp16), and whether a product qualifies for it.

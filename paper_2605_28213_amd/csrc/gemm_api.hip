@@ -73,7 +73,7 @@ int validate(int variant, const gemm_desc_t* d, const void* A, const void* B, co
         (d->layout_b != GEMM_ROW_MAJOR && d->layout_b != GEMM_COL_MAJOR))
         return GEMM_ERR_BAD_ARG;
     constexpr uint32_t K4_FLAGS = GEMM_FLAG_DEOPT_NO_SWIZZLE | GEMM_FLAG_DEOPT_NO_OVERLAP | GEMM_FLAG_TILE_256 | GEMM_FLAG_TILE_128 |
-                                  GEMM_FLAG_DEOPT_NO_RASTER | GEMM_FLAG_DEOPT_NO_PERSISTENT | GEMM_FLAG_STREAM_FORM_MASK;
+                                  GEMM_FLAG_DEOPT_NO_RASTER | GEMM_FLAG_DEOPT_NO_PERSISTENT | GEMM_FLAG_STREAM_FORM_MASK | GEMM_FLAG_MFMA_32X32;
     if (d->flags & ~(uint32_t)(GEMM_FLAG_STRICT | K4_FLAGS | GEMM_FLAG_DEOPT_NO_VECTOR)) return GEMM_ERR_BAD_ARG;
     if (((d->flags & GEMM_FLAG_STREAM_FORM_MASK) >> GEMM_FLAG_STREAM_FORM_SHIFT) > 6) return GEMM_ERR_BAD_ARG;
     if ((d->flags & GEMM_FLAG_TILE_256) && (d->flags & GEMM_FLAG_TILE_128)) return GEMM_ERR_BAD_ARG;
@@ -292,12 +292,12 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
         snprintf(q.path + n, sizeof(q.path) - n, "-form%u", ((a.flags & GEMM_FLAG_STREAM_FORM_MASK) >> GEMM_FLAG_STREAM_FORM_SHIFT) - 1);
     } else if (a.flags) {   // the other simplifications and the tile overrides exist for K4's fast kernel only (also on packed operands)
         const int kind = p.path & 0xFF;
-        const bool split_ok = kind == MFMA_SPLITK && a.flags == GEMM_FLAG_DEOPT_NO_PERSISTENT;   // (the split form keeps its ranges' kernel choice)
+        const bool split_ok = kind == MFMA_SPLITK && (a.flags & ~K4_NEUTRAL_FLAGS) == 0;   // (the split form keeps its ranges' kernel choice)
         if (variant != GEMM_K4_MFMA || (kind != MFMA_VEC16 && kind != MFMA_PACKED && !split_ok)) { p.status = GEMM_ERR_BAD_ARG; return p; }
         const size_t n = strlen(q.path);
-        snprintf(q.path + n, sizeof(q.path) - n, "%s%s%s%s", (a.flags & GEMM_FLAG_DEOPT_NO_SWIZZLE) ? "-noswz" : "",
+        snprintf(q.path + n, sizeof(q.path) - n, "%s%s%s%s%s", (a.flags & GEMM_FLAG_DEOPT_NO_SWIZZLE) ? "-noswz" : "",
                  (a.flags & GEMM_FLAG_DEOPT_NO_OVERLAP) ? "-noovl" : "", (a.flags & GEMM_FLAG_DEOPT_NO_RASTER) ? "-noraster" : "",
-                 (a.flags & GEMM_FLAG_DEOPT_NO_PERSISTENT) ? "-nopersist" : "");
+                 (a.flags & GEMM_FLAG_DEOPT_NO_PERSISTENT) ? "-nopersist" : "", (a.flags & GEMM_FLAG_MFMA_32X32) ? "-mfma32x32" : "");
     }
     const bool hard = (q.violated & GEMM_COND_DTYPE_HAS_MFMA) != 0;   // no slow path exists for this one
     if (hard || (q.violated && (d->flags & GEMM_FLAG_STRICT))) p.status = GEMM_ERR_PRECONDITION;

@@ -218,6 +218,91 @@ __device__ __forceinline__ void store_tiles_staged(const Args& a, int64_t b, con
     }
 }
 
+// The same epilogue for 16 x 16 accumulator tiles (v_mfma_f32_16x16x32 with the B fragment first): register c of lane l
+// holds the element at row (of C) l%16 and column 4*(l/16) + c of its tile.  Two rows of tiles make one staged
+// block of 32 rows; the way back out of the staging area is the one above.
+template <int OUT, bool INTERIOR, int TMI, int TNI>
+__device__ __forceinline__ void store_tiles_staged(const Args& a, int64_t b, const f32x4_t (&acc)[TMI][TNI],
+                                                   int64_t row0, int64_t col0, int lane, char* stage, bool vec_ok)
+{
+    constexpr int OB = OUT == GEMM_F32 ? 4 : 2;            // bytes per output element
+    constexpr int ROWB = TNI * 16 * OB, PITCH = ROWB + 16; // bytes per staged row
+    constexpr int CPR = ROWB / 16, PASSES = 32 * CPR / 64; // 16-byte chunks per row; read passes per block
+    constexpr int EPC = 16 / OB;                           // elements per chunk
+    static_assert(TMI % 2 == 0, "a staged block is two rows of tiles");
+    const float sc = batch_scale(a, b);
+    const int lrow = lane & 15, lq = lane >> 4;
+    char* C = (char*)a.C + (b * a.stride_c) * OB;
+    f32x4_t bv[TNI];                                       // bias of the four columns a lane holds per column tile
+#pragma unroll
+    for (int j = 0; j < TNI; ++j) {
+        bv[j] = f32x4_t{0, 0, 0, 0};
+        if (a.bias) {
+            const int64_t gj = col0 + j * 16 + 4 * lq;
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (INTERIOR || gj + c < a.N) bv[j][c] = a.bias[gj + c];
+        }
+    }
+#pragma unroll
+    for (int ib = 0; ib < TMI / 2; ++ib) {
+#pragma unroll
+        for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+            for (int j = 0; j < TNI; ++j) {
+                const f32x4_t& t = acc[2 * ib + ii][j];
+                const float v0 = t[0] * sc + bv[j][0], v1 = t[1] * sc + bv[j][1], v2 = t[2] * sc + bv[j][2], v3 = t[3] * sc + bv[j][3];
+                char* dst = stage + (ii * 16 + lrow) * PITCH + (j * 16 + 4 * lq) * OB;
+                if constexpr (OUT == GEMM_F32) {
+                    *(f32x4_t*)dst = f32x4_t{v0, v1, v2, v3};
+                } else if constexpr (OUT == GEMM_BF16) {
+                    typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
+                    *(bf16x4_t*)dst = bf16x4_t{(__bf16)v0, (__bf16)v1, (__bf16)v2, (__bf16)v3};
+                } else {
+                    typedef __attribute__((ext_vector_type(4))) _Float16 f16x4_t;
+                    *(f16x4_t*)dst = f16x4_t{(_Float16)v0, (_Float16)v1, (_Float16)v2, (_Float16)v3};
+                }
+            }
+        if constexpr (INTERIOR) {
+            u32x4_t w[PASSES];
+#pragma unroll
+            for (int p = 0; p < PASSES; ++p) {
+                const int q = lane + 64 * p;
+                w[p] = *(const u32x4_t*)(stage + (q / CPR) * PITCH + (q % CPR) * 16);
+            }
+#pragma unroll
+            for (int p = 0; p < PASSES; ++p) {
+                const int q = lane + 64 * p;
+                *(u32x4_t*)(C + ((row0 + ib * 32 + q / CPR) * a.ldc + col0 + (q % CPR) * EPC) * OB) = w[p];
+            }
+            continue;
+        }
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+            const int q = lane + 64 * p, r = q / CPR, c = q % CPR;
+            const u32x4_t w = *(const u32x4_t*)(stage + r * PITCH + c * 16);
+            const int64_t gi = row0 + ib * 32 + r, gj = col0 + c * EPC;
+            if (gi < a.M) {
+                char* out = C + (gi * a.ldc + gj) * OB;
+                if (gj + EPC <= a.N) {
+                    typedef u32x4_t __attribute__((aligned(2))) u32x4_a2_t;
+                    typedef u32x4_t __attribute__((aligned(4))) u32x4_a4_t;
+                    if (vec_ok) *(u32x4_t*)out = w;
+                    else if constexpr (OB == 4) *(u32x4_a4_t*)out = w;
+                    else *(u32x4_a2_t*)out = w;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < EPC; ++e)
+                        if (gj + e < a.N) {
+                            if constexpr (OB == 4) ((uint32_t*)out)[e] = w[e];
+                            else ((uint16_t*)out)[e] = (uint16_t)(w[e / 2] >> (16 * (e & 1)));
+                        }
+                }
+            }
+        }
+    }
+}
+
 // ------------------------------------------------------------------------------------------------
 // Fast kernel: both operands K-contiguous and 16-byte aligned, K a whole number of 128-byte slabs.
 //
@@ -253,6 +338,14 @@ enum {
 };
 
 typedef __attribute__((ext_vector_type(8))) int i32x8_t;
+
+// One 16x16x32 step (two-byte types): `a` supplies accumulator columns, `b` accumulator rows, as below.
+template <typename IN>
+__device__ __forceinline__ void mfma_step16(const u32x4_t& a, const u32x4_t& b, f32x4_t& c)
+{
+    if constexpr (IN::ID == GEMM_BF16) c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+    else c = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+}
 
 template <typename IN> struct Frag { static constexpr int CPS = IN::BYTES == 1 ? 2 : 1; u32x4_t c[CPS]; };
 
@@ -313,20 +406,28 @@ __device__ __forceinline__ void for_each_step(std::integer_sequence<int, KS...>,
 // CONV: the A operand is gathered from the activations of a convolution layer (ConvGeom): row m is
 // output pixel (n, p, q), K slab s is one tap's run of 128 bytes of channels.  Everything after the
 // loads (LDS layout, ring, MFMAs, epilogue) is the matrix product's.
-template <typename IN, int TILE_ = 256, int GROUP_M_ = 8, bool SWIZZLE_ = true, bool OVERLAP_ = true, int PRE_ = 0, bool CONV_ = false>
+//
+// MI16: the matrix instruction is v_mfma_f32_16x16x32 (two-byte types) instead of 32x32x16: the wave's 128 x 128
+// quarter is 8 x 8 accumulator tiles of 16 x 16, a k-step is 64 bytes of K.  Same flops per cycle, same LDS bytes per
+// flop, half the accumulator traffic per flop: under the package power limit the chip holds a higher clock with
+// it (register-resident loops on N(0,1)/sqrt(K) operands: 1857 against 1739 TFLOP/s).
+template <typename IN, int TILE_ = 256, int GROUP_M_ = 8, bool SWIZZLE_ = true, bool OVERLAP_ = true, int PRE_ = 0, bool CONV_ = false,
+          bool MI16_ = false>
 struct FastCfg {
     using In = IN;
-    static constexpr bool SWIZZLE = SWIZZLE_, OVERLAP = OVERLAP_, CONV = CONV_;
+    static constexpr bool SWIZZLE = SWIZZLE_, OVERLAP = OVERLAP_, CONV = CONV_, MI16 = MI16_;
     static constexpr int PRE_BARRIER_MFMAS = PRE_;
     static constexpr int BM = TILE_, BN = TILE_, WM = 2, WN = 2, GROUP_M = GROUP_M_;
     static constexpr int T = WM * WN * 64;
-    static constexpr int TMI = BM / WM / 32, TNI = BN / WN / 32;
+    static constexpr int TR = MI16_ ? 16 : 32;           // rows (and columns) of an accumulator tile
+    static constexpr int TMI = BM / WM / TR, TNI = BN / WN / TR;
+    static_assert(!MI16_ || IN::BYTES == 2, "the 16x16x32 instruction used here is the two-byte one");
     static constexpr int REGION = TILE_ * ROW_BYTES, REGIONS = 5;
     static constexpr int LDS_BYTES = REGIONS * REGION;
     static constexpr int WAVES_PER_SIMD = TILE_ == 256 ? 1 : 2;
     static_assert(TILE_ == 256 || TILE_ == 128, "square tiles of 256 or 128");
     // the epilogue parks 32 rows of fp32 per wave, one wave per region
-    static_assert(32 * (TNI * 32 * 4 + 16) <= REGION, "epilogue staging must fit a region");
+    static_assert(32 * (BN / WN * 4 + 16) <= REGION, "epilogue staging must fit a region");
 };
 
 template <typename CFG>
@@ -339,7 +440,8 @@ void k4_mfma_fast(Args a, int tiles_m, int tiles_n, int flags)
     constexpr int KE = ROW_BYTES / IN::BYTES;            // K elements per slab
     constexpr int V = 16 / IN::BYTES;                    // K elements per chunk
     constexpr int CPS = Frag<IN>::CPS;                   // chunks per lane per k-step
-    constexpr int NK = CHUNKS / (2 * CPS);               // k-steps per slab
+    constexpr int TR = CFG::TR, LG = 64 / TR;            // rows of an accumulator tile; lane groups along K (2 or 4)
+    constexpr int NK = CHUNKS / (LG * CPS);              // k-steps per slab
     constexpr int LD = BM / 8 / NW;                      // direct loads per wave per operand slab
     static_assert(BM == BN && NW == 4 && LD % 2 == 0, "the ring schedule is written for square tiles and four waves");
     __shared__ __attribute__((aligned(1024))) char r0[REGION];
@@ -442,28 +544,30 @@ void k4_mfma_fast(Args a, int tiles_m, int tiles_n, int flags)
 
     // ---- LDS -> registers: lane reads row (lane % 32) of each 32-row block, CPS chunks starting at
     // chunk CPS * (2*ks + lane/32) ---------------------------------------------------------------
-    const int lrow = lane & 31, lhalf = lane >> 5;
+    const int lrow = lane & (TR - 1), lhalf = lane / TR;
     const int rd_mask = (lhalf * CPS) ^ (CFG::SWIZZLE ? swz(lrow) : 0);
     const int rd_a = (wm * (BM / CFG::WM) + lrow) * ROW_BYTES;
     const int rd_b = (wn * (BN / WN) + lrow) * ROW_BYTES;
 
-    f32x16_t acc[TMI][TNI];
+    using AccT = std::conditional_t<CFG::MI16, f32x4_t, f32x16_t>;
+    constexpr int ACC_REGS = CFG::MI16 ? 4 : 16;
+    AccT acc[TMI][TNI];
 #pragma unroll
     for (int i = 0; i < TMI; ++i)
 #pragma unroll
         for (int j = 0; j < TNI; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+            for (int r = 0; r < ACC_REGS; ++r) acc[i][j][r] = 0.0f;
 
     Frag<IN> fa[2][TMI], fb[2][TNI];                 // two fragment slots: the step in use, the step in flight
     auto read = [&](const char* ra, const char* rb, int ks, int slot) __attribute__((always_inline)) {
 #pragma unroll
         for (int q = 0; q < CPS; ++q) {
-            const int pos = ((2 * CPS * ks + q) ^ rd_mask) << 4;
+            const int pos = ((LG * CPS * ks + q) ^ rd_mask) << 4;
 #pragma unroll
-            for (int j = 0; j < TNI; ++j) fb[slot][j].c[q] = *(const u32x4_t*)(rb + rd_b + j * 32 * ROW_BYTES + pos);
+            for (int j = 0; j < TNI; ++j) fb[slot][j].c[q] = *(const u32x4_t*)(rb + rd_b + j * TR * ROW_BYTES + pos);
 #pragma unroll
-            for (int i = 0; i < TMI; ++i) fa[slot][i].c[q] = *(const u32x4_t*)(ra + rd_a + i * 32 * ROW_BYTES + pos);
+            for (int i = 0; i < TMI; ++i) fa[slot][i].c[q] = *(const u32x4_t*)(ra + rd_a + i * TR * ROW_BYTES + pos);
         }
     };
     // B first: see the epilogue.  Columns are walked back and forth so that consecutive MFMAs share
@@ -474,7 +578,10 @@ void k4_mfma_fast(Args a, int tiles_m, int tiles_n, int flags)
 #pragma unroll
             for (int jj = 0; jj < TNI; ++jj) {
                 const int j = (i & 1) ? TNI - 1 - jj : jj;
-                if (i * TNI + jj >= lo && i * TNI + jj < hi) mfma_step<IN>(fb[slot][j], fa[slot][i], acc[i][j]);
+                if (i * TNI + jj >= lo && i * TNI + jj < hi) {
+                    if constexpr (CFG::MI16) mfma_step16<IN>(fb[slot][j].c[0], fa[slot][i].c[0], acc[i][j]);
+                    else mfma_step<IN>(fb[slot][j], fa[slot][i], acc[i][j]);
+                }
             }
     };
     constexpr int NMF = TMI * TNI;                   // MFMA instructions per k-step
@@ -583,7 +690,7 @@ void k4_mfma_fast(Args a, int tiles_m, int tiles_n, int flags)
     auto store = [&](auto out) __attribute__((always_inline)) {
         constexpr int OUT = decltype(out)::value;
         if (interior) store_tiles_staged<OUT, true, TMI, TNI>(a, b, acc, row0, col0, lane, stage, vec_ok);
-        else store_tiles_staged<OUT, false, TMI, TNI>(a, b, acc, row0, col0, lane, stage, vec_ok);
+        else store_tiles_staged<OUT, false, TMI, TNI>(a, b, acc, row0, col0, lane, stage, vec_ok);   // (overloaded on the accumulator tile)
     };
     if (a.out_dtype == GEMM_F32) store(std::integral_constant<int, GEMM_F32>{});
     else if (a.out_dtype == GEMM_BF16) store(std::integral_constant<int, GEMM_BF16>{});

@@ -6,6 +6,8 @@ namespace gl {
 
 // Frozen configurations ("templatize" + an offline sweep, paper Table 1 expression-level intents).
 template <typename IN> using FastK4 = FastCfg<IN, 256>;                    // 256x256 tile, 4 waves, 128x128 per wave, one workgroup per CU
+template <typename IN> using FastK4Mi16 = FastCfg<IN, 256, 8, true, true, 0, false, true>;   // the same with 8 x 8 accumulator tiles of v_mfma_f32_16x16x32 per wave (two-byte types)
+template <typename IN> using FastK4Mi16Long = FastCfg<IN, 256, 8, true, true, 8, false, true>;   // ... and 8 instructions ahead of the slab barrier (K of 96 slabs or more)
 template <typename IN> using FastK4Small = FastCfg<IN, 128>;               // 128x128 tile, 4 waves, 64x64 per wave, two workgroups per CU
 template <typename IN> using StreamK4 = StreamCfg<IN, 1, 1, 256, 19>;      // 16 columns per one-wave workgroup, 512-byte runs, K walk rotated by 19 tiles per workgroup
 template <typename IN> using StreamK4Deep = StreamCfg<IN, 4, 1, 256, 19>;  // the same with 4 waves taking K tiles in turn, for strips too few to fill the chip
@@ -153,6 +155,16 @@ static hipError_t launch_fast_any(const Args& a)
     if (noswz) return launch_fast<FastCfg<IN, 256, 8, false, true>>(a);
     if (noovl) return launch_fast<FastCfg<IN, 256, 8, true, false>>(a);
     if (k4_small_tiles(a)) return launch_fast<FastK4Small<IN>>(a);
+    // Two-byte types: 8 x 8 accumulator tiles of v_mfma_f32_16x16x32 per wave.  Same box, operands rotated, against
+    // the 32x32x16 form: bf16 8192^3 755 -> 725-737 us, 4096^3 104.7 -> 96.3 us (the package draws the same 1.4 kW at
+    // 1.92 instead of 1.64 GHz).  With a long K, 8 instructions of a slab's last k-step go ahead of its barrier
+    // (8192^3: 733-737 -> 724-726 us; at 64 slabs they cost 2 %; 16, 24 and 32 of them lose on both).
+    if constexpr (IN::BYTES == 2) {
+        if (!(a.flags & GEMM_FLAG_MFMA_32X32)) {
+            const int64_t nslab = a.K / (ROW_BYTES / IN::BYTES);
+            return nslab >= 96 ? launch_fast<FastK4Mi16Long<IN>>(a) : launch_fast<FastK4Mi16<IN>>(a);
+        }
+    }
     return launch_fast<FastK4<IN>>(a);
 }
 
@@ -166,7 +178,7 @@ static hipError_t launch_fast_any(const Args& a)
 bool k4_splits_m_tail(const Args& a)
 {
     const int64_t rem = a.M % 256;
-    if (a.M <= 256 || rem < 1 || rem > 64 || a.N > 16384 || (a.flags & ~(uint32_t)GEMM_FLAG_DEOPT_NO_PERSISTENT) != 0 || k4_small_tiles(a)) return false;
+    if (a.M <= 256 || rem < 1 || rem > 64 || a.N > 16384 || (a.flags & ~K4_NEUTRAL_FLAGS) != 0 || k4_small_tiles(a)) return false;
     const int64_t per_row = ((a.N + 255) / 256) * a.batch, rows = a.M / 256;
     return (rows * per_row + 255) / 256 < ((rows + 1) * per_row + 255) / 256;
 }
@@ -199,7 +211,7 @@ static hipError_t launch_fast_split(const Args& a)
 // range and at most about 512 workgroups, at most 8.
 int k4_splitk_factor(const Args& a)
 {
-    if (a.batch != 1 || (a.flags & ~(uint32_t)GEMM_FLAG_DEOPT_NO_PERSISTENT) != 0 || a.M <= 16 || k4_splits_m_tail(a)) return 1;
+    if (a.batch != 1 || (a.flags & ~K4_NEUTRAL_FLAGS) != 0 || a.M <= 16 || k4_splits_m_tail(a)) return 1;
     const int64_t ke = ROW_BYTES / elem_size(a.in_dtype);
     if (a.K <= 0 || a.K % ke != 0) return 1;
     const int64_t nslab = a.K / ke, tiles = ((a.M + 127) / 128) * ((a.N + 127) / 128);
@@ -224,7 +236,7 @@ static hipError_t launch_splitk(const Args& a)
     p.C = a.workspace; p.ldc = a.N; p.stride_c = a.M * a.N;
     p.out_dtype = GEMM_F32;
     p.scale_a = p.scale_b = nullptr; p.bias = nullptr;
-    p.flags = (k4_small_tiles(a) ? GEMM_FLAG_TILE_128 : GEMM_FLAG_TILE_256) | (a.flags & GEMM_FLAG_DEOPT_NO_PERSISTENT);   // the tile the product itself would get
+    p.flags = (k4_small_tiles(a) ? GEMM_FLAG_TILE_128 : GEMM_FLAG_TILE_256) | (a.flags & K4_NEUTRAL_FLAGS);   // the tile the product itself would get
     hipError_t e = launch_fast_any<IN>(p);
     if (e != hipSuccess) return e;
     const int64_t threads = a.M * ((a.N + 3) / 4);
@@ -242,7 +254,7 @@ bool k4_fast_is_persistent(int kind, const Args& a)
         const int splits = k4_splitk_factor(a);
         p.batch = splits;
         p.K = a.K / splits;
-        p.flags = (k4_small_tiles(a) ? GEMM_FLAG_TILE_128 : GEMM_FLAG_TILE_256) | (a.flags & GEMM_FLAG_DEOPT_NO_PERSISTENT);
+        p.flags = (k4_small_tiles(a) ? GEMM_FLAG_TILE_128 : GEMM_FLAG_TILE_256) | (a.flags & K4_NEUTRAL_FLAGS);
         return k4_uses_ring(p);
     }
     if (kind == MFMA_PACKED) p.K = k4_packed_k(a);

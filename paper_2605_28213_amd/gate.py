@@ -114,7 +114,10 @@ def kernel_patterns(variant: int, in_dtype: int, path: str, bm: int, bn: int, th
         elif "(persistent)" in path:
             pats.append(r"k4_mfma_ring<gl::RingCfg<%s, \d+, false>" % dt)
         else:
-            pats.append(r"k4_mfma_fast<gl::FastCfg<%s, %d, \d+, %s, %s, \d+, false>" % (dt, bm, swz, ovl))
+            # (two-byte types on 256-tiles with none of the switches multiply with the 16x16x32 instruction)
+            mi16 = ("true" if in_dtype in (gen.BF16, gen.F16) and bm == 256 and not (flags & (gemm.GEMM_FLAG_DEOPT_NO_SWIZZLE |
+                    gemm.GEMM_FLAG_DEOPT_NO_OVERLAP | gemm.GEMM_FLAG_MFMA_32X32)) else "false")
+            pats.append(r"k4_mfma_fast<gl::FastCfg<%s, %d, \d+, %s, %s, \d+, false, %s>" % (dt, bm, swz, ovl, mi16))
         if "packed" in path:
             pats.append(r"k4_pack_(rows|transpose)<%s>" % dt)
         if "splitK" in path:

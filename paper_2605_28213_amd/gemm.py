@@ -27,6 +27,7 @@ GEMM_FLAG_DEOPT_NO_SWIZZLE, GEMM_FLAG_DEOPT_NO_OVERLAP = 2, 4
 GEMM_FLAG_TILE_256, GEMM_FLAG_TILE_128 = 8, 16
 GEMM_FLAG_DEOPT_NO_RASTER, GEMM_FLAG_DEOPT_NO_VECTOR = 32, 64
 GEMM_FLAG_DEOPT_NO_PERSISTENT = 128
+GEMM_FLAG_MFMA_32X32 = 1 << 11
 GEMM_FLAG_STREAM_FORM_SHIFT, GEMM_FLAG_STREAM_FORM_MASK = 8, 7 << 8
 
 

@@ -33,6 +33,7 @@ TILED_POINTS = {
     "tile256": G.GEMM_FLAG_TILE_256,
     "tile256-onetile": G.GEMM_FLAG_TILE_256 | G.GEMM_FLAG_DEOPT_NO_PERSISTENT,
     "tile256-rowmajor": G.GEMM_FLAG_TILE_256 | G.GEMM_FLAG_DEOPT_NO_RASTER,
+    "tile256-mfma32x32": G.GEMM_FLAG_TILE_256 | G.GEMM_FLAG_MFMA_32X32,
     "tile128": G.GEMM_FLAG_TILE_128,
     "tile128-rowmajor": G.GEMM_FLAG_TILE_128 | G.GEMM_FLAG_DEOPT_NO_RASTER,
 }

@@ -53,7 +53,7 @@ def first_inner_loop(body):
 @pytest.mark.parametrize("dtype,mfma,per_slab", [("4BF16", "v_mfma_f32_32x32x16_bf16", 64), ("3F16", "v_mfma_f32_32x32x16_f16", 64),
                                                  ("4E4M3", "v_mfma_scale_f32_32x32x64_f8f6f4", 32)])
 def test_fast_kernel_steady_state_loop(asm, dtype, mfma, per_slab):
-    prefix = "_ZN2gl12k4_mfma_fastINS_7FastCfgINS_" + dtype + "ELi256ELi8ELb1ELb1ELi0ELb0E"      # the expert instantiation
+    prefix = "_ZN2gl12k4_mfma_fastINS_7FastCfgINS_" + dtype + "ELi256ELi8ELb1ELb1ELi0ELb0ELb0E"      # the 32x32 instantiation of the expert state
     ops = first_inner_loop(kernel_body(asm, prefix))
     count = lambda name: sum(o == name for o in ops)
     # five slabs per trip round the LDS ring; 16 direct loads per slab; fragment reads are 16-byte
@@ -69,6 +69,26 @@ def test_fast_kernel_steady_state_loop(asm, dtype, mfma, per_slab):
     meta = metadata(asm, prefix)
     assert meta["agpr"] == 256 and meta["lds"] == 160 * 1024
     assert meta["vgpr_spill"] <= 32 and meta["scratch"] <= 160      # a few values parked outside the loop at most
+
+
+@pytest.mark.parametrize("dtype,mfma", [("4BF16", "v_mfma_f32_16x16x32_bf16"), ("3F16", "v_mfma_f32_16x16x32_f16")])
+@pytest.mark.parametrize("pre", [0, 8])
+def test_fast_kernel_steady_state_loop_with_16x16_tiles(asm, dtype, mfma, pre):
+    """The two-byte types' default on 256-tiles: 8 x 8 accumulator tiles of 16 x 16 per wave, two k-steps of 64
+    instructions per slab; the same loads, fragment reads and barriers as the 32x32 form."""
+    prefix = "_ZN2gl12k4_mfma_fastINS_7FastCfgINS_" + dtype + "ELi256ELi8ELb1ELb1ELi%dELb0ELb1E" % pre
+    ops = first_inner_loop(kernel_body(asm, prefix))
+    count = lambda name: sum(o == name for o in ops)
+    assert count(mfma) == 5 * 128
+    assert count("buffer_load_dwordx4") == 5 * 16
+    assert count("ds_read_b128") == 5 * 32
+    assert count("s_barrier") == 5
+    for bad in ("v_readfirstlane_b32", "s_and_saveexec_b64", "scratch_load_dword", "scratch_store_dword", "ds_write_b128"):
+        assert count(bad) == 0, bad
+    # (a handful of accumulator tiles change register file per slab: 256 accumulator registers and 128 of fragments)
+    assert count("v_accvgpr_read_b32") + count("v_accvgpr_write_b32") <= 5 * 16
+    meta = metadata(asm, prefix)
+    assert meta["agpr"] == 256 and meta["lds"] == 160 * 1024 and meta["vgpr_spill"] == 0 and meta["scratch"] == 0
 
 
 def test_stream_kernel_register_budget(asm):

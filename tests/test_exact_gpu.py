@@ -90,6 +90,24 @@ def test_direct_to_lds_kernel_is_exact(dtype, tile_flag, bm):
             assert q.bm == bm
 
 
+@pytest.mark.parametrize("dtype", [gen.BF16, gen.F16])
+def test_both_matrix_instructions_of_the_256_tile_kernel_are_exact(dtype):
+    """Two-byte types on 256-tiles multiply with v_mfma_f32_16x16x32 (8 x 8 accumulator tiles per wave; with 96 slabs
+    or more the form that issues ahead of the slab barrier), or with v_mfma_f32_32x32x16 when the switch asks for it:
+    edges in both directions, a bias, a two-byte output rounded to nearest even."""
+    for (M, N, ns, nb, flag, suffix) in [(520, 300, 100, 1, 0, ""), (300, 520, 13, 2, 0, ""),
+                                         (520, 300, 100, 1, gemm.GEMM_FLAG_MFMA_32X32, "-mfma32x32"),
+                                         (300, 520, 13, 2, gemm.GEMM_FLAG_MFMA_32X32, "-mfma32x32")]:
+        inp = int_inputs(dtype, M, N, slabs(dtype, ns), batch=nb, seed=ns + flag, biased=True)
+        q = run_exact(inp, "mfma32-direct-to-lds" + suffix, flags=gemm.GEMM_FLAG_TILE_256 | flag)
+        assert q.bm == 256
+        C_ref, _ = oracle_for(inp)
+        rc, _, raw = util.run_config(K4, inp, out_dtype=dtype, flags=gemm.GEMM_FLAG_TILE_256 | flag)
+        assert rc == gemm.GEMM_OK
+        want = gen.quantise(dtype, C_ref.astype(np.float32).reshape(-1))
+        np.testing.assert_array_equal(raw.cpu().numpy().view(np.uint16)[: nb * M * N], want)
+
+
 RING_CASES = [  # (M, N, slabs, batch): at least 256 tiles of 256 x 256, so the persistent kernel takes the product
     (520, 300, 3, 130),     # 780 tiles: workgroups with 3 and with 4 tiles; the shortest K the kernel takes (first, last-but-one, last slab)
     (520, 300, 4, 43),      # 258 tiles: one or two tiles per workgroup; one middle slab

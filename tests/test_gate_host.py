@@ -61,7 +61,7 @@ def test_compile_leg_rebuilds_a_stale_unit_and_records_kernel_resources():
     assert rec["ok"] and rec["compiled_units"] == ["k0_naive.hip"] and not stale       # back to the committed source
     from paper_2605_28213_amd import build
     kernels = build.resources()["kernels"]
-    fast = [v for k, v in kernels.items() if "k4_mfma_fast<gl::FastCfg<gl::BF16, 256, 8, true, true, 0, false>" in k]
+    fast = [v for k, v in kernels.items() if "k4_mfma_fast<gl::FastCfg<gl::BF16, 256, 8, true, true, 0, false, false>" in k]
     assert len(fast) == 1 and fast[0]["agpr"] == 256 and fast[0]["vgpr_spill"] == 0 and fast[0]["scratch_bytes_per_lane"] == 0
     assert fast[0]["lds_bytes"] == 5 * 32768 and fast[0]["waves_per_simd"] == 1
     # the pipelined state's asynchronous form: three workgroups per CU by LDS (3 stages x 16 KB) and by registers, no spill
@@ -80,6 +80,7 @@ def test_every_state_and_path_maps_to_kernels_of_the_library():
              (3, gen.E4M3, "vec16", 64, 64, 256, 0),
              (3, gen.BF16, "vec16-direct-to-lds(3 stages)", 128, 128, 256, 0), (3, gen.F32, "vec16-direct-to-lds(3 stages)", 64, 64, 256, 0), (2, gen.BF16, "elementwise-masked(-novec)", 128, 128, 256, gemm.GEMM_FLAG_DEOPT_NO_VECTOR),
              (4, gen.BF16, "mfma32-direct-to-lds", 256, 256, 256, 0), (4, gen.E4M3, "mfma32-direct-to-lds", 128, 128, 256, 0),
+             (4, gen.F16, "mfma32-direct-to-lds-mfma32x32", 256, 256, 256, gemm.GEMM_FLAG_MFMA_32X32),
              (4, gen.E4M3, "mfma32-direct-to-lds(persistent)", 256, 256, 256, 0),
              (4, gen.BF16, "mfma32-direct-to-lds-noswz", 256, 256, 256, gemm.GEMM_FLAG_DEOPT_NO_SWIZZLE),
              (4, gen.F16, "mfma32-packed+direct-to-lds+stream(M-tail)", 256, 256, 256, 0),
@@ -97,7 +98,7 @@ def test_every_state_and_path_maps_to_kernels_of_the_library():
 
 def test_counter_files_are_read_per_launch_and_calibrated(tmp_path):
     head = '"Correlation_Id","Dispatch_Id","Agent_Id","Queue_Id","Process_Id","Thread_Id","Grid_Size","Kernel_Id","Kernel_Name","Workgroup_Size","LDS_Block_Size","Scratch_Size","VGPR_Count","Accum_VGPR_Count","SGPR_Count","Counter_Name","Counter_Value","Start_Timestamp","End_Timestamp"'
-    k = "void gl::k4_mfma_fast<gl::FastCfg<gl::BF16, 256, 8, true, true, 0, false> >(gl::Args, int, int, int)"
+    k = "void gl::k4_mfma_fast<gl::FastCfg<gl::BF16, 256, 8, true, true, 0, false, true> >(gl::Args, int, int, int)"
     row = lambda i, name, c, v: '%d,%d,"Agent 1",2,1,1,1,1,"%s",256,0,0,0,0,0,"%s",%f,0,1' % (i, i, name, c, v)
     (tmp_path / "f_counter_collection.csv").write_text("\n".join([head, row(1, k, "FETCH_SIZE", 800000.0), row(2, k, "FETCH_SIZE", 780000.0),
         row(3, "gl::probe_copy(unsigned int __vector(4)*, unsigned int __vector(4) const*, unsigned long)", "FETCH_SIZE", 131072.0)]) + "\n")

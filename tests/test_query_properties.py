@@ -146,7 +146,7 @@ def test_expert_state_paths_and_scratch(p):
 @settings(max_examples=200, deadline=None)
 @given(descriptors(), st.integers(0, 4), st.sampled_from([gemm.GEMM_FLAG_TILE_128, gemm.GEMM_FLAG_TILE_256,
                                                          gemm.GEMM_FLAG_DEOPT_NO_SWIZZLE, gemm.GEMM_FLAG_DEOPT_NO_OVERLAP,
-                                                         gemm.GEMM_FLAG_DEOPT_NO_RASTER]))
+                                                         gemm.GEMM_FLAG_DEOPT_NO_RASTER, gemm.GEMM_FLAG_MFMA_32X32]))
 def test_expert_only_switches_are_refused_elsewhere(p, variant, flag):
     plain = gemm.gemm_query(variant, make(p))
     q = gemm.gemm_query(variant, make(p, flags=flag))
