@@ -233,12 +233,17 @@ int gemm_default_desc(gemm_desc_t *d, int64_t M, int64_t N, int64_t K, int dtype
  *                           finite values of the dtype); *flops receives the flop count of the launch;
  *                           sink: workgroups*256 floats.  Errors: GEMM_ERR_BAD_ARG,
  *                           GEMM_ERR_UNSUPPORTED_DTYPE (fp32), GEMM_ERR_LAUNCH.
+ *   gemm_probe_mfma16       the same for the 16x16x32 instruction the expert kernel uses for bf16 / fp16 on
+ *                           256 x 256 tiles: iters x 128 instructions per wave (the flops of 2 x iters of
+ *                           the loop above) on 2 x gemm_probe_mfma_operand_bytes bytes; bf16 and fp16 only.
  */
 int gemm_probe_copy(void *dst, const void *src, size_t bytes, void *stream);
 int gemm_probe_stream_read(const void *src, size_t bytes, void *sink, void *stream);
 size_t gemm_probe_mfma_operand_bytes(int dtype, int workgroups);
 int gemm_probe_mfma(int dtype, const void *operands, size_t operand_bytes, int workgroups, int iters,
                     void *sink, size_t sink_bytes, double *flops, void *stream);
+int gemm_probe_mfma16(int dtype, const void *operands, size_t operand_bytes, int workgroups, int iters,
+                      void *sink, size_t sink_bytes, double *flops, void *stream);
 
 const char *gemm_status_string(int status);
 /* The HIP runtime's message for the calling thread's most recent GEMM_ERR_LAUNCH ("no error" if none). */

@@ -89,6 +89,44 @@ void probe_mfma(const char* __restrict__ operands, int iters, float* sink)
     sink[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
 
+// The same loop with v_mfma_f32_16x16x32 (two-byte types): 8 x 8 accumulator tiles of 16 x 16 per wave, two k-steps of
+// 64 instructions per iteration -- the flops of two iterations of the loop above, on twice the operand bytes per lane.
+template <typename IN>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void probe_mfma16(const char* __restrict__ operands, int iters, float* sink)
+{
+    f32x4_t acc[8][8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[i][j] = f32x4_t{0, 0, 0, 0};
+    u32x4_t fa[2][8], fb[2][8];
+    const u32x4_t* p = (const u32x4_t*)operands + ((size_t)blockIdx.x * 256 + threadIdx.x) * 32;
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { fa[s][i] = p[s * 16 + i]; fb[s][i] = p[s * 16 + 8 + i]; }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+#pragma unroll
+                for (int jj = 0; jj < 8; ++jj) {
+                    const int j = (i & 1) ? 7 - jj : jj;
+                    mfma_step16<IN>(fb[s][j], fa[s][i], acc[i][j]);
+                }
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) s += acc[i][j][r];
+    sink[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
+}
+
 }  // namespace gl
 
 using namespace gl;
@@ -132,6 +170,22 @@ int gemm_probe_mfma(int dtype, const void* operands, size_t operand_bytes, int w
     if (dtype == GEMM_BF16) hipLaunchKernelGGL(probe_mfma<BF16>, grid, block, 0, st, (const char*)operands, iters, (float*)sink);
     else if (dtype == GEMM_F16) hipLaunchKernelGGL(probe_mfma<F16>, grid, block, 0, st, (const char*)operands, iters, (float*)sink);
     else hipLaunchKernelGGL(probe_mfma<E4M3>, grid, block, 0, st, (const char*)operands, iters, (float*)sink);
+    return hipGetLastError() == hipSuccess ? GEMM_OK : GEMM_ERR_LAUNCH;
+}
+
+int gemm_probe_mfma16(int dtype, const void* operands, size_t operand_bytes, int workgroups, int iters, void* sink,
+                      size_t sink_bytes, double* flops, void* stream)
+{
+    if (dtype != GEMM_BF16 && dtype != GEMM_F16) return GEMM_ERR_UNSUPPORTED_DTYPE;
+    const size_t need = 2 * gemm_probe_mfma_operand_bytes(dtype, workgroups);  // 32 chunks of 16 bytes per lane: twice the other loop's
+    if (need == 0 || !operands || !sink || iters < 1 || ((uintptr_t)operands & 15u)) return GEMM_ERR_BAD_ARG;
+    if (operand_bytes < need || sink_bytes < (size_t)workgroups * 256 * sizeof(float)) return GEMM_ERR_BAD_ARG;
+    if (flops) *flops = (double)workgroups * 4 * iters * 2 * 64 * (2.0 * 16 * 16 * 32);
+    dim3 grid((unsigned)workgroups), block(256);
+    (void)hipGetLastError();
+    hipStream_t st = (hipStream_t)stream;
+    if (dtype == GEMM_BF16) hipLaunchKernelGGL(probe_mfma16<BF16>, grid, block, 0, st, (const char*)operands, iters, (float*)sink);
+    else hipLaunchKernelGGL(probe_mfma16<F16>, grid, block, 0, st, (const char*)operands, iters, (float*)sink);
     return hipGetLastError() == hipSuccess ? GEMM_OK : GEMM_ERR_LAUNCH;
 }
 

@@ -111,6 +111,8 @@ def lib() -> ctypes.CDLL:
         L.gemm_probe_mfma_operand_bytes.argtypes = [ci, ci]
         L.gemm_probe_mfma.restype = ci
         L.gemm_probe_mfma.argtypes = [ci, vp, st, ci, ci, vp, st, ctypes.POINTER(ctypes.c_double), vp]
+        L.gemm_probe_mfma16.restype = ci
+        L.gemm_probe_mfma16.argtypes = [ci, vp, st, ci, ci, vp, st, ctypes.POINTER(ctypes.c_double), vp]
         _lib = L
     return _lib
 
@@ -244,6 +246,15 @@ def gemm_probe_mfma(dtype: int, operands: Any, operand_bytes: int, workgroups: i
     fl = ctypes.c_double(0.0)
     rc = int(lib().gemm_probe_mfma(dtype, _addr(operands), operand_bytes, workgroups, iters, _addr(sink), sink_bytes,
                                    ctypes.byref(fl), _stream_addr(stream)))
+    return rc, fl.value
+
+
+def gemm_probe_mfma16(dtype: int, operands: Any, operand_bytes: int, workgroups: int, iters: int, sink: Any,
+                      sink_bytes: int, stream: Any = None):
+    """Returns (status, flops of the launch)."""
+    fl = ctypes.c_double(0.0)
+    rc = int(lib().gemm_probe_mfma16(dtype, _addr(operands), operand_bytes, workgroups, iters, _addr(sink), sink_bytes,
+                                     ctypes.byref(fl), _stream_addr(stream)))
     return rc, fl.value
 
 
