@@ -64,7 +64,9 @@ typedef enum {
     GEMM_K0_NAIVE = 0,      /* one thread per output element, operands read from global memory */
     GEMM_K1_LDS_TILED = 1,  /* + "tile / sm_stage": workgroup output tiles, K slabs staged through LDS */
     GEMM_K2_VECTORIZED = 2, /* + "vectorize_global": 16-byte global loads, element-masked tails */
-    GEMM_K3_PIPELINED = 3,  /* + "pipeline": double-buffered LDS, next slab in flight during compute */
+    GEMM_K3_PIPELINED = 3,  /* + "cp.async + pipeline": slabs travel global -> LDS without registers, three stages deep
+                               (operands kept in storage format, decoded on read); where that form's conditions
+                               fail, two LDS buffers with the next slab fetched through registers */
     GEMM_K4_MFMA = 4,       /* + "mma" / "swizzle": wave64 MFMA, swizzled LDS operand layout (fp32: its masked kernel only) */
     GEMM_VARIANT_COUNT = 5
 } gemm_variant_t;

@@ -415,7 +415,7 @@ const char* gemm_variant_name(int v)
 
 const char* gemm_variant_intent(int v)
 {
-    static const char* intents[] = {"(start of lineage)", "tile / sm_stage", "vectorize_global", "pipeline (double-buffered LDS)",
+    static const char* intents[] = {"(start of lineage)", "tile / sm_stage", "vectorize_global", "cp.async + pipeline (direct-to-LDS loads, three stages)",
                                     "mma + operand-layout swizzle"};
     return (v >= 0 && v < GEMM_VARIANT_COUNT) ? intents[v] : "?";
 }

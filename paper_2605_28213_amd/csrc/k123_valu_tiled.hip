@@ -10,6 +10,9 @@
 //                                    precondition, is fetched element by element under a mask.
 //   K3 = K2 + "pipeline"             two LDS buffers; slab s+1 travels global->registers while slab
 //                                    s is consumed from LDS.  Precondition: staged data movement.
+//                                    (This is K3's register-staged form, for operands its asynchronous
+//                                    form in k3_async.hip does not take: K strided, K not whole
+//                                    64-byte slabs, rows not 16-byte aligned.)
 //
 // "templatize" (Table 1): the tile shape and the two switches are template parameters, so each
 // state is one instantiation of a single kernel and a transition is one changed constant.

@@ -12,6 +12,7 @@
 //   fast kernel:   global --global_load_lds_dwordx4 (no registers)--> LDS[buf^1]   (next slab)
 //   masked kernel: global --> registers --ds_write_b128--> LDS[buf^1]               (next slab)
 //   LDS[buf] --ds_read_b128--> MFMA operand registers --> v_mfma_f32_32x32x16       (this slab)
+//                              (bf16 / fp16 on 256 x 256 tiles, one tile per workgroup: v_mfma_f32_16x16x32, see FastCfg)
 // LDS rows are 128 bytes (eight 16-byte chunks); chunk c of row r lives at chunk position
 // c ^ swz(r).
 #pragma once
