@@ -402,7 +402,10 @@ Geometry geometry_k4(int path, const Args& a)
         default: return of(StreamK4Rows96<BF16>{});
         }
     }
-    if (kind == MFMA_THIN_BROW) return Geometry{a.M <= 16 ? 16 : a.M <= 32 ? 32 : 64, 64, 32, 512, 2, 33280, ((a.N + 63) / 64) * a.batch};
+    if (kind == MFMA_THIN_BROW) {
+        const int cols = k4_thin_cols(a);
+        return Geometry{a.M <= 16 ? 16 : a.M <= 32 ? 32 : 64, cols, 2048 / cols, 512, 2, cols == 64 ? 33280 : 32768, ((a.N + cols - 1) / cols) * a.batch};
+    }
     if (kind == MFMA_VEC16_BROW) return Geometry{256, 256, ROW_BYTES / es, 256, 2, FastK4<BF16>::LDS_BYTES, K4_RING_WORKGROUPS};
     if (kind == MFMA_VEC16 || kind == MFMA_PACKED || kind == MFMA_SPLITK) {
         // (with a row remainder split off, the grid of the tiled part: the remainder is a second launch)

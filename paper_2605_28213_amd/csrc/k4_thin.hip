@@ -14,7 +14,7 @@ bool k4_brow_splits_m_tail(const Args& a)
 {
     const int64_t rem = a.M % 256;
     if (a.M <= 256 || rem < 1 || rem > 64 || a.N > 16384 || a.batch > 65535 || a.flags != 0) return false;
-    if ((a.K + 32) * a.b_sk * 2 >= ((int64_t)1 << 31)) return false;      // (the thin kernel's last k tile is addressed past K)
+    if ((a.K + 64) * a.b_sk * 2 >= ((int64_t)1 << 31)) return false;      // (the thin kernel's last k tile is addressed past K)
     const int64_t per_row = ((a.N + 255) / 256) * a.batch, rows = a.M / 256;
     if (rows * per_row < K4_RING_WORKGROUPS) return false;
     return (rows * per_row + 255) / 256 < ((rows + 1) * per_row + 255) / 256;
@@ -27,15 +27,21 @@ bool k4_thin_takes_row_major_b(const Args& a)
 {
     if (a.flags != 0 || (a.in_dtype != GEMM_BF16 && a.in_dtype != GEMM_F16)) return false;
     if (a.a_sk != 1 || a.b_sj != 1 || a.M < 1 || a.M > 64 || a.N < 1 || a.K < 1 || a.batch > 65535) return false;
-    if ((a.K + 32) * a.b_sk * 2 >= ((int64_t)1 << 31) || a.M * a.a_si * 2 >= ((int64_t)1 << 31)) return false;
+    if ((a.K + 64) * a.b_sk * 2 >= ((int64_t)1 << 31) || a.M * a.a_si * 2 >= ((int64_t)1 << 31)) return false;
     return tail_element_in_last_page(a.A, (a.batch - 1) * a.stride_a + (a.M - 1) * a.a_si + a.K, a.K, 2) &&
            tail_element_in_last_page(a.B, (a.batch - 1) * a.stride_b + (a.K - 1) * a.b_sk + a.N, a.N, 2);
 }
 
-template <typename IN, int MG>
+// Strips of 64 columns (128-byte pieces of B's rows).  The kernel also compiles for strips of 32 (twice the workgroups,
+// 64-byte pieces, k tiles of 64 rows); measured on fp16 3 / 33 / 64 x 4093 x 4097, where 64-column strips number 64:
+// 17.6 / 38 / 61 us against 18.2 / 43 / 65 us, and with the waits fixed for both (every prefetch issued) 18.2 / 41 / 67
+// against the same: not what bounds it, so the narrow form is not instantiated.
+int k4_thin_cols(const Args&) { return 64; }
+
+template <typename IN, int MG, int COLS>
 static hipError_t launch_thin_cfg(const Args& a)
 {
-    using CFG = ThinCfg<IN, MG>;
+    using CFG = ThinCfg<IN, MG, COLS>;
     dim3 grid((unsigned)((a.N + CFG::COLS - 1) / CFG::COLS), (unsigned)a.batch, 1), block(CFG::WAVES * 64, 1, 1);
     hipLaunchKernelGGL(k4_thin_brow<CFG>, grid, block, 0, a.stream, a);
     return hipGetLastError();
@@ -44,7 +50,7 @@ static hipError_t launch_thin_cfg(const Args& a)
 template <typename IN>
 static hipError_t launch_thin(const Args& a)
 {
-    return a.M <= 16 ? launch_thin_cfg<IN, 1>(a) : a.M <= 32 ? launch_thin_cfg<IN, 2>(a) : launch_thin_cfg<IN, 4>(a);
+    return a.M <= 16 ? launch_thin_cfg<IN, 1, 64>(a) : a.M <= 32 ? launch_thin_cfg<IN, 2, 64>(a) : launch_thin_cfg<IN, 4, 64>(a);
 }
 
 // a.M <= 64, A and B row-major, two-byte types, B below 2 GiB, a.batch <= 65535 (checked by the caller's rule)

@@ -1,16 +1,17 @@
 // K4, thin products with a ROW-MAJOR B: C (R x N, R <= 64) = A (R x K, row-major) . B (K x N, row-major), two-byte
 // types, nothing aligned, any K.  Bound by reading B once (the counterpart of k4_stream, which wants B column-major).
 //
-// A workgroup owns a strip of 64 columns of C; its 8 waves split K (wave w takes the 32-row k tiles w, w + 8, ...)
-// and add their partial sums in LDS at the end.  Per k tile a wave loads the strip's 32 rows x 128 bytes of B as it
-// lies in memory (four 16-byte loads per lane, under-aligned, through a buffer resource that ends with the matrix:
-// rows past K come back as zeros, columns past N are whatever follows and only feed outputs that are never stored),
-// parks it in a wave-private LDS tile and reads the fragments of v_mfma_f32_16x16x32 back with the transposing read
-// ds_read_b64_tr_b16 (see RingCfg in k4_ring.hpp for its lane layout: a block of 16 lanes turns a 4 k x 16 n patch
-// into 4 consecutive k per lane); chunk c of k row r is kept at c ^ (r & 7), so that the four rows a block reads lie
-// in different banks.  A's fragments (16 rows x 8 consecutive k per lane) come straight from memory: A is small and
-// stays in L2.  K ragged: A's elements past K are masked to zero in registers (B's are zeros already).  The loads of
-// the next one or two k tiles are in flight while a tile is multiplied (register sets taken in turn).
+// A workgroup owns a strip of 64 (or 32) columns of C; its 8 waves split K (wave w takes the k tiles w, w + 8, ...)
+// and add their partial sums in LDS at the end.  A k tile is 4 KB: 32 k rows x 128 bytes, or 64 x 64 on the narrow
+// strips.  Per tile a wave loads the strip's part of B as it lies in memory (four 16-byte loads per lane,
+// under-aligned, through a buffer resource that ends with the matrix: rows past K come back as zeros, columns past N
+// are whatever follows and only feed outputs that are never stored), parks it in a wave-private LDS tile and reads
+// the fragments of v_mfma_f32_16x16x32 back with the transposing read ds_read_b64_tr_b16 (see RingCfg in
+// k4_ring.hpp for its lane layout: a block of 16 lanes turns a 4 k x 16 n patch into 4 consecutive k per lane);
+// chunk c of k row r is kept at c ^ swz(r), so that what a block reads with one instruction lies in 16 different
+// 8-byte slots.  A's fragments (16 rows x 8 consecutive k per lane) come straight from memory: A is small and stays
+// in L2.  K ragged: A's elements past K are masked to zero in registers (B's are zeros already).  The loads of the
+// next one or two k tiles are in flight while a tile is multiplied (register sets taken in turn).
 //
 // Used for the thin remainder of rows that the persistent kernel's row-major-B form would otherwise multiply as
 // one more, mostly empty, row of tiles (fp16 4099 x 4093 x 4097: 215 -> 150 us), and for whole products of at most
@@ -21,23 +22,32 @@
 
 namespace gl {
 
-template <typename IN, int MG_>
+template <typename IN, int MG_, int COLS_ = 64>
 struct ThinCfg {
     using In = IN;
     static constexpr int MG = MG_, ROWS = 16 * MG_;      // groups of 16 rows of A (and C)
-    static constexpr int WAVES = 8, COLS = 64, TK = 32;  // waves per workgroup; columns per strip; k rows per tile
-    static constexpr int TILE_BYTES = TK * COLS * 2;     // 4 KB per wave
+    static constexpr int WAVES = 8, COLS = COLS_;        // waves per workgroup; columns per strip
+    static constexpr int RB = COLS_ * 2;                 // bytes of a k row of the strip
+    static constexpr int TK = 4096 / RB;                 // k rows per tile: a tile is 4 KB per wave (32 rows x 128 B or 64 x 64 B)
+    static constexpr int KS = TK / 32;                   // matrix-instruction k-steps per tile
+    static constexpr int TILE_BYTES = 4096;
+    static constexpr int SETS = MG_ <= 2 ? 3 : 2;        // k tiles held in registers per wave (one in hand, the rest landing)
     static constexpr int LDS_BYTES = WAVES * TILE_BYTES > WAVES * 16 * (COLS + 1) * 4 ? WAVES * TILE_BYTES : WAVES * 16 * (COLS + 1) * 4;
-    static constexpr int SETS = MG_ <= 2 ? 3 : 2;         // k tiles held in registers per wave (one in hand, the rest landing)
     static_assert(IN::BYTES == 2, "two-byte types (the transposing read used here is the 16-bit one)");
     static_assert(MG_ == 1 || MG_ == 2 || MG_ == 4, "16, 32 or 64 rows");
+    static_assert(COLS_ == 64 || COLS_ == 32, "strips of 64 or of 32 columns");
+    // chunk c (16 bytes) of k row r is parked at c ^ swz(r): the four rows a block of 16 lanes reads with one
+    // transposing instruction, and the two chunks of a 16-column patch, then fall into 16 different 8-byte slots
+    __device__ static constexpr int swz(int r) { return COLS_ == 64 ? (r & 7) : (r & 2); }
 };
 
 template <typename CFG>
 __global__ __launch_bounds__(CFG::WAVES * 64) void k4_thin_brow(Args a)
 {
     using IN = typename CFG::In;
-    constexpr int MG = CFG::MG, WAVES = CFG::WAVES, COLS = CFG::COLS, TK = CFG::TK;
+    constexpr int MG = CFG::MG, WAVES = CFG::WAVES, COLS = CFG::COLS, TK = CFG::TK, RB = CFG::RB, KS = CFG::KS;
+    constexpr int LPR = RB / 16, RPL = 64 / LPR;         // lanes per k row of a load; k rows per load instruction
+    constexpr int NJB = COLS / 16;                       // 16-column blocks of the strip
     __shared__ __attribute__((aligned(16))) char lds[CFG::LDS_BYTES];
     const int t = threadIdx.x, lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -54,17 +64,17 @@ __global__ __launch_bounds__(CFG::WAVES * 64) void k4_thin_brow(Args a)
     const __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc((void*)A, 0, (int)bytes_a, RSRC_FLAGS);
     const __amdgpu_buffer_rsrc_t rsrc_b = __builtin_amdgcn_make_buffer_rsrc((void*)B, 0, (int)bytes_b, RSRC_FLAGS);
 
-    // B loads: load n (0..3) of a lane covers k row 8 n + lane/8 of the tile, chunk lane%8 (8 columns)
-    const int brow = lane >> 3, bchunk = lane & 7;
+    // B loads: load n (0..3) of a lane covers k row RPL n + lane/LPR of the tile, chunk lane%LPR (8 columns)
+    const int brow = lane / LPR, bchunk = lane % LPR;
     const int voff_b = (int)((brow * a.b_sk + bchunk * 8) * 2);
-    const int step_b = (int)(8 * a.b_sk * 2);                              // bytes from load n to load n + 1
-    // parked at: row * 128 + ((chunk ^ (row & 7)) << 4); rows 8 n + lane/8: (row & 7) = lane/8 for every n
-    const int park = brow * 128 + ((bchunk ^ brow) << 4);
-    // fragment reads (per 16-column block jb and half h of the lane's 8 k): lane l of a block of 16 points at k row
-    // 8 (l/16) + 4 h + (l%16)/4 and columns 16 jb + 4 (l%4) .. +3
+    const int step_b = (int)(RPL * a.b_sk * 2);                            // bytes from load n to load n + 1
+    // parked at: row * RB + ((chunk ^ swz(row)) << 4); rows RPL n + lane/LPR: swz(row) = swz(lane/LPR) for every n
+    const int park = brow * RB + ((bchunk ^ CFG::swz(brow)) << 4);
+    // fragment reads (per k-step ks, 16-column block jb and half h of the lane's 8 k): lane l of a block of 16 points
+    // at k row 32 ks + 8 (l/16) + 4 h + (l%16)/4 and columns 16 jb + 4 (l%4) .. +3
     const int l16 = lane & 15, kq = lane >> 4;
     const int fr_row = 8 * kq + (l16 >> 2), fr_col = 4 * (l16 & 3);
-    // A fragments: lane holds row l16 of a group, k 8 kq .. 8 kq + 7 of the tile
+    // A fragments: lane holds row l16 of a group, k 8 kq .. 8 kq + 7 of a k-step
     int voff_a[MG];
 #pragma unroll
     for (int m = 0; m < MG; ++m) {
@@ -74,83 +84,96 @@ __global__ __launch_bounds__(CFG::WAVES * 64) void k4_thin_brow(Args a)
 
     typedef short v4s_t __attribute__((ext_vector_type(4)));
     typedef __attribute__((address_space(3))) v4s_t* tr_ptr;
-    f32x4_t acc[MG][4];
+    f32x4_t acc[MG][NJB];
 #pragma unroll
     for (int m = 0; m < MG; ++m)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[m][j] = f32x4_t{0, 0, 0, 0};
+        for (int j = 0; j < NJB; ++j) acc[m][j] = f32x4_t{0, 0, 0, 0};
 
     const int64_t tiles = (a.K + TK - 1) / TK;
-    // One k tile in registers: 4 loads of B (k rows 8 n + lane/8), one load of A per row group.
-    struct Held { u32x4_t b[4]; u32x4_t a[MG]; };
+    // One k tile in registers: 4 loads of B, one load of A per row group and k-step.
+    struct Held { u32x4_t b[4]; u32x4_t a[KS][MG]; };
     auto fetch = [&](Held& h, int64_t kt) __attribute__((always_inline)) {
-        const int k0 = (int)(kt * TK);
+        // (the tile number is the same in every lane; said once more, or each load is wrapped in a loop over the
+        // lanes' "different" scalar offsets and the waits around it turn conservative)
+        const int k0 = __builtin_amdgcn_readfirstlane((int)(kt * TK));
+        const int so_b = __builtin_amdgcn_readfirstlane((int)(k0 * a.b_sk * 2));
 #pragma unroll
         for (int n = 0; n < 4; ++n)
-            h.b[n] = __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc_b, voff_b + n * step_b, (int)(k0 * a.b_sk * 2), 0));
+            h.b[n] = __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc_b, voff_b + n * step_b, so_b, 0));
 #pragma unroll
-        for (int m = 0; m < MG; ++m) h.a[m] = __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc_a, voff_a[m], k0 * 2, 0));
-    };
-    auto multiply = [&](Held& h, int64_t kt) __attribute__((always_inline)) {
-        // A's elements beyond K are the next row's first ones (or the slack element): zero them
-        const int valid = (int)(a.K - kt * TK) - 8 * kq;                   // this lane's k that lie inside K
-        if (valid < 8) {
+        for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
             for (int m = 0; m < MG; ++m)
+                h.a[ks][m] = __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc_a, voff_a[m], (k0 + 32 * ks) * 2, 0));
+    };
+    auto multiply = [&](Held& h, int64_t kt) __attribute__((always_inline)) {
 #pragma unroll
-                for (int d = 0; d < 4; ++d) {
-                    const int left = valid - 2 * d;
-                    h.a[m][d] = left <= 0 ? 0u : left == 1 ? (h.a[m][d] & 0xFFFFu) : h.a[m][d];
-                }
-        }
+        for (int n = 0; n < 4; ++n) *(u32x4_t*)(tile + n * RPL * RB + park) = h.b[n];
 #pragma unroll
-        for (int n = 0; n < 4; ++n) *(u32x4_t*)(tile + n * 8 * 128 + park) = h.b[n];
+        for (int ks = 0; ks < KS; ++ks) {
+            // A's elements beyond K are the next row's first ones (or the slack element): zero them
+            const int valid = (int)(a.K - kt * TK) - 32 * ks - 8 * kq;     // this lane's k that lie inside K
+            if (valid < 8) {
 #pragma unroll
-        for (int jb = 0; jb < 4; ++jb) {
-            u32x4_t fb;
+                for (int m = 0; m < MG; ++m)
 #pragma unroll
-            for (int hh = 0; hh < 2; ++hh) {
-                const int row = fr_row + 4 * hh, chunk = (16 * jb + fr_col) >> 3;
-                const int off = row * 128 + ((chunk ^ (row & 7)) << 4) + ((fr_col >> 2) & 1) * 8;
-                const v4s_t v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((tr_ptr)(tile + off));
-                const uint32_t lo = (uint32_t)(uint16_t)v[0] | ((uint32_t)(uint16_t)v[1] << 16);
-                const uint32_t hi = (uint32_t)(uint16_t)v[2] | ((uint32_t)(uint16_t)v[3] << 16);
-                if (hh == 0) { fb.x = lo; fb.y = hi; } else { fb.z = lo; fb.w = hi; }
+                    for (int d = 0; d < 4; ++d) {
+                        const int left = valid - 2 * d;
+                        h.a[ks][m][d] = left <= 0 ? 0u : left == 1 ? (h.a[ks][m][d] & 0xFFFFu) : h.a[ks][m][d];
+                    }
             }
 #pragma unroll
-            for (int m = 0; m < MG; ++m) mfma16<IN>(h.a[m], fb, acc[m][jb]);
+            for (int jb = 0; jb < NJB; ++jb) {
+                u32x4_t fb;
+#pragma unroll
+                for (int hh = 0; hh < 2; ++hh) {
+                    const int row = 32 * ks + fr_row + 4 * hh, chunk = (16 * jb + fr_col) >> 3;
+                    const int off = row * RB + ((chunk ^ CFG::swz(row)) << 4) + ((fr_col >> 2) & 1) * 8;
+                    const v4s_t v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((tr_ptr)(tile + off));
+                    const uint32_t lo = (uint32_t)(uint16_t)v[0] | ((uint32_t)(uint16_t)v[1] << 16);
+                    const uint32_t hi = (uint32_t)(uint16_t)v[2] | ((uint32_t)(uint16_t)v[3] << 16);
+                    if (hh == 0) { fb.x = lo; fb.y = hi; } else { fb.z = lo; fb.w = hi; }
+                }
+#pragma unroll
+                for (int m = 0; m < MG; ++m) mfma16<IN>(h.a[ks][m], fb, acc[m][jb]);
+            }
         }
     };
-    // Wave w takes k tiles w, w + WAVES, ...  Up to 32 rows, two tiles' loads are in flight while a third is
-    // multiplied (three register sets taken in turn: 8 KB of B per wave on its way beside the tile in hand); with
-    // 64 rows the accumulators leave room for two sets.
+    // Wave w takes k tiles w, w + WAVES, ...  Two tiles' loads are in flight while a third is multiplied (three
+    // register sets taken in turn: 8 KB of B per wave on its way beside the tile in hand); with 64 rows the
+    // accumulators and A's fragments leave room for two sets.  Every prefetch is issued, also past the last tile
+    // (clamped to tile number `tiles`, whose rows all lie past K: the range check answers those loads with zeros
+    // without touching memory): were a prefetch conditional, the compiler's wait before each use would have to
+    // allow for the path on which it was skipped, i.e. wait for the youngest loads too, and nothing would overlap.
+    auto ahead = [&](int64_t k) __attribute__((always_inline)) { return k < tiles ? k : tiles; };
     int64_t kt = wave;
     if constexpr (CFG::SETS == 3) {
         Held h0, h1, h2;
-        if (kt < tiles) fetch(h0, kt);
-        if (kt + WAVES < tiles) fetch(h1, kt + WAVES);
+        fetch(h0, ahead(kt));
+        fetch(h1, ahead(kt + WAVES));
         while (kt < tiles) {
-            if (kt + 2 * WAVES < tiles) fetch(h2, kt + 2 * WAVES);
+            fetch(h2, ahead(kt + 2 * WAVES));
             multiply(h0, kt);
             kt += WAVES;
             if (kt >= tiles) break;
-            if (kt + 2 * WAVES < tiles) fetch(h0, kt + 2 * WAVES);
+            fetch(h0, ahead(kt + 2 * WAVES));
             multiply(h1, kt);
             kt += WAVES;
             if (kt >= tiles) break;
-            if (kt + 2 * WAVES < tiles) fetch(h1, kt + 2 * WAVES);
+            fetch(h1, ahead(kt + 2 * WAVES));
             multiply(h2, kt);
             kt += WAVES;
         }
     } else {
         Held h0, h1;
-        if (kt < tiles) fetch(h0, kt);
+        fetch(h0, ahead(kt));
         while (kt < tiles) {
-            if (kt + WAVES < tiles) fetch(h1, kt + WAVES);
+            fetch(h1, ahead(kt + WAVES));
             multiply(h0, kt);
             kt += WAVES;
             if (kt >= tiles) break;
-            if (kt + WAVES < tiles) fetch(h0, kt + WAVES);
+            fetch(h0, ahead(kt + WAVES));
             multiply(h1, kt);
             kt += WAVES;
         }
@@ -164,7 +187,7 @@ __global__ __launch_bounds__(CFG::WAVES * 64) void k4_thin_brow(Args a)
     for (int m = 0; m < MG; ++m) {
         __syncthreads();
 #pragma unroll
-        for (int jb = 0; jb < 4; ++jb)
+        for (int jb = 0; jb < NJB; ++jb)
 #pragma unroll
             for (int r = 0; r < 4; ++r) part[(wave * 16 + 4 * kq + r) * (COLS + 1) + jb * 16 + l16] = acc[m][jb][r];
         __syncthreads();

@@ -186,6 +186,10 @@ THIN_CASES = [  # (M, N, K, batch, lda - K, ldb - N, biased)
     (33, 257, 1031, 1, 0, 0, True),            # four row groups (two sets of registers), one-column last strip
     (64, 2048, 1024, 1, 0, 0, False),          # everything whole and aligned
     (64, 777, 95, 2, 5, 1, False),             # fewer k tiles than waves x sets
+    # many strips
+    (5, 8200, 100, 1, 0, 0, False),
+    (20, 4100, 203, 2, 1, 1, True),            # two row groups, batched
+    (40, 1030, 300, 8, 0, 3, False),           # four row groups (two sets of registers)
 ]
 
 
@@ -198,7 +202,8 @@ def test_thin_kernel_reads_a_row_major_b_in_place(dtype, case):
     M, N, K, nb, pa, pb, biased = case
     inp = int_inputs(dtype, M, N, K, ROW, ROW, batch=nb, lda=K + pa, ldb=N + pb, seed=K + M, biased=biased)
     q = run_exact(inp, "mfma16-thin(B-row-major)")
-    assert q.violated == 0 and q.workspace_bytes == 0 and q.grid == -(-N // 64) * nb
+    cols = 64
+    assert q.violated == 0 and q.workspace_bytes == 0 and q.grid == -(-N // cols) * nb and q.bn == cols
     C_ref, _ = oracle_for(inp)
     rc, _, raw = util.run_config(K4, inp, out_dtype=dtype)
     assert rc == gemm.GEMM_OK

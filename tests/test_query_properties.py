@@ -109,7 +109,7 @@ def test_expert_state_paths_and_scratch(p):
         # a thin remainder of rows that would cost a round of tiles goes to the thin kernel (which also reads B in place)
         per_row, rows = math.ceil(p["N"] / 256) * p["batch"], p["M"] // 256
         thin_tail = (p["M"] > 256 and 1 <= p["M"] % 256 <= 64 and p["N"] <= 16384 and rows * per_row >= 256
-                     and (p["K"] + 32) * p["ldb"] * 2 < 1 << 31
+                     and (p["K"] + 64) * p["ldb"] * 2 < 1 << 31
                      and math.ceil(rows * per_row / 256) < math.ceil((rows + 1) * per_row / 256))
         assert q.path == "mfma32-direct-to-lds(persistent,B-row-major)" + ("+thin(M-tail)" if thin_tail else "")
         assert q.violated == 0 and q.grid == 256
@@ -117,10 +117,11 @@ def test_expert_state_paths_and_scratch(p):
         lent = gemm.gemm_query(gemm.GEMM_K4_MFMA, make(p, workspace=4096, workspace_bytes=1 << 30))
         assert lent.status == gemm.GEMM_OK and lent.path == q.path
     elif (p["dt"] in (gemm.GEMM_BF16, gemm.GEMM_F16) and p["la"] == gemm.GEMM_ROW_MAJOR and p["lb"] == gemm.GEMM_ROW_MAJOR
-          and p["M"] <= 64 and (p["K"] + 32) * p["ldb"] * 2 < 1 << 31 and p["M"] * p["lda"] * 2 < 1 << 31):
+          and p["M"] <= 64 and (p["K"] + 64) * p["ldb"] * 2 < 1 << 31 and p["M"] * p["lda"] * 2 < 1 << 31):
         # at most 64 rows, both operands row-major: the thin kernel reads B once, in place; no scratch, lent or not
         assert q.path == "mfma16-thin(B-row-major)" and q.violated == 0 and q.workspace_bytes == 0
-        assert q.grid == math.ceil(p["N"] / 64) * p["batch"] and q.bn == 64 and q.bm >= min(p["M"], 64) and q.threads == 512
+        cols = 64
+        assert q.grid == math.ceil(p["N"] / cols) * p["batch"] and q.bn == cols and q.bm >= min(p["M"], 64) and q.threads == 512
         lent = gemm.gemm_query(gemm.GEMM_K4_MFMA, make(p, workspace=4096, workspace_bytes=1 << 30))
         assert lent.path == q.path
     else:
