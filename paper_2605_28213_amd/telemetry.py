@@ -132,18 +132,25 @@ def main() -> None:
     wgs, iters = 1024, 400
     need = gemm.gemm_probe_mfma_operand_bytes(gemm.GEMM_BF16, wgs)
     sink = torch.zeros(wgs * 256, dtype=torch.float32, device="cuda")
-    zeros = torch.zeros(need, dtype=torch.uint8, device="cuda")
     k = [0]
     flops = [0.0]
 
-    def gemm_launch():
-        A, B, C = sets[k[0] % 3]
-        k[0] += 1
-        assert gemm.gemm_run_ex(gemm.GEMM_K4_MFMA, d, A, B, C) == gemm.GEMM_OK
+    d32 = gemm.make_desc(cfg.M, cfg.N, cfg.K, cfg.in_dtype, cfg.out_dtype, cfg.layout_a, cfg.layout_b, stream=stream,
+                         flags=gemm.GEMM_FLAG_MFMA_32X32)
 
-    def probe(src):
+    def gemm_launch_with(desc):
         def f():
-            rc, fl = gemm.gemm_probe_mfma(gemm.GEMM_BF16, src, need, wgs, iters, sink, sink.numel() * 4, stream)
+            A, B, C = sets[k[0] % 3]
+            k[0] += 1
+            assert gemm.gemm_run_ex(gemm.GEMM_K4_MFMA, desc, A, B, C) == gemm.GEMM_OK
+        return f
+
+    def probe(src, shape16=False):
+        def f():
+            if shape16:     # the 16x16x32 loop: twice the operand bytes per lane, the same flops in half the iterations
+                rc, fl = gemm.gemm_probe_mfma16(gemm.GEMM_BF16, src, 2 * need, wgs, iters // 2, sink, sink.numel() * 4, stream)
+            else:
+                rc, fl = gemm.gemm_probe_mfma(gemm.GEMM_BF16, src, need, wgs, iters, sink, sink.numel() * 4, stream)
             assert rc == gemm.GEMM_OK
             flops[0] = fl
         return f
@@ -153,9 +160,13 @@ def main() -> None:
     print(f"power cap {cap} W; idle: {idle[0]} W, {idle[1]} MHz")
     print("| what | launches | us per launch | TFLOP/s | of 2500 | socket W (mean / max after 1 s) | sclk MHz (mean, min-max after 1 s) |")
     print("|---|---|---|---|---|---|---|")
-    for name, fn, fl in (("K4 on the headline workload, 3 operand sets", gemm_launch, cfg.flops),
-                         ("matrix-instruction probe on the headline operands' values", probe(sets[0][0]), None),
-                         ("matrix-instruction probe on zeros", probe(zeros), None)):
+    zeros = torch.zeros(2 * need, dtype=torch.uint8, device="cuda")
+    for name, fn, fl in (("K4 on the headline workload (16x16x32 instruction), 3 operand sets", gemm_launch_with(d), cfg.flops),
+                         ("the same with the 32x32x16 instruction (GEMM_FLAG_MFMA_32X32)", gemm_launch_with(d32), cfg.flops),
+                         ("16x16x32 probe on the headline operands' values", probe(sets[0][0], True), None),
+                         ("32x32x16 probe on the headline operands' values", probe(sets[0][0]), None),
+                         ("16x16x32 probe on zeros", probe(zeros, True), None),
+                         ("32x32x16 probe on zeros", probe(zeros), None)):
         torch.cuda.synchronize()
         time.sleep(2.0)
         n, wall, samples = run_for(args.seconds, fn, stream.synchronize)
