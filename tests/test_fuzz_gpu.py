@@ -243,3 +243,76 @@ def test_random_selection(i):
         assert rc == gemm.GEMM_OK, (TOPK_CASES[i], variant, topk.topk_last_launch_error())
         np.testing.assert_array_equal(idx, ridx)
         np.testing.assert_array_equal(val.view(np.uint32), rval.view(np.uint32))
+
+
+def draw_thin_case(rng, i):
+    """At most 64 rows with both operands row-major (two-byte types): the thin kernel, as a product of its own or,
+    for the second half of the family, as the remainder of a product the persistent kernel reads in place."""
+    dtype = int(rng.choice([gen.BF16, gen.F16]))
+    rows = int(rng.integers(1, 65))
+    if i % 2 == 0:
+        M, N, K, batch = rows, int(rng.integers(1, 3000)), int(rng.integers(1, 2500)), int(rng.choice([1, 1, 2, 5]))
+    else:       # whole rounds of 256-tiles plus a thin remainder that would cost one more
+        tn = int(rng.integers(1, 5))
+        batch = 256 // tn // 2 + int(rng.integers(0, 2))
+        M, N, K = 512 + rows, 256 * (tn - 1) + int(rng.integers(97, 257)), int(rng.integers(130, 400))
+    out = int(rng.choice([dtype, gen.F32]))
+    return gen.Config(f"thin{i}", M, N, K, dtype, out, ROW, ROW, str(rng.choice(["uniform", "normal"])), batch=batch,
+                      scaled=bool(rng.random() < 0.3), biased=bool(rng.random() < 0.3), lda=K + int(rng.integers(0, 4)),
+                      ldb=N + int(rng.integers(0, 4)), ldc=N + int(rng.integers(0, 3)))
+
+
+THIN_CASES = [draw_thin_case(np.random.default_rng(4000 + i), i) for i in range(24)]
+
+
+@pytest.mark.parametrize("i", range(len(THIN_CASES)))
+def test_random_case_for_the_thin_kernel(i):
+    cfg = THIN_CASES[i]
+    inp = gen.make_inputs(cfg, 400 + i)
+    C_ref, D = oracle_for(inp)
+    q = gemm.gemm_query(4, gemm.make_desc(cfg.M, cfg.N, cfg.K, cfg.in_dtype, cfg.out_dtype, ROW, ROW, lda=inp.lda, ldb=inp.ldb,
+                                          ldc=inp.ldc, batch=cfg.batch, stride_a=inp.stride_a, stride_b=inp.stride_b, stride_c=inp.stride_c))
+    if i % 2 == 0:
+        assert q.path == "mfma16-thin(B-row-major)", (cfg, q.path)
+    else:       # (the remainder is split off only where it saves a round of tiles; either way B is read in place)
+        assert q.path.startswith("mfma32-direct-to-lds(persistent,B-row-major)"), (cfg, q.path)
+    rc, C, _ = util.run_config(4, inp)
+    assert rc == gemm.GEMM_OK, (cfg, gemm.gemm_status_string(rc), gemm.gemm_last_launch_error())
+    err = util.norm_err(C[:, :, : cfg.N], C_ref, D)
+    assert err <= util.TOL[cfg.in_dtype], (cfg, err)
+
+
+def draw_pipelined_case(rng, i):
+    """K3 on operands its asynchronous form takes (K contiguous in both, rows 16-byte aligned, K whole 64-byte slabs):
+    every input type, both tile sizes, ragged M and N, padded leading dimensions, batch, scales, bias."""
+    dtype = int(rng.choice([gen.F32, gen.BF16, gen.F16, gen.E4M3]))
+    es = gen.ELEM_BYTES[dtype]
+    K = 64 // es * int(rng.integers(1, 14))
+    big = bool(rng.random() < 0.4)          # at least 256 tiles of 128 x 128: the large-tile form
+    if big:
+        M, N, batch = int(rng.integers(1500, 2300)), int(rng.integers(1900, 2300)), 1
+    else:
+        M, N, batch = int(rng.integers(1, 500)), int(rng.integers(1, 500)), int(rng.choice([1, 2, 3]))
+    ld = K + 16 // es * int(rng.integers(0, 3))
+    out = int(rng.choice({gen.F32: [gen.F32], gen.BF16: [gen.BF16, gen.F32], gen.F16: [gen.F16, gen.F32], gen.E4M3: [gen.BF16, gen.F32]}[dtype]))
+    return gen.Config(f"pipe{i}", M, N, K, dtype, out, ROW, COL, str(rng.choice(["uniform", "normal"])), batch=batch,
+                      scaled=bool(rng.random() < 0.3), biased=bool(rng.random() < 0.3), lda=ld, ldb=ld, ldc=N + int(rng.integers(0, 3)))
+
+
+PIPE_CASES = [draw_pipelined_case(np.random.default_rng(5000 + i), i) for i in range(24)]
+
+
+@pytest.mark.parametrize("i", range(len(PIPE_CASES)))
+def test_random_case_for_the_pipelined_state(i):
+    cfg = PIPE_CASES[i]
+    inp = gen.make_inputs(cfg, 500 + i)
+    C_ref, D = oracle_for(inp)
+    q = gemm.gemm_query(3, gemm.make_desc(cfg.M, cfg.N, cfg.K, cfg.in_dtype, cfg.out_dtype, ROW, COL, lda=inp.lda, ldb=inp.ldb,
+                                          ldc=inp.ldc, batch=cfg.batch, stride_a=inp.stride_a, stride_b=inp.stride_b, stride_c=inp.stride_c))
+    # (a batch stride that is not a multiple of 16 bytes breaks the alignment condition: then the register-staged form runs)
+    aligned = cfg.batch == 1 or ((cfg.M * inp.lda * gen.ELEM_BYTES[cfg.in_dtype]) % 16 == 0 and (cfg.N * inp.ldb * gen.ELEM_BYTES[cfg.in_dtype]) % 16 == 0)
+    assert (q.path == "vec16-direct-to-lds(3 stages)") == aligned, (cfg, q.path)
+    rc, C, _ = util.run_config(3, inp)
+    assert rc == gemm.GEMM_OK, (cfg, gemm.gemm_status_string(rc), gemm.gemm_last_launch_error())
+    err = util.norm_err(C[:, :, : cfg.N], C_ref, D)
+    assert err <= util.TOL[cfg.in_dtype], (cfg, err)
