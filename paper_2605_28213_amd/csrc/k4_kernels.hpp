@@ -411,7 +411,7 @@ __device__ __forceinline__ void for_each_step(std::integer_sequence<int, KS...>,
 // MI16: the matrix instruction is v_mfma_f32_16x16x32 (two-byte types) instead of 32x32x16: the wave's 128 x 128
 // quarter is 8 x 8 accumulator tiles of 16 x 16, a k-step is 64 bytes of K.  Same flops per cycle, same LDS bytes per
 // flop, half the accumulator traffic per flop: under the package power limit the chip holds a higher clock with
-// it (register-resident loops on N(0,1)/sqrt(K) operands: 1857 against 1739 TFLOP/s).
+// it (register-resident loops on N(0,1)/sqrt(K) operands: 2017 against 1743 TFLOP/s).
 template <typename IN, int TILE_ = 256, int GROUP_M_ = 8, bool SWIZZLE_ = true, bool OVERLAP_ = true, int PRE_ = 0, bool CONV_ = false,
           bool MI16_ = false>
 struct FastCfg {

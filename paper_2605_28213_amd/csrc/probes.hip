@@ -114,9 +114,19 @@ void probe_mfma16(const char* __restrict__ operands, int iters, float* sink)
 #pragma unroll
                 for (int jj = 0; jj < 8; ++jj) {
                     const int j = (i & 1) ? 7 - jj : jj;
-                    mfma_step16<IN>(fb[s][j], fa[s][i], acc[i][j]);
+                    // From inline assembly, with the accumulator tile tied to its registers: through the builtin the
+                    // compiler shuffled 80 of the 256 accumulator registers between the register files per 128
+                    // instructions at the loop's back edge, and the loop then measured those moves (2100 instead of
+                    // 2400 TFLOP/s on zeros).  The loop holds nothing but matrix instructions, which interlock.
+                    if constexpr (IN::ID == GEMM_BF16)
+                        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(fb[s][j]), "v"(fa[s][i]));
+                    else
+                        asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(fb[s][j]), "v"(fa[s][i]));
                 }
     }
+    // (the compiler does not know that the statements above are matrix instructions: the wait states their results
+    // need before a vector instruction may read them, placed by hand)
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
     float s = 0.0f;
 #pragma unroll
     for (int i = 0; i < 8; ++i)
