@@ -33,24 +33,37 @@ bool k4_thin_takes_row_major_b(const Args& a)
 }
 
 // Strips of 64 columns (128-byte pieces of B's rows).  The kernel also compiles for strips of 32 (twice the workgroups,
-// 64-byte pieces, k tiles of 64 rows); measured on fp16 3 / 33 / 64 x 4093 x 4097, where 64-column strips number 64:
-// 17.6 / 38 / 61 us against 18.2 / 43 / 65 us, and with the waits fixed for both (every prefetch issued) 18.2 / 41 / 67
-// against the same: not what bounds it, so the narrow form is not instantiated.
+// 64-byte pieces, k tiles of 64 rows); measured on fp16 3 / 33 / 64 x 4093 x 4097, where 64-column strips number 64,
+// before A's odd rows were loaded as aligned dwords: 17.6 / 38 / 61 us against 18.2 / 43 / 65 us, and with the waits
+// fixed for both (every prefetch issued) 18.2 / 41 / 67 against the same: not what bounds it, so the narrow form is
+// not instantiated.
 int k4_thin_cols(const Args&) { return 64; }
 
-template <typename IN, int MG, int COLS>
+template <typename IN, int MG, int COLS, bool ODD>
 static hipError_t launch_thin_cfg(const Args& a)
 {
-    using CFG = ThinCfg<IN, MG, COLS>;
+    using CFG = ThinCfg<IN, MG, COLS, ODD>;
     dim3 grid((unsigned)((a.N + CFG::COLS - 1) / CFG::COLS), (unsigned)a.batch, 1), block(CFG::WAVES * 64, 1, 1);
     hipLaunchKernelGGL(k4_thin_brow<CFG>, grid, block, 0, a.stream, a);
     return hipGetLastError();
 }
 
+template <typename IN, bool ODD>
+static hipError_t launch_thin_rows(const Args& a)
+{
+    return a.M <= 16 ? launch_thin_cfg<IN, 1, 64, ODD>(a) : a.M <= 32 ? launch_thin_cfg<IN, 2, 64, ODD>(a) : launch_thin_cfg<IN, 4, 64, ODD>(a);
+}
+
+// Does any row of A (of any batch item) start 2 bytes off a dword?
+static bool k4_thin_rows_off_dword(const Args& a)
+{
+    return ((uintptr_t)a.A & 2) || (a.M > 1 && (a.a_si & 1)) || (a.batch > 1 && (a.stride_a & 1));
+}
+
 template <typename IN>
 static hipError_t launch_thin(const Args& a)
 {
-    return a.M <= 16 ? launch_thin_cfg<IN, 1, 64>(a) : a.M <= 32 ? launch_thin_cfg<IN, 2, 64>(a) : launch_thin_cfg<IN, 4, 64>(a);
+    return k4_thin_rows_off_dword(a) ? launch_thin_rows<IN, true>(a) : launch_thin_rows<IN, false>(a);
 }
 
 // a.M <= 64, A and B row-major, two-byte types, B below 2 GiB, a.batch <= 65535 (checked by the caller's rule)

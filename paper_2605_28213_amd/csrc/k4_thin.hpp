@@ -10,21 +10,28 @@
 // k4_ring.hpp for its lane layout: a block of 16 lanes turns a 4 k x 16 n patch into 4 consecutive k per lane);
 // chunk c of k row r is kept at c ^ swz(r), so that what a block reads with one instruction lies in 16 different
 // 8-byte slots.  A's fragments (16 rows x 8 consecutive k per lane) come straight from memory: A is small and stays
-// in L2.  K ragged: A's elements past K are masked to zero in registers (B's are zeros already).  The loads of the
+// in L2 (rows of A that start 2 bytes off a dword: see ThinCfg::ODD).  K ragged: A's elements past K are masked to zero in registers (B's are zeros already).  The loads of the
 // next one or two k tiles are in flight while a tile is multiplied (register sets taken in turn).
 //
 // Used for the thin remainder of rows that the persistent kernel's row-major-B form would otherwise multiply as
 // one more, mostly empty, row of tiles (fp16 4099 x 4093 x 4097: 215 -> 150 us), and for whole products of at most
-// 64 rows with both operands row-major (3 / 33 / 64 rows x 4093 x 4097: 18 / 43 / 65 us; 64 workgroups).
+// 64 rows with both operands row-major (3 / 33 / 64 rows x 4093 x 4097: 18 / 29 / 40 us; 64 workgroups).
 // Paper Table 1: "smem_transpose" on the small side of the lineage's expert state.
 #pragma once
 #include "k4_kernels.hpp"
 
 namespace gl {
 
-template <typename IN, int MG_, int COLS_ = 64>
+template <typename IN, int MG_, int COLS_ = 64, bool ODD_ = false>
 struct ThinCfg {
     using In = IN;
+    // ODD: some row of A starts on an odd element, i.e. 2 bytes off a dword.  A's fragment loads (16 bytes per lane,
+    // 16 rows per instruction) are served at a fraction of the aligned rate from such addresses (64 rows x 4096 x 4096
+    // fp16: 26 us with leading dimensions of 4096, 31 with 4098, 67 with 4097, 62 with A's alone 4097), so this
+    // form loads the five aligned dwords that hold a lane's 16 bytes and shifts them into place in registers (41 us).
+    // B's loads (a row's 128 bytes over 8 consecutive lanes) lose little off a dword (3 rows: 16.9 against 16.2 us)
+    // and a fifth dword per load costs them more than that (21 us), so they stay as they are.
+    static constexpr bool ODD = ODD_;
     static constexpr int MG = MG_, ROWS = 16 * MG_;      // groups of 16 rows of A (and C)
     static constexpr int WAVES = 8, COLS = COLS_;        // waves per workgroup; columns per strip
     static constexpr int RB = COLS_ * 2;                 // bytes of a k row of the strip
@@ -56,9 +63,12 @@ __global__ __launch_bounds__(CFG::WAVES * 64) void k4_thin_brow(Args a)
     char* tile = lds + wave * CFG::TILE_BYTES;
 
     // buffer resources over this batch item's A and this strip's part of B (both below 2 GiB: checked by the host)
+    // (ODD: A's resource starts at the dword that holds its first element, and a lane's offset carries the two bytes)
     const char* A = (const char*)a.A + b * a.stride_a * 2;
     const char* B = (const char*)a.B + (b * a.stride_b + j0) * 2;
-    const int64_t bytes_a = ((a.M - 1) * a.a_si + a.K) * 2 + 2;          // (+ one element: the dword that holds an odd row's last one)
+    const int rem_a = CFG::ODD ? (int)((uintptr_t)A & 2) : 0;
+    A -= rem_a;
+    const int64_t bytes_a = ((a.M - 1) * a.a_si + a.K) * 2 + 2 + rem_a;  // (+ one element: the dword that holds an odd row's last one)
     const int64_t bytes_b = ((a.K - 1) * a.b_sk + (a.N - j0)) * 2 + 2;
     constexpr int RSRC_FLAGS = 0x00020000;
     const __amdgpu_buffer_rsrc_t rsrc_a = __builtin_amdgcn_make_buffer_rsrc((void*)A, 0, (int)bytes_a, RSRC_FLAGS);
@@ -75,11 +85,15 @@ __global__ __launch_bounds__(CFG::WAVES * 64) void k4_thin_brow(Args a)
     const int l16 = lane & 15, kq = lane >> 4;
     const int fr_row = 8 * kq + (l16 >> 2), fr_col = 4 * (l16 & 3);
     // A fragments: lane holds row l16 of a group, k 8 kq .. 8 kq + 7 of a k-step
-    int voff_a[MG];
+    int voff_a[MG], sh_a[MG];
 #pragma unroll
     for (int m = 0; m < MG; ++m) {
         const int64_t r = m * 16 + l16 < a.M ? m * 16 + l16 : a.M - 1;      // (rows past M: clamped, never stored)
-        voff_a[m] = (int)((r * a.a_si + 8 * kq) * 2);
+        // (ODD: the lane's byte offset is rounded down to a dword and sh_a = 0 or 16 bits are shifted out after the
+        // load; k tiles are whole dwords apart, so the shift is the same for every load of a lane)
+        const int byte_a = (int)((r * a.a_si + 8 * kq) * 2) + rem_a;
+        voff_a[m] = CFG::ODD ? byte_a & ~3 : byte_a;
+        sh_a[m] = (byte_a & 2) * 8;
     }
 
     typedef short v4s_t __attribute__((ext_vector_type(4)));
@@ -91,8 +105,12 @@ __global__ __launch_bounds__(CFG::WAVES * 64) void k4_thin_brow(Args a)
         for (int j = 0; j < NJB; ++j) acc[m][j] = f32x4_t{0, 0, 0, 0};
 
     const int64_t tiles = (a.K + TK - 1) / TK;
-    // One k tile in registers: 4 loads of B, one load of A per row group and k-step.
-    struct Held { u32x4_t b[4]; u32x4_t a[KS][MG]; };
+    // One k tile in registers: 4 loads of B, one load of A per row group and k-step (ODD: and the dword after it).
+    struct Held { u32x4_t b[4]; u32x4_t a[KS][MG]; uint32_t ax[KS][MG]; };
+    auto shifted = [](const u32x4_t v, uint32_t x, int sh) __attribute__((always_inline)) {
+        return u32x4_t{__builtin_amdgcn_alignbit(v.y, v.x, sh), __builtin_amdgcn_alignbit(v.z, v.y, sh),
+                       __builtin_amdgcn_alignbit(v.w, v.z, sh), __builtin_amdgcn_alignbit(x, v.w, sh)};
+    };
     auto fetch = [&](Held& h, int64_t kt) __attribute__((always_inline)) {
         // (the tile number is the same in every lane; said once more, or each load is wrapped in a loop over the
         // lanes' "different" scalar offsets and the waits around it turn conservative)
@@ -106,12 +124,22 @@ __global__ __launch_bounds__(CFG::WAVES * 64) void k4_thin_brow(Args a)
 #pragma unroll
             for (int m = 0; m < MG; ++m)
                 h.a[ks][m] = __builtin_bit_cast(u32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc_a, voff_a[m], (k0 + 32 * ks) * 2, 0));
+        if constexpr (CFG::ODD) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                for (int m = 0; m < MG; ++m) h.ax[ks][m] = __builtin_amdgcn_raw_buffer_load_b32(rsrc_a, voff_a[m] + 16, (k0 + 32 * ks) * 2, 0);
+        }
     };
     auto multiply = [&](Held& h, int64_t kt) __attribute__((always_inline)) {
 #pragma unroll
         for (int n = 0; n < 4; ++n) *(u32x4_t*)(tile + n * RPL * RB + park) = h.b[n];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
+            if constexpr (CFG::ODD) {
+#pragma unroll
+                for (int m = 0; m < MG; ++m) h.a[ks][m] = shifted(h.a[ks][m], h.ax[ks][m], sh_a[m]);
+            }
             // A's elements beyond K are the next row's first ones (or the slack element): zero them
             const int valid = (int)(a.K - kt * TK) - 32 * ks - 8 * kq;     // this lane's k that lie inside K
             if (valid < 8) {

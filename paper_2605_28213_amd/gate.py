@@ -105,7 +105,7 @@ def kernel_patterns(variant: int, in_dtype: int, path: str, bm: int, bn: int, th
     if "stream(small" in path:
         return [r"k4_stream<gl::StreamCfg<%s, %d, " % (dt, threads // 64)]
     if path.startswith("mfma16-thin"):
-        return [r"k4_thin_brow<gl::ThinCfg<%s, %d, %d>" % (dt, 1 if bm <= 16 else 2 if bm <= 32 else 4, bn)]
+        return [r"k4_thin_brow<gl::ThinCfg<%s, %d, %d, " % (dt, 1 if bm <= 16 else 2 if bm <= 32 else 4, bn)]
     if "direct-to-lds" in path:
         swz = "false" if flags & gemm.GEMM_FLAG_DEOPT_NO_SWIZZLE else "true"
         ovl = "false" if flags & gemm.GEMM_FLAG_DEOPT_NO_OVERLAP else "true"

@@ -212,6 +212,48 @@ def test_thin_kernel_reads_a_row_major_b_in_place(dtype, case):
     np.testing.assert_array_equal(got, want)
 
 
+OFF_DWORD_CASES = [  # (M, N, K, batch, lda, ldb, extra batch stride of A, of B, A's address off by an element, B's)
+    (3, 200, 300, 1, 300, 200, 0, 0, True, False),     # even rows throughout, A starts 2 bytes off a dword
+    (16, 129, 130, 1, 130, 130, 0, 0, False, True),    # ... B does
+    (33, 257, 515, 1, 516, 258, 0, 0, True, True),     # ... both do (four row groups)
+    (20, 70, 1000, 3, 1000, 70, 1, 0, False, False),   # even rows, A's batch items an odd number of elements apart
+    (64, 100, 96, 4, 96, 100, 0, 1, False, False),     # ... B's
+    (7, 333, 1025, 2, 1025, 333, 1, 1, True, True),    # odd rows, odd batch strides, both addresses off
+    (48, 4097, 65, 1, 65, 4097, 0, 0, True, False),    # odd rows and A off: even rows of A are the aligned ones
+]
+
+
+@pytest.mark.parametrize("dtype", [gen.BF16, gen.F16])
+@pytest.mark.parametrize("case", OFF_DWORD_CASES, ids=["%dx%dx%d_b%d_ld%d_%d_s%d_%d_%s_%s" % c for c in OFF_DWORD_CASES])
+def test_thin_kernel_realigns_rows_that_start_two_bytes_off_a_dword(dtype, case):
+    """Rows of A that start on an odd element are loaded as whole aligned dwords and shifted into place in registers
+    (B's are loaded where they lie): the start of an operand, an odd batch stride and an odd leading dimension each
+    put rows 2 bytes off a dword.  The elements before the first and after the last one of each operand hold 3 (as
+    the gaps between rows do): a kernel that let them into a sum would be off by an integer."""
+    M, N, K, nb, lda, ldb, xa, xb, off_a, off_b = case
+    inp = int_inputs(dtype, M, N, K, ROW, ROW, batch=nb, lda=lda, ldb=ldb, seed=M + K)
+    sa, sb = M * lda + xa, K * ldb + xb
+    three = gen.quantise(dtype, np.full(1, 3.0, dtype=np.float32))[0]
+
+    def spread(x, per_item, stride, lead):            # batch items `stride` apart behind `lead` elements, 3 elsewhere
+        out = np.full(lead + nb * stride + 8, three, dtype=x.dtype)
+        for b in range(nb):
+            out[lead + b * stride: lead + b * stride + per_item] = x[b * per_item: (b + 1) * per_item]
+        return out
+    A, B = spread(inp.A, M * lda, sa, int(off_a)), spread(inp.B, K * ldb, sb, int(off_b))
+    dA, dB = util.dev(A), util.dev(B)
+    dA, dB = dA[2 * int(off_a):], dB[2 * int(off_b):]
+    assert dA.data_ptr() % 4 == 2 * int(off_a) and dB.data_ptr() % 4 == 2 * int(off_b)
+    moved = gen.Inputs(inp.cfg, inp.seed, A[int(off_a):], B[int(off_b):], lda, ldb, inp.ldc, sa, sb, inp.stride_c)
+    d = gemm.make_desc(M, N, K, dtype, gen.F32, ROW, ROW, lda=lda, ldb=ldb, ldc=inp.ldc, batch=nb, stride_a=sa, stride_b=sb,
+                       stride_c=inp.stride_c)
+    assert gemm.gemm_query(K4, d, dA, dB).path == "mfma16-thin(B-row-major)"
+    C_ref, _ = oracle_for(moved)
+    rc, C, _ = util.run_config(K4, moved, dA=dA, dB=dB)
+    assert rc == gemm.GEMM_OK, gemm.gemm_status_string(rc)
+    np.testing.assert_array_equal(C[:, :, :N], C_ref)
+
+
 @pytest.mark.parametrize("dtype", DTYPES)
 @pytest.mark.parametrize("flags,tag", [(gemm.GEMM_FLAG_DEOPT_NO_SWIZZLE, "-noswz"), (gemm.GEMM_FLAG_DEOPT_NO_OVERLAP, "-noovl"),
                                        (gemm.GEMM_FLAG_DEOPT_NO_RASTER, "-noraster"),

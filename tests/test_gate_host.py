@@ -70,7 +70,7 @@ def test_compile_leg_rebuilds_a_stale_unit_and_records_kernel_resources():
     assert all(v["waves_per_simd"] >= 3 and v["lds_bytes"] == 3 * 16384 for k, v in pipe.items() if ", 8>" in k)
     # the thin kernel for a row-major B: at most 256 registers (two waves per SIMD in a workgroup of eight), no spill
     thin = {k: v for k, v in kernels.items() if "k4_thin_brow<" in k}
-    assert len(thin) == 6 and all(v["vgpr_spill"] == 0 and v["scratch_bytes_per_lane"] == 0 and v["waves_per_simd"] >= 2 for v in thin.values())
+    assert len(thin) == 12 and all(v["vgpr_spill"] == 0 and v["scratch_bytes_per_lane"] == 0 and v["waves_per_simd"] >= 2 for v in thin.values())
 
 
 def test_every_state_and_path_maps_to_kernels_of_the_library():
