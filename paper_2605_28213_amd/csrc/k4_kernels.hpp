@@ -423,13 +423,32 @@ struct FastCfg {
     static constexpr int TR = MI16_ ? 16 : 32;           // rows (and columns) of an accumulator tile
     static constexpr int TMI = BM / WM / TR, TNI = BN / WN / TR;
     static_assert(!MI16_ || IN::BYTES == 2, "the 16x16x32 instruction used here is the two-byte one");
-    static constexpr int REGION = TILE_ * ROW_BYTES, REGIONS = 5;
+    // DEPTH = slabs ahead of the one in use that the ring holds or is being sent (the last of them half: A only)
+    static constexpr int DEPTH = 2;
+    static constexpr int REGION = TILE_ * ROW_BYTES, REGIONS = 2 * DEPTH + 1;
     static constexpr int LDS_BYTES = REGIONS * REGION;
     static constexpr int WAVES_PER_SIMD = TILE_ == 256 ? 1 : 2;
     static_assert(TILE_ == 256 || TILE_ == 128, "square tiles of 256 or 128");
     // the epilogue parks 32 rows of fp32 per wave, one wave per region
     static_assert(32 * (BN / WN * 4 + 16) <= REGION, "epilogue staging must fit a region");
 };
+
+// 128-tiles with a ring of nine regions (144 KB: one workgroup per CU), for products that give each CU at most one
+// 128-tile anyway: the second workgroup that would hide this one's memory waits is not there, so the LDS it would
+// have used holds two more slabs of prefetch (distance 3.5 slabs instead of 1.5).
+template <typename IN>
+struct FastCfgDeep : FastCfg<IN, 128> {
+    static constexpr int DEPTH = 4;
+    static constexpr int REGIONS = 2 * DEPTH + 1;
+    static constexpr int LDS_BYTES = REGIONS * FastCfg<IN, 128>::REGION;
+    static constexpr int WAVES_PER_SIMD = 1;
+};
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
 
 template <typename CFG>
 __global__ __launch_bounds__(CFG::T) __attribute__((amdgpu_waves_per_eu(CFG::WAVES_PER_SIMD, CFG::WAVES_PER_SIMD)))
@@ -444,12 +463,26 @@ void k4_mfma_fast(Args a, int tiles_m, int tiles_n, int flags)
     constexpr int TR = CFG::TR, LG = 64 / TR;            // rows of an accumulator tile; lane groups along K (2 or 4)
     constexpr int NK = CHUNKS / (LG * CPS);              // k-steps per slab
     constexpr int LD = BM / 8 / NW;                      // direct loads per wave per operand slab
+    constexpr int D = CFG::DEPTH, R = CFG::REGIONS;      // slabs of prefetch; regions of the ring
     static_assert(BM == BN && NW == 4 && LD % 2 == 0, "the ring schedule is written for square tiles and four waves");
+    static_assert(R == 2 * D + 1 && (R == 5 || R == 9) && (2 * D - 1) * LD < 64, "five or nine regions; waits count loads in six bits");
+    // (one object per region: the compiler then knows that a load into one region and a read from another cannot
+    // touch the same bytes, and waits for no load on its own account)
     __shared__ __attribute__((aligned(1024))) char r0[REGION];
     __shared__ __attribute__((aligned(1024))) char r1[REGION];
     __shared__ __attribute__((aligned(1024))) char r2[REGION];
     __shared__ __attribute__((aligned(1024))) char r3[REGION];
     __shared__ __attribute__((aligned(1024))) char r4[REGION];
+    __shared__ __attribute__((aligned(1024))) char r5[R > 5 ? REGION : 1024];   // (never referenced with five regions)
+    __shared__ __attribute__((aligned(1024))) char r6[R > 5 ? REGION : 1024];
+    __shared__ __attribute__((aligned(1024))) char r7[R > 5 ? REGION : 1024];
+    __shared__ __attribute__((aligned(1024))) char r8[R > 5 ? REGION : 1024];
+    auto region = [&](auto idx) __attribute__((always_inline)) -> char* {        // region idx mod R, known at compile time
+        constexpr int i = decltype(idx)::value % R;
+        if constexpr (i == 0) return r0; else if constexpr (i == 1) return r1; else if constexpr (i == 2) return r2;
+        else if constexpr (i == 3) return r3; else if constexpr (i == 4) return r4; else if constexpr (i == 5) return r5;
+        else if constexpr (i == 6) return r6; else if constexpr (i == 7) return r7; else return r8;
+    };
 
     const int t = threadIdx.x, lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -588,15 +621,16 @@ void k4_mfma_fast(Args a, int tiles_m, int tiles_n, int flags)
     constexpr int NMF = TMI * TNI;                   // MFMA instructions per k-step
     constexpr int NRD = (TMI + TNI) * CPS;           // fragment reads per k-step
     constexpr int HALF = LD / 2;                     // loads per issue group
-    // issue groups of a slab, in order: B_s+1 second half, A_s+2 first half, A_s+2 second half (before
-    // the barrier, spread over the first NK-1 k-steps), B_s+2 first half (after it, last k-step)
+    // issue groups of a slab, in order (D = 2 in the five-region ring): B_s+D-1 second half, A_s+D first half,
+    // A_s+D second half (before the barrier, spread over the first NK-1 k-steps), B_s+D first half (after it, last
+    // k-step, into the region A_s leaves).  Operand slab q lives in region q mod R (A_s: q = 2s, B_s: 2s+1).
     constexpr int GROUPS_PER_STEP = NK > 1 ? (3 + NK - 2) / (NK - 1) : 3;
     static_assert(NK >= 2, "the barrier k-step is not the one that prefetches");
 
     const int64_t nslab = a.K / KE;                  // K is a whole number of slabs
     // `first`: slab 0 in the branch-free form; its pre-barrier loads were issued by the prologue.  In the
     // branching form the same holds for s == 0.
-    auto kstep = [&](auto full, auto first, auto step, int64_t s, char* ra, char* rb, char* na, char* nb, char* fifth) __attribute__((always_inline)) {
+    auto kstep = [&](auto full, auto first, auto step, int64_t s, char* ra, char* rb, char* na, char* nb, char* pb, char* pa) __attribute__((always_inline)) {
         constexpr bool FULL = decltype(full)::value, FIRST = decltype(first)::value;
         constexpr int ks = decltype(step)::value;
         constexpr int G0 = FIRST ? 3 : ks * GROUPS_PER_STEP;
@@ -605,9 +639,9 @@ void k4_mfma_fast(Args a, int tiles_m, int tiles_n, int flags)
         constexpr int PRE = (ks + 1 == NK && FULL && CFG::OVERLAP) ? CFG::PRE_BARRIER_MFMAS : 0;
         if constexpr (ks + 1 < NK) {
             read(ra, rb, ks + 1, (ks + 1) & 1);
-            if constexpr (G0 <= 0 && 0 < G1) { if (FULL || (s > 0 && s + 1 < nslab)) issue_b(s + 1, nb, HALF, LD); }
-            if constexpr (G0 <= 1 && 1 < G1) { if (FULL || (s > 0 && s + 2 < nslab)) issue_a(s + 2, fifth, 0, HALF); }
-            if constexpr (G0 <= 2 && 2 < G1) { if (FULL || (s > 0 && s + 2 < nslab)) issue_a(s + 2, fifth, HALF, LD); }
+            if constexpr (G0 <= 0 && 0 < G1) { if (FULL || (s > 0 && s + D - 1 < nslab)) issue_b(s + D - 1, pb, HALF, LD); }
+            if constexpr (G0 <= 1 && 1 < G1) { if (FULL || (s > 0 && s + D < nslab)) issue_a(s + D, pa, 0, HALF); }
+            if constexpr (G0 <= 2 && 2 < G1) { if (FULL || (s > 0 && s + D < nslab)) issue_a(s + D, pa, HALF, LD); }
         } else {
             // The slab's last k-step holds the barrier.  Its first PRE MFMAs (operands already in
             // registers) are issued ahead of it, so the matrix pipe has work while the waves meet.
@@ -615,18 +649,17 @@ void k4_mfma_fast(Args a, int tiles_m, int tiles_n, int flags)
                 mfmas(ks & 1, 0, PRE);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            // landed after this wait: A_s+1, B_s+1; possibly still in flight: the LD loads of A_s+2
+            // landed after this wait: A_s+1, B_s+1; possibly still in flight: what was issued after them, the
+            // slabs s+2 .. s+D-1 and A_s+D, LD loads each
             if constexpr (FULL) {
-                static_assert(LD == 8 || LD == 4, "the wait below counts the LD loads of the A_s+2 group");
-                if constexpr (LD == 8) asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
-                else asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)" ::: "memory");
+                asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((2 * (D - 2) + 1) * LD) : "memory");
             } else {
                 asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
             }
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
             if (FULL || s + 1 < nslab) read(na, nb, 0, 0);
-            if (FULL || s + 2 < nslab) issue_b(s + 2, ra, 0, HALF);
+            if (FULL || s + D < nslab) issue_b(s + D, ra, 0, HALF);
         }
         if constexpr (!CFG::OVERLAP) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         mfmas(ks & 1, PRE, NMF);
@@ -638,47 +671,69 @@ void k4_mfma_fast(Args a, int tiles_m, int tiles_n, int flags)
     // requested interleaving can be realised by the instruction scheduler.
     using yes = std::integral_constant<bool, true>;
     using no = std::integral_constant<bool, false>;
-    auto slab = [&](auto full, auto first, int64_t s, char* ra, char* rb, char* na, char* nb, char* fifth) __attribute__((always_inline)) {
+    auto slab = [&](auto full, auto first, int64_t s, char* ra, char* rb, char* na, char* nb, char* pb, char* pa) __attribute__((always_inline)) {
         for_each_step(std::make_integer_sequence<int, NK>{}, [&](auto step) __attribute__((always_inline)) {
-            kstep(full, first, step, s, ra, rb, na, nb, fifth);
+            kstep(full, first, step, s, ra, rb, na, nb, pb, pa);
         });
     };
+    // slab s with its regions known at compile time: U = 2s mod R
+    auto slab_at = [&](auto full, auto first, auto u, int64_t s) __attribute__((always_inline)) {
+        constexpr int U = decltype(u)::value;
+        using std::integral_constant;
+        slab(full, first, s, region(integral_constant<int, U>{}), region(integral_constant<int, U + 1>{}), region(integral_constant<int, U + 2>{}),
+             region(integral_constant<int, U + 3>{}), region(integral_constant<int, U + 2 * D - 1>{}), region(integral_constant<int, U + 2 * D>{}));
+    };
 
-    // Prologue: fill the whole ring at once (A_0, B_0, A_1, B_1, A_2: all five regions), then wait for
+    // Prologue: fill the whole ring at once (A_0, B_0, ..., A_D-1, B_D-1, A_D: all R regions), then wait for
     // slab 0 only; the rest lands while slab 0 is multiplied.  Slab 0 then issues no pre-barrier loads,
-    // and its barrier wait finds the same picture as in the steady state (youngest LD loads = A_2).
-    if (nslab > 0) { issue_a(0, r0, 0, LD); issue_b(0, r1, 0, LD); }
-    if (nslab > 1) { issue_a(1, r2, 0, LD); issue_b(1, r3, 0, LD); }
-    if (nslab > 2) issue_a(2, r4, 0, LD);
-    static_assert(LD == 8 || LD == 4, "the waits below count loads");
-    if (nslab > 2) { if constexpr (LD == 8) asm volatile("s_waitcnt vmcnt(24)" ::: "memory"); else asm volatile("s_waitcnt vmcnt(12)" ::: "memory"); }
-    else if (nslab > 1) { if constexpr (LD == 8) asm volatile("s_waitcnt vmcnt(16)" ::: "memory"); else asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); }
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // and its barrier wait finds the same picture as in the steady state (youngest loads: A_D).
+    for_each_step(std::make_integer_sequence<int, D>{}, [&](auto i) __attribute__((always_inline)) {
+        constexpr int I = decltype(i)::value;
+        if (nslab > I) {
+            issue_a(I, region(std::integral_constant<int, 2 * I>{}), 0, LD);
+            issue_b(I, region(std::integral_constant<int, 2 * I + 1>{}), 0, LD);
+        }
+    });
+    if (nslab > D) issue_a(D, region(std::integral_constant<int, 2 * D>{}), 0, LD);
+    // (everything issued but the 2 LD loads of slab 0 may still be in flight)
+    if (nslab > D) {
+        wait_vmcnt<(2 * D - 1) * LD>();
+    } else {
+        bool waited = false;
+        for_each_step(std::make_integer_sequence<int, D>{}, [&](auto i) __attribute__((always_inline)) {
+            constexpr int N = D - decltype(i)::value;        // D, D-1, ..., 1 slabs issued
+            if (!waited && nslab >= N) {
+                wait_vmcnt<(2 * N - 2) * LD>();
+                waited = true;
+            }
+        });
+        if (!waited) wait_vmcnt<0>();
+    }
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     if (nslab > 0) read(r0, r1, 0, 0);
     int64_t s = 0;
-    if (nslab > 6) {
-        slab(yes{}, yes{}, 0, r0, r1, r2, r3, r4);
+    if (nslab > R + D - 1) {
+        slab_at(yes{}, yes{}, std::integral_constant<int, 0>{}, 0);
         s = 1;
     }
-    // five slabs bring the ring back to where it was
-    for (; s + 6 < nslab; s += 5) {
-        slab(yes{}, no{}, s, r2, r3, r4, r0, r1);
-        slab(yes{}, no{}, s + 1, r4, r0, r1, r2, r3);
-        slab(yes{}, no{}, s + 2, r1, r2, r3, r4, r0);
-        slab(yes{}, no{}, s + 3, r3, r4, r0, r1, r2);
-        slab(yes{}, no{}, s + 4, r0, r1, r2, r3, r4);
+    // R slabs bring the ring back to where it was (s = 1 mod R at the top of every trip)
+    for (; s + R + D - 1 < nslab; s += R) {
+        for_each_step(std::make_integer_sequence<int, R>{}, [&](auto t) __attribute__((always_inline)) {
+            constexpr int T = decltype(t)::value;
+            slab_at(yes{}, no{}, std::integral_constant<int, (2 * (1 + T)) % R>{}, s + T);
+        });
     }
-    // tail: at most six slabs, region pointers rotate at run time, waits are conservative
+    // tail: at most R + D - 1 slabs, region pointers rotate at run time, waits are conservative
     {
         auto reg = [&](int i) __attribute__((always_inline)) -> char* {
-            i %= 5;
-            return i == 0 ? r0 : i == 1 ? r1 : i == 2 ? r2 : i == 3 ? r3 : r4;
+            i %= R;
+            if constexpr (R == 5) return i == 0 ? r0 : i == 1 ? r1 : i == 2 ? r2 : i == 3 ? r3 : r4;
+            else return i == 0 ? r0 : i == 1 ? r1 : i == 2 ? r2 : i == 3 ? r3 : i == 4 ? r4 : i == 5 ? r5 : i == 6 ? r6 : i == 7 ? r7 : r8;
         };
         for (; s < nslab; ++s) {
-            const int u = (int)((2 * s) % 5);
-            slab(no{}, no{}, s, reg(u), reg(u + 1), reg(u + 2), reg(u + 3), reg(u + 4));
+            const int u = (int)((2 * s) % R);
+            slab(no{}, no{}, s, reg(u), reg(u + 1), reg(u + 2), reg(u + 3), reg(u + 2 * D - 1), reg(u + 2 * D));
         }
     }
 

@@ -9,6 +9,7 @@ template <typename IN> using FastK4 = FastCfg<IN, 256>;                    // 25
 template <typename IN> using FastK4Mi16 = FastCfg<IN, 256, 8, true, true, 0, false, true>;   // the same with 8 x 8 accumulator tiles of v_mfma_f32_16x16x32 per wave (two-byte types)
 template <typename IN> using FastK4Mi16Long = FastCfg<IN, 256, 8, true, true, 8, false, true>;   // ... and 8 instructions ahead of the slab barrier (K of 96 slabs or more)
 template <typename IN> using FastK4Small = FastCfg<IN, 128>;               // 128x128 tile, 4 waves, 64x64 per wave, two workgroups per CU
+template <typename IN> using FastK4SmallDeep = FastCfgDeep<IN>;            // ... with a ring of nine regions, one workgroup per CU
 template <typename IN> using StreamK4 = StreamCfg<IN, 1, 1, 256, 19>;      // 16 columns per one-wave workgroup, 512-byte runs, K walk rotated by 19 tiles per workgroup
 template <typename IN> using StreamK4Deep = StreamCfg<IN, 4, 1, 256, 19>;  // the same with 4 waves taking K tiles in turn, for strips too few to fill the chip
 template <typename IN> using StreamK4Rows32 = StreamCfg<IN, 2, 2, 256, 19, 2>;   // 17..32 rows: 32 columns, two groups of A
@@ -145,6 +146,19 @@ bool k4_small_tiles(const Args& a)
     return r128 * cost128 < r256 * 10;
 }
 
+// 128-tiles that number at most one per CU take the nine-region ring (FastCfgDeep) when K is at least 32 slabs: its
+// steady-state loop is nine slabs long and entered from 13 slabs on, and what comes before and after it waits for
+// every load.  Same box, operands rotated, nine regions against five: bf16 2048^3 (256 tiles, 32 slabs) 23.8 against
+// 26.2 us, 2048 x 1024 x 2048 (128 tiles) 20.0 / 23.8, 1536^2 x 8192 (144 tiles, 128 slabs) 55.2 / 58.4, 1024^2 x 4096
+// 34.7 / 35.6; with 16 slabs it loses (1024^3 16.9 / 15.6, e4m3 2048^3 19.9 / 18.8) and with 8 badly (2048^2 x 512
+// 17.0 / 11.6).  The gain is small because these products are bound by what L2 delivers (2048^3: 268 MB from L2 to
+// LDS in about 18 us), not by the distance of the prefetch.
+static bool k4_small_tiles_deep(const Args& a)
+{
+    const int64_t nslab = a.K / (ROW_BYTES / elem_size(a.in_dtype));
+    return nslab >= 32 && ((a.M + 127) / 128) * ((a.N + 127) / 128) * a.batch <= 256;
+}
+
 // The expert instantiation, or one of its validated simplifications when the caller asks for it.
 template <typename IN>
 static hipError_t launch_fast_any(const Args& a)
@@ -154,7 +168,7 @@ static hipError_t launch_fast_any(const Args& a)
     if (noswz && noovl) return launch_fast<FastCfg<IN, 256, 8, false, false>>(a);
     if (noswz) return launch_fast<FastCfg<IN, 256, 8, false, true>>(a);
     if (noovl) return launch_fast<FastCfg<IN, 256, 8, true, false>>(a);
-    if (k4_small_tiles(a)) return launch_fast<FastK4Small<IN>>(a);
+    if (k4_small_tiles(a)) return k4_small_tiles_deep(a) ? launch_fast<FastK4SmallDeep<IN>>(a) : launch_fast<FastK4Small<IN>>(a);
     // Two-byte types: 8 x 8 accumulator tiles of v_mfma_f32_16x16x32 per wave.  Same box, operands rotated, against
     // the 32x32x16 form: bf16 8192^3 755 -> 725-737 us, 4096^3 104.7 -> 96.3 us (the package draws the same 1.4 kW at
     // 1.92 instead of 1.64 GHz).  With a long K, 8 instructions of a slab's last k-step go ahead of its barrier
@@ -247,7 +261,7 @@ static hipError_t launch_splitk(const Args& a)
 // The arguments the fast kernel is launched with on each of its three paths, as far as the choice between its
 // persistent and its one-tile-per-workgroup form depends on them (mirrors launch_packed, launch_splitk and
 // launch_fast_split).
-bool k4_fast_is_persistent(int kind, const Args& a)
+static Args fast_kernel_args(int kind, const Args& a)
 {
     Args p = a;
     if (kind == MFMA_SPLITK) {
@@ -255,12 +269,14 @@ bool k4_fast_is_persistent(int kind, const Args& a)
         p.batch = splits;
         p.K = a.K / splits;
         p.flags = (k4_small_tiles(a) ? GEMM_FLAG_TILE_128 : GEMM_FLAG_TILE_256) | (a.flags & K4_NEUTRAL_FLAGS);
-        return k4_uses_ring(p);
+        return p;
     }
     if (kind == MFMA_PACKED) p.K = k4_packed_k(a);
     if (k4_splits_m_tail(p)) p.M = p.M - p.M % 256;
-    return k4_uses_ring(p);
+    return p;
 }
+
+bool k4_fast_is_persistent(int kind, const Args& a) { return k4_uses_ring(fast_kernel_args(kind, a)); }
 
 int64_t k4_packed_k(const Args& a)
 {
@@ -416,6 +432,9 @@ Geometry geometry_k4(int path, const Args& a)
         int64_t g = ((top.M + bt - 1) / bt) * ((a.N + bt - 1) / bt) * a.batch * (kind == MFMA_SPLITK ? k4_splitk_factor(a) : 1);
         if (k4_fast_is_persistent(kind, a)) g = K4_RING_WORKGROUPS;      // persistent workgroups, several tiles each
         // stages: slabs in flight beyond the one in use
+        const Args p = fast_kernel_args(kind, a);
+        if (k4_small_tiles(p) && !k4_uses_ring(p) && !(p.flags & (GEMM_FLAG_DEOPT_NO_SWIZZLE | GEMM_FLAG_DEOPT_NO_OVERLAP)) && k4_small_tiles_deep(p))
+            return Geometry{bt, bt, ROW_BYTES / es, 256, FastK4SmallDeep<BF16>::DEPTH, FastK4SmallDeep<BF16>::LDS_BYTES, g};
         return Geometry{bt, bt, ROW_BYTES / es, 256, 2, small ? FastK4Small<BF16>::LDS_BYTES : FastK4<BF16>::LDS_BYTES, g};
     }
     const int bt = masked_tile(a);

@@ -90,7 +90,7 @@ def _stats(ms: Sequence[float]) -> Dict[str, float]:
 
 
 # ---- compile leg -------------------------------------------------------------------------------------
-def kernel_patterns(variant: int, in_dtype: int, path: str, bm: int, bn: int, threads: int, flags: int = 0) -> List[str]:
+def kernel_patterns(variant: int, in_dtype: int, path: str, bm: int, bn: int, threads: int, flags: int = 0, stages: int = 2) -> List[str]:
     """Regular expressions (on demangled names) of the kernels a state launches on the path the query names."""
     dt = "gl::" + _DT[in_dtype]
     if variant == gemm.GEMM_K0_NAIVE:
@@ -113,6 +113,8 @@ def kernel_patterns(variant: int, in_dtype: int, path: str, bm: int, bn: int, th
             pats.append(r"k4_mfma_ring<gl::RingCfg<%s, \d+, true>" % dt)
         elif "(persistent)" in path:
             pats.append(r"k4_mfma_ring<gl::RingCfg<%s, \d+, false>" % dt)
+        elif bm == 128 and stages == 4:
+            pats.append(r"k4_mfma_fast<gl::FastCfgDeep<%s> >" % dt)     # 128-tiles, at most one per CU, long K: nine-region ring
         else:
             # (two-byte types on 256-tiles with none of the switches multiply with the 16x16x32 instruction)
             mi16 = ("true" if in_dtype in (gen.BF16, gen.F16) and bm == 256 and not (flags & (gemm.GEMM_FLAG_DEOPT_NO_SWIZZLE |
@@ -325,7 +327,7 @@ def run_gate(variant: int, cfg: gen.Config, reference: Callable[[gen.Inputs], Re
             if q.status != gemm.GEMM_OK:
                 entry["verdict"] = f"failed(query: {gemm.gemm_status_string(q.status)})"
                 return _finish(entry, ledger_path)
-            patterns = kernel_patterns(variant, cfg.in_dtype, q.path, q.bm, q.bn, q.threads, extra_flags)
+            patterns = kernel_patterns(variant, cfg.in_dtype, q.path, q.bm, q.bn, q.threads, extra_flags, q.stages)
             try:
                 entry["compile"]["kernels"] = kernel_resources(patterns)
             except Exception as e:      # a library built by other means carries no record: say so, do not guess

@@ -255,6 +255,24 @@ def test_thin_kernel_realigns_rows_that_start_two_bytes_off_a_dword(dtype, case)
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
+def test_nine_region_ring_of_the_small_tile_kernel_is_exact(dtype):
+    """128-tiles that number at most one per CU, K of 32 slabs or more: prefetch 3.5 slabs deep.  33 slabs: first slab,
+    three trips of the nine-slab loop, five slabs of tail; 45: four trips and eight; 32: the fewest.  M and N end
+    inside a tile; a batch; a leading dimension beyond K; and the same kernel under split-K's K ranges."""
+    for (M, N, ns, nb, pad, tile) in [(520, 300, 33, 2, 0, gemm.GEMM_FLAG_TILE_128), (257, 513, 45, 1, 8, gemm.GEMM_FLAG_TILE_128),
+                                      (1000, 900, 32, 1, 0, 0), (128, 128, 40, 3, 0, gemm.GEMM_FLAG_TILE_128)]:
+        K = slabs(dtype, ns)
+        inp = int_inputs(dtype, M, N, K, batch=nb, lda=K + pad * 16 // gen.ELEM_BYTES[dtype], seed=ns)
+        q = run_exact(inp, "mfma32-direct-to-lds", flags=tile)
+        assert (q.bm, q.stages, q.lds_bytes) == (128, 4, 9 * 128 * 128), (q.bm, q.stages, q.lds_bytes)
+    # 31 slabs, or more than 256 tiles: the five-region ring
+    for (M, N, ns, nb) in [(520, 300, 31, 2), (2100, 2100, 33, 1)]:
+        inp = int_inputs(dtype, M, N, slabs(dtype, ns), batch=nb, seed=ns)
+        q = run_exact(inp, "mfma32-direct-to-lds", flags=gemm.GEMM_FLAG_TILE_128)
+        assert (q.bm, q.stages, q.lds_bytes) == (128, 2, 5 * 128 * 128)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
 @pytest.mark.parametrize("flags,tag", [(gemm.GEMM_FLAG_DEOPT_NO_SWIZZLE, "-noswz"), (gemm.GEMM_FLAG_DEOPT_NO_OVERLAP, "-noovl"),
                                        (gemm.GEMM_FLAG_DEOPT_NO_RASTER, "-noraster"),
                                        (gemm.GEMM_FLAG_DEOPT_NO_RASTER | gemm.GEMM_FLAG_TILE_128, "-noraster")])

@@ -88,6 +88,8 @@ def test_every_state_and_path_maps_to_kernels_of_the_library():
              (4, gen.BF16, "mfma16-thin(B-row-major)", 32, 64, 512, 0),
              (4, gen.BF16, "mfma32-direct-to-lds+splitK(4)", 128, 128, 256, 0), (4, gen.BF16, "mfma16-stream(small-M)", 16, 16, 64, 0),
              (4, gen.F32, "mfma32-elementwise-masked", 64, 64, 256, 0), (4, gen.F16, "mfma32-vec16-masked", 128, 128, 256, 0)]
+    deep = gate.kernel_patterns(4, gen.BF16, "mfma32-direct-to-lds", 128, 128, 256, 0, stages=4)    # nine-region ring of the 128-tile kernel
+    assert deep == [r"k4_mfma_fast<gl::FastCfgDeep<gl::BF16> >"] and gate.kernel_resources(deep)
     for (v, dt, path, bm, bn, threads, flags) in cases:
         pats = gate.kernel_patterns(v, dt, path, bm, bn, threads, flags)
         found = gate.kernel_resources(pats)
