@@ -95,6 +95,41 @@ def draw_cols_case(rng, i):
                       lda=c.ld[0], ldb=c.ld[1], ldc=n + int(rng.integers(0, 5)))
 
 
+def draw_long_k_few_tiles_case(rng, i):
+    """At most 256 tiles of 128 x 128 and K of 32 to 70 slabs, aligned operands, B column-major, 128-tiles asked for:
+    the nine-region ring of the small-tile kernel (first slab, trips of nine, tails of every length)."""
+    dtype = int(rng.choice([gen.BF16, gen.F16, gen.E4M3]))
+    es = gen.ELEM_BYTES[dtype]
+    batch = int(rng.choice([1, 1, 2, 3]))
+    tm, tn = int(rng.integers(1, 7)), int(rng.integers(1, 7))
+    M = 128 * (tm - 1) + int(rng.integers(97, 129))
+    N = 128 * (tn - 1) + int(rng.integers(97, 129))
+    K = 128 // es * int(rng.integers(32, 71))
+    lda = K + 16 // es * int(rng.integers(0, 3))
+    ldb = K + 16 // es * int(rng.integers(0, 3))
+    out = int(rng.choice([gen.BF16 if dtype == gen.E4M3 else dtype, gen.F32]))
+    return gen.Config(f"deep{i}", M, N, K, dtype, out, ROW, COL, str(rng.choice(["uniform", "normal"])), batch=batch,
+                      scaled=bool(rng.random() < 0.3), biased=bool(rng.random() < 0.3), lda=lda, ldb=ldb, ldc=N + int(rng.integers(0, 3)))
+
+
+DEEP_CASES = [draw_long_k_few_tiles_case(np.random.default_rng(8000 + i), i) for i in range(16)]
+
+
+@pytest.mark.parametrize("i", range(len(DEEP_CASES)))
+def test_random_case_for_the_nine_region_ring(i):
+    cfg = DEEP_CASES[i]
+    inp = gen.make_inputs(cfg, 800 + i)
+    C_ref, D = oracle_for(inp)
+    q = gemm.gemm_query(4, gemm.make_desc(cfg.M, cfg.N, cfg.K, cfg.in_dtype, cfg.out_dtype, ROW, COL, lda=inp.lda, ldb=inp.ldb, ldc=inp.ldc,
+                                          batch=cfg.batch, stride_a=inp.stride_a, stride_b=inp.stride_b, stride_c=inp.stride_c,
+                                          flags=gemm.GEMM_FLAG_TILE_128))
+    assert (q.path, q.bm, q.stages) == ("mfma32-direct-to-lds", 128, 4), (cfg, q)
+    rc, C, _ = util.run_config(4, inp, flags=gemm.GEMM_FLAG_TILE_128)
+    assert rc == gemm.GEMM_OK, (cfg, gemm.gemm_status_string(rc), gemm.gemm_last_launch_error())
+    err = util.norm_err(C[:, :, : cfg.N], C_ref, D)
+    assert err <= util.TOL[cfg.in_dtype], (cfg, err)
+
+
 COLS_CASES = [draw_cols_case(np.random.default_rng(2500 + i), i) for i in range(24)]
 
 
