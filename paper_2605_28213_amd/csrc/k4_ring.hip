@@ -30,8 +30,8 @@ bool k4_uses_ring(const Args& a)
 // that reads such a B without a packing pass.  When the last row of an operand has an odd number of elements
 // (K odd for A, N odd for B) the kernel's loads reach the one element after the operand (RING_BROW_SLACK): with the
 // pointers known, such a product is only taken when that element lies in the same 4 KiB page as the operand's last
-// byte, so that it is mapped whatever follows the operand.
-bool k4_ring_takes_row_major_b(const Args& a)
+// byte, so that it is mapped whatever follows the operand (for A there is a second way: k4_brow_splits_last_row).
+static bool brow_shape_fits(const Args& a)
 {
     if (a.flags != 0 || a.in_dtype == GEMM_FP8_E4M3 || a.in_dtype == GEMM_F32) return false;
     if (a.a_sk != 1 || a.b_sj != 1 || a.M <= 0 || a.N <= 0 || a.K <= 0) return false;
@@ -39,10 +39,33 @@ bool k4_ring_takes_row_major_b(const Args& a)
     const int64_t ke = ROW_BYTES / es;
     const int64_t tiles = ((a.M + 255) / 256) * ((a.N + 255) / 256) * a.batch;
     if ((a.K + ke - 1) / ke < 3 || tiles < K4_RING_WORKGROUPS || tiles >= ((int64_t)1 << 31)) return false;
-    if (a.a_si * es > ((int64_t)1 << 22) || a.K * a.b_sk * es >= ((int64_t)1 << 31)) return false;
-    return tail_element_in_last_page(a.A, (a.batch - 1) * a.stride_a + (a.M - 1) * a.a_si + a.K, a.K, es) &&
-           tail_element_in_last_page(a.B, (a.batch - 1) * a.stride_b + (a.K - 1) * a.b_sk + a.N, a.N, es);
+    return a.a_si * es <= ((int64_t)1 << 22) && a.K * a.b_sk * es < ((int64_t)1 << 31);
 }
+static bool brow_a_tail_mapped(const Args& a) { return tail_element_in_last_page(a.A, (a.batch - 1) * a.stride_a + (a.M - 1) * a.a_si + a.K, a.K, elem_size(a.in_dtype)); }
+static bool brow_b_tail_mapped(const Args& a) { return tail_element_in_last_page(a.B, (a.batch - 1) * a.stride_b + (a.K - 1) * a.b_sk + a.N, a.N, elem_size(a.in_dtype)); }
+
+// A ends with an odd-length row at the very end of a page: the element after it, which the persistent kernel's loads
+// of that row would touch, may not be mapped.  The row is then left to the thin kernel (which loads aligned dwords
+// of A whenever a row starts off a dword, and so never reaches past the operand's last dword), and the rows before it,
+// whose one element of slack is the next row's first, stay here: instead of the masked kernel for the whole product
+// (fp16 4096 x 4093 x 4097 with such an A: 1540 us).
+bool k4_brow_splits_last_row(const Args& a)
+{
+    if (a.M < 2 || brow_a_tail_mapped(a)) return false;
+    Args top = a;
+    top.M = a.M - 1;
+    Args bot = a;
+    bot.M = 1;
+    return brow_shape_fits(top) && k4_thin_takes_row_major_b(bot);
+}
+
+bool k4_ring_takes_row_major_b(const Args& a)
+{
+    if (!brow_shape_fits(a) || !brow_b_tail_mapped(a)) return false;
+    return brow_a_tail_mapped(a) || k4_brow_splits_last_row(a);
+}
+
+static hipError_t launch_brow_rows(const Args& a);
 
 template <typename IN, bool BROW = false>
 static hipError_t launch_ring(const Args& a)
@@ -59,11 +82,30 @@ static hipError_t launch_ring(const Args& a)
 
 hipError_t launch_k4_ring_row_major_b(const Args& a)
 {
+    if (k4_brow_splits_last_row(a)) {        // the element after A is not known to be mapped: see the rule
+        const int es = elem_size(a.in_dtype);
+        Args top = a;
+        top.M = a.M - 1;
+        top.A = (const char*)a.A;            // (its last row's slack element is row M-1's first)
+        hipError_t e = launch_brow_rows(top);
+        if (e != hipSuccess) return e;
+        Args bot = a;
+        bot.M = 1;
+        bot.A = (const char*)a.A + (a.M - 1) * a.a_si * es;
+        bot.C = (char*)a.C + (a.M - 1) * a.ldc * (a.out_dtype == GEMM_F32 ? 4 : 2);
+        return launch_k4_thin_row_major_b(bot);
+    }
+    return launch_brow_rows(a);
+}
+
+// (the rows given here end with an element of slack that is mapped)
+static hipError_t launch_brow_rows(const Args& a)
+{
     if (k4_brow_splits_m_tail(a)) {          // a thin remainder of rows that would cost a round of tiles: see the rule
         const int64_t rem = a.M % 256, top_rows = a.M - rem;
         Args top = a;
         top.M = top_rows;
-        hipError_t e = launch_k4_ring_row_major_b(top);
+        hipError_t e = launch_brow_rows(top);
         if (e != hipSuccess) return e;
         Args bot = a;
         bot.M = rem;

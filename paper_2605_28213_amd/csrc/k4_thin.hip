@@ -22,14 +22,15 @@ bool k4_brow_splits_m_tail(const Args& a)
 
 // A whole product of at most 64 rows with A and B row-major (two-byte types): B below 2 GiB and A's rows below
 // 16 MiB (32-bit byte offsets), the batch within the grid's second dimension, and the element after an odd-length
-// last row mapped (see tail_element_in_last_page).
+// last row of B mapped (see tail_element_in_last_page).  Nothing is asked of A's address: its loads are aligned
+// dwords (rows that start on one, or the form that rounds them down to one), and an aligned dword that holds an
+// element of A lies in A's pages.
 bool k4_thin_takes_row_major_b(const Args& a)
 {
     if (a.flags != 0 || (a.in_dtype != GEMM_BF16 && a.in_dtype != GEMM_F16)) return false;
     if (a.a_sk != 1 || a.b_sj != 1 || a.M < 1 || a.M > 64 || a.N < 1 || a.K < 1 || a.batch > 65535) return false;
     if ((a.K + 64) * a.b_sk * 2 >= ((int64_t)1 << 31) || a.M * a.a_si * 2 >= ((int64_t)1 << 31)) return false;
-    return tail_element_in_last_page(a.A, (a.batch - 1) * a.stride_a + (a.M - 1) * a.a_si + a.K, a.K, 2) &&
-           tail_element_in_last_page(a.B, (a.batch - 1) * a.stride_b + (a.K - 1) * a.b_sk + a.N, a.N, 2);
+    return tail_element_in_last_page(a.B, (a.batch - 1) * a.stride_b + (a.K - 1) * a.b_sk + a.N, a.N, 2);
 }
 
 // Strips of 64 columns (128-byte pieces of B's rows).  The kernel also compiles for strips of 32 (twice the workgroups,

@@ -212,6 +212,32 @@ def test_thin_kernel_reads_a_row_major_b_in_place(dtype, case):
     np.testing.assert_array_equal(got, want)
 
 
+@pytest.mark.parametrize("dtype", [gen.BF16, gen.F16])
+def test_row_major_b_with_a_ending_at_the_end_of_a_page(dtype):
+    """K odd and A's last byte the last of a 4 KiB page: the element after A, which the persistent kernel's loads of
+    the last row touch, may not be mapped, so that row goes to the thin kernel and the rest stays in place (here the
+    page after A belongs to the same allocation)."""
+    M, N, K, nb = 520, 2100, 301, 15                    # 3 x 9 tiles x 15 >= 256
+    inp = int_inputs(dtype, M, N, K, ROW, ROW, batch=nb, seed=5)
+    raw = np.ascontiguousarray(inp.A).view(np.uint8)
+    buf = torch.empty(raw.size + 2 * 4096, dtype=torch.uint8, device="cuda")
+    lead = (-(buf.data_ptr() + raw.size)) % 4096       # A's end lands on a page boundary
+    assert lead % 2 == 0
+    dA = buf[lead: lead + raw.size]
+    dA.copy_(torch.from_numpy(raw.copy()))
+    assert (dA.data_ptr() + raw.size) % 4096 == 0
+    dB = util.dev(inp.B)
+    d = gemm.make_desc(M, N, K, dtype, gen.F32, ROW, ROW, lda=inp.lda, ldb=inp.ldb, ldc=inp.ldc, batch=nb, stride_a=inp.stride_a,
+                       stride_b=inp.stride_b, stride_c=inp.stride_c)
+    assert gemm.gemm_query(K4, d).path == "mfma32-direct-to-lds(persistent,B-row-major)"            # (no addresses: nothing known)
+    q = gemm.gemm_query(K4, d, dA, dB)
+    assert q.path == "mfma32-direct-to-lds(persistent,B-row-major)+thin(last row)" and q.violated == 0, q.path
+    C_ref, _ = oracle_for(inp)
+    rc, C, _ = util.run_config(K4, inp, dA=dA, dB=dB)
+    assert rc == gemm.GEMM_OK, gemm.gemm_status_string(rc)
+    np.testing.assert_array_equal(C[:, :, :N], C_ref)
+
+
 OFF_DWORD_CASES = [  # (M, N, K, batch, lda, ldb, extra batch stride of A, of B, A's address off by an element, B's)
     (3, 200, 300, 1, 300, 200, 0, 0, True, False),     # even rows throughout, A starts 2 bytes off a dword
     (16, 129, 130, 1, 130, 130, 0, 0, False, True),    # ... B does
