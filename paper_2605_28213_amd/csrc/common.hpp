@@ -146,7 +146,9 @@ hipError_t launch_k4_ring_row_major_b(const Args& a);
 // form above hands this kernel a remainder of rows that would cost it a round of tiles (the rule says when).
 bool k4_brow_splits_m_tail(const Args& a);
 bool k4_thin_takes_row_major_b(const Args& a);      // a whole product for the thin kernel
-bool k4_brow_splits_last_row(const Args& a);        // the persistent row-major-B form leaves A's last row to the thin kernel (element after A not known to be mapped)
+bool k4_brow_splits_last_col(const Args& a);        // ... and C's last column to the masked kernel (element after B not known to be mapped)
+bool k4_brow_splits_last_row(const Args& a);
+int k4_brow_splits(const Args& a);                  // bit 0: last column split off, bit 1: last row, bit 2: thin remainder of rows        // the persistent row-major-B form leaves A's last row to the thin kernel (element after A not known to be mapped)
 int k4_thin_cols(const Args& a);                    // columns per strip (= per workgroup) it is launched with: 64 or 32
 // Both row-major-B kernels load rows as dwords from their first element, so the dword that holds the last element
 // of an odd-length last row reaches one element past the operand.  With the pointer known, such a product is only

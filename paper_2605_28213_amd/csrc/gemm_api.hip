@@ -233,8 +233,12 @@ Plan make_plan(int variant, const gemm_desc_t* d, const void* A, const void* B, 
             // remainder of rows that would cost a whole round of tiles goes to the thin kernel, which reads B in place
             // as well; lent scratch is not used (ragged fp16 workload: 150 us in place, 157 us packed).
             p.path = MFMA_VEC16_BROW | (3 << 8);
-            path = k4_brow_splits_last_row(a) ? "mfma32-direct-to-lds(persistent,B-row-major)+thin(last row)"
-                   : k4_brow_splits_m_tail(a) ? "mfma32-direct-to-lds(persistent,B-row-major)+thin(M-tail)" : "mfma32-direct-to-lds(persistent,B-row-major)";
+            static const char* const BROW_PATHS[8] = {
+                "mfma32-direct-to-lds(persistent,B-row-major)", "mfma32-direct-to-lds(persistent,B-row-major)+masked(last col)",
+                "mfma32-direct-to-lds(persistent,B-row-major)+thin(last row)", "mfma32-direct-to-lds(persistent,B-row-major)+split(row,col)",
+                "mfma32-direct-to-lds(persistent,B-row-major)+thin(M-tail)", "mfma32-direct-to-lds(persistent,B-row-major)+split(M-tail,col)",
+                "", ""};
+            path = BROW_PATHS[k4_brow_splits(a) & 7];
             required = GEMM_COND_DTYPE_HAS_MFMA | GEMM_COND_LDS_STAGED | GEMM_COND_K_CONTIG_A;
         } else if (!f32 && d->layout_a == GEMM_ROW_MAJOR && d->layout_b == GEMM_ROW_MAJOR && k4_thin_takes_row_major_b(a)) {
             // at most 64 rows, A and B row-major: B is read once, in place, by the thin kernel (no scratch)

@@ -30,7 +30,8 @@ bool k4_uses_ring(const Args& a)
 // that reads such a B without a packing pass.  When the last row of an operand has an odd number of elements
 // (K odd for A, N odd for B) the kernel's loads reach the one element after the operand (RING_BROW_SLACK): with the
 // pointers known, such a product is only taken when that element lies in the same 4 KiB page as the operand's last
-// byte, so that it is mapped whatever follows the operand (for A there is a second way: k4_brow_splits_last_row).
+// byte, so that it is mapped whatever follows the operand, or the row (of A) or column (of C) that needs that element is
+// left to a kernel that does not reach past the operand: k4_brow_splits_last_row, k4_brow_splits_last_col.
 static bool brow_shape_fits(const Args& a)
 {
     if (a.flags != 0 || a.in_dtype == GEMM_FP8_E4M3 || a.in_dtype == GEMM_F32) return false;
@@ -59,10 +60,40 @@ bool k4_brow_splits_last_row(const Args& a)
     return brow_shape_fits(top) && k4_thin_takes_row_major_b(bot);
 }
 
+// The same for B (N odd, B's last byte the last of a page): the last column of C is left to the masked kernel, which
+// loads element by element, and the columns before it, a B of even row length, stay here.
+bool k4_brow_splits_last_col(const Args& a)
+{
+    if (a.N < 2 || brow_b_tail_mapped(a)) return false;
+    Args left = a;
+    left.N = a.N - 1;
+    return brow_shape_fits(left);
+}
+
+// The columns the persistent kernel keeps (all, or all but the last).
+static Args brow_kept_columns(const Args& a)
+{
+    Args inner = a;
+    if (k4_brow_splits_last_col(a)) inner.N = a.N - 1;
+    return inner;
+}
+
 bool k4_ring_takes_row_major_b(const Args& a)
 {
-    if (!brow_shape_fits(a) || !brow_b_tail_mapped(a)) return false;
-    return brow_a_tail_mapped(a) || k4_brow_splits_last_row(a);
+    if (!brow_shape_fits(a)) return false;
+    if (!brow_b_tail_mapped(a) && !k4_brow_splits_last_col(a)) return false;
+    const Args inner = brow_kept_columns(a);            // (B's rows are of even length there, or its tail is mapped)
+    return brow_a_tail_mapped(inner) || k4_brow_splits_last_row(inner);
+}
+
+// What a product on this path hands to other kernels: 1 = C's last column (masked kernel), 2 = A's last row,
+// 4 = a thin remainder of rows (thin kernel both).
+int k4_brow_splits(const Args& a)
+{
+    const Args inner = brow_kept_columns(a);
+    int m = inner.N != a.N ? 1 : 0;
+    if (k4_brow_splits_last_row(inner)) return m | 2;
+    return m | (k4_brow_splits_m_tail(inner) ? 4 : 0);
 }
 
 static hipError_t launch_brow_rows(const Args& a);
@@ -82,6 +113,19 @@ static hipError_t launch_ring(const Args& a)
 
 hipError_t launch_k4_ring_row_major_b(const Args& a)
 {
+    if (k4_brow_splits_last_col(a)) {        // the element after B is not known to be mapped: see the rule
+        const int es = elem_size(a.in_dtype);
+        Args left = a;
+        left.N = a.N - 1;
+        hipError_t e = launch_k4_ring_row_major_b(left);      // (its B has rows of even length: this branch is not taken again)
+        if (e != hipSuccess) return e;
+        Args right = a;
+        right.N = 1;
+        right.B = (const char*)a.B + (a.N - 1) * es;
+        right.C = (char*)a.C + (a.N - 1) * (a.out_dtype == GEMM_F32 ? 4 : 2);
+        if (a.bias) right.bias = a.bias + (a.N - 1);
+        return launch_k4(MFMA_ELEMENTWISE, right);
+    }
     if (k4_brow_splits_last_row(a)) {        // the element after A is not known to be mapped: see the rule
         const int es = elem_size(a.in_dtype);
         Args top = a;

@@ -126,7 +126,9 @@ def kernel_patterns(variant: int, in_dtype: int, path: str, bm: int, bn: int, th
             pats.append(r"k4_splitk_reduce<%s>" % dt)
         if "stream(M-tail)" in path:
             pats.append(r"k4_stream<gl::StreamCfg<%s, " % dt)
-        if "+thin(" in path:
+        if "+masked(" in path or "+split(" in path:
+            pats.append(r"k4_mfma_masked<%s, " % dt)
+        if "+thin(" in path or "+split(" in path:
             pats.append(r"k4_thin_brow<gl::ThinCfg<%s, " % dt)
         return pats
     return [r"k4_mfma_masked<%s, %d, %d, " % (dt, bm, bn)]

@@ -212,26 +212,33 @@ def test_thin_kernel_reads_a_row_major_b_in_place(dtype, case):
     np.testing.assert_array_equal(got, want)
 
 
-@pytest.mark.parametrize("dtype", [gen.BF16, gen.F16])
-def test_row_major_b_with_a_ending_at_the_end_of_a_page(dtype):
-    """K odd and A's last byte the last of a 4 KiB page: the element after A, which the persistent kernel's loads of
-    the last row touch, may not be mapped, so that row goes to the thin kernel and the rest stays in place (here the
-    page after A belongs to the same allocation)."""
-    M, N, K, nb = 520, 2100, 301, 15                    # 3 x 9 tiles x 15 >= 256
-    inp = int_inputs(dtype, M, N, K, ROW, ROW, batch=nb, seed=5)
-    raw = np.ascontiguousarray(inp.A).view(np.uint8)
+def at_page_end(arr, at_end):
+    """The array's bytes on the GPU, ending with a 4 KiB page when `at_end` (the page after belongs to the same allocation)."""
+    raw = np.ascontiguousarray(arr).view(np.uint8)
     buf = torch.empty(raw.size + 2 * 4096, dtype=torch.uint8, device="cuda")
-    lead = (-(buf.data_ptr() + raw.size)) % 4096       # A's end lands on a page boundary
+    lead = (-(buf.data_ptr() + raw.size)) % 4096 if at_end else 256
     assert lead % 2 == 0
-    dA = buf[lead: lead + raw.size]
-    dA.copy_(torch.from_numpy(raw.copy()))
-    assert (dA.data_ptr() + raw.size) % 4096 == 0
-    dB = util.dev(inp.B)
+    d = buf[lead: lead + raw.size]
+    d.copy_(torch.from_numpy(raw.copy()))
+    assert ((d.data_ptr() + raw.size) % 4096 == 0) == at_end
+    return d
+
+
+@pytest.mark.parametrize("dtype", [gen.BF16, gen.F16])
+@pytest.mark.parametrize("a_end,b_end,suffix", [(True, False, "+thin(last row)"), (False, True, "+masked(last col)"),
+                                                (True, True, "+split(row,col)")])
+def test_row_major_b_with_an_operand_ending_at_the_end_of_a_page(dtype, a_end, b_end, suffix):
+    """K and N odd and an operand's last byte the last of a 4 KiB page: the element after it, which the persistent
+    kernel's loads of the operand's last row touch, may not be mapped.  A's last row then goes to the thin kernel, C's
+    last column (B's last element of every row) to the masked kernel, and the rest stays in place."""
+    M, N, K, nb = 520, 2101, 301, 15                    # 3 x 9 tiles x 15 >= 256, also without the last column
+    inp = int_inputs(dtype, M, N, K, ROW, ROW, batch=nb, seed=5, biased=True)
+    dA, dB = at_page_end(inp.A, a_end), at_page_end(inp.B, b_end)
     d = gemm.make_desc(M, N, K, dtype, gen.F32, ROW, ROW, lda=inp.lda, ldb=inp.ldb, ldc=inp.ldc, batch=nb, stride_a=inp.stride_a,
                        stride_b=inp.stride_b, stride_c=inp.stride_c)
     assert gemm.gemm_query(K4, d).path == "mfma32-direct-to-lds(persistent,B-row-major)"            # (no addresses: nothing known)
     q = gemm.gemm_query(K4, d, dA, dB)
-    assert q.path == "mfma32-direct-to-lds(persistent,B-row-major)+thin(last row)" and q.violated == 0, q.path
+    assert q.path == "mfma32-direct-to-lds(persistent,B-row-major)" + suffix and q.violated == 0, q.path
     C_ref, _ = oracle_for(inp)
     rc, C, _ = util.run_config(K4, inp, dA=dA, dB=dB)
     assert rc == gemm.GEMM_OK, gemm.gemm_status_string(rc)
